@@ -1,0 +1,174 @@
+/*
+ * dpsgd.h - C-ABI of the MI355X-native D-PSGD hot path.
+ *
+ * One synchronous iteration of decentralized parallel SGD (Algorithm 1) over n simulated
+ * workers whose iterates are the rows of an n x d fp32 matrix X resident in one GPU's HBM:
+ *
+ *     G[i]      = minibatch gradient of F at X[i] on worker i's batch     (Algorithm 1 step 3, footnote [a])
+ *     X_next[i] = sum_j W_ij X[j] - gamma * G[i]                          (Algorithm 1 steps 4-5;
+ *                                                                          global form of Section 3)
+ *     xbar      = (1/n) sum_i X[i]                                        (Algorithm 1 step 7)
+ *
+ * Conventions shared by every call
+ *   - Rows are workers: X and G are n x d fp32, row-major with a row stride of `ld` floats
+ *     (ld >= d).  This is the transpose of Section 3's X_k (columns = nodes); the two agree
+ *     because W is symmetric.  Vectorised kernels are used when ld is a multiple of 4 and the
+ *     base pointers are 16-byte aligned; any other ld still works (scalar path).
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library owns only the context (device copy of W and its
+ *     workspace) and frees it in dpsgd_destroy.
+ *   - All device work is enqueued on the hipStream_t given to dpsgd_create; no call
+ *     synchronises the host with the device except dpsgd_create and dpsgd_destroy.
+ *     Device outputs (G, X_out, loss, consensus, xbar) are valid in stream order.
+ *   - Every call returns a dpsgd_status.  Arguments and the topology are validated on the
+ *     host before anything touches the device.
+ *   - One context must not be used from two threads at once; calls that share a context and a
+ *     workspace must be ordered on its stream.
+ */
+#ifndef DPSGD_H
+#define DPSGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dpsgd_ctx dpsgd_ctx;
+
+typedef enum {
+    DPSGD_OK = 0,
+    DPSGD_EINVAL = 1,       /* null pointer, size out of range, model/dimension mismatch */
+    DPSGD_ETOPOLOGY = 2,    /* W violates Section 3's requirements or the CSR is malformed */
+    DPSGD_ENOMEM = 3,       /* host or device allocation failed */
+    DPSGD_EDEVICE = 4,      /* a HIP call failed (no device, launch error) */
+    DPSGD_EUNSUPPORTED = 5  /* valid request this build has no kernel for */
+} dpsgd_status;
+
+/* ---- topology: the weight matrix W of Section 3 (symmetric, doubly stochastic, W_ij in [0,1],
+ *      W_ij = 0 when i and j are not connected). */
+typedef enum {
+    DPSGD_TOPO_CSR = 0,      /* caller-supplied CSR (host arrays) */
+    DPSGD_TOPO_RING = 1,     /* Theorem 3's matrix: W_ii = W_i,i+-1 = 1/3 (indices mod n) */
+    DPSGD_TOPO_TORUS2D = 2,  /* worker i = r*dim1 + c; itself and (r+-1,c), (r,c+-1) at 1/5 */
+    DPSGD_TOPO_COMPLETE = 3  /* W = (1/n) 1 1^T, the centralized special case */
+} dpsgd_topo_kind;
+
+typedef struct {
+    int32_t kind;            /* dpsgd_topo_kind */
+    int32_t dim0, dim1;      /* TORUS2D only: dim0*dim1 == n */
+    const int32_t *rowptr;   /* CSR only, host, n+1 entries, rowptr[0] == 0, non-decreasing */
+    const int32_t *colidx;   /* CSR only, host, nnz entries, strictly ascending inside a row */
+    const float *vals;       /* CSR only, host, nnz entries in [0,1] */
+} dpsgd_topology;
+
+/* Builds (tags) or validates (CSR) W on the host and writes its CSR form; touches no device.
+ * Tags with coinciding neighbours (ring with n < 3, torus with a dimension < 3) accumulate the
+ * duplicate weights, so the result always satisfies Section 3.  Tag values are (float)(1.0/3.0),
+ * (float)(1.0/5.0), (float)(1.0/n).
+ * Validation (DPSGD_ETOPOLOGY on failure): rowptr monotone from 0; column indices in [0,n),
+ * strictly ascending per row; values in [0,1]; |row sum - 1| <= 1e-6; W_ij == W_ji bitwise.
+ * rowptr_out (n+1), colidx_out, vals_out (capacity *nnz_inout entries) are host arrays; any of the
+ * three may be NULL to query only the size.  On return *nnz_inout is the number of non-zeros;
+ * DPSGD_EINVAL if the capacity passed in was too small. */
+dpsgd_status dpsgd_topology_build(int32_t n, const dpsgd_topology *W, int32_t *rowptr_out,
+                                  int32_t *colidx_out, float *vals_out, int64_t *nnz_inout);
+
+/* ---- workload model: fixes F of Section 3's problem statement (F_i = F for all i), the length d
+ *      of a worker's parameter vector and the order of the parameters inside it.
+ *
+ * Flattening order: layer by layer, weight (out x in [x 3 x 3], row-major) then its bias.
+ *   LSQ       widths = {features}.  F = (1/(2B)) ||A x - y||^2 over the minibatch rows.
+ *   SOFTMAX   widths = {features, classes}.  Linear layer + softmax cross-entropy (natural log,
+ *             mean over the minibatch).
+ *   MLP       widths = {features, hidden..., classes}.  ReLU hidden layers (ReLU'(0) = 0),
+ *             softmax cross-entropy.
+ *   RESNET20  widths = {in_ch, height, width, base_ch, blocks_per_stage, classes}.  3x3 stem conv,
+ *             3 stages of basic blocks with base, 2*base, 4*base channels (first conv of stages
+ *             2 and 3 has stride 2), no batch-norm, ONE scalar bias per conv added before the
+ *             ReLU, parameter-free shortcuts (identity; on a stage change every second pixel and
+ *             zero-padded channels), global average pool, fully connected layer with bias,
+ *             softmax cross-entropy.  Inputs are [B][in_ch][height][width].
+ * The minibatch gradient is the MEAN of the B sample gradients (footnote [a]). */
+typedef enum { DPSGD_MODEL_LSQ = 0, DPSGD_MODEL_SOFTMAX = 1, DPSGD_MODEL_MLP = 2, DPSGD_MODEL_RESNET20 = 3 } dpsgd_model_kind;
+
+typedef struct {
+    int32_t kind;            /* dpsgd_model_kind */
+    int32_t n_widths;        /* entries in widths */
+    const int32_t *widths;   /* host */
+    int32_t compute_bf16;    /* 0: fp32 arithmetic.  1: bf16 MFMA operands (weights and activations
+                                rounded to bf16, ties to even), fp32 accumulation, fp32 G */
+} dpsgd_model;
+
+/* Length d the model implies, or -1 if the description is invalid.  Host only. */
+int64_t dpsgd_model_dim(const dpsgd_model *model);
+
+/* One minibatch per worker (Algorithm 1 step 2 has already happened in the caller). */
+typedef struct {
+    const void *inputs;      /* device, [n][batch][features]; fp32, or bf16 if input_is_bf16 */
+    const void *targets;     /* device, [n][batch]; fp32 y for LSQ, int32 class labels otherwise */
+    int32_t batch;           /* B >= 1, samples per worker */
+    int32_t input_is_bf16;   /* 0 or 1 */
+} dpsgd_batch;
+
+/* ---- context */
+
+/* Creates a context for n workers with d parameters each (row stride ld floats, ld >= d; pass 0
+ * for ld == d), the weight matrix W (copied; the caller's arrays may be freed afterwards), the
+ * step length gamma (finite) and a hipStream_t (NULL = the default stream).
+ * Uses the current HIP device.  DPSGD_EINVAL / DPSGD_ETOPOLOGY are decided before any device call. */
+dpsgd_status dpsgd_create(dpsgd_ctx **out, int32_t n, int64_t d, int64_t ld, const dpsgd_topology *W,
+                          float gamma, void *hip_stream);
+
+/* Waits for the context's stream, then frees the context and everything it owns.  NULL is accepted. */
+dpsgd_status dpsgd_destroy(dpsgd_ctx *ctx);
+
+/* Changes the step length for later dpsgd_mix_step calls (learning-rate schedules, Section 5.3). */
+dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
+
+/* Launch-shape knobs for measurements; unknown keys give DPSGD_EINVAL.  Defaults are chosen from
+ * (n, d).  Keys: "mix_bands" (row bands per workgroup of the ring kernel, 0 = auto),
+ * "mix_vec" (floats per lane: 0 = auto, 1, 2 or 4), "mix_force_csr" (1: run the generic CSR
+ * kernel even for ring / torus tags). */
+dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value);
+
+/* CSR of the context's W (host arrays as in dpsgd_topology_build). */
+dpsgd_status dpsgd_topology_export(const dpsgd_ctx *ctx, int32_t *rowptr_out, int32_t *colidx_out,
+                                   float *vals_out, int64_t *nnz_inout);
+
+/* ---- the iteration */
+
+/* Algorithm 1 step 3 for all workers: G[i] = (1/B) sum_b grad_x F(X[i]; sample b of worker i),
+ * evaluated at the worker's own iterate X[i].
+ *   X      device, n x d (stride ld), read only
+ *   G      device, n x d (stride ld), overwritten (padding columns d..ld-1 are left untouched)
+ *   loss   device, n floats: each worker's minibatch loss; may be NULL
+ * dpsgd_model_dim(model) must equal the context's d (else DPSGD_EINVAL).  Activations live in a
+ * workspace owned by the context, (re)allocated when the model or batch size changes. */
+dpsgd_status dpsgd_grad(dpsgd_ctx *ctx, const dpsgd_model *model, const float *X, const dpsgd_batch *batch,
+                        float *G, float *loss);
+
+/* Algorithm 1 steps 4 and 5 fused: X_out[i] = sum_j W_ij X_in[j] - gamma * G[i].
+ *   X_in, G  device, n x d (stride ld), read only
+ *   X_out    device, n x d (stride ld); may be the same buffer as X_in (in place): every workgroup
+ *            owns whole columns and reads all of them before it writes
+ *   consensus device, 1 float, may be NULL: M = (1/n) sum_i || xbar - X_out[i] ||^2 of the OUTPUT
+ *            iterates (the consensus distance of Theorem 4 / eq. 13), reduced in a fixed order.
+ * Each X and G element is read once from HBM and each X_out element written once. */
+dpsgd_status dpsgd_mix_step(dpsgd_ctx *ctx, const float *X_in, const float *G, float *X_out, float *consensus);
+
+/* Footnote [c]'s admissible reordering: update first, then average,
+ *   X_out[i] = sum_j W_ij (X_in[j] - gamma G[j]).  Same arguments as dpsgd_mix_step. */
+dpsgd_status dpsgd_mix_step_swapped(dpsgd_ctx *ctx, const float *X_in, const float *G, float *X_out,
+                                    float *consensus);
+
+/* Algorithm 1 step 7: xbar = (1/n) sum_i X[i].  X device n x d (stride ld); xbar device, d floats. */
+dpsgd_status dpsgd_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
+
+/* Static, never NULL. */
+const char *dpsgd_strerror(dpsgd_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPSGD_H */

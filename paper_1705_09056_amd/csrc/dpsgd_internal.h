@@ -1,0 +1,73 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "dpsgd.h"
+
+struct dpsgd_model_desc {
+    int32_t kind = -1;
+    int32_t compute_bf16 = 0;
+    std::vector<int32_t> widths;
+    int32_t batch = 0;
+    int32_t input_is_bf16 = 0;
+    bool operator==(const dpsgd_model_desc &o) const
+    {
+        return kind == o.kind && compute_bf16 == o.compute_bf16 && widths == o.widths && batch == o.batch &&
+               input_is_bf16 == o.input_is_bf16;
+    }
+};
+
+struct dpsgd_ctx {
+    int32_t n = 0;
+    int64_t d = 0, ld = 0;
+    float gamma = 0.f;
+    hipStream_t stream = nullptr;
+
+    // W, host and device copies (CSR, ascending columns)
+    int32_t topo_kind = 0, dim0 = 0, dim1 = 0;
+    std::vector<int32_t> rowptr, colidx;
+    std::vector<float> vals;
+    int32_t *d_rowptr = nullptr, *d_colidx = nullptr;
+    float *d_vals = nullptr;
+    bool ring_uniform = false;   // Theorem 3's ring with n >= 3: three equal weights per row
+    float ring_w = 0.f;
+
+    // per-workgroup partial sums of the consensus distance
+    double *d_partials = nullptr;
+    int64_t partials_cap = 0;
+
+    // launch-shape options (0 = auto)
+    int32_t opt_mix_bands = 0, opt_mix_vec = 0, opt_mix_force_csr = 0;
+
+    // gradient workspace (activations, bf16 operand copies), owned by the context
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    dpsgd_model_desc ws_model;
+};
+
+namespace dpsgd {
+
+// ---- mix.hip
+dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, float *consensus,
+                        bool swapped);
+dpsgd_status launch_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
+int64_t mix_partials_needed(const dpsgd_ctx *ctx);
+
+// ---- grad_*.hip : each returns the workspace it needs and runs on ctx->stream
+size_t grad_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m);
+dpsgd_status launch_grad(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
+                         const void *targets, float *G, float *loss);
+
+inline dpsgd_status hip_status(hipError_t e) { return e == hipSuccess ? DPSGD_OK : DPSGD_EDEVICE; }
+
+}  // namespace dpsgd
+
+#define DPSGD_HIP_TRY(expr)                                   \
+    do {                                                      \
+        hipError_t _e = (expr);                               \
+        if (_e != hipSuccess) return DPSGD_EDEVICE;           \
+    } while (0)

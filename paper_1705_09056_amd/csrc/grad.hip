@@ -1,0 +1,23 @@
+// Dispatch of dpsgd_grad to the kernels of each workload model and arithmetic.
+#include "grad_common.h"
+
+namespace dpsgd {
+
+static bool is_dense(const dpsgd_model_desc &m) { return m.kind == DPSGD_MODEL_SOFTMAX || m.kind == DPSGD_MODEL_MLP; }
+
+size_t grad_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m)
+{
+    if (m.kind == DPSGD_MODEL_RESNET20) return resnet_workspace_bytes(ctx, m);
+    if (is_dense(m) && m.compute_bf16) return mlp_bf16_workspace_bytes(ctx, m);
+    return f32_workspace_bytes(ctx, m);
+}
+
+dpsgd_status launch_grad(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
+                         const void *targets, float *G, float *loss)
+{
+    if (m.kind == DPSGD_MODEL_RESNET20) return launch_grad_resnet(ctx, m, X, inputs, targets, G, loss);
+    if (is_dense(m) && m.compute_bf16) return launch_grad_mlp_bf16(ctx, m, X, inputs, targets, G, loss);
+    return launch_grad_f32(ctx, m, X, inputs, targets, G, loss);
+}
+
+}  // namespace dpsgd

@@ -1,0 +1,551 @@
+// Gossip-mix + SGD update (Algorithm 1 steps 4-5 fused), node average (step 7) and the
+// consensus distance (eq. 10/13 in the proof of Theorem 1) for gfx950.
+//
+// The work is bound by HBM bandwidth: 12 bytes per (worker, parameter) - X read once, G read
+// once, X_next written once - whatever the degree of W.  To read each replica once, a workgroup
+// owns a slab of columns for ALL n rows:
+//   * ring (Theorem 3's W): each lane owns V consecutive columns and walks the rows keeping
+//     x_{i-1}, x_i, x_{i+1} in registers.  The waves of a workgroup split the rows into bands;
+//     each band loads its two halo rows before a barrier, so the update may be done in place.
+//   * any other W (CSR): the workgroup stages its n x (64 V) slab in LDS, then every wave forms
+//     its rows from LDS in CSR order.
+// The consensus distance of the OUTPUT is accumulated on the fly per column (sums of deviations
+// from a per-lane shift, so that no large numbers cancel), reduced across bands in LDS, across
+// lanes with wave shuffles, and across workgroups in a fixed order by a second tiny kernel.
+#include "dpsgd_internal.h"
+
+namespace dpsgd {
+namespace {
+
+typedef long long i64;
+
+template <int V> struct VecT;
+template <> struct VecT<1> { typedef float type; };
+template <> struct VecT<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct VecT<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+template <int V> __device__ __forceinline__ typename VecT<V>::type vload(const float *p)
+{
+    return *reinterpret_cast<const typename VecT<V>::type *>(p);
+}
+template <int V> __device__ __forceinline__ void vstore(float *p, typename VecT<V>::type v)
+{
+    *reinterpret_cast<typename VecT<V>::type *>(p) = v;
+}
+template <int V> __device__ __forceinline__ float hsum(typename VecT<V>::type v);
+template <> __device__ __forceinline__ float hsum<1>(float v) { return v; }
+template <> __device__ __forceinline__ float hsum<2>(VecT<2>::type v) { return v.x + v.y; }
+template <> __device__ __forceinline__ float hsum<4>(VecT<4>::type v) { return (v.x + v.y) + (v.z + v.w); }
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+// Per-column running sums of (x - shift) and (x - shift)^2 over the rows a lane has produced.
+template <int V> struct ColStats {
+    typedef typename VecT<V>::type vec;
+    vec shift, s1, s2;
+    float cnt;
+    __device__ __forceinline__ void init() { shift = (vec)(0.f); s1 = (vec)(0.f); s2 = (vec)(0.f); cnt = 0.f; }
+    __device__ __forceinline__ void add(vec x)
+    {
+        if (cnt == 0.f) shift = x;
+        vec e = x - shift;
+        s1 += e;
+        s2 += e * e;
+        cnt += 1.f;
+    }
+    // fold `o` (own shift) into this one (keeps this shift)
+    __device__ __forceinline__ void merge(vec oshift, vec os1, vec os2, float ocnt)
+    {
+        if (ocnt == 0.f) return;
+        if (cnt == 0.f) { shift = oshift; s1 = os1; s2 = os2; cnt = ocnt; return; }
+        vec dlt = oshift - shift;
+        s1 += os1 + ocnt * dlt;
+        s2 += os2 + 2.f * dlt * os1 + ocnt * dlt * dlt;
+        cnt += ocnt;
+    }
+    // sum over this lane's columns of sum_i (x_i - mean)^2
+    __device__ __forceinline__ float m2() const
+    {
+        if (cnt == 0.f) return 0.f;
+        vec r = s2 - s1 * s1 * (1.f / cnt);
+        return hsum<V>(r);
+    }
+};
+
+// Combine the per-band ColStats of one column group through LDS; band 0 ends up with the total.
+// lds must hold bands * 64 * (3 V + 1) floats.  Called by every thread of the workgroup.
+template <int V>
+__device__ __forceinline__ void combine_bands(ColStats<V> &st, float *lds, int band, int lane, int bands)
+{
+    typedef typename VecT<V>::type vec;
+    if (bands == 1) return;
+    const int stride = 3 * V + 1;
+    float *mine = lds + ((size_t)band * 64 + lane) * stride;
+    if (band > 0) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            mine[v] = ((const float *)&st.shift)[v];
+            mine[V + v] = ((const float *)&st.s1)[v];
+            mine[2 * V + v] = ((const float *)&st.s2)[v];
+        }
+        mine[3 * V] = st.cnt;
+    }
+    __syncthreads();
+    if (band == 0) {
+        for (int b = 1; b < bands; ++b) {
+            const float *o = lds + ((size_t)b * 64 + lane) * stride;
+            vec sh, a1, a2;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                ((float *)&sh)[v] = o[v];
+                ((float *)&a1)[v] = o[V + v];
+                ((float *)&a2)[v] = o[2 * V + v];
+            }
+            st.merge(sh, a1, a2, o[3 * V]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------- ring
+// grid.x = column groups of 64*V columns; block = 64 * bands threads; wave b owns rows
+// [b*rpb, min(n,(b+1)*rpb)).  U rows are fetched ahead of the row being formed.
+template <int V, int U, bool CONS>
+__global__ void __launch_bounds__(512)
+mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld, float w,
+                float gamma, int bands, int rpb, double *__restrict__ partials)
+{
+    typedef typename VecT<V>::type vec;
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x & 63;
+    const int band = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const i64 c0 = ((i64)blockIdx.x * 64 + lane) * V;
+    const bool active = c0 + V <= ncols;
+    const int r0 = band * rpb;
+    const int r1 = min(n, r0 + rpb);
+    const float *xin = Xin + c0;
+    const float *gin = G + c0;
+    float *xout = Xout + c0;
+
+    vec xm = (vec)(0.f), xc = (vec)(0.f), xhalo = (vec)(0.f);
+    if (active && r0 < r1) {
+        xm = vload<V>(xin + (i64)((r0 + n - 1) % n) * ld);
+        xc = vload<V>(xin + (i64)r0 * ld);
+        xhalo = vload<V>(xin + (i64)(r1 % n) * ld);
+    }
+    // Every band has fetched the rows its neighbours are about to overwrite.
+    if (bands > 1) __syncthreads();
+
+    ColStats<V> st;
+    st.init();
+    if (active) {
+        vec xa[U], ga[U], xb[U], gb[U];
+        auto fetch = [&](int base, vec(&xs)[U], vec(&gs)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = base + u;
+                if (row < r1) {
+                    gs[u] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gin + (i64)row * ld));
+                    xs[u] = (row + 1 < r1) ? vload<V>(xin + (i64)(row + 1) * ld) : xhalo;
+                }
+            }
+        };
+        auto form = [&](int base, vec(&xs)[U], vec(&gs)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = base + u;
+                if (row < r1) {
+                    vec acc = w * xm;
+                    acc = w * xc + acc;
+                    acc = w * xs[u] + acc;
+                    vec o = acc - gamma * gs[u];
+                    vstore<V>(xout + (i64)row * ld, o);
+                    if (CONS) st.add(o);
+                    xm = xc;
+                    xc = xs[u];
+                }
+            }
+        };
+        fetch(r0, xa, ga);
+        for (int base = r0; base < r1; base += 2 * U) {
+            fetch(base + U, xb, gb);
+            form(base, xa, ga);
+            fetch(base + 2 * U, xa, ga);
+            form(base + U, xb, gb);
+        }
+    }
+    if (CONS) {
+        combine_bands<V>(st, lds, band, lane, bands);
+        if (band == 0) {
+            double v = wave_sum((double)st.m2());
+            if (lane == 0) partials[blockIdx.x] = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------ CSR via LDS slab
+// grid.x = column groups of 64*V columns; block = 64 * RG threads; lane = column vector,
+// wave = row group (rows rg, rg+RG, ...).  Dynamic LDS: n * 64 * V floats (+ stats region).
+template <int V, bool CONS, bool SWAPPED>
+__global__ void __launch_bounds__(1024)
+mix_csr_slab_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld,
+                    const int *__restrict__ rowptr, const int *__restrict__ colidx, const float *__restrict__ vals,
+                    float gamma, int rgroups, double *__restrict__ partials)
+{
+    typedef typename VecT<V>::type vec;
+    extern __shared__ float lds[];
+    vec *slab = reinterpret_cast<vec *>(lds);   // [n][64]
+    const int lane = threadIdx.x & 63;
+    const int rg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const i64 c0 = ((i64)blockIdx.x * 64 + lane) * V;
+    const bool active = c0 + V <= ncols;
+    const float *xin = Xin + c0;
+    const float *gin = G + c0;
+    float *xout = Xout + c0;
+
+    if (active) {
+        for (int row = rg; row < n; row += rgroups) {
+            vec x = vload<V>(xin + (i64)row * ld);
+            if (SWAPPED) x = x - gamma * vload<V>(gin + (i64)row * ld);
+            slab[(size_t)row * 64 + lane] = x;
+        }
+    }
+    __syncthreads();   // the whole slab is in LDS; from here on rows may be overwritten
+
+    ColStats<V> st;
+    st.init();
+    if (active) {
+        for (int row = rg; row < n; row += rgroups) {
+            const int p0 = rowptr[row], p1 = rowptr[row + 1];
+            vec g = (vec)(0.f);
+            if (!SWAPPED) g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gin + (i64)row * ld));
+            vec acc = (vec)(0.f);
+            for (int p = p0; p < p1; ++p) acc = vals[p] * slab[(size_t)colidx[p] * 64 + lane] + acc;
+            vec o = SWAPPED ? acc : acc - gamma * g;
+            vstore<V>(xout + (i64)row * ld, o);
+            if (CONS) st.add(o);
+        }
+    }
+    if (CONS) {
+        __syncthreads();   // slab no longer needed; reuse LDS for the statistics
+        combine_bands<V>(st, lds, rg, lane, rgroups);
+        if (rg == 0) {
+            double v = wave_sum((double)st.m2());
+            if (lane == 0) partials[blockIdx.x] = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------- CSR without a slab (large n)
+// One thread per (row, column); neighbours are gathered from global memory.  Out of place only.
+template <bool SWAPPED>
+__global__ void __launch_bounds__(256)
+mix_csr_gather_kernel(const float *__restrict__ Xin, const float *__restrict__ G, float *__restrict__ Xout, int n,
+                      i64 ncols, i64 ld, const int *__restrict__ rowptr, const int *__restrict__ colidx,
+                      const float *__restrict__ vals, float gamma)
+{
+    const i64 c = (i64)blockIdx.x * 256 + threadIdx.x;
+    const int row = blockIdx.y;
+    if (c >= ncols || row >= n) return;
+    float acc = 0.f;
+    for (int p = rowptr[row]; p < rowptr[row + 1]; ++p) {
+        const i64 j = colidx[p];
+        float x = Xin[j * ld + c];
+        if (SWAPPED) x -= gamma * G[j * ld + c];
+        acc = vals[p] * x + acc;
+    }
+    Xout[(i64)row * ld + c] = SWAPPED ? acc : acc - gamma * G[(i64)row * ld + c];
+}
+
+// ---------------------------------------------------------------- column statistics / mean
+// Same slab ownership as the ring kernel (lane = V columns, wave = row band), read only.
+// MEAN: writes xbar.  CONS: writes the per-workgroup partial of sum_i ||x_i - xbar||^2.
+template <int V, bool MEAN, bool CONS>
+__global__ void __launch_bounds__(512)
+column_stats_kernel(const float *__restrict__ X, int n, i64 ncols, i64 ld, int bands, int rpb, float inv_n,
+                    float *__restrict__ xbar, double *__restrict__ partials)
+{
+    typedef typename VecT<V>::type vec;
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x & 63;
+    const int band = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const i64 c0 = ((i64)blockIdx.x * 64 + lane) * V;
+    const bool active = c0 + V <= ncols;
+    const int r0 = band * rpb, r1 = min(n, r0 + rpb);
+    ColStats<V> st;
+    st.init();
+    vec sum = (vec)(0.f);
+    if (active) {
+        const float *x = X + c0;
+#pragma unroll 4
+        for (int row = r0; row < r1; ++row) {
+            vec v = vload<V>(x + (i64)row * ld);
+            if (MEAN) sum += v;
+            if (CONS) st.add(v);
+        }
+    }
+    if (MEAN) {
+        vec *acc = reinterpret_cast<vec *>(lds);   // [bands][64]
+        if (bands > 1) {
+            acc[(size_t)band * 64 + lane] = sum;
+            __syncthreads();
+            if (band == 0)
+                for (int b = 1; b < bands; ++b) sum += acc[(size_t)b * 64 + lane];   // ascending rows
+            __syncthreads();
+        }
+        if (band == 0 && active) vstore<V>(xbar + c0, sum * inv_n);
+    }
+    if (CONS) {
+        combine_bands<V>(st, lds, band, lane, bands);
+        if (band == 0) {
+            double v = wave_sum((double)st.m2());
+            if (lane == 0) partials[blockIdx.x] = v;
+        }
+    }
+}
+
+// Fixed-order sum of the per-workgroup partials: consensus = (sum partials) / n.
+__global__ void __launch_bounds__(256) consensus_finalize_kernel(const double *__restrict__ partials, i64 count,
+                                                                  double inv_n, float *__restrict__ out)
+{
+    __shared__ double sh[256];
+    double s = 0.0;
+    for (i64 i = threadIdx.x; i < count; i += 256) s += partials[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = (float)(sh[0] * inv_n);
+}
+
+// --------------------------------------------------------------------------- host helpers
+struct Plan {
+    int vec;        // floats per lane for the bulk launch
+    i64 bulk_cols;  // columns covered by the vector launch (multiple of vec)
+    i64 tail_cols;  // remaining columns, handled with vec = 1
+};
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int pick_vec(const dpsgd_ctx *ctx, std::initializer_list<const void *> ptrs, int cap)
+{
+    int v = 4;
+    if (ctx->opt_mix_vec) v = ctx->opt_mix_vec;
+    if (v > cap) v = cap;
+    while (v > 1) {
+        bool ok = (ctx->ld % v) == 0;
+        for (const void *p : ptrs) ok = ok && aligned(p, sizeof(float) * (size_t)v);
+        if (ok && ctx->d >= v) break;
+        v >>= 1;
+    }
+    return v;
+}
+
+Plan make_plan(const dpsgd_ctx *ctx, int vec)
+{
+    Plan p;
+    p.vec = vec;
+    p.bulk_cols = ctx->d - ctx->d % vec;
+    p.tail_cols = ctx->d - p.bulk_cols;
+    return p;
+}
+
+i64 groups_for(i64 cols, int vec) { return (cols + 64LL * vec - 1) / (64LL * vec); }
+
+// Row bands per workgroup: one band when there are already plenty of waves, more when the
+// matrix is narrow, so that the chip still sees a few thousand waves.
+constexpr int kMaxBands = 8;   // the ring kernel is compiled for at most 8 waves per workgroup
+
+int pick_bands(const dpsgd_ctx *ctx, i64 groups)
+{
+    int bands = ctx->opt_mix_bands;
+    if (bands == 0) {
+        bands = 1;
+        while (bands < kMaxBands && groups * bands < 8192 && ctx->n / (bands * 2) >= 4) bands *= 2;
+    }
+    if (bands > kMaxBands) bands = kMaxBands;
+    if (bands > ctx->n) bands = ctx->n;
+    if (bands < 1) bands = 1;
+    return bands;
+}
+
+size_t stats_lds_bytes(int bands, int vec) { return bands > 1 ? (size_t)bands * 64 * (3 * vec + 1) * sizeof(float) : 0; }
+
+template <int V>
+dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols,
+                         bool cons, double *partials, i64 *nparts)
+{
+    const i64 groups = groups_for(ncols, V);
+    const int bands = pick_bands(ctx, groups);
+    const int rpb = (ctx->n + bands - 1) / bands;
+    const int used = (ctx->n + rpb - 1) / rpb;   // every launched band owns at least one row
+    dim3 grid((unsigned)groups), block(64u * (unsigned)used);
+    if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
+    const size_t shm = cons ? stats_lds_bytes(used, V) : 0;
+    if (cons)
+        hipLaunchKernelGGL((mix_ring_kernel<V, 4, true>), grid, block, shm, ctx->stream, Xin + col0, G + col0,
+                           Xout + col0, ctx->n, ncols, ctx->ld, ctx->ring_w, ctx->gamma, used, rpb, partials);
+    else
+        hipLaunchKernelGGL((mix_ring_kernel<V, 4, false>), grid, block, shm, ctx->stream, Xin + col0, G + col0,
+                           Xout + col0, ctx->n, ncols, ctx->ld, ctx->ring_w, ctx->gamma, used, rpb, partials);
+    *nparts = groups;
+    return hip_status(hipGetLastError());
+}
+
+constexpr size_t kSlabLdsBudget = 64 * 1024;
+
+template <int V, bool SWAPPED>
+dpsgd_status slab_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols,
+                         bool cons, double *partials, i64 *nparts)
+{
+    const i64 groups = groups_for(ncols, V);
+    if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
+    int rgroups = ctx->n < 4 ? ctx->n : 4;
+    size_t shm = (size_t)ctx->n * 64 * V * sizeof(float);
+    const size_t stats = stats_lds_bytes(rgroups, V);
+    if (cons && stats > shm) shm = stats;
+    dim3 grid((unsigned)groups), block(64u * (unsigned)rgroups);
+    if (cons)
+        hipLaunchKernelGGL((mix_csr_slab_kernel<V, true, SWAPPED>), grid, block, shm, ctx->stream, Xin + col0,
+                           G + col0, Xout + col0, ctx->n, ncols, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals,
+                           ctx->gamma, rgroups, partials);
+    else
+        hipLaunchKernelGGL((mix_csr_slab_kernel<V, false, SWAPPED>), grid, block, shm, ctx->stream, Xin + col0,
+                           G + col0, Xout + col0, ctx->n, ncols, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals,
+                           ctx->gamma, rgroups, partials);
+    *nparts = groups;
+    return hip_status(hipGetLastError());
+}
+
+template <int V, bool MEAN, bool CONS>
+dpsgd_status stats_launch(dpsgd_ctx *ctx, const float *X, i64 col0, i64 ncols, float *xbar, double *partials,
+                          i64 *nparts)
+{
+    const i64 groups = groups_for(ncols, V);
+    if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
+    const int bands = pick_bands(ctx, groups);
+    const int rpb = (ctx->n + bands - 1) / bands;
+    const int used = (ctx->n + rpb - 1) / rpb;
+    size_t shm = 0;
+    if (MEAN && used > 1) shm = (size_t)used * 64 * V * sizeof(float);
+    if (CONS && stats_lds_bytes(used, V) > shm) shm = stats_lds_bytes(used, V);
+    hipLaunchKernelGGL((column_stats_kernel<V, MEAN, CONS>), dim3((unsigned)groups), dim3(64u * (unsigned)used), shm,
+                       ctx->stream, X + col0, ctx->n, ncols, ctx->ld, used, rpb, 1.0f / (float)ctx->n,
+                       xbar ? xbar + col0 : nullptr, partials);
+    *nparts = groups;
+    return hip_status(hipGetLastError());
+}
+
+dpsgd_status finalize_consensus(dpsgd_ctx *ctx, i64 count, float *consensus)
+{
+    hipLaunchKernelGGL(consensus_finalize_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->d_partials, count,
+                       1.0 / (double)ctx->n, consensus);
+    return hip_status(hipGetLastError());
+}
+
+// sum_i ||x_i - xbar||^2 / n of a matrix already in memory (used when the mix kernel itself
+// cannot accumulate it).
+dpsgd_status consensus_of(dpsgd_ctx *ctx, const float *X, float *consensus)
+{
+    const int vec = pick_vec(ctx, {X}, 4);
+    const Plan p = make_plan(ctx, vec);
+    i64 n1 = 0, n2 = 0;
+    dpsgd_status st = DPSGD_OK;
+    if (p.bulk_cols) {
+        if (vec == 4) st = stats_launch<4, false, true>(ctx, X, 0, p.bulk_cols, nullptr, ctx->d_partials, &n1);
+        else if (vec == 2) st = stats_launch<2, false, true>(ctx, X, 0, p.bulk_cols, nullptr, ctx->d_partials, &n1);
+        else st = stats_launch<1, false, true>(ctx, X, 0, p.bulk_cols, nullptr, ctx->d_partials, &n1);
+    }
+    if (st == DPSGD_OK && p.tail_cols)
+        st = stats_launch<1, false, true>(ctx, X, p.bulk_cols, p.tail_cols, nullptr, ctx->d_partials + n1, &n2);
+    if (st != DPSGD_OK) return st;
+    return finalize_consensus(ctx, n1 + n2, consensus);
+}
+
+}  // namespace
+
+int64_t mix_partials_needed(const dpsgd_ctx *ctx)
+{
+    // one partial per workgroup of the widest possible launch (vec = 1) plus the tail launch
+    return groups_for(ctx->d, 1) + 8;
+}
+
+dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, float *consensus, bool swapped)
+{
+    const bool cons = consensus != nullptr;
+    const bool ring = ctx->ring_uniform && !ctx->opt_mix_force_csr && !swapped;
+    i64 n1 = 0, n2 = 0;
+    dpsgd_status st = DPSGD_OK;
+
+    if (ring) {
+        const int vec = pick_vec(ctx, {Xin, G, Xout}, 4);
+        const Plan p = make_plan(ctx, vec);
+        if (p.bulk_cols) {
+            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1);
+            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1);
+            else st = ring_launch<1>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1);
+        }
+        if (st == DPSGD_OK && p.tail_cols)
+            st = ring_launch<1>(ctx, Xin, G, Xout, p.bulk_cols, p.tail_cols, cons, ctx->d_partials + n1, &n2);
+        if (st != DPSGD_OK) return st;
+        return cons ? finalize_consensus(ctx, n1 + n2, consensus) : DPSGD_OK;
+    }
+
+    // widest vector whose n-row slab fits the LDS budget
+    int cap = 4;
+    while (cap >= 1 && (size_t)ctx->n * 64 * cap * sizeof(float) > kSlabLdsBudget) cap >>= 1;
+    if (cap >= 1) {
+        const int vec = pick_vec(ctx, {Xin, G, Xout}, cap);
+        const Plan p = make_plan(ctx, vec);
+#define DPSGD_SLAB(V, C0, NC, PART, NP)                                                              \
+    (swapped ? slab_launch<V, true>(ctx, Xin, G, Xout, C0, NC, cons, PART, NP)                       \
+             : slab_launch<V, false>(ctx, Xin, G, Xout, C0, NC, cons, PART, NP))
+        if (p.bulk_cols) {
+            if (vec == 4) st = DPSGD_SLAB(4, 0, p.bulk_cols, ctx->d_partials, &n1);
+            else if (vec == 2) st = DPSGD_SLAB(2, 0, p.bulk_cols, ctx->d_partials, &n1);
+            else st = DPSGD_SLAB(1, 0, p.bulk_cols, ctx->d_partials, &n1);
+        }
+        if (st == DPSGD_OK && p.tail_cols) st = DPSGD_SLAB(1, p.bulk_cols, p.tail_cols, ctx->d_partials + n1, &n2);
+#undef DPSGD_SLAB
+        if (st != DPSGD_OK) return st;
+        return cons ? finalize_consensus(ctx, n1 + n2, consensus) : DPSGD_OK;
+    }
+
+    // n too large for an LDS slab: gather from global memory, out of place only
+    if (Xin == Xout) return DPSGD_EUNSUPPORTED;
+    const i64 gx = (ctx->d + 255) / 256;
+    if (gx > 0x7fffffffLL || ctx->n > 65535) return DPSGD_EUNSUPPORTED;
+    dim3 grid((unsigned)gx, (unsigned)ctx->n);
+    if (swapped)
+        hipLaunchKernelGGL(mix_csr_gather_kernel<true>, grid, dim3(256), 0, ctx->stream, Xin, G, Xout, ctx->n, ctx->d,
+                           ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma);
+    else
+        hipLaunchKernelGGL(mix_csr_gather_kernel<false>, grid, dim3(256), 0, ctx->stream, Xin, G, Xout, ctx->n,
+                           ctx->d, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma);
+    st = hip_status(hipGetLastError());
+    if (st != DPSGD_OK) return st;
+    return cons ? consensus_of(ctx, Xout, consensus) : DPSGD_OK;
+}
+
+dpsgd_status launch_mean(dpsgd_ctx *ctx, const float *X, float *xbar)
+{
+    const int vec = pick_vec(ctx, {X, xbar}, 4);
+    const Plan p = make_plan(ctx, vec);
+    i64 np = 0;
+    dpsgd_status st = DPSGD_OK;
+    if (p.bulk_cols) {
+        if (vec == 4) st = stats_launch<4, true, false>(ctx, X, 0, p.bulk_cols, xbar, nullptr, &np);
+        else if (vec == 2) st = stats_launch<2, true, false>(ctx, X, 0, p.bulk_cols, xbar, nullptr, &np);
+        else st = stats_launch<1, true, false>(ctx, X, 0, p.bulk_cols, xbar, nullptr, &np);
+    }
+    if (st == DPSGD_OK && p.tail_cols) st = stats_launch<1, true, false>(ctx, X, p.bulk_cols, p.tail_cols, xbar, nullptr, &np);
+    return st;
+}
+
+}  // namespace dpsgd
