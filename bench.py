@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the D-PSGD hot path on one MI355X.
+
+A "step" is one synchronous iteration of Algorithm 1 over all n simulated workers:
+dpsgd_grad (step 3) followed by dpsgd_mix_step (steps 4-5, with the consensus distance).  Inputs
+(replicas, a pool of pre-generated minibatches) are resident in HBM before the timed region;
+drawing the minibatches (step 2) is not timed.
+
+Prints ONE JSON line: worker-iterations/s, plus the roofline of the dominant kernel (the fused
+mix+step kernel: 12 bytes per (worker, parameter)) measured with HIP events around every mix
+launch inside the timed region, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed iterations (0 = the workload's K)")
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mlp3_ring64",
+                    help="lsq_ring8 | softmax_ring16 | mlp2_ring32 | mlp3_ring64 | mlp3_torus8x8 | resnet20_ring112")
+    ap.add_argument("--pool", type=int, default=4, help="distinct minibatches kept in HBM and cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-consensus", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, seconds_budget=20.0):
+    """The oracle as it stands, on this machine's host cores, on a bounded sample of the workload:
+    the gradient of `m` workers (OpenMP over workers) and the mix+step on a column sample, scaled to
+    one full iteration of all n workers."""
+    import numpy as np
+
+    import oracle
+    from paper_1705_09056_amd import synth
+
+    threads = oracle.num_threads()
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    # per-worker gradient cost estimate (fp64 scalar flops) to size the sample
+    flops_per_worker = {0: 4.0 * cfg.batch * d, 1: 4.0 * cfg.batch * d, 2: 6.0 * cfg.batch * d,
+                        3: 6.0 * 40.6e6 * cfg.batch}[cfg.model_kind]
+    est_rate = 0.8e9  # scalar fp64 flop/s per core of the plain loops, order of magnitude
+    all_workers_s = flops_per_worker * cfg.n / max(1, min(threads, cfg.n)) / est_rate
+    m = cfg.n if all_workers_s <= seconds_budget else min(cfg.n, threads)
+    workers = list(range(m))
+    x0 = synth.make_x0(cfg).astype(np.float64)
+    X = np.tile(x0, (m, 1))
+    inp, tgt = synth.make_batch(cfg, 0, workers)
+    t0 = time.perf_counter()
+    oracle.grad_all(cfg.model_kind, cfg.widths, X, inp, tgt)
+    t_grad = time.perf_counter() - t0
+    # mix + step on a column sample of all n rows
+    dcols = int(min(d, max(1, 4_000_000 // cfg.n)))
+    rng = np.random.default_rng(0)
+    Xs = rng.standard_normal((cfg.n, dcols))
+    Gs = rng.standard_normal((cfg.n, dcols))
+    topo = oracle.ring(cfg.n) if cfg.topology == "ring" else oracle.torus(*cfg.torus_dims)
+    t0 = time.perf_counter()
+    oracle.mix_step(topo, Xs, Gs, cfg.gamma)
+    t_mix = (time.perf_counter() - t0) * (d / dcols)
+    # m workers ran on min(m, threads) cores at once; all n workers need n/m such rounds
+    t_iter = t_grad * (cfg.n / m) + t_mix
+    return {
+        "value": cfg.n / t_iter, "unit": "worker-iters/s", "cores": int(min(threads, m)), "kind": "oracle",
+        "sample": f"gradient of {m} of {cfg.n} workers (one minibatch each, OpenMP over workers, {t_grad:.2f} s) "
+                  f"scaled by n/{m}; mix+step on {dcols} of {d} columns (single thread, scaled to d)",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding across GPUs); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1705_09056_amd import binding as B
+    from paper_1705_09056_amd import synth
+    from paper_1705_09056_amd.configs import MODEL_LSQ, by_name
+
+    cfg = by_name(args.workload)
+    K = args.steps or cfg.iters
+    W = args.warmup
+    torch.cuda.set_device(0)
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    ld = synth.padded_stride(d)
+    topo = B.Topology.ring() if cfg.topology == "ring" else B.Topology.torus(*cfg.torus_dims)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=cfg.bf16)
+
+    # replicas: n copies of x_0 (Algorithm 1, Require)
+    x0 = torch.from_numpy(synth.make_x0(cfg)).cuda()
+    X = torch.zeros(cfg.n, ld, device="cuda")
+    X[:, :d] = x0
+    G = torch.zeros_like(X)
+    loss = torch.zeros(cfg.n, device="cuda")
+    cons = None if args.no_consensus else torch.zeros(1, device="cuda")
+    pool = []
+    for k in range(max(1, args.pool)):
+        inp, tgt = synth.make_batch(cfg, k)
+        if cfg.bf16:
+            inp_d = torch.from_numpy(synth.bf16_bits(inp).astype(np.int16)).view(torch.bfloat16).cuda()
+        else:
+            inp_d = torch.from_numpy(inp).cuda()
+        pool.append((inp_d, torch.from_numpy(tgt).cuda()))
+
+    ctx = B.Dpsgd(cfg.n, d, topo, cfg.gamma, ld=ld)
+
+    def step(k, ev=None):
+        inp_d, tgt_d = pool[k % len(pool)]
+        ctx.grad(model, X, inp_d, tgt_d, cfg.batch, G, loss, input_is_bf16=cfg.bf16)
+        if ev is not None:
+            ev[0].record()
+        ctx.mix_step(X, G, X, cons)
+        if ev is not None:
+            ev[1].record()
+
+    for k in range(W):
+        step(k)
+    torch.cuda.synchronize()
+    # HIP events on the stream the library launches on (torch's current stream was handed to dpsgd_create)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    t_begin.record()
+    for k in range(K):
+        step(W + k, evs[k])
+    t_end.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    total_ms = t_begin.elapsed_time(t_end)
+    mix_ms = sum(a.elapsed_time(b) for a, b in evs) / K
+    final_loss = float(loss.mean().item())
+    final_cons = None if cons is None else float(cons.item())
+    ctx.close()
+
+    mix_bytes = 12.0 * cfg.n * d
+    achieved = mix_bytes / (mix_ms * 1e-3) / 1e9
+    out = {
+        "metric": "worker-iters/sec (grad+mix) at n workers",
+        "value": cfg.n * K / (total_ms * 1e-3),
+        "unit": "worker-iters/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": total_ms / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "model_kind": int(cfg.model_kind), "widths": list(cfg.widths), "n": cfg.n,
+                   "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "gamma": cfg.gamma,
+                   "minibatch_pool": len(pool), "consensus": cons is not None},
+        "roofline": {"kernel": "mix_step (Algorithm 1 steps 4-5 fused)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_ms},
+        "mix_fraction_of_step": mix_ms / (total_ms / K),
+        "wall_s": wall,
+        "final_mean_loss": final_loss, "final_consensus": final_cons,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

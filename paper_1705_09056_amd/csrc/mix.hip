@@ -113,7 +113,7 @@ __device__ __forceinline__ void combine_bands(ColStats<V> &st, float *lds, int b
 
 // ------------------------------------------------------------------------------- ring
 // grid.x = column groups of 64*V columns; block = 64 * bands threads; wave b owns rows
-// [b*rpb, min(n,(b+1)*rpb)).  U rows are fetched ahead of the row being formed.
+// [b*rpb, min(n,(b+1)*rpb)).
 template <int V, int U, bool CONS>
 __global__ void __launch_bounds__(512)
 mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld, float w,
@@ -142,41 +142,46 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
 
     ColStats<V> st;
     st.init();
-    if (active) {
-        vec xa[U], ga[U], xb[U], gb[U];
-        auto fetch = [&](int base, vec(&xs)[U], vec(&gs)[U]) {
+    if (active && r0 < r1) {
+        // Rows r0 .. r1-2 read their successor from memory in branch-free chunks of U rows (2U
+        // loads in flight per lane); the band's last row takes the halo fetched above.
+        auto form = [&](vec xn, vec g, float *dst) {
+            vec acc = w * xm;
+            acc = w * xc + acc;
+            acc = w * xn + acc;
+            vec o = acc - gamma * g;
+            vstore<V>(dst, o);
+            if (CONS) st.add(o);
+            xm = xc;
+            xc = xn;
+        };
+        int row = r0;
+        const int rlast = r1 - 1;
+        const float *xp = xin + (i64)(row + 1) * ld;
+        const float *gp = gin + (i64)row * ld;
+        float *op = xout + (i64)row * ld;
+        for (; row + U <= rlast; row += U) {
+            vec xs[U], gs[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int row = base + u;
-                if (row < r1) {
-                    gs[u] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gin + (i64)row * ld));
-                    xs[u] = (row + 1 < r1) ? vload<V>(xin + (i64)(row + 1) * ld) : xhalo;
-                }
+                gs[u] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gp + (i64)u * ld));
+                xs[u] = vload<V>(xp + (i64)u * ld);
             }
-        };
-        auto form = [&](int base, vec(&xs)[U], vec(&gs)[U]) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = base + u;
-                if (row < r1) {
-                    vec acc = w * xm;
-                    acc = w * xc + acc;
-                    acc = w * xs[u] + acc;
-                    vec o = acc - gamma * gs[u];
-                    vstore<V>(xout + (i64)row * ld, o);
-                    if (CONS) st.add(o);
-                    xm = xc;
-                    xc = xs[u];
-                }
-            }
-        };
-        fetch(r0, xa, ga);
-        for (int base = r0; base < r1; base += 2 * U) {
-            fetch(base + U, xb, gb);
-            form(base, xa, ga);
-            fetch(base + 2 * U, xa, ga);
-            form(base + U, xb, gb);
+            for (int u = 0; u < U; ++u) form(xs[u], gs[u], op + (i64)u * ld);
+            xp += (i64)U * ld;
+            gp += (i64)U * ld;
+            op += (i64)U * ld;
         }
+        for (; row < rlast; ++row) {
+            vec g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gp));
+            vec xn = vload<V>(xp);
+            form(xn, g, op);
+            xp += ld;
+            gp += ld;
+            op += ld;
+        }
+        form(xhalo, __builtin_nontemporal_load(reinterpret_cast<const vec *>(gp)), op);
     }
     if (CONS) {
         combine_bands<V>(st, lds, band, lane, bands);
@@ -208,27 +213,47 @@ mix_csr_slab_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
     float *xout = Xout + c0;
 
     if (active) {
-        for (int row = rg; row < n; row += rgroups) {
+        auto stage = [&](int row) {
             vec x = vload<V>(xin + (i64)row * ld);
             if (SWAPPED) x = x - gamma * vload<V>(gin + (i64)row * ld);
-            slab[(size_t)row * 64 + lane] = x;
+            return x;
+        };
+        int row = rg;
+        for (; row + 3 * rgroups < n; row += 4 * rgroups) {   // four independent loads in flight
+            vec x0 = stage(row), x1 = stage(row + rgroups), x2 = stage(row + 2 * rgroups), x3 = stage(row + 3 * rgroups);
+            slab[(size_t)row * 64 + lane] = x0;
+            slab[(size_t)(row + rgroups) * 64 + lane] = x1;
+            slab[(size_t)(row + 2 * rgroups) * 64 + lane] = x2;
+            slab[(size_t)(row + 3 * rgroups) * 64 + lane] = x3;
         }
+        for (; row < n; row += rgroups) slab[(size_t)row * 64 + lane] = stage(row);
     }
     __syncthreads();   // the whole slab is in LDS; from here on rows may be overwritten
 
     ColStats<V> st;
     st.init();
     if (active) {
-        for (int row = rg; row < n; row += rgroups) {
+        auto form = [&](int row, vec g) {
             const int p0 = rowptr[row], p1 = rowptr[row + 1];
-            vec g = (vec)(0.f);
-            if (!SWAPPED) g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gin + (i64)row * ld));
             vec acc = (vec)(0.f);
             for (int p = p0; p < p1; ++p) acc = vals[p] * slab[(size_t)colidx[p] * 64 + lane] + acc;
             vec o = SWAPPED ? acc : acc - gamma * g;
             vstore<V>(xout + (i64)row * ld, o);
             if (CONS) st.add(o);
+        };
+        auto gload = [&](int row) {
+            return SWAPPED ? (vec)(0.f)
+                           : __builtin_nontemporal_load(reinterpret_cast<const vec *>(gin + (i64)row * ld));
+        };
+        int row = rg;
+        for (; row + 3 * rgroups < n; row += 4 * rgroups) {
+            vec g0 = gload(row), g1 = gload(row + rgroups), g2 = gload(row + 2 * rgroups), g3 = gload(row + 3 * rgroups);
+            form(row, g0);
+            form(row + rgroups, g1);
+            form(row + 2 * rgroups, g2);
+            form(row + 3 * rgroups, g3);
         }
+        for (; row < n; row += rgroups) form(row, gload(row));
     }
     if (CONS) {
         __syncthreads();   // slab no longer needed; reuse LDS for the statistics
