@@ -54,10 +54,10 @@ def lib():
         L.orc_model_dim.restype = C.c_int64
         L.orc_model_dim.argtypes = [C.c_int32, C.c_int32, i32p]
         L.orc_loss_grad.restype = C.c_double
-        L.orc_loss_grad.argtypes = [C.c_int32, C.c_int32, i32p, f64p, f64p, C.c_void_p, C.c_int32, f64p]
+        L.orc_loss_grad.argtypes = [C.c_int32, C.c_int32, i32p, f64p, f64p, C.c_void_p, C.c_int32, f64p, C.c_int32]
         L.orc_grad_all.restype = None
         L.orc_grad_all.argtypes = [C.c_int32, C.c_int32, i32p, C.c_int32, C.c_int64, f64p, f64p, C.c_void_p,
-                                   C.c_int32, f64p, f64p]
+                                   C.c_int32, f64p, f64p, C.c_int32]
         L.orc_num_threads.restype = C.c_int32
         _lib = L
     return _lib
@@ -159,8 +159,9 @@ def _targets(kind, targets):
     return t, t.ctypes.data_as(C.c_void_p)
 
 
-def loss_grad(kind: int, widths, x, inputs, targets, want_grad: bool = True):
-    """One worker: (loss, grad or None).  inputs [B][features]."""
+def loss_grad(kind: int, widths, x, inputs, targets, want_grad: bool = True, bf16_operands: bool = False):
+    """One worker: (loss, grad or None).  inputs [B][features].  ``bf16_operands`` rounds the operands
+    of every contraction to bf16 (the precision the bf16 workloads prescribe); sums stay fp64."""
     w, wp = _i32(widths)
     nl = len(w) - 1 if kind in (SOFTMAX, MLP) else 0
     x, xp = _f64(x)
@@ -169,11 +170,11 @@ def loss_grad(kind: int, widths, x, inputs, targets, want_grad: bool = True):
     t, tp = _targets(kind, targets)
     g = np.empty_like(x) if want_grad else None
     gp = g.ctypes.data_as(C.POINTER(C.c_double)) if want_grad else None
-    loss = lib().orc_loss_grad(kind, nl, wp, xp, ip, tp, B, gp)
+    loss = lib().orc_loss_grad(kind, nl, wp, xp, ip, tp, B, gp, 1 if bf16_operands else 0)
     return float(loss), g
 
 
-def grad_all(kind: int, widths, X, inputs, targets):
+def grad_all(kind: int, widths, X, inputs, targets, bf16_operands: bool = False):
     """All workers: (G [n][d], loss [n]).  inputs [n][B][features], targets [n][B]."""
     w, wp = _i32(widths)
     nl = len(w) - 1 if kind in (SOFTMAX, MLP) else 0
@@ -185,13 +186,13 @@ def grad_all(kind: int, widths, X, inputs, targets):
     G = np.empty_like(X)
     loss = np.empty(n, dtype=np.float64)
     lib().orc_grad_all(kind, nl, wp, n, d, Xp, ip, tp, B, G.ctypes.data_as(C.POINTER(C.c_double)),
-                       loss.ctypes.data_as(C.POINTER(C.c_double)))
+                       loss.ctypes.data_as(C.POINTER(C.c_double)), 1 if bf16_operands else 0)
     return G, loss
 
 
-def iteration(kind: int, widths, topo: Topology, gamma: float, X, inputs, targets):
+def iteration(kind: int, widths, topo: Topology, gamma: float, X, inputs, targets, bf16_operands: bool = False):
     """One iteration of Algorithm 1: returns (X_next, G, loss)."""
-    G, loss = grad_all(kind, widths, X, inputs, targets)
+    G, loss = grad_all(kind, widths, X, inputs, targets, bf16_operands)
     return mix_step(topo, X, G, gamma), G, loss
 
 

@@ -34,6 +34,29 @@
 
 enum { ORC_LSQ = 0, ORC_SOFTMAX = 1, ORC_MLP = 2, ORC_RESNET20 = 3 };
 
+/* Nearest bf16 (8-bit significand, ties to even) of v, returned as a double.  Used only by the
+ * "bf16 operands" mode of the gradients: the workloads that prescribe bf16 compute round every
+ * operand of a contraction (weights, stored activations, back-propagated deltas) to bf16 and
+ * accumulate wider; the oracle then accumulates in fp64.  ReLU decisions are thereby taken on the
+ * same rounded values as in a bf16 kernel. */
+static double rbf(double v)
+{
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (double)f; /* inf / nan unchanged */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+static double *rounded_copy(const double *src, size_t n)
+{
+    double *r = (double *)malloc(sizeof(double) * n);
+    for (size_t i = 0; i < n; ++i) r[i] = rbf(src[i]);
+    return r;
+}
+
 /* ------------------------------------------------------------------ topology */
 
 /* Emit row i of a dense scratch row as CSR (ascending columns, zeros dropped). */
@@ -271,15 +294,17 @@ static double lsq_loss_grad(int F, const double *x, const double *A, const doubl
  * (ReLU'(0) = 0), softmax cross-entropy (mean over the batch) on the last z.
  * Parameters: for each layer W_l [out][in] row-major, then b_l [out]. */
 static double mlp_loss_grad(int L, const int32_t *w, const double *x, const double *in, const int32_t *label,
-                            int B, double *g)
+                            int B, double *g, int bf16)
 {
     double **act = (double **)calloc((size_t)L + 1, sizeof(double *)); /* act[l]: [B][w[l]] */
-    act[0] = (double *)in;
+    act[0] = bf16 ? rounded_copy(in, (size_t)B * w[0]) : (double *)in;
     const double **Wl = (const double **)calloc((size_t)L, sizeof(double *));
     const double **bl = (const double **)calloc((size_t)L, sizeof(double *));
     size_t off = 0;
     for (int l = 0; l < L; ++l) {
-        Wl[l] = x + off; off += (size_t)w[l + 1] * w[l];
+        /* bf16 mode: the weight operand of every contraction is rounded; biases stay as they are */
+        Wl[l] = bf16 ? rounded_copy(x + off, (size_t)w[l + 1] * w[l]) : x + off;
+        off += (size_t)w[l + 1] * w[l];
         bl[l] = x + off; off += (size_t)w[l + 1];
     }
     for (int l = 0; l < L; ++l) {
@@ -290,6 +315,7 @@ static double mlp_loss_grad(int L, const int32_t *w, const double *x, const doub
                 double z = bl[l][o];
                 for (int k = 0; k < I; ++k) z += Wl[l][(size_t)o * I + k] * act[l][(size_t)b * I + k];
                 if (l < L - 1 && z < 0.0) z = 0.0;
+                if (l < L - 1 && bf16) z = rbf(z); /* stored hidden activation */
                 act[l + 1][(size_t)b * O + o] = z;
             }
     }
@@ -297,6 +323,7 @@ static double mlp_loss_grad(int L, const int32_t *w, const double *x, const doub
     double *dz = g ? (double *)malloc(sizeof(double) * (size_t)B * C) : NULL;
     double loss = softmax_xent(act[L], label, B, C, dz);
     if (g) {
+        if (bf16) for (size_t t = 0; t < (size_t)B * C; ++t) dz[t] = rbf(dz[t]);
         size_t end = off;
         for (int l = L - 1; l >= 0; --l) {
             int I = w[l], O = w[l + 1];
@@ -319,7 +346,8 @@ static double mlp_loss_grad(int L, const int32_t *w, const double *x, const doub
                         double s = 0.0;
                         for (int o = 0; o < O; ++o) s += dz[(size_t)b * O + o] * Wl[l][(size_t)o * I + k];
                         /* act[l] = ReLU(z_{l-1}); positive exactly where z_{l-1} > 0 */
-                        dprev[(size_t)b * I + k] = act[l][(size_t)b * I + k] > 0.0 ? s : 0.0;
+                        s = act[l][(size_t)b * I + k] > 0.0 ? s : 0.0;
+                        dprev[(size_t)b * I + k] = bf16 ? rbf(s) : s;
                     }
                 free(dz);
                 dz = dprev;
@@ -328,6 +356,10 @@ static double mlp_loss_grad(int L, const int32_t *w, const double *x, const doub
         free(dz);
     }
     for (int l = 1; l <= L; ++l) free(act[l]);
+    if (bf16) {
+        free(act[0]);
+        for (int l = 0; l < L; ++l) free((void *)Wl[l]);
+    }
     free(act); free(Wl); free(bl);
     return loss;
 }
@@ -421,8 +453,13 @@ typedef struct { int Ci, Co, H, W, stride; size_t w_off, b_off; } conv_desc;
  *                                      a = ReLU(v + shortcut(a))
  *     (channels base, 2 base, 4 base; the first conv of stages 2 and 3 has stride 2)
  *   global average pool, fully connected layer with bias, softmax cross-entropy (mean). */
-static double resnet_loss_grad(const int32_t *wd, const double *x, const double *in, const int32_t *label,
-                               int B, double *g)
+static void round_all(double *v, size_t n) { for (size_t t = 0; t < n; ++t) v[t] = rbf(v[t]); }
+
+/* bf16 mode: the image, every conv weight, every stored activation (after its ReLU) and every
+ * back-propagated delta entering a convolution are rounded to bf16; biases, the pooled features
+ * and the fully connected layer are not. */
+static double resnet_loss_grad(const int32_t *wd, const double *x_master, const double *in_raw,
+                               const int32_t *label, int B, double *g, int bf16)
 {
     int cin = wd[0], H0 = wd[1], W0 = wd[2], base = wd[3], blocks = wd[4], classes = wd[5];
     int nconv = 1 + 6 * blocks;
@@ -445,6 +482,10 @@ static double resnet_loss_grad(const int32_t *wd, const double *x, const double 
     }
     size_t fcw_off = off, fcb_off = off + (size_t)classes * cprev;
     int Cl = cprev, Hl = H, Wl = W;
+    /* x: conv weights as the convolutions see them; xb: biases and the FC layer (never rounded) */
+    const double *xb = x_master;
+    const double *x = bf16 ? rounded_copy(x_master, fcw_off) : x_master;
+    const double *in = bf16 ? rounded_copy(in_raw, (size_t)B * cin * H0 * W0) : in_raw;
 
     /* forward; keep every block input a[j], every u[j] and the pre-ReLU sums */
     int nb = 3 * blocks;
@@ -452,18 +493,21 @@ static double resnet_loss_grad(const int32_t *wd, const double *x, const double 
     double **u = (double **)calloc((size_t)nb, sizeof(double *));
     size_t sz0 = (size_t)B * base * H0 * W0;
     a[0] = (double *)malloc(sizeof(double) * sz0);
-    conv_fwd(in, B, cin, H0, W0, x + cd[0].w_off, x[cd[0].b_off], base, 1, a[0]);
+    conv_fwd(in, B, cin, H0, W0, x + cd[0].w_off, xb[cd[0].b_off], base, 1, a[0]);
     for (size_t t = 0; t < sz0; ++t) if (a[0][t] < 0.0) a[0][t] = 0.0;
+    if (bf16) round_all(a[0], sz0);
     for (int j = 0; j < nb; ++j) {
         conv_desc *c1 = &cd[1 + 2 * j], *c2 = &cd[2 + 2 * j];
         size_t szo = (size_t)B * c2->Co * c2->H * c2->W;
         u[j] = (double *)malloc(sizeof(double) * szo);
-        conv_fwd(a[j], B, c1->Ci, c1->H, c1->W, x + c1->w_off, x[c1->b_off], c1->Co, c1->stride, u[j]);
+        conv_fwd(a[j], B, c1->Ci, c1->H, c1->W, x + c1->w_off, xb[c1->b_off], c1->Co, c1->stride, u[j]);
         for (size_t t = 0; t < szo; ++t) if (u[j][t] < 0.0) u[j][t] = 0.0;
+        if (bf16) round_all(u[j], szo);
         a[j + 1] = (double *)malloc(sizeof(double) * szo);
-        conv_fwd(u[j], B, c2->Ci, c2->H, c2->W, x + c2->w_off, x[c2->b_off], c2->Co, 1, a[j + 1]);
+        conv_fwd(u[j], B, c2->Ci, c2->H, c2->W, x + c2->w_off, xb[c2->b_off], c2->Co, 1, a[j + 1]);
         shortcut_add(a[j], B, c1->Ci, c1->H, c1->W, c1->Co, c1->stride, a[j + 1]);
         for (size_t t = 0; t < szo; ++t) if (a[j + 1][t] < 0.0) a[j + 1][t] = 0.0;
+        if (bf16) round_all(a[j + 1], szo);
     }
     double *pool = (double *)malloc(sizeof(double) * (size_t)B * Cl);
     for (int b = 0; b < B; ++b)
@@ -475,8 +519,8 @@ static double resnet_loss_grad(const int32_t *wd, const double *x, const double 
     double *z = (double *)malloc(sizeof(double) * (size_t)B * classes);
     for (int b = 0; b < B; ++b)
         for (int o = 0; o < classes; ++o) {
-            double s = x[fcb_off + o];
-            for (int c = 0; c < Cl; ++c) s += x[fcw_off + (size_t)o * Cl + c] * pool[(size_t)b * Cl + c];
+            double s = xb[fcb_off + o];
+            for (int c = 0; c < Cl; ++c) s += xb[fcw_off + (size_t)o * Cl + c] * pool[(size_t)b * Cl + c];
             z[(size_t)b * classes + o] = s;
         }
     double *dz = g ? (double *)malloc(sizeof(double) * (size_t)B * classes) : NULL;
@@ -492,7 +536,7 @@ static double resnet_loss_grad(const int32_t *wd, const double *x, const double 
                 g[fcb_off + o] += go;
                 for (int c = 0; c < Cl; ++c) {
                     g[fcw_off + (size_t)o * Cl + c] += go * pool[(size_t)b * Cl + c];
-                    dpool[(size_t)b * Cl + c] += go * x[fcw_off + (size_t)o * Cl + c];
+                    dpool[(size_t)b * Cl + c] += go * xb[fcw_off + (size_t)o * Cl + c];
                 }
             }
         size_t szl = (size_t)B * Cl * Hl * Wl;
@@ -508,9 +552,11 @@ static double resnet_loss_grad(const int32_t *wd, const double *x, const double 
             size_t szi = (size_t)B * c1->Ci * c1->H * c1->W;
             /* through the block's final ReLU: a[j+1] > 0 exactly where its argument was > 0 */
             for (size_t t = 0; t < szo; ++t) if (!(a[j + 1][t] > 0.0)) da[t] = 0.0;
+            if (bf16) round_all(da, szo);
             double *du = (double *)calloc(szo, sizeof(double));
             conv_bwd(u[j], B, c2->Ci, c2->H, c2->W, x + c2->w_off, c2->Co, 1, da, g + c2->w_off, g + c2->b_off, du);
             for (size_t t = 0; t < szo; ++t) if (!(u[j][t] > 0.0)) du[t] = 0.0;
+            if (bf16) round_all(du, szo);
             double *dprev = (double *)calloc(szi, sizeof(double));
             conv_bwd(a[j], B, c1->Ci, c1->H, c1->W, x + c1->w_off, c1->Co, c1->stride, du, g + c1->w_off,
                      g + c1->b_off, dprev);
@@ -519,12 +565,14 @@ static double resnet_loss_grad(const int32_t *wd, const double *x, const double 
             da = dprev;
         }
         for (size_t t = 0; t < sz0; ++t) if (!(a[0][t] > 0.0)) da[t] = 0.0;
+        if (bf16) round_all(da, sz0);
         conv_bwd(in, B, cin, H0, W0, x + cd[0].w_off, base, 1, da, g + cd[0].w_off, g + cd[0].b_off, NULL);
         free(da); free(dz);
     }
     for (int j = 0; j <= nb; ++j) free(a[j]);
     for (int j = 0; j < nb; ++j) free(u[j]);
     free(a); free(u); free(pool); free(z); free(cd);
+    if (bf16) { free((void *)x); free((void *)in); }
     return loss;
 }
 
@@ -532,15 +580,16 @@ static double resnet_loss_grad(const int32_t *wd, const double *x, const double 
 
 /* Algorithm 1 step 3 (with footnote [a]) for ONE worker: loss and, if g != NULL, the mean over the
  * B samples of grad_x F(x; sample).  inputs [B][features] fp64; targets: fp64 y[B] for LSQ, int32
- * labels[B] otherwise.  Returns the minibatch loss. */
+ * labels[B] otherwise.  bf16_operands != 0 selects the rounding mode described at rbf() (ignored by
+ * least squares).  Returns the minibatch loss. */
 double orc_loss_grad(int32_t kind, int32_t n_layers, const int32_t *widths, const double *x,
-                     const double *inputs, const void *targets, int32_t B, double *g)
+                     const double *inputs, const void *targets, int32_t B, double *g, int32_t bf16_operands)
 {
     switch (kind) {
     case ORC_LSQ: return lsq_loss_grad(widths[0], x, inputs, (const double *)targets, B, g);
     case ORC_SOFTMAX:
-    case ORC_MLP: return mlp_loss_grad(n_layers, widths, x, inputs, (const int32_t *)targets, B, g);
-    case ORC_RESNET20: return resnet_loss_grad(widths, x, inputs, (const int32_t *)targets, B, g);
+    case ORC_MLP: return mlp_loss_grad(n_layers, widths, x, inputs, (const int32_t *)targets, B, g, bf16_operands);
+    case ORC_RESNET20: return resnet_loss_grad(widths, x, inputs, (const int32_t *)targets, B, g, bf16_operands);
     default: return NAN;
     }
 }
@@ -549,7 +598,7 @@ double orc_loss_grad(int32_t kind, int32_t n_layers, const int32_t *widths, cons
  * X, G: [n][d]; inputs [n][B][features]; targets [n][B]; loss [n] (may be NULL). */
 void orc_grad_all(int32_t kind, int32_t n_layers, const int32_t *widths, int32_t n, int64_t d,
                   const double *X, const double *inputs, const void *targets, int32_t B, double *G,
-                  double *loss)
+                  double *loss, int32_t bf16_operands)
 {
     int64_t feat = (kind == ORC_RESNET20) ? (int64_t)widths[0] * widths[1] * widths[2] : widths[0];
 #pragma omp parallel for schedule(dynamic, 1)
@@ -557,7 +606,7 @@ void orc_grad_all(int32_t kind, int32_t n_layers, const int32_t *widths, int32_t
         const void *t = (kind == ORC_LSQ) ? (const void *)((const double *)targets + (size_t)i * B)
                                           : (const void *)((const int32_t *)targets + (size_t)i * B);
         double l = orc_loss_grad(kind, n_layers, widths, X + (size_t)i * d, inputs + (size_t)i * B * feat, t, B,
-                                 G + (size_t)i * d);
+                                 G + (size_t)i * d, bf16_operands);
         if (loss) loss[i] = l;
     }
 }
@@ -566,9 +615,9 @@ void orc_grad_all(int32_t kind, int32_t n_layers, const int32_t *widths, int32_t
 void orc_iteration(int32_t kind, int32_t n_layers, const int32_t *widths, int32_t n, int64_t d,
                    const int32_t *rowptr, const int32_t *col, const double *val, double gamma,
                    const double *X, const double *inputs, const void *targets, int32_t B,
-                   double *G, double *loss, double *Xn)
+                   double *G, double *loss, double *Xn, int32_t bf16_operands)
 {
-    orc_grad_all(kind, n_layers, widths, n, d, X, inputs, targets, B, G, loss);
+    orc_grad_all(kind, n_layers, widths, n, d, X, inputs, targets, B, G, loss, bf16_operands);
     orc_mix_step(n, d, rowptr, col, val, X, G, gamma, Xn);
 }
 

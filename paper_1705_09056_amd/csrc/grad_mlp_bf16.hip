@@ -1,6 +1,617 @@
+// Per-worker minibatch gradients of softmax regression / ReLU MLPs with bf16 MFMA operands
+// (Algorithm 1 step 3, footnote [a]) for gfx950.
+//
+// Every worker multiplies its own minibatch with its OWN weights, so each layer is a batch of n
+// skinny GEMMs (M = minibatch rows) with distinct weight operands: a weight is used only B times
+// per pass and the kernels are bound by streaming the fp32 master weights from HBM (forward,
+// data gradient) and by writing the fp32 gradient (weight gradient).  Design:
+//   forward   Z[b][o]  = sum_k A[b][k] W[o][k] + bias[o]      W streamed once, fp32 -> bf16 in
+//                                                             registers, staged in LDS (double
+//                                                             buffered), A tile shared by 4 waves
+//   dgrad     dA[b][k] = sum_o dZ[b][o] W[o][k]               W streamed once, transposed on the
+//                                                             way into LDS
+//   wgrad     dW[o][k] = sum_b dZ^T[o][b] A^T[k][b]           operands are tiny (L2-resident
+//                                                             transposed bf16 copies), output
+//                                                             streamed to G once
+// MFMA: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  Lane l of an A (B) operand holds row
+// (column) l%32 and the 8 consecutive k values 8*(l/32)..+7; accumulator register v of lane l is
+// element (row (v/4)*8 + (l/32)*4 + v%4, column l%32).
 #include "grad_common.h"
+
 namespace dpsgd {
-size_t mlp_bf16_workspace_bytes(const dpsgd_ctx *, const dpsgd_model_desc &) { return 256; }
-dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *, const dpsgd_model_desc &, const float *, const void *, const void *,
-                                  float *, float *) { return DPSGD_EUNSUPPORTED; }
+namespace {
+
+typedef long long i64;
+typedef unsigned short bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int KC = 64;        // contraction elements staged per step
+constexpr int PITCH = KC + 8; // LDS row pitch in bf16 elements (144 B: 16 B aligned, spreads banks)
+
+__device__ __forceinline__ bf16_t f2bf(float f)
+{   // round to nearest, ties to even
+    unsigned u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
 }
+__device__ __forceinline__ unsigned pack2(float a, float b) { return (unsigned)f2bf(a) | ((unsigned)f2bf(b) << 16); }
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
+__device__ __forceinline__ bf16x8 frag(const bf16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+__device__ __forceinline__ bf16x8 zero_frag()
+{
+    u32x4 z = {0u, 0u, 0u, 0u};
+    return __builtin_bit_cast(bf16x8, z);
+}
+
+// ------------------------------------------------------------------ input preparation
+// in: [n*B][F] fp32 or bf16 -> a [n][B][F] bf16 (only when the input is fp32) and
+// at [n][F][Bp] bf16 (transposed, zero padded).  32x32 tiles through LDS.
+template <bool IN_BF16>
+__global__ void __launch_bounds__(256)
+prep_input_kernel(const void *__restrict__ in, bf16_t *__restrict__ a, bf16_t *__restrict__ at, int B, int Bp, int F)
+{
+    __shared__ bf16_t tile[32][33];
+    const int w = blockIdx.z, b0 = blockIdx.y * 32, f0 = blockIdx.x * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    for (int r = ty; r < 32; r += 8) {
+        const int b = b0 + r, f = f0 + tx;
+        bf16_t v = 0;
+        if (b < B && f < F) {
+            const i64 idx = ((i64)w * B + b) * F + f;
+            v = IN_BF16 ? ((const bf16_t *)in)[idx] : f2bf(((const float *)in)[idx]);
+            if (!IN_BF16) a[idx] = v;
+        }
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int f = f0 + r, b = b0 + tx;
+        if (f < F && b < Bp) at[((i64)w * F + f) * Bp + b] = tile[tx][r];
+    }
+}
+
+// --------------------------------------------------------------------------- forward
+struct FwdArgs {
+    const bf16_t *act;     // [n][B][K]
+    const float *X;        // replicas
+    i64 ld, woff, boff;
+    int B, Bp, K, O;
+    bf16_t *h;             // [n][B][O]   (hidden layers)
+    bf16_t *ht;            // [n][O][Bp]  (hidden layers)
+    float *z;              // [n][B][O]   (last layer, fp32 logits)
+};
+
+// grid (ceil(O / (32 WN)), ceil(B / (32 WM MT)), n), block 256 = WM x WN waves.
+template <int WM, int WN, int MT, bool VEC, bool LAST>
+__global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
+{
+    constexpr int TO = 32 * WN, MBLK = 32 * WM * MT;
+    constexpr int WQ = TO / 16;     // float4 units of the W tile per thread
+    constexpr int AQ = MBLK / 32;   // 16-byte units of the A tile per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *Wt = reinterpret_cast<bf16_t *>(smem);          // [2][TO][PITCH]
+    bf16_t *At = Wt + 2 * TO * PITCH;                        // [2][MBLK][PITCH]
+    const int w = blockIdx.z, o0 = blockIdx.x * TO, b0 = blockIdx.y * MBLK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, half = lane >> 5;
+    const float *Wg = g.X + (i64)w * g.ld + g.woff;
+    const bf16_t *Ag = g.act + (i64)w * g.B * g.K;
+
+    f32x4 wreg[WQ];
+    u32x4 areg[AQ];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 4;
+            const int o = o0 + row, k = k0 + kq;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (o < g.O) {
+                const float *p = Wg + (i64)o * g.K + k;
+                if (VEC) {
+                    if (k < g.K) v = *reinterpret_cast<const f32x4 *>(p);
+                } else {
+                    if (k < g.K) v.x = p[0];
+                    if (k + 1 < g.K) v.y = p[1];
+                    if (k + 2 < g.K) v.z = p[2];
+                    if (k + 3 < g.K) v.w = p[3];
+                }
+            }
+            wreg[q] = v;
+        }
+#pragma unroll
+        for (int q = 0; q < AQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 3, kq = (u & 7) * 8;
+            const int b = b0 + row, k = k0 + kq;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (b < g.B) {
+                const bf16_t *p = Ag + (i64)b * g.K + k;
+                if (VEC) {
+                    if (k < g.K) v = *reinterpret_cast<const u32x4 *>(p);
+                } else {
+                    unsigned short e[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) e[i] = (k + i < g.K) ? p[i] : (unsigned short)0;
+                    v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
+                    v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
+                }
+            }
+            areg[q] = v;
+        }
+    };
+    auto stage = [&](int buf) {
+        bf16_t *Wb = Wt + buf * TO * PITCH, *Ab = At + buf * MBLK * PITCH;
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 4;
+            u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
+            *reinterpret_cast<u32x2 *>(Wb + row * PITCH + kq) = p;
+        }
+#pragma unroll
+        for (int q = 0; q < AQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 3, kq = (u & 7) * 8;
+            *reinterpret_cast<u32x4 *>(Ab + row * PITCH + kq) = areg[q];
+        }
+    };
+
+    f32x16 acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
+
+    const int nchunks = (g.K + KC - 1) / KC;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) fetch((c + 1) * KC);
+        const bf16_t *Wb = Wt + buf * TO * PITCH + (wn * 32 + l32) * PITCH + 8 * half;
+        const bf16_t *Ab = At + buf * MBLK * PITCH + (wm * MT * 32 + l32) * PITCH + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            const bf16x8 bw = frag(Wb + ks * 16);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const bf16x8 aa = frag(Ab + m * 32 * PITCH + ks * 16);
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aa, bw, acc[m], 0, 0, 0);
+            }
+        }
+        if (c + 1 < nchunks) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane owns output column o, 16 rows per m-tile
+    const int o = o0 + wn * 32 + l32;
+    if (o >= g.O) return;
+    const float bias = g.X[(i64)w * g.ld + g.boff + o];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int bt = b0 + (wm * MT + m) * 32;
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            const int bb = bt + grp * 8 + half * 4;   // 4 consecutive rows bb..bb+3
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[i] = acc[m][grp * 4 + i] + bias;
+                if (!LAST) v[i] = v[i] > 0.f ? v[i] : 0.f;
+            }
+            if (LAST) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (bb + i < g.B) g.z[((i64)w * g.B + bb + i) * g.O + o] = v[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (bb + i < g.B) g.h[((i64)w * g.B + bb + i) * g.O + o] = f2bf(v[i]);
+                    else v[i] = 0.f;
+                }
+                if (bb < g.Bp) {
+                    u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
+                    *reinterpret_cast<u32x2 *>(g.ht + ((i64)w * g.O + o) * g.Bp + bb) = p;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------- softmax cross-entropy
+// z fp32 [n][B][C] -> dz bf16 [n][B][C], dzt bf16 [n][C][Bp] (zero padded), loss[n].
+__global__ void __launch_bounds__(256)
+softmax_xent_bf16_kernel(const float *__restrict__ z, const int *__restrict__ labels, int B, int Bp, int C,
+                         bf16_t *__restrict__ dz, bf16_t *__restrict__ dzt, float *__restrict__ loss)
+{
+    __shared__ float red[256];
+    const int w = blockIdx.x;
+    const float invB = 1.0f / (float)B;
+    float local = 0.f;
+    for (int b = threadIdx.x; b < Bp; b += 256) {
+        if (b >= B) {
+            for (int c = 0; c < C; ++c) dzt[((i64)w * C + c) * Bp + b] = 0;
+            continue;
+        }
+        const float *zb = z + ((i64)w * B + b) * C;
+        int lab = labels[(i64)w * B + b];
+        lab = lab < 0 ? 0 : (lab >= C ? C - 1 : lab);
+        float mx = zb[0];
+        for (int c = 1; c < C; ++c) mx = fmaxf(mx, zb[c]);
+        float se = 0.f;
+        for (int c = 0; c < C; ++c) se += expf(zb[c] - mx);
+        const float lse = mx + logf(se);
+        local += lse - zb[lab];
+        for (int c = 0; c < C; ++c) {
+            const bf16_t v = f2bf((expf(zb[c] - lse) - (c == lab ? 1.f : 0.f)) * invB);
+            dz[((i64)w * B + b) * C + c] = v;
+            dzt[((i64)w * C + c) * Bp + b] = v;
+        }
+    }
+    red[threadIdx.x] = local;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (loss && threadIdx.x == 0) loss[w] = red[0] * invB;
+}
+
+// ----------------------------------------------------------------------- weight gradient
+struct WgradArgs {
+    const bf16_t *dzt;   // [n][O][Bp]
+    const bf16_t *at;    // [n][K][Bp]
+    float *G;
+    i64 ld, woff, boff;
+    int Bp, K, O;
+};
+
+// grid (ceil(K / 256), ceil(O / 128), n); wave = 32 rows o, walks 8 tiles of 32 columns k.
+__global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g)
+{
+    const int w = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int o_base = blockIdx.y * 128 + wave * 32;
+    if (o_base >= g.O) return;
+    const int o = o_base + l32;            // row this lane feeds into the A operand
+    const bool o_ok = o < g.O;
+    const bf16_t *Ap = g.dzt + ((i64)w * g.O + (o_ok ? o : 0)) * g.Bp + 8 * half;
+    const int steps = g.Bp / 16;
+    float *Gw = g.G + (i64)w * g.ld + g.woff;
+
+    if (blockIdx.x == 0) {   // bias gradient: gb[o] = sum_b dZ[b][o]
+        float s = 0.f;
+        if (o_ok)
+            for (int st = 0; st < steps; ++st)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) s += bf2f(Ap[st * 16 + j]);
+        s += __shfl_down(s, 32, 64);
+        if (half == 0 && o_ok) g.G[(i64)w * g.ld + g.boff + o] = s;
+    }
+
+    for (int t = 0; t < 8; ++t) {
+        const int k_base = blockIdx.x * 256 + t * 32;
+        if (k_base >= g.K) break;
+        const int k = k_base + l32;
+        const bool k_ok = k < g.K;
+        const bf16_t *Bp_ = g.at + ((i64)w * g.K + (k_ok ? k : 0)) * g.Bp + 8 * half;
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        for (int st = 0; st < steps; ++st) {
+            const bf16x8 a = o_ok ? frag(Ap + st * 16) : zero_frag();
+            const bf16x8 b = k_ok ? frag(Bp_ + st * 16) : zero_frag();
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+        }
+        if (k_ok) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int orow = o_base + (v >> 2) * 8 + half * 4 + (v & 3);
+                if (orow < g.O) __builtin_nontemporal_store(acc[v], Gw + (i64)orow * g.K + k);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------- data gradient
+struct DgradArgs {
+    const bf16_t *dz;     // [n][B][O]
+    const float *X;
+    i64 ld, woff;
+    const bf16_t *hprev;  // [n][B][K] post-ReLU activations of the layer below (mask)
+    bf16_t *dzp;          // [n][B][K]
+    bf16_t *dzpt;         // [n][K][Bp]
+    int B, Bp, K, O;
+};
+
+// grid (ceil(K / (32 WN)), ceil(B / (32 WM MT)), n), block 256.
+template <int WM, int WN, int MT, bool VEC>
+__global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
+{
+    constexpr int TK = 32 * WN, MBLK = 32 * WM * MT;
+    constexpr int WQ = TK / 16;     // float4 units of the [64 o][TK k] W tile per thread
+    constexpr int DQ = MBLK / 32;   // 16-byte units of the dZ tile per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int WP = TK + 8;                               // pitch of the W tile (bf16 elements)
+    bf16_t *Wt = reinterpret_cast<bf16_t *>(smem);          // [2][KC o][WP]    as in memory: rows o, k contiguous
+    bf16_t *Dt = Wt + 2 * KC * WP;                           // [2][MBLK][PITCH] rows b, o contiguous
+    const int w = blockIdx.z, kt0 = blockIdx.x * TK, b0 = blockIdx.y * MBLK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, half = lane >> 5;
+    const float *Wg = g.X + (i64)w * g.ld + g.woff;
+    const bf16_t *Dg = g.dz + (i64)w * g.B * g.O;
+
+    f32x4 wreg[WQ];
+    u32x4 dreg[DQ];
+    auto fetch = [&](int oc) {
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, orow = u / (TK / 4), kq = (u % (TK / 4)) * 4;
+            const int o = oc + orow, k = kt0 + kq;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (o < g.O) {
+                const float *p = Wg + (i64)o * g.K + k;
+                if (VEC) {
+                    if (k < g.K) v = *reinterpret_cast<const f32x4 *>(p);
+                } else {
+                    if (k < g.K) v.x = p[0];
+                    if (k + 1 < g.K) v.y = p[1];
+                    if (k + 2 < g.K) v.z = p[2];
+                    if (k + 3 < g.K) v.w = p[3];
+                }
+            }
+            wreg[q] = v;
+        }
+#pragma unroll
+        for (int q = 0; q < DQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 3, oq = (u & 7) * 8;
+            const int b = b0 + row, o = oc + oq;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (b < g.B) {
+                const bf16_t *p = Dg + (i64)b * g.O + o;
+                if (VEC) {
+                    if (o < g.O) v = *reinterpret_cast<const u32x4 *>(p);
+                } else {
+                    unsigned short e[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) e[i] = (o + i < g.O) ? p[i] : (unsigned short)0;
+                    v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
+                    v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
+                }
+            }
+            dreg[q] = v;
+        }
+    };
+    auto stage = [&](int buf) {
+        bf16_t *Wb = Wt + buf * KC * WP, *Db = Dt + buf * MBLK * PITCH;
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, orow = u / (TK / 4), kq = (u % (TK / 4)) * 4;
+            u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
+            *reinterpret_cast<u32x2 *>(Wb + orow * WP + kq) = p;
+        }
+#pragma unroll
+        for (int q = 0; q < DQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 3, oq = (u & 7) * 8;
+            *reinterpret_cast<u32x4 *>(Db + row * PITCH + oq) = dreg[q];
+        }
+    };
+
+    f32x16 acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
+
+    const int nchunks = (g.O + KC - 1) / KC;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) fetch((c + 1) * KC);
+        // B operand: column k of the tile, 8 consecutive o (the transpose happens in these reads:
+        // consecutive lanes read consecutive k of one LDS row)
+        const bf16_t *Wb = Wt + buf * KC * WP + (8 * half) * WP + wn * 32 + l32;
+        const bf16_t *Db = Dt + buf * MBLK * PITCH + (wm * MT * 32 + l32) * PITCH + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            unsigned short e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = Wb[(ks * 16 + j) * WP];
+            u32x4 pk = {e[0] | ((unsigned)e[1] << 16), e[2] | ((unsigned)e[3] << 16), e[4] | ((unsigned)e[5] << 16),
+                        e[6] | ((unsigned)e[7] << 16)};
+            const bf16x8 bw = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const bf16x8 aa = frag(Db + m * 32 * PITCH + ks * 16);
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aa, bw, acc[m], 0, 0, 0);
+            }
+        }
+        if (c + 1 < nchunks) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    const int k = kt0 + wn * 32 + l32;
+    if (k >= g.K) return;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int bt = b0 + (wm * MT + m) * 32;
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            const int bb = bt + grp * 8 + half * 4;
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[i] = 0.f;
+                if (bb + i < g.B) {
+                    const i64 idx = ((i64)w * g.B + bb + i) * g.K + k;
+                    const bf16_t hp = g.hprev[idx];
+                    const bool pos = (hp & 0x7fffu) != 0 && (hp & 0x8000u) == 0;   // ReLU'(z) = [z > 0]
+                    v[i] = pos ? acc[m][grp * 4 + i] : 0.f;
+                    g.dzp[idx] = f2bf(v[i]);
+                }
+            }
+            if (bb < g.Bp) {
+                u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
+                *reinterpret_cast<u32x2 *>(g.dzpt + ((i64)w * g.K + k) * g.Bp + bb) = p;
+            }
+        }
+    }
+}
+
+int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+struct Tiling { int wm, wn, mt; };
+Tiling pick_tiling(int B)
+{
+    if (B <= 32) return {1, 4, 1};
+    if (B <= 64) return {1, 4, 2};
+    return {2, 2, 2};
+}
+
+template <int WM, int WN, int MT>
+dpsgd_status fwd_launch(hipStream_t s, int n, const FwdArgs &a, bool vec, bool last)
+{
+    constexpr int TO = 32 * WN, MBLK = 32 * WM * MT;
+    dim3 grid((unsigned)((a.O + TO - 1) / TO), (unsigned)((a.B + MBLK - 1) / MBLK), (unsigned)n);
+    const size_t shm = (size_t)2 * (TO + MBLK) * PITCH * sizeof(bf16_t);
+    if (vec && last) hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, true, true>), grid, dim3(256), shm, s, a);
+    else if (vec) hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, true, false>), grid, dim3(256), shm, s, a);
+    else if (last) hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, false, true>), grid, dim3(256), shm, s, a);
+    else hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, false, false>), grid, dim3(256), shm, s, a);
+    return hip_status(hipGetLastError());
+}
+
+template <int WM, int WN, int MT>
+dpsgd_status dgrad_launch(hipStream_t s, int n, const DgradArgs &a, bool vec)
+{
+    constexpr int TK = 32 * WN, MBLK = 32 * WM * MT;
+    dim3 grid((unsigned)((a.K + TK - 1) / TK), (unsigned)((a.B + MBLK - 1) / MBLK), (unsigned)n);
+    const size_t shm = (size_t)2 * (KC * (TK + 8) + MBLK * PITCH) * sizeof(bf16_t);
+    if (vec) hipLaunchKernelGGL((mlp_dgrad_kernel<WM, WN, MT, true>), grid, dim3(256), shm, s, a);
+    else hipLaunchKernelGGL((mlp_dgrad_kernel<WM, WN, MT, false>), grid, dim3(256), shm, s, a);
+    return hip_status(hipGetLastError());
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+size_t mlp_bf16_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m)
+{
+    const size_t n = (size_t)ctx->n, B = (size_t)m.batch, Bp = (size_t)round_up(m.batch, 32);
+    const size_t L = m.widths.size() - 1;
+    size_t bytes = 0;
+    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
+    if (!m.input_is_bf16) bytes += pad(n * B * (size_t)m.widths[0] * 2);
+    bytes += pad(n * (size_t)m.widths[0] * Bp * 2);
+    for (size_t l = 1; l < L; ++l) {
+        bytes += pad(n * B * (size_t)m.widths[l] * 2);      // h
+        bytes += pad(n * (size_t)m.widths[l] * Bp * 2);     // ht
+    }
+    bytes += pad(n * B * (size_t)m.widths[L] * 4);          // logits
+    size_t widest = 0;
+    for (size_t l = 1; l <= L; ++l) widest = widest > (size_t)m.widths[l] ? widest : (size_t)m.widths[l];
+    bytes += 2 * (pad(n * B * widest * 2) + pad(n * widest * Bp * 2));   // dz / dzt, ping-pong
+    return bytes + 256;
+}
+
+dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
+                                  const void *targets, float *G, float *loss)
+{
+    hipStream_t s = ctx->stream;
+    const int n = ctx->n, B = m.batch, Bp = round_up(B, 32);
+    const int L = (int)m.widths.size() - 1;
+    if (n > 65535) return DPSGD_EUNSUPPORTED;
+    unsigned char *ws = (unsigned char *)ctx->ws;
+    auto take = [&](size_t bytes) {
+        unsigned char *p = ws;
+        ws += (bytes + 255) / 256 * 256;
+        return p;
+    };
+    const size_t nB = (size_t)n * B;
+    std::vector<const bf16_t *> act(L), actt(L);   // act[l]: input of layer l, [n][B][w_l]; actt[l]: [n][w_l][Bp]
+    bf16_t *a0 = nullptr;
+    if (!m.input_is_bf16) a0 = (bf16_t *)take(nB * m.widths[0] * 2);
+    bf16_t *at0 = (bf16_t *)take((size_t)n * m.widths[0] * Bp * 2);
+    act[0] = m.input_is_bf16 ? (const bf16_t *)inputs : a0;
+    actt[0] = at0;
+    std::vector<bf16_t *> h(L, nullptr), ht(L, nullptr);
+    for (int l = 1; l < L; ++l) {
+        h[l] = (bf16_t *)take(nB * m.widths[l] * 2);
+        ht[l] = (bf16_t *)take((size_t)n * m.widths[l] * Bp * 2);
+        act[l] = h[l];
+        actt[l] = ht[l];
+    }
+    float *logits = (float *)take(nB * m.widths[L] * 4);
+    size_t widest = 0;
+    for (int l = 1; l <= L; ++l) widest = widest > (size_t)m.widths[l] ? widest : (size_t)m.widths[l];
+    bf16_t *dz[2], *dzt[2];
+    for (int i = 0; i < 2; ++i) {
+        dz[i] = (bf16_t *)take(nB * widest * 2);
+        dzt[i] = (bf16_t *)take((size_t)n * widest * Bp * 2);
+    }
+    std::vector<i64> woff(L), boff(L);
+    i64 off = 0;
+    for (int l = 0; l < L; ++l) {
+        woff[l] = off; off += (i64)m.widths[l + 1] * m.widths[l];
+        boff[l] = off; off += m.widths[l + 1];
+    }
+
+    {   // bf16 copy (if needed) and transposed copy of the inputs
+        const int F = m.widths[0];
+        dim3 grid((unsigned)((F + 31) / 32), (unsigned)(Bp / 32), (unsigned)n);
+        if (m.input_is_bf16)
+            hipLaunchKernelGGL(prep_input_kernel<true>, grid, dim3(256), 0, s, inputs, a0, at0, B, Bp, F);
+        else
+            hipLaunchKernelGGL(prep_input_kernel<false>, grid, dim3(256), 0, s, inputs, a0, at0, B, Bp, F);
+    }
+    const Tiling t = pick_tiling(B);
+    const bool base_ok = aligned16(X) && (ctx->ld % 4) == 0;
+    dpsgd_status st = DPSGD_OK;
+    for (int l = 0; l < L && st == DPSGD_OK; ++l) {
+        FwdArgs a{};
+        a.act = act[l]; a.X = X; a.ld = ctx->ld; a.woff = woff[l]; a.boff = boff[l];
+        a.B = B; a.Bp = Bp; a.K = m.widths[l]; a.O = m.widths[l + 1];
+        const bool last = (l == L - 1);
+        if (last) a.z = logits; else { a.h = h[l + 1]; a.ht = ht[l + 1]; }
+        const bool vec = base_ok && (a.K % 8) == 0 && (woff[l] % 4) == 0 && aligned16(act[l]);
+        if (t.mt == 1) st = fwd_launch<1, 4, 1>(s, n, a, vec, last);
+        else if (t.wm == 1) st = fwd_launch<1, 4, 2>(s, n, a, vec, last);
+        else st = fwd_launch<2, 2, 2>(s, n, a, vec, last);
+    }
+    if (st != DPSGD_OK) return st;
+    const int C = m.widths[L];
+    int cur = 0;
+    hipLaunchKernelGGL(softmax_xent_bf16_kernel, dim3((unsigned)n), dim3(256), 0, s, logits, (const int *)targets, B, Bp,
+                       C, dz[cur], dzt[cur], loss);
+    for (int l = L - 1; l >= 0 && st == DPSGD_OK; --l) {
+        const int K = m.widths[l], O = m.widths[l + 1];
+        WgradArgs wa{};
+        wa.dzt = dzt[cur]; wa.at = actt[l]; wa.G = G; wa.ld = ctx->ld; wa.woff = woff[l]; wa.boff = boff[l];
+        wa.Bp = Bp; wa.K = K; wa.O = O;
+        dim3 wgrid((unsigned)((K + 255) / 256), (unsigned)((O + 127) / 128), (unsigned)n);
+        hipLaunchKernelGGL(mlp_wgrad_kernel, wgrid, dim3(256), 0, s, wa);
+        st = hip_status(hipGetLastError());
+        if (l > 0 && st == DPSGD_OK) {
+            DgradArgs da{};
+            da.dz = dz[cur]; da.X = X; da.ld = ctx->ld; da.woff = woff[l]; da.hprev = h[l];
+            da.dzp = dz[cur ^ 1]; da.dzpt = dzt[cur ^ 1];
+            da.B = B; da.Bp = Bp; da.K = K; da.O = O;
+            const bool vec = base_ok && (K % 4) == 0 && (O % 8) == 0 && (woff[l] % 4) == 0;
+            if (t.mt == 1) st = dgrad_launch<1, 4, 1>(s, n, da, vec);
+            else if (t.wm == 1) st = dgrad_launch<1, 4, 2>(s, n, da, vec);
+            else st = dgrad_launch<2, 2, 2>(s, n, da, vec);
+            cur ^= 1;
+        }
+    }
+    return st;
+}
+
+}  // namespace dpsgd

@@ -333,20 +333,46 @@ column_stats_kernel(const float *__restrict__ X, int n, i64 ncols, i64 ld, int b
     }
 }
 
-// Fixed-order sum of the per-workgroup partials: consensus = (sum partials) / n.
-__global__ void __launch_bounds__(256) consensus_finalize_kernel(const double *__restrict__ partials, i64 count,
-                                                                  double inv_n, float *__restrict__ out)
+// Fixed-order sum of the per-workgroup partials in two stages: block b of the first stage sums the
+// contiguous slice [b*per, (b+1)*per) into stage1[b]; the second stage (one block) adds those and
+// writes consensus = (sum partials) / n.  The order depends only on the launch shape.
+__device__ __forceinline__ double block_sum_256(double s, double *sh)
 {
-    __shared__ double sh[256];
-    double s = 0.0;
-    for (i64 i = threadIdx.x; i < count; i += 256) s += partials[i];
     sh[threadIdx.x] = s;
     __syncthreads();
     for (int off = 128; off > 0; off >>= 1) {
         if ((int)threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
         __syncthreads();
     }
-    if (threadIdx.x == 0) out[0] = (float)(sh[0] * inv_n);
+    return sh[0];
+}
+
+__global__ void __launch_bounds__(256) consensus_stage1_kernel(const double *__restrict__ partials, i64 count, i64 per,
+                                                                double *__restrict__ stage1)
+{
+    __shared__ double sh[256];
+    const i64 lo = (i64)blockIdx.x * per, hi = lo + per < count ? lo + per : count;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    i64 i = lo + threadIdx.x;
+    for (; i + 768 < hi; i += 1024) {
+        s0 += partials[i];
+        s1 += partials[i + 256];
+        s2 += partials[i + 512];
+        s3 += partials[i + 768];
+    }
+    for (; i < hi; i += 256) s0 += partials[i];
+    const double t = block_sum_256((s0 + s1) + (s2 + s3), sh);
+    if (threadIdx.x == 0) stage1[blockIdx.x] = t;
+}
+
+__global__ void __launch_bounds__(256) consensus_stage2_kernel(const double *__restrict__ stage1, int count, double inv_n,
+                                                                float *__restrict__ out)
+{
+    __shared__ double sh[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < count; i += 256) s += stage1[i];
+    const double t = block_sum_256(s, sh);
+    if (threadIdx.x == 0) out[0] = (float)(t * inv_n);
 }
 
 // --------------------------------------------------------------------------- host helpers
@@ -467,9 +493,17 @@ dpsgd_status stats_launch(dpsgd_ctx *ctx, const float *X, i64 col0, i64 ncols, f
     return hip_status(hipGetLastError());
 }
 
+constexpr int kStage1Blocks = 128;   // the partials buffer keeps this many extra slots at its end
+
 dpsgd_status finalize_consensus(dpsgd_ctx *ctx, i64 count, float *consensus)
 {
-    hipLaunchKernelGGL(consensus_finalize_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->d_partials, count,
+    double *stage1 = ctx->d_partials + (ctx->partials_cap - kStage1Blocks);
+    i64 per = (count + kStage1Blocks - 1) / kStage1Blocks;
+    if (per < 256) per = 256;
+    const int blocks = (int)((count + per - 1) / per);
+    hipLaunchKernelGGL(consensus_stage1_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, ctx->d_partials, count,
+                       per, stage1);
+    hipLaunchKernelGGL(consensus_stage2_kernel, dim3(1), dim3(256), 0, ctx->stream, stage1, blocks,
                        1.0 / (double)ctx->n, consensus);
     return hip_status(hipGetLastError());
 }
@@ -498,7 +532,7 @@ dpsgd_status consensus_of(dpsgd_ctx *ctx, const float *X, float *consensus)
 int64_t mix_partials_needed(const dpsgd_ctx *ctx)
 {
     // one partial per workgroup of the widest possible launch (vec = 1) plus the tail launch
-    return groups_for(ctx->d, 1) + 8;
+    return groups_for(ctx->d, 1) + 8 + kStage1Blocks;
 }
 
 dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, float *consensus, bool swapped)
