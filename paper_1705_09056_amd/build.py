@@ -17,7 +17,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libdpsgd_hip.so")
 
-SOURCES = ["api.cpp", "mix.hip", "grad.hip", "grad_f32.hip", "grad_mlp_bf16.hip", "grad_resnet.hip"]
+SOURCES = ["api.cpp", "mix.hip", "grad.hip", "grad_f32.hip", "grad_mlp_bf16.hip", "grad_resnet.hip", "conv_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,6 +1,421 @@
+// Per-worker minibatch gradient of the BN-free ResNet-20-style CNN (Algorithm 1 step 3,
+// footnote [a]): 3x3 stem, 3 stages of basic blocks (base, 2 base, 4 base channels; stride 2 at
+// the first conv of stages 2 and 3), one scalar bias per conv, parameter-free shortcuts, global
+// average pool, fully connected layer, softmax cross-entropy.
+//
+// Arithmetic: the image, every conv weight, every stored activation (after its ReLU) and every
+// delta entering a convolution are bf16 (round to nearest even); sums are fp32; biases, pooling
+// and the fully connected layer are fp32.  Activations and deltas are NHWC bf16 in the workspace.
+//
+// This file holds the shape-generic kernels (any channel count, image size, stride): one thread
+// per output element for forward and data gradient, one workgroup per (worker, c_out, c_in) for
+// the weight gradient.  They define the results; faster kernels for the benchmark's channel
+// counts are dispatched from conv_mfma.hip and must agree with these.
 #include "grad_common.h"
+#include "resnet_common.h"
+
 namespace dpsgd {
-size_t resnet_workspace_bytes(const dpsgd_ctx *, const dpsgd_model_desc &) { return 256; }
-dpsgd_status launch_grad_resnet(dpsgd_ctx *, const dpsgd_model_desc &, const float *, const void *, const void *,
-                                float *, float *) { return DPSGD_EUNSUPPORTED; }
+namespace {
+
+typedef long long i64;
+
+// ------------------------------------------------------------------------------ forward
+// IN_MODE 0: NHWC bf16 activation; 1: NCHW bf16 image; 2: NCHW fp32 image (rounded on load).
+template <int IN_MODE>
+__global__ void __launch_bounds__(256)
+conv_fwd_generic_kernel(const void *__restrict__ in, const float *__restrict__ X, i64 ld, ConvDesc c, int B, i64 total,
+                        const bf16_t *__restrict__ sc, int scC, int scH, int scW, int scS, bf16_t *__restrict__ out)
+{
+    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int co = (int)(idx % c.Co);
+    i64 t = idx / c.Co;
+    const int x = (int)(t % c.Wo); t /= c.Wo;
+    const int y = (int)(t % c.Ho); t /= c.Ho;
+    const int b = (int)(t % B);
+    const int w = (int)(t / B);
+    const float *Wg = X + (i64)w * ld + c.w_off + (i64)co * c.Ci * 9;
+    float acc = 0.f;
+    for (int ci = 0; ci < c.Ci; ++ci)
+        for (int ky = 0; ky < 3; ++ky) {
+            const int iy = y * c.stride + ky - 1;
+            if (iy < 0 || iy >= c.H) continue;
+            for (int kx = 0; kx < 3; ++kx) {
+                const int ix = x * c.stride + kx - 1;
+                if (ix < 0 || ix >= c.W) continue;
+                float v;
+                if (IN_MODE == 0)
+                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.H + iy) * c.W + ix) * c.Ci + ci]);
+                else if (IN_MODE == 1)
+                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]);
+                else
+                    v = bf2f(f2bf(((const float *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]));
+                acc = v * bf2f(f2bf(Wg[(ci * 3 + ky) * 3 + kx])) + acc;
+            }
+        }
+    float v = acc + X[(i64)w * ld + c.b_off];
+    if (sc && co < scC) v += bf2f(sc[((((i64)w * B + b) * scH + y * scS) * scW + x * scS) * scC + co]);
+    v = v > 0.f ? v : 0.f;
+    out[idx] = f2bf(v);
 }
+
+// ------------------------------------------------------------------------ data gradient
+// din[w][b][iy][ix][ci] = round( [act > 0] * ( sum_{co,ky,kx} dout[oy][ox][co] w[co][ci][ky][kx]
+//                                              + shortcut delta ) ),  oy = (iy + 1 - ky)/stride.
+__global__ void __launch_bounds__(256)
+conv_dgrad_generic_kernel(const bf16_t *__restrict__ dout, const float *__restrict__ X, i64 ld, ConvDesc c, int B,
+                          i64 total, const bf16_t *__restrict__ scd, int scC, int scH, int scW, int scS,
+                          const bf16_t *__restrict__ act, bf16_t *__restrict__ din)
+{
+    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int ci = (int)(idx % c.Ci);
+    i64 t = idx / c.Ci;
+    const int ix = (int)(t % c.W); t /= c.W;
+    const int iy = (int)(t % c.H); t /= c.H;
+    const int b = (int)(t % B);
+    const int w = (int)(t / B);
+    const float *Wg = X + (i64)w * ld + c.w_off;
+    float acc = 0.f;
+    for (int ky = 0; ky < 3; ++ky) {
+        const int ty = iy + 1 - ky;
+        if (ty < 0 || ty % c.stride) continue;
+        const int oy = ty / c.stride;
+        if (oy >= c.Ho) continue;
+        for (int kx = 0; kx < 3; ++kx) {
+            const int tx = ix + 1 - kx;
+            if (tx < 0 || tx % c.stride) continue;
+            const int ox = tx / c.stride;
+            if (ox >= c.Wo) continue;
+            const bf16_t *dp = dout + ((((i64)w * B + b) * c.Ho + oy) * c.Wo + ox) * c.Co;
+            for (int co = 0; co < c.Co; ++co)
+                acc = bf2f(dp[co]) * bf2f(f2bf(Wg[(((i64)co * c.Ci + ci) * 3 + ky) * 3 + kx])) + acc;
+        }
+    }
+    if (scd && (iy % scS) == 0 && (ix % scS) == 0 && iy / scS < scH && ix / scS < scW)
+        acc += bf2f(scd[((((i64)w * B + b) * scH + iy / scS) * scW + ix / scS) * scC + ci]);
+    const bool pos = bf16_positive(act[idx]);
+    din[idx] = f2bf(pos ? acc : 0.f);
+}
+
+// ---------------------------------------------------------------------- weight gradient
+// One workgroup per (c_in, c_out, worker): 9 tap sums over all (b, y, x), fixed-order reduction.
+template <int IN_MODE>
+__global__ void __launch_bounds__(256)
+conv_wgrad_generic_kernel(const void *__restrict__ in, const bf16_t *__restrict__ dout, ConvDesc c, int B,
+                          float *__restrict__ G, i64 ld)
+{
+    __shared__ float red[9][256];
+    const int ci = blockIdx.x, co = blockIdx.y, w = blockIdx.z;
+    float acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[t] = 0.f;
+    const int npix = B * c.Ho * c.Wo;
+    for (int p = threadIdx.x; p < npix; p += 256) {
+        const int x = p % c.Wo, y = (p / c.Wo) % c.Ho, b = p / (c.Wo * c.Ho);
+        const float go = bf2f(dout[((i64)w * npix + p) * c.Co + co]);
+        if (go == 0.f) continue;
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+            const int iy = y * c.stride + ky - 1;
+            if (iy < 0 || iy >= c.H) continue;
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx) {
+                const int ix = x * c.stride + kx - 1;
+                if (ix < 0 || ix >= c.W) continue;
+                float v;
+                if (IN_MODE == 0)
+                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.H + iy) * c.W + ix) * c.Ci + ci]);
+                else if (IN_MODE == 1)
+                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]);
+                else
+                    v = bf2f(f2bf(((const float *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]));
+                acc[ky * 3 + kx] = go * v + acc[ky * 3 + kx];
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 9; ++t) red[t][threadIdx.x] = acc[t];
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off)
+#pragma unroll
+            for (int t = 0; t < 9; ++t) red[t][threadIdx.x] += red[t][threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x < 9) G[(i64)w * ld + c.w_off + ((i64)co * c.Ci + ci) * 9 + threadIdx.x] = red[threadIdx.x][0];
+}
+
+// Scalar bias gradient: sum of one worker's delta tensor (count elements), fixed order.
+__global__ void __launch_bounds__(1024)
+sum_delta_kernel(const bf16_t *__restrict__ d, i64 count, float *__restrict__ G, i64 ld, i64 b_off)
+{
+    __shared__ float red[1024];
+    const int w = blockIdx.x;
+    const bf16_t *p = d + (i64)w * count;
+    float s0 = 0.f, s1 = 0.f;
+    i64 i = threadIdx.x;
+    for (; i + 1024 < count; i += 2048) {
+        s0 += bf2f(p[i]);
+        s1 += bf2f(p[i + 1024]);
+    }
+    for (; i < count; i += 1024) s0 += bf2f(p[i]);
+    red[threadIdx.x] = s0 + s1;
+    __syncthreads();
+    for (int off = 512; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) G[(i64)w * ld + b_off] = red[0];
+}
+
+// ------------------------------------------------------------ head: pool, FC, loss, FC grads
+// One workgroup per worker.  a: [B][HW][C] bf16.  pool / dpool: [n][B][C] fp32, z: [n][B][K] fp32.
+__global__ void __launch_bounds__(256)
+head_kernel(const bf16_t *__restrict__ a, const float *__restrict__ X, i64 ld, i64 fcw_off, i64 fcb_off, int B, int HW,
+            int C, int K, const int *__restrict__ labels, float *__restrict__ pool, float *__restrict__ z,
+            float *__restrict__ dpool, float *__restrict__ G, float *__restrict__ loss)
+{
+    __shared__ float red[256];
+    const int w = blockIdx.x, tid = threadIdx.x;
+    const float *fw = X + (i64)w * ld + fcw_off, *fb = X + (i64)w * ld + fcb_off;
+    float *pw = pool + (i64)w * B * C, *zw = z + (i64)w * B * K, *dpw = dpool + (i64)w * B * C;
+    const float inv_hw = 1.0f / (float)HW;
+    for (int e = tid; e < B * C; e += 256) {
+        const int b = e / C, ch = e % C;
+        const bf16_t *p = a + (((i64)w * B + b) * HW) * C + ch;
+        float s = 0.f;
+        for (int t = 0; t < HW; ++t) s += bf2f(p[(i64)t * C]);
+        pw[e] = s * inv_hw;
+    }
+    __syncthreads();
+    for (int e = tid; e < B * K; e += 256) {
+        const int b = e / K, o = e % K;
+        float s = fb[o];
+        for (int ch = 0; ch < C; ++ch) s = fw[o * C + ch] * pw[b * C + ch] + s;
+        zw[e] = s;
+    }
+    __syncthreads();
+    const float invB = 1.0f / (float)B;
+    float local = 0.f;
+    for (int b = tid; b < B; b += 256) {
+        float *zb = zw + b * K;
+        int lab = labels[(i64)w * B + b];
+        lab = lab < 0 ? 0 : (lab >= K ? K - 1 : lab);
+        float mx = zb[0];
+        for (int o = 1; o < K; ++o) mx = fmaxf(mx, zb[o]);
+        float se = 0.f;
+        for (int o = 0; o < K; ++o) se += expf(zb[o] - mx);
+        const float lse = mx + logf(se);
+        local += lse - zb[lab];
+        for (int o = 0; o < K; ++o) zb[o] = (expf(zb[o] - lse) - (o == lab ? 1.f : 0.f)) * invB;   // dz in place
+    }
+    red[tid] = local;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off) red[tid] += red[tid + off];
+        __syncthreads();
+    }
+    if (loss && tid == 0) loss[w] = red[0] * invB;
+    for (int e = tid; e < K * C; e += 256) {
+        const int o = e / C, ch = e % C;
+        float s = 0.f;
+        for (int b = 0; b < B; ++b) s = zw[b * K + o] * pw[b * C + ch] + s;
+        G[(i64)w * ld + fcw_off + e] = s;
+    }
+    for (int o = tid; o < K; o += 256) {
+        float s = 0.f;
+        for (int b = 0; b < B; ++b) s += zw[b * K + o];
+        G[(i64)w * ld + fcb_off + o] = s;
+    }
+    for (int e = tid; e < B * C; e += 256) {
+        const int b = e / C, ch = e % C;
+        float s = 0.f;
+        for (int o = 0; o < K; ++o) s = zw[b * K + o] * fw[o * C + ch] + s;
+        dpw[e] = s * inv_hw;
+    }
+}
+
+// dv[w][b][t][c] = round([a > 0] * dpool[w][b][c])   (dpool already divided by H*W)
+__global__ void __launch_bounds__(256)
+pool_bwd_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dpool, int HW, int C, i64 total,
+                bf16_t *__restrict__ dv)
+{
+    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int ch = (int)(idx % C);
+    const i64 wb = idx / ((i64)HW * C);
+    dv[idx] = bf16_positive(a[idx]) ? f2bf(dpool[wb * C + ch]) : (bf16_t)0;
+}
+
+unsigned blocks_for(i64 total) { return (unsigned)((total + 255) / 256); }
+
+}  // namespace
+
+ResnetPlan make_resnet_plan(const dpsgd_model_desc &m)
+{
+    ResnetPlan p;
+    const int cin = m.widths[0], H0 = m.widths[1], W0 = m.widths[2], base = m.widths[3], blocks = m.widths[4];
+    p.classes = m.widths[5];
+    auto out_dim = [](int h, int s) { return (h + 2 - 3) / s + 1; };
+    i64 off = 0;
+    int H = H0, W = W0, cprev = base;
+    auto add = [&](int Ci, int Co, int h, int w, int s) {
+        ConvDesc c;
+        c.Ci = Ci; c.Co = Co; c.H = h; c.W = w; c.stride = s; c.Ho = out_dim(h, s); c.Wo = out_dim(w, s);
+        c.w_off = off; off += (i64)Co * Ci * 9;
+        c.b_off = off; off += 1;
+        p.convs.push_back(c);
+    };
+    add(cin, base, H, W, 1);
+    for (int s = 0; s < 3; ++s) {
+        const int c = base << s;
+        for (int j = 0; j < blocks; ++j) {
+            const int stride = (s > 0 && j == 0) ? 2 : 1;
+            add(cprev, c, H, W, stride);
+            H = out_dim(H, stride); W = out_dim(W, stride);
+            add(c, c, H, W, 1);
+            cprev = c;
+        }
+    }
+    p.fcw_off = off; off += (i64)p.classes * cprev;
+    p.fcb_off = off;
+    p.C_last = cprev; p.H_last = H; p.W_last = W;
+    p.nblocks = 3 * blocks;
+    return p;
+}
+
+size_t resnet_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m)
+{
+    const ResnetPlan p = make_resnet_plan(m);
+    const size_t nB = (size_t)ctx->n * m.batch;
+    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
+    size_t bytes = 0, biggest = 0;
+    for (size_t q = 0; q < p.convs.size(); ++q) {   // output of every conv: a[0], then u[j], a[j+1]
+        const size_t e = nB * p.convs[q].Ho * p.convs[q].Wo * p.convs[q].Co;
+        bytes += pad(e * 2);
+        biggest = e > biggest ? e : biggest;
+    }
+    bytes += 3 * pad(biggest * 2);                                   // delta buffers
+    bytes += 2 * pad(nB * p.C_last * 4) + pad(nB * p.classes * 4);   // pool, dpool, logits
+    return bytes + 256;
+}
+
+dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
+                                const void *targets, float *G, float *loss)
+{
+    hipStream_t s = ctx->stream;
+    const ResnetPlan p = make_resnet_plan(m);
+    const int n = ctx->n, B = m.batch;
+    const i64 nB = (i64)n * B;
+    if (n > 65535) return DPSGD_EUNSUPPORTED;
+    for (const ConvDesc &c : p.convs)
+        if (c.Ho < 1 || c.Wo < 1 || c.Ci > 65535 || c.Co > 65535) return DPSGD_EUNSUPPORTED;
+    unsigned char *ws = (unsigned char *)ctx->ws;
+    auto take = [&](size_t bytes) {
+        unsigned char *q = ws;
+        ws += (bytes + 255) / 256 * 256;
+        return q;
+    };
+    const int nconv = (int)p.convs.size();
+    std::vector<bf16_t *> outp(nconv);   // outp[0] = a[0]; outp[1+2j] = u[j]; outp[2+2j] = a[j+1]
+    size_t biggest = 0;
+    for (int q = 0; q < nconv; ++q) {
+        const size_t e = (size_t)nB * p.convs[q].Ho * p.convs[q].Wo * p.convs[q].Co;
+        outp[q] = (bf16_t *)take(e * 2);
+        biggest = e > biggest ? e : biggest;
+    }
+    bf16_t *dbuf[3];
+    for (int i = 0; i < 3; ++i) dbuf[i] = (bf16_t *)take(biggest * 2);
+    float *pool = (float *)take((size_t)nB * p.C_last * 4);
+    float *dpool = (float *)take((size_t)nB * p.C_last * 4);
+    float *logits = (float *)take((size_t)nB * p.classes * 4);
+    auto a_of = [&](int j) { return outp[j == 0 ? 0 : 2 * j]; };   // block input/output j
+    auto u_of = [&](int j) { return outp[1 + 2 * j]; };
+
+    // ---- forward
+    {
+        const ConvDesc &c = p.convs[0];
+        const i64 total = nB * c.Ho * c.Wo * c.Co;
+        if (m.input_is_bf16)
+            hipLaunchKernelGGL(conv_fwd_generic_kernel<1>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld, c,
+                               B, total, nullptr, 0, 0, 0, 1, outp[0]);
+        else
+            hipLaunchKernelGGL(conv_fwd_generic_kernel<2>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld, c,
+                               B, total, nullptr, 0, 0, 0, 1, outp[0]);
+    }
+    for (int j = 0; j < p.nblocks; ++j) {
+        const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
+        dpsgd_status st = conv_forward(ctx, c1, B, a_of(j), X, nullptr, 0, 0, 0, 1, u_of(j));
+        if (st != DPSGD_OK) return st;
+        st = conv_forward(ctx, c2, B, u_of(j), X, a_of(j), c1.Ci, c1.H, c1.W, c1.stride, a_of(j + 1));
+        if (st != DPSGD_OK) return st;
+    }
+    const int HWl = p.H_last * p.W_last;
+    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, a_of(p.nblocks), X, ctx->ld, p.fcw_off, p.fcb_off, B,
+                       HWl, p.C_last, p.classes, (const int *)targets, pool, logits, dpool, G, loss);
+
+    // ---- backward
+    bf16_t *dv = dbuf[0], *du = dbuf[1], *dnext = dbuf[2];
+    {
+        const i64 total = nB * HWl * p.C_last;
+        hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks), dpool, HWl, p.C_last,
+                           total, dv);
+    }
+    for (int j = p.nblocks - 1; j >= 0; --j) {
+        const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
+        // conv2: weights and bias from dv and u; du = [u > 0] * dgrad(dv)
+        dpsgd_status st = conv_weight_grad(ctx, c2, B, u_of(j), dv, G);
+        if (st != DPSGD_OK) return st;
+        st = conv_data_grad(ctx, c2, B, dv, X, nullptr, 0, 0, 0, 1, u_of(j), du);
+        if (st != DPSGD_OK) return st;
+        // conv1: weights and bias from du and a_j; next dv = [a_j > 0] * (dgrad(du) + shortcut delta)
+        st = conv_weight_grad(ctx, c1, B, a_of(j), du, G);
+        if (st != DPSGD_OK) return st;
+        st = conv_data_grad(ctx, c1, B, du, X, dv, c2.Co, c2.Ho, c2.Wo, c1.stride, a_of(j), dnext);
+        if (st != DPSGD_OK) return st;
+        bf16_t *t = dv; dv = dnext; dnext = t;
+    }
+    {   // stem: weight and bias gradient only
+        const ConvDesc &c = p.convs[0];
+        dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)n);
+        if (m.input_is_bf16)
+            hipLaunchKernelGGL(conv_wgrad_generic_kernel<1>, grid, dim3(256), 0, s, inputs, dv, c, B, G, ctx->ld);
+        else
+            hipLaunchKernelGGL(conv_wgrad_generic_kernel<2>, grid, dim3(256), 0, s, inputs, dv, c, B, G, ctx->ld);
+        hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)n), dim3(1024), 0, s, dv, (i64)B * c.Ho * c.Wo * c.Co, G,
+                           ctx->ld, c.b_off);
+    }
+    return hip_status(hipGetLastError());
+}
+
+// ---- shape-generic building blocks (used directly, and as the fallback of the MFMA dispatch)
+dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const float *X,
+                                  const bf16_t *sc, int scC, int scH, int scW, int scS, bf16_t *out)
+{
+    const i64 total = (i64)ctx->n * B * c.Ho * c.Wo * c.Co;
+    hipLaunchKernelGGL(conv_fwd_generic_kernel<0>, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, in, X, ctx->ld, c, B,
+                       total, sc, scC, scH, scW, scS, out);
+    return hip_status(hipGetLastError());
+}
+
+dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *dout, const float *X,
+                                    const bf16_t *scd, int scC, int scH, int scW, int scS, const bf16_t *act, bf16_t *din)
+{
+    const i64 total = (i64)ctx->n * B * c.H * c.W * c.Ci;
+    hipLaunchKernelGGL(conv_dgrad_generic_kernel, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, dout, X, ctx->ld, c, B,
+                       total, scd, scC, scH, scW, scS, act, din);
+    return hip_status(hipGetLastError());
+}
+
+dpsgd_status conv_weight_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const bf16_t *dout,
+                                      float *G)
+{
+    dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)ctx->n);
+    hipLaunchKernelGGL(conv_wgrad_generic_kernel<0>, grid, dim3(256), 0, ctx->stream, in, dout, c, B, G, ctx->ld);
+    hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)ctx->n), dim3(1024), 0, ctx->stream, dout,
+                       (i64)B * c.Ho * c.Wo * c.Co, G, ctx->ld, c.b_off);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace dpsgd

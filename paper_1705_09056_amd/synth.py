@@ -106,15 +106,21 @@ def padded_stride(d: int, multiple: int = 64) -> int:
 # ----------------------------------------------------------------------- draws
 def make_x0(cfg: Workload) -> np.ndarray:
     """Common initial point x_0 (Algorithm 1, Require): zeros for the convex
-    workloads, one Kaiming-normal draw N(0, 2/fan_in) with zero biases otherwise."""
+    workloads, one Kaiming-normal draw N(0, 2/fan_in) with zero biases otherwise.
+    In the CNN, which has no normalisation layers, the second conv of each of the
+    R residual blocks is scaled by 1/sqrt(2R) so that the residual sums keep the
+    activations at unit scale at x_0."""
     d = model_dim(cfg.model_kind, cfg.widths)
     x0 = np.zeros(d, dtype=np.float32)
     if cfg.model_kind in (MODEL_MLP, MODEL_RESNET20):
         g = rng(cfg.index, _TAG_X0)
+        nblocks = 3 * cfg.widths[4] if cfg.model_kind == MODEL_RESNET20 else 0
         for p in param_layout(cfg.model_kind, cfg.widths):
             if p.fan_in:
-                x0[p.offset:p.offset + p.size] = (
-                    g.standard_normal(p.size, dtype=np.float32) * np.float32(np.sqrt(2.0 / p.fan_in)))
+                std = np.sqrt(2.0 / p.fan_in)
+                if p.name.endswith(".W2"):
+                    std /= np.sqrt(2.0 * nblocks)
+                x0[p.offset:p.offset + p.size] = g.standard_normal(p.size, dtype=np.float32) * np.float32(std)
     return x0
 
 
