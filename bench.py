@@ -23,6 +23,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per mix launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by what the
+# same counters read for a plain copy of known size (2.0 and 1.0); see profiles/.
+MEASURED_MIX_TRAFFIC = {"mlp3_ring64": 22.76e9}
 
 
 def parse():
@@ -35,6 +38,9 @@ def parse():
     ap.add_argument("--pool", type=int, default=4, help="distinct minibatches kept in HBM and cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-consensus", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy (reference for the FETCH_SIZE / WRITE_SIZE "
+                         "counters under rocprofv3 --pmc) and exit")
     return ap.parse_args()
 
 
@@ -88,6 +94,16 @@ def main():
 
     import numpy as np
     import torch
+
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")    # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
 
     from paper_1705_09056_amd import binding as B
     from paper_1705_09056_amd import synth
@@ -164,7 +180,8 @@ def main():
                    "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "gamma": cfg.gamma,
                    "minibatch_pool": len(pool), "consensus": cons is not None},
         "roofline": {"kernel": "mix_step (Algorithm 1 steps 4-5 fused)", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_MIX_TRAFFIC.get(cfg.name),
                      "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_ms},
         "mix_fraction_of_step": mix_ms / (total_ms / K),
         "wall_s": wall,
