@@ -1,22 +1,278 @@
-// Dispatch of the CNN's convolutions: MFMA kernels for the benchmark's channel counts, the
-// shape-generic kernels otherwise.
+// 3x3 convolutions of the CNN workload as implicit GEMMs on bf16 MFMA (gfx950), and their
+// dispatch: MFMA kernels for channel counts 16/32/64 on images whose width is a multiple of 8,
+// the shape-generic kernels otherwise.
+//
+// Forward and data gradient share one kernel: out(y,x,o) = sum_{tap,c} P(y*S+ky-1, x*S+kx-1, c) *
+// Weff[o][c][tap], where P is the source tensor (zero outside; for the data gradient of a stride-2
+// conv the delta with zeros inserted between its pixels) and Weff the conv's weights (for the data
+// gradient: channels transposed, taps reversed).  A workgroup owns 8 output rows of one image: it
+// stages the (8-1)*S+3 source rows with their halo in LDS (NHWC, pixel pitch padded by 16 bytes so
+// that 16 lanes reading 16 bytes each spread over all banks), keeps its slice of the packed weights
+// in registers for the whole tile, and issues v_mfma_f32_16x16x32_bf16: A = 16 consecutive output
+// pixels x 32 contraction values (8 channels of one tap per lane, one 16-byte LDS read), B = 32 x
+// 16 output channels.  Accumulator register i of lane l is (pixel 4*(l/16)+i, channel l%16), so a
+// lane writes 4 consecutive pixels of one channel: one 8-byte store into the channel-major copy,
+// four 2-byte stores into the NHWC tensor.
 #include "resnet_common.h"
 
 namespace dpsgd {
+namespace {
 
-dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const float *X, const bf16_t *sc,
-                          int scC, int scH, int scW, int scS, bf16_t *out)
+typedef long long i64;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int ksteps(int ci) { return (9 * ci + 31) / 32; }
+// waves of a workgroup that split the output channels: as few as keep <= 18 weight fragments per lane
+constexpr int wave_cols(int ci, int co)
 {
-    return conv_forward_generic(ctx, c, B, in, X, sc, scC, scH, scW, scS, out);
+    int wc = 1;
+    while (ksteps(ci) * (co / 16) / wc > 18) wc *= 2;
+    return wc;
 }
 
-dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *dout, const float *X,
-                            const bf16_t *scd, int scC, int scH, int scW, int scS, const bf16_t *act, bf16_t *din)
+// ------------------------------------------------------------------------- weight packing
+// wpack[w][s][t][lane][j] = Weff[o = 16 t + lane%16][c][tap], contraction index 32 s + 8 (lane/16) + j
+// = tap * CI + c (CI = contraction channels rounded up to 8); zero beyond tap 8 or channel c_real.
+// DGRAD: Weff[o = c_in][c = c_out][tap] = W[c_out][c_in][8 - tap].
+template <bool DGRAD>
+__global__ void __launch_bounds__(256)
+pack_weights_kernel(const float *__restrict__ X, i64 ld, ConvDesc c, int CI, int CO, int KS, bf16_t *__restrict__ wpack)
 {
-    return conv_data_grad_generic(ctx, c, B, dout, X, scd, scC, scH, scW, scS, act, din);
+    const int w = blockIdx.y;
+    const int per_worker = KS * (CO / 16) * 64 * 8;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= per_worker) return;
+    const int j = e & 7, lane = (e >> 3) & 63, st = e >> 9;
+    const int t = st % (CO / 16), s = st / (CO / 16);
+    const int kk = 32 * s + 8 * (lane >> 4) + j;
+    const int tap = kk / CI, ch = kk % CI, o = 16 * t + (lane & 15);
+    float v = 0.f;
+    const int c_real = DGRAD ? c.Co : c.Ci, o_real = DGRAD ? c.Ci : c.Co;
+    if (tap < 9 && ch < c_real && o < o_real) {
+        const float *Wg = X + (i64)w * ld + c.w_off;
+        v = DGRAD ? Wg[((i64)ch * c.Ci + o) * 9 + (8 - tap)] : Wg[((i64)o * c.Ci + ch) * 9 + tap];
+    }
+    wpack[(i64)w * per_worker + e] = f2bf(v);
 }
 
-dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const bf16_t *dout, float *G)
+// --------------------------------------------------------------- forward / data gradient
+struct ConvMfmaArgs {
+    const bf16_t *src;      // NHWC [n*B][Hs][Ws][CI]
+    int Hs, Ws;
+    const bf16_t *wpack;    // [n][KS][CO/16][64][8]
+    bf16_t *dst, *dstT;     // NHWC [n*B][Hd][Wd][CO], channel-major [n*B][CO][Hd][Wd]
+    int Hd, Wd, B;
+    const float *X;         // forward: scalar bias at X[w*ld + b_off]
+    i64 ld, b_off;
+    ShortcutRef sc;         // forward: block input; data gradient: delta of the block output
+    const bf16_t *act;      // data gradient: activation whose sign masks the result (same shape as dst)
+};
+
+template <int CI, int CO, int STRIDE, int DILATE, bool DGRAD>
+__global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
+{
+    constexpr int KS = ksteps(CI), NT = CO / 16, WC = wave_cols(CI, CO), NTW = NT / WC, WP = 4 / WC;
+    constexpr int PP = CI + 8;   // LDS pixel pitch (bf16 elements)
+    constexpr int TH = 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *patch = reinterpret_cast<bf16_t *>(smem);
+    const int band = blockIdx.x, b = blockIdx.y, w = blockIdx.z;
+    const i64 img = (i64)w * a.B + b;
+    const int y0 = band * TH;
+    const int PR = (TH - 1) * STRIDE + 3, PC = (a.Wd - 1) * STRIDE + 3;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wc = wave % WC, wp = wave / WC;
+    const int n16 = lane & 15, g = lane >> 4;
+
+    // stage the source rows (with halo, zeros outside / between dilated pixels)
+    {
+        constexpr int C8 = CI / 8;
+        const int units = PR * PC * C8;
+        const bf16_t *src = a.src + img * a.Hs * a.Ws * CI;
+        for (int u = tid; u < units; u += 256) {
+            const int c8 = u % C8, pc = (u / C8) % PC, pr = u / (C8 * PC);
+            int vr = y0 * STRIDE - 1 + pr, vc = pc - 1;
+            bool ok = vr >= 0 && vc >= 0;
+            if (DILATE == 2) {
+                ok = ok && !(vr & 1) && !(vc & 1);
+                vr >>= 1;
+                vc >>= 1;
+            }
+            ok = ok && vr < a.Hs && vc < a.Ws;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (ok) v = *reinterpret_cast<const u32x4 *>(src + ((i64)vr * a.Ws + vc) * CI + c8 * 8);
+            *reinterpret_cast<u32x4 *>(patch + (pr * PC + pc) * PP + c8 * 8) = v;
+        }
+    }
+
+    // this wave's weight fragments
+    bf16x8 wf[KS][NTW];
+    {
+        const bf16_t *wp_ = a.wpack + (i64)w * (KS * NT * 512) + lane * 8;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int t = 0; t < NTW; ++t)
+                wf[s][t] = *reinterpret_cast<const bf16x8 *>(wp_ + (s * NT + wc * NTW + t) * 512);
+    }
+    // per k-step offset of this lane's 8 contraction values inside the patch (relative to the
+    // pixel's top-left tap): the tap and the first channel follow from 32 s + 8 g
+    int koff[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const int kk = 32 * s + 8 * g;
+        int tap = kk / CI;
+        const int c0 = kk % CI;
+        tap = tap > 8 ? 8 : tap;   // padded taps carry zero weights; read finite data
+        koff[s] = ((tap / 3) * PC + (tap % 3)) * PP + c0;
+    }
+    __syncthreads();
+
+    const int mtot = TH * a.Wd / 16;
+    float bias = 0.f;
+    if (!DGRAD) bias = a.X[(i64)w * a.ld + a.b_off];
+    for (int mt = wp; mt < mtot; mt += WP) {
+        const int pi = mt * 16 + n16;                  // this lane's pixel as an A-operand row
+        const int py = pi / a.Wd, px = pi % a.Wd;
+        const bf16_t *pa = patch + ((py * STRIDE) * PC + px * STRIDE) * PP;
+        f32x4 acc[NTW];
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const bf16x8 av = *reinterpret_cast<const bf16x8 *>(pa + koff[s]);
+#pragma unroll
+            for (int t = 0; t < NTW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wf[s][t], acc[t], 0, 0, 0);
+        }
+        // epilogue: this lane holds pixels q0..q0+3 (consecutive x of one row) of channel o
+        const int q0 = mt * 16 + 4 * g;
+        const int y = y0 + q0 / a.Wd, x0 = q0 % a.Wd;
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) {
+            const int o = (wc * NTW + t) * 16 + n16;
+            bf16_t r[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int x = x0 + i;
+                float v = acc[t][i];
+                const i64 di = ((img * a.Hd + y) * a.Wd + x) * CO + o;
+                if (!DGRAD) {
+                    v += bias;
+                    if (a.sc.p && o < a.sc.C)
+                        v += bf2f(a.sc.p[((img * a.sc.H + (i64)y * a.sc.S) * a.sc.W + x * a.sc.S) * a.sc.C + o]);
+                    v = v > 0.f ? v : 0.f;
+                } else {
+                    if (a.sc.p && (y % a.sc.S) == 0 && (x % a.sc.S) == 0)
+                        v += bf2f(a.sc.p[((img * a.sc.H + y / a.sc.S) * a.sc.W + x / a.sc.S) * a.sc.C + o]);
+                    v = bf16_positive(a.act[di]) ? v : 0.f;
+                }
+                r[i] = f2bf(v);
+                a.dst[di] = r[i];
+            }
+            u32x2 pk = {(unsigned)r[0] | ((unsigned)r[1] << 16), (unsigned)r[2] | ((unsigned)r[3] << 16)};
+            *reinterpret_cast<u32x2 *>(a.dstT + ((img * CO + o) * a.Hd + y) * a.Wd + x0) = pk;
+        }
+    }
+}
+
+bool pow2_channels(int c) { return c == 16 || c == 32 || c == 64; }
+
+// Can the MFMA kernel produce a tensor of Hd x Wd from a source of width Ws?
+bool tile_ok(int Hd, int Wd, int stride, int ci)
+{
+    if (Hd % 8 || Wd % 8 || Wd > 64) return false;
+    const size_t pr = 7 * stride + 3, pc = (size_t)(Wd - 1) * stride + 3;
+    return pr * pc * (ci + 8) * 2 <= 64 * 1024;
+}
+
+bool fwd_mfma_ok(const ConvDesc &c)
+{
+    if (!pow2_channels(c.Ci) || !pow2_channels(c.Co)) return false;
+    if (c.stride == 1) return c.Ci == c.Co && tile_ok(c.Ho, c.Wo, 1, c.Ci);
+    return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && tile_ok(c.Ho, c.Wo, 2, c.Ci);
+}
+
+bool dgrad_mfma_ok(const ConvDesc &c)
+{
+    if (!pow2_channels(c.Ci) || !pow2_channels(c.Co)) return false;
+    if (c.stride == 1) return c.Ci == c.Co && tile_ok(c.H, c.W, 1, c.Co);
+    return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && c.H == 2 * c.Ho && c.W == 2 * c.Wo &&
+           tile_ok(c.H, c.W, 1, c.Co);
+}
+
+template <int CI, int CO, int STRIDE, int DILATE, bool DGRAD>
+dpsgd_status launch_conv(dpsgd_ctx *ctx, const ConvMfmaArgs &a)
+{
+    const size_t pr = 7 * STRIDE + 3, pc = (size_t)(a.Wd - 1) * STRIDE + 3;
+    const size_t shm = pr * pc * (CI + 8) * sizeof(bf16_t);
+    dim3 grid((unsigned)(a.Hd / 8), (unsigned)a.B, (unsigned)ctx->n);
+    hipLaunchKernelGGL((conv3x3_mfma_kernel<CI, CO, STRIDE, DILATE, DGRAD>), grid, dim3(256), shm, ctx->stream, a);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+size_t conv_pack_bytes(const ConvDesc &c, bool dgrad)
+{
+    const bool ok = dgrad ? dgrad_mfma_ok(c) : fwd_mfma_ok(c);
+    if (!ok) return 0;
+    const int ci = dgrad ? c.Co : c.Ci, co = dgrad ? c.Ci : c.Co;
+    return (size_t)ksteps(ci) * 32 * co * sizeof(bf16_t);
+}
+
+size_t conv_wgrad_partial_bytes(const ConvDesc &, int) { return 0; }
+
+dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d)
+{
+    if (fwd_mfma_ok(c)) {
+        const int KS = ksteps(c.Ci), per = KS * 32 * c.Co;
+        hipLaunchKernelGGL(pack_weights_kernel<false>, dim3((unsigned)((per + 255) / 256), (unsigned)ctx->n), dim3(256), 0,
+                           ctx->stream, X, ctx->ld, c, c.Ci, c.Co, KS, wpack_f);
+    }
+    if (dgrad_mfma_ok(c)) {
+        const int KS = ksteps(c.Co), per = KS * 32 * c.Ci;
+        hipLaunchKernelGGL(pack_weights_kernel<true>, dim3((unsigned)((per + 255) / 256), (unsigned)ctx->n), dim3(256), 0,
+                           ctx->stream, X, ctx->ld, c, c.Co, c.Ci, KS, wpack_d);
+    }
+    return hip_status(hipGetLastError());
+}
+
+dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, const bf16_t *wpack,
+                          ShortcutRef sc, Tensor out)
+{
+    if (!fwd_mfma_ok(c) || !out.t) return conv_forward_generic(ctx, c, B, in, X, sc, out);
+    ConvMfmaArgs a{};
+    a.src = in.p; a.Hs = c.H; a.Ws = c.W; a.wpack = wpack; a.dst = out.p; a.dstT = out.t; a.Hd = c.Ho; a.Wd = c.Wo;
+    a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = c.b_off; a.sc = sc; a.act = nullptr;
+    if (c.stride == 1) {
+        if (c.Ci == 16) return launch_conv<16, 16, 1, 1, false>(ctx, a);
+        if (c.Ci == 32) return launch_conv<32, 32, 1, 1, false>(ctx, a);
+        return launch_conv<64, 64, 1, 1, false>(ctx, a);
+    }
+    if (c.Ci == 16) return launch_conv<16, 32, 2, 1, false>(ctx, a);
+    return launch_conv<32, 64, 2, 1, false>(ctx, a);
+}
+
+dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X, const bf16_t *wpack_d,
+                            ShortcutRef scd, const bf16_t *act, Tensor din)
+{
+    if (!dgrad_mfma_ok(c) || !din.t) return conv_data_grad_generic(ctx, c, B, dout, X, scd, act, din);
+    ConvMfmaArgs a{};
+    a.src = dout.p; a.Hs = c.Ho; a.Ws = c.Wo; a.wpack = wpack_d; a.dst = din.p; a.dstT = din.t; a.Hd = c.H; a.Wd = c.W;
+    a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = 0; a.sc = scd; a.act = act;
+    if (c.stride == 1) {
+        if (c.Ci == 16) return launch_conv<16, 16, 1, 1, true>(ctx, a);
+        if (c.Ci == 32) return launch_conv<32, 32, 1, 1, true>(ctx, a);
+        return launch_conv<64, 64, 1, 1, true>(ctx, a);
+    }
+    if (c.Ci == 16) return launch_conv<32, 16, 1, 2, true>(ctx, a);
+    return launch_conv<64, 32, 1, 2, true>(ctx, a);
+}
+
+dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *)
 {
     return conv_weight_grad_generic(ctx, c, B, in, dout, G);
 }

@@ -24,7 +24,8 @@ typedef long long i64;
 template <int IN_MODE>
 __global__ void __launch_bounds__(256)
 conv_fwd_generic_kernel(const void *__restrict__ in, const float *__restrict__ X, i64 ld, ConvDesc c, int B, i64 total,
-                        const bf16_t *__restrict__ sc, int scC, int scH, int scW, int scS, bf16_t *__restrict__ out)
+                        const bf16_t *__restrict__ sc, int scC, int scH, int scW, int scS, bf16_t *__restrict__ out,
+                        bf16_t *__restrict__ outT)
 {
     const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
@@ -57,6 +58,7 @@ conv_fwd_generic_kernel(const void *__restrict__ in, const float *__restrict__ X
     if (sc && co < scC) v += bf2f(sc[((((i64)w * B + b) * scH + y * scS) * scW + x * scS) * scC + co]);
     v = v > 0.f ? v : 0.f;
     out[idx] = f2bf(v);
+    if (outT) outT[((((i64)w * B + b) * c.Co + co) * c.Ho + y) * c.Wo + x] = f2bf(v);   // channel-major copy
 }
 
 // ------------------------------------------------------------------------ data gradient
@@ -65,7 +67,7 @@ conv_fwd_generic_kernel(const void *__restrict__ in, const float *__restrict__ X
 __global__ void __launch_bounds__(256)
 conv_dgrad_generic_kernel(const bf16_t *__restrict__ dout, const float *__restrict__ X, i64 ld, ConvDesc c, int B,
                           i64 total, const bf16_t *__restrict__ scd, int scC, int scH, int scW, int scS,
-                          const bf16_t *__restrict__ act, bf16_t *__restrict__ din)
+                          const bf16_t *__restrict__ act, bf16_t *__restrict__ din, bf16_t *__restrict__ dinT)
 {
     const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
@@ -96,6 +98,7 @@ conv_dgrad_generic_kernel(const bf16_t *__restrict__ dout, const float *__restri
         acc += bf2f(scd[((((i64)w * B + b) * scH + iy / scS) * scW + ix / scS) * scC + ci]);
     const bool pos = bf16_positive(act[idx]);
     din[idx] = f2bf(pos ? acc : 0.f);
+    if (dinT) dinT[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix] = f2bf(pos ? acc : 0.f);
 }
 
 // ---------------------------------------------------------------------- weight gradient
@@ -239,13 +242,16 @@ head_kernel(const bf16_t *__restrict__ a, const float *__restrict__ X, i64 ld, i
 // dv[w][b][t][c] = round([a > 0] * dpool[w][b][c])   (dpool already divided by H*W)
 __global__ void __launch_bounds__(256)
 pool_bwd_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dpool, int HW, int C, i64 total,
-                bf16_t *__restrict__ dv)
+                bf16_t *__restrict__ dv, bf16_t *__restrict__ dvT)
 {
     const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int ch = (int)(idx % C);
+    const int t = (int)((idx / C) % HW);
     const i64 wb = idx / ((i64)HW * C);
-    dv[idx] = bf16_positive(a[idx]) ? f2bf(dpool[wb * C + ch]) : (bf16_t)0;
+    const bf16_t v = bf16_positive(a[idx]) ? f2bf(dpool[wb * C + ch]) : (bf16_t)0;
+    dv[idx] = v;
+    if (dvT) dvT[(wb * C + ch) * HW + t] = v;
 }
 
 unsigned blocks_for(i64 total) { return (unsigned)((total + 255) / 256); }
@@ -285,20 +291,59 @@ ResnetPlan make_resnet_plan(const dpsgd_model_desc &m)
     return p;
 }
 
+
+// Workspace layout, shared by resnet_workspace_bytes and launch_grad_resnet.
+namespace {
+struct Workspace {
+    std::vector<Tensor> out;              // output of every conv: out[0] = a_0, out[1+2j] = u_j, out[2+2j] = a_{j+1}
+    Tensor delta[3];                      // rotating delta buffers
+    std::vector<bf16_t *> wpack_f, wpack_d;
+    bf16_t *image_bf16 = nullptr;         // bf16 copy of an fp32 image (channel-major, as given)
+    float *pool = nullptr, *dpool = nullptr, *logits = nullptr, *partials = nullptr;
+    size_t bytes = 0;
+};
+
+Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPlan &p, unsigned char *base)
+{
+    Workspace w;
+    size_t off = 0;
+    auto take = [&](size_t b) {
+        unsigned char *q = base ? base + off : nullptr;
+        off += (b + 255) / 256 * 256;
+        return q;
+    };
+    const size_t nB = (size_t)ctx->n * m.batch;
+    size_t biggest = 0, part = 0;
+    for (const ConvDesc &c : p.convs) {
+        const size_t e = nB * c.Ho * c.Wo * c.Co;
+        Tensor t;
+        t.p = (bf16_t *)take(e * 2);
+        t.t = (bf16_t *)take(e * 2);
+        w.out.push_back(t);
+        biggest = e > biggest ? e : biggest;
+        w.wpack_f.push_back((bf16_t *)take(conv_pack_bytes(c, false) * ctx->n));
+        w.wpack_d.push_back((bf16_t *)take(conv_pack_bytes(c, true) * ctx->n));
+        const size_t pb = conv_wgrad_partial_bytes(c, m.batch) * ctx->n;
+        part = pb > part ? pb : part;
+    }
+    for (int i = 0; i < 3; ++i) {
+        w.delta[i].p = (bf16_t *)take(biggest * 2);
+        w.delta[i].t = (bf16_t *)take(biggest * 2);
+    }
+    if (!m.input_is_bf16) w.image_bf16 = (bf16_t *)take(nB * p.convs[0].Ci * p.convs[0].H * p.convs[0].W * 2);
+    w.pool = (float *)take(nB * p.C_last * 4);
+    w.dpool = (float *)take(nB * p.C_last * 4);
+    w.logits = (float *)take(nB * p.classes * 4);
+    w.partials = (float *)take(part);
+    w.bytes = off + 256;
+    return w;
+}
+}  // namespace
+
 size_t resnet_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m)
 {
     const ResnetPlan p = make_resnet_plan(m);
-    const size_t nB = (size_t)ctx->n * m.batch;
-    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
-    size_t bytes = 0, biggest = 0;
-    for (size_t q = 0; q < p.convs.size(); ++q) {   // output of every conv: a[0], then u[j], a[j+1]
-        const size_t e = nB * p.convs[q].Ho * p.convs[q].Wo * p.convs[q].Co;
-        bytes += pad(e * 2);
-        biggest = e > biggest ? e : biggest;
-    }
-    bytes += 3 * pad(biggest * 2);                                   // delta buffers
-    bytes += 2 * pad(nB * p.C_last * 4) + pad(nB * p.classes * 4);   // pool, dpool, logits
-    return bytes + 256;
+    return carve(ctx, m, p, nullptr).bytes;
 }
 
 dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
@@ -308,30 +353,19 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     const ResnetPlan p = make_resnet_plan(m);
     const int n = ctx->n, B = m.batch;
     const i64 nB = (i64)n * B;
-    if (n > 65535) return DPSGD_EUNSUPPORTED;
+    if (n > 65535 || B > 65535) return DPSGD_EUNSUPPORTED;
     for (const ConvDesc &c : p.convs)
         if (c.Ho < 1 || c.Wo < 1 || c.Ci > 65535 || c.Co > 65535) return DPSGD_EUNSUPPORTED;
-    unsigned char *ws = (unsigned char *)ctx->ws;
-    auto take = [&](size_t bytes) {
-        unsigned char *q = ws;
-        ws += (bytes + 255) / 256 * 256;
-        return q;
-    };
+    Workspace ws = carve(ctx, m, p, (unsigned char *)ctx->ws);
     const int nconv = (int)p.convs.size();
-    std::vector<bf16_t *> outp(nconv);   // outp[0] = a[0]; outp[1+2j] = u[j]; outp[2+2j] = a[j+1]
-    size_t biggest = 0;
-    for (int q = 0; q < nconv; ++q) {
-        const size_t e = (size_t)nB * p.convs[q].Ho * p.convs[q].Wo * p.convs[q].Co;
-        outp[q] = (bf16_t *)take(e * 2);
-        biggest = e > biggest ? e : biggest;
-    }
-    bf16_t *dbuf[3];
-    for (int i = 0; i < 3; ++i) dbuf[i] = (bf16_t *)take(biggest * 2);
-    float *pool = (float *)take((size_t)nB * p.C_last * 4);
-    float *dpool = (float *)take((size_t)nB * p.C_last * 4);
-    float *logits = (float *)take((size_t)nB * p.classes * 4);
-    auto a_of = [&](int j) { return outp[j == 0 ? 0 : 2 * j]; };   // block input/output j
-    auto u_of = [&](int j) { return outp[1 + 2 * j]; };
+    auto a_of = [&](int j) { return ws.out[j == 0 ? 0 : 2 * j]; };   // block input/output j
+    auto u_of = [&](int j) { return ws.out[1 + 2 * j]; };
+    const ShortcutRef none{nullptr, 0, 0, 0, 1};
+    dpsgd_status st;
+
+    // bf16 operands of the convolutions in the layout the MFMA kernels read (no-op for generic convs)
+    for (int q = 0; q < nconv; ++q)
+        if ((st = conv_pack_weights(ctx, p.convs[q], X, ws.wpack_f[q], ws.wpack_d[q])) != DPSGD_OK) return st;
 
     // ---- forward
     {
@@ -339,81 +373,76 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         const i64 total = nB * c.Ho * c.Wo * c.Co;
         if (m.input_is_bf16)
             hipLaunchKernelGGL(conv_fwd_generic_kernel<1>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld, c,
-                               B, total, nullptr, 0, 0, 0, 1, outp[0]);
+                               B, total, nullptr, 0, 0, 0, 1, ws.out[0].p, ws.out[0].t);
         else
             hipLaunchKernelGGL(conv_fwd_generic_kernel<2>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld, c,
-                               B, total, nullptr, 0, 0, 0, 1, outp[0]);
+                               B, total, nullptr, 0, 0, 0, 1, ws.out[0].p, ws.out[0].t);
     }
     for (int j = 0; j < p.nblocks; ++j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
-        dpsgd_status st = conv_forward(ctx, c1, B, a_of(j), X, nullptr, 0, 0, 0, 1, u_of(j));
-        if (st != DPSGD_OK) return st;
-        st = conv_forward(ctx, c2, B, u_of(j), X, a_of(j), c1.Ci, c1.H, c1.W, c1.stride, a_of(j + 1));
-        if (st != DPSGD_OK) return st;
+        if ((st = conv_forward(ctx, c1, B, a_of(j), X, ws.wpack_f[1 + 2 * j], none, u_of(j))) != DPSGD_OK) return st;
+        const ShortcutRef sc{a_of(j).p, c1.Ci, c1.H, c1.W, c1.stride};
+        if ((st = conv_forward(ctx, c2, B, u_of(j), X, ws.wpack_f[2 + 2 * j], sc, a_of(j + 1))) != DPSGD_OK) return st;
     }
     const int HWl = p.H_last * p.W_last;
-    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, a_of(p.nblocks), X, ctx->ld, p.fcw_off, p.fcb_off, B,
-                       HWl, p.C_last, p.classes, (const int *)targets, pool, logits, dpool, G, loss);
+    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, a_of(p.nblocks).p, X, ctx->ld, p.fcw_off, p.fcb_off,
+                       B, HWl, p.C_last, p.classes, (const int *)targets, ws.pool, ws.logits, ws.dpool, G, loss);
 
     // ---- backward
-    bf16_t *dv = dbuf[0], *du = dbuf[1], *dnext = dbuf[2];
+    Tensor dv = ws.delta[0], du = ws.delta[1], dnext = ws.delta[2];
     {
         const i64 total = nB * HWl * p.C_last;
-        hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks), dpool, HWl, p.C_last,
-                           total, dv);
+        hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks).p, ws.dpool, HWl,
+                           p.C_last, total, dv.p, dv.t);
     }
     for (int j = p.nblocks - 1; j >= 0; --j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
-        // conv2: weights and bias from dv and u; du = [u > 0] * dgrad(dv)
-        dpsgd_status st = conv_weight_grad(ctx, c2, B, u_of(j), dv, G);
-        if (st != DPSGD_OK) return st;
-        st = conv_data_grad(ctx, c2, B, dv, X, nullptr, 0, 0, 0, 1, u_of(j), du);
-        if (st != DPSGD_OK) return st;
-        // conv1: weights and bias from du and a_j; next dv = [a_j > 0] * (dgrad(du) + shortcut delta)
-        st = conv_weight_grad(ctx, c1, B, a_of(j), du, G);
-        if (st != DPSGD_OK) return st;
-        st = conv_data_grad(ctx, c1, B, du, X, dv, c2.Co, c2.Ho, c2.Wo, c1.stride, a_of(j), dnext);
-        if (st != DPSGD_OK) return st;
-        bf16_t *t = dv; dv = dnext; dnext = t;
+        // conv2: weight and bias gradient from dv and u; du = [u > 0] * dgrad(dv)
+        if ((st = conv_weight_grad(ctx, c2, B, u_of(j), dv, G, ws.partials)) != DPSGD_OK) return st;
+        if ((st = conv_data_grad(ctx, c2, B, dv, X, ws.wpack_d[2 + 2 * j], none, u_of(j).p, du)) != DPSGD_OK) return st;
+        // conv1: from du and a_j; next dv = [a_j > 0] * (dgrad(du) + shortcut delta)
+        if ((st = conv_weight_grad(ctx, c1, B, a_of(j), du, G, ws.partials)) != DPSGD_OK) return st;
+        const ShortcutRef scd{dv.p, c2.Co, c2.Ho, c2.Wo, c1.stride};
+        if ((st = conv_data_grad(ctx, c1, B, du, X, ws.wpack_d[1 + 2 * j], scd, a_of(j).p, dnext)) != DPSGD_OK) return st;
+        Tensor t = dv; dv = dnext; dnext = t;
     }
     {   // stem: weight and bias gradient only
         const ConvDesc &c = p.convs[0];
         dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)n);
         if (m.input_is_bf16)
-            hipLaunchKernelGGL(conv_wgrad_generic_kernel<1>, grid, dim3(256), 0, s, inputs, dv, c, B, G, ctx->ld);
+            hipLaunchKernelGGL(conv_wgrad_generic_kernel<1>, grid, dim3(256), 0, s, inputs, dv.p, c, B, G, ctx->ld);
         else
-            hipLaunchKernelGGL(conv_wgrad_generic_kernel<2>, grid, dim3(256), 0, s, inputs, dv, c, B, G, ctx->ld);
-        hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)n), dim3(1024), 0, s, dv, (i64)B * c.Ho * c.Wo * c.Co, G,
+            hipLaunchKernelGGL(conv_wgrad_generic_kernel<2>, grid, dim3(256), 0, s, inputs, dv.p, c, B, G, ctx->ld);
+        hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)n), dim3(1024), 0, s, dv.p, (i64)B * c.Ho * c.Wo * c.Co, G,
                            ctx->ld, c.b_off);
     }
     return hip_status(hipGetLastError());
 }
 
 // ---- shape-generic building blocks (used directly, and as the fallback of the MFMA dispatch)
-dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const float *X,
-                                  const bf16_t *sc, int scC, int scH, int scW, int scS, bf16_t *out)
+dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, ShortcutRef sc,
+                                  Tensor out)
 {
     const i64 total = (i64)ctx->n * B * c.Ho * c.Wo * c.Co;
-    hipLaunchKernelGGL(conv_fwd_generic_kernel<0>, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, in, X, ctx->ld, c, B,
-                       total, sc, scC, scH, scW, scS, out);
+    hipLaunchKernelGGL(conv_fwd_generic_kernel<0>, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, in.p, X, ctx->ld, c,
+                       B, total, sc.p, sc.C, sc.H, sc.W, sc.S, out.p, out.t);
     return hip_status(hipGetLastError());
 }
 
-dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *dout, const float *X,
-                                    const bf16_t *scd, int scC, int scH, int scW, int scS, const bf16_t *act, bf16_t *din)
+dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X,
+                                    ShortcutRef scd, const bf16_t *act, Tensor din)
 {
     const i64 total = (i64)ctx->n * B * c.H * c.W * c.Ci;
-    hipLaunchKernelGGL(conv_dgrad_generic_kernel, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, dout, X, ctx->ld, c, B,
-                       total, scd, scC, scH, scW, scS, act, din);
+    hipLaunchKernelGGL(conv_dgrad_generic_kernel, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, dout.p, X, ctx->ld, c,
+                       B, total, scd.p, scd.C, scd.H, scd.W, scd.S, act, din.p, din.t);
     return hip_status(hipGetLastError());
 }
 
-dpsgd_status conv_weight_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const bf16_t *dout,
-                                      float *G)
+dpsgd_status conv_weight_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G)
 {
     dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)ctx->n);
-    hipLaunchKernelGGL(conv_wgrad_generic_kernel<0>, grid, dim3(256), 0, ctx->stream, in, dout, c, B, G, ctx->ld);
-    hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)ctx->n), dim3(1024), 0, ctx->stream, dout,
+    hipLaunchKernelGGL(conv_wgrad_generic_kernel<0>, grid, dim3(256), 0, ctx->stream, in.p, dout.p, c, B, G, ctx->ld);
+    hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)ctx->n), dim3(1024), 0, ctx->stream, dout.p,
                        (i64)B * c.Ho * c.Wo * c.Co, G, ctx->ld, c.b_off);
     return hip_status(hipGetLastError());
 }

@@ -33,22 +33,38 @@ struct ResnetPlan {
 
 ResnetPlan make_resnet_plan(const dpsgd_model_desc &m);
 
-// out = round(ReLU(conv(in) + bias + shortcut)); in/out NHWC bf16 [n][B][H][W][C].  sc (may be null):
-// the block input, added at (y*scS, x*scS) for the first scC output channels.
-dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const float *X, const bf16_t *sc,
-                          int scC, int scH, int scW, int scS, bf16_t *out);
-// din = round([act > 0] * (conv^T(dout) + shortcut delta)); scd (may be null): delta of the block output.
-dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *dout, const float *X,
-                            const bf16_t *scd, int scC, int scH, int scW, int scS, const bf16_t *act, bf16_t *din);
-// G[w_off..] = dout (*) in, G[b_off] = sum(dout).
-dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const bf16_t *dout, float *G);
+// An activation or delta tensor: NHWC bf16 [n][B][H][W][C] and its channel-major copy
+// [n][B][C][H][W] (the weight gradient contracts over pixels and wants them contiguous).
+struct Tensor {
+    bf16_t *p = nullptr;
+    bf16_t *t = nullptr;
+};
+// Forward: the block input added to the block output at (y*S, x*S) for the first C channels.
+// Backward: the delta of the block output added to the block input's delta at multiples of S.
+struct ShortcutRef {
+    const bf16_t *p;
+    int C, H, W, S;
+};
 
-dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const float *X,
-                                  const bf16_t *sc, int scC, int scH, int scW, int scS, bf16_t *out);
-dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *dout, const float *X,
-                                    const bf16_t *scd, int scC, int scH, int scW, int scS, const bf16_t *act,
-                                    bf16_t *din);
-dpsgd_status conv_weight_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, const bf16_t *in, const bf16_t *dout,
-                                      float *G);
+// out = round(ReLU(conv(in) + bias + shortcut)).  wpack: this conv's packed bf16 weights (see conv_pack_weights).
+dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, const bf16_t *wpack,
+                          ShortcutRef sc, Tensor out);
+// din = round([act > 0] * (conv^T(dout) + shortcut delta)).
+dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X, const bf16_t *wpack_d,
+                            ShortcutRef scd, const bf16_t *act, Tensor din);
+// G[w_off..] = dout (*) in, G[b_off] = sum(dout).  partials: scratch of conv_wgrad_partial_bytes(c, B) * n bytes.
+dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials);
+
+// Bytes per worker of the packed weights of one conv (forward operand, or data-gradient operand).
+size_t conv_pack_bytes(const ConvDesc &c, bool dgrad);
+size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B);
+// Rounds one conv's fp32 weights of every worker to bf16 in MFMA operand order (both operands).
+dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d);
+
+dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, ShortcutRef sc,
+                                  Tensor out);
+dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X,
+                                    ShortcutRef scd, const bf16_t *act, Tensor din);
+dpsgd_status conv_weight_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G);
 
 }  // namespace dpsgd
