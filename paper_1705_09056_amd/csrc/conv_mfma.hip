@@ -180,6 +180,183 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 
 bool pow2_channels(int c) { return c == 16 || c == 32 || c == 64; }
 
+// ----------------------------------------------------------------------- weight gradient
+// dW[co][ci][tap] = sum over pixels of dout[pixel][co] * in[pixel shifted by tap][ci]: for each tap a
+// 16x16 (co x ci) MFMA tile whose contraction runs over 32 consecutive output pixels, so both
+// operands come from the channel-major copies: A = 8 consecutive pixels of one delta channel
+// (16-byte global load), B = 8 consecutive pixels of one input channel shifted by the tap.  The
+// workgroup stages the input rows of an 8-row band in LDS as [ci][row][8 zeros | W | 8 zeros]; the
+// kx = 0 / 2 operands are the aligned 16-byte read funnel-shifted by one element with the
+// neighbouring dword.  Waves split the output-channel tiles first, then the pixels; a workgroup
+// owns a strided subset of the worker's images and writes its partial sums, which
+// wgrad_reduce_kernel adds in a fixed order.
+struct WgradMfmaArgs {
+    const bf16_t *inT;     // [n*B][CIr][H][W]
+    const bf16_t *doutT;   // [n*B][CO][Ho][Wo]
+    int H, W, Ho, Wo, B, CIr, splits;
+    float *part;           // [n][splits][CO*CIr*9 + 1]
+};
+
+template <int CI, int CO>
+__global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
+{
+    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16, RB = 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *band = reinterpret_cast<bf16_t *>(smem);   // [CI][RB + 2][WPAD]
+    const int sp = blockIdx.x, w = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int mi = wave % WM, kq = wave / WM;
+    const int n16 = lane & 15, g = lane >> 4;
+    const int WPAD = a.W + 16, ROWS = RB + 2;
+    const int psz = CO * a.CIr * 9 + 1;
+
+    f32x4 acc[NTI][9];
+#pragma unroll
+    for (int t = 0; t < NTI; ++t)
+#pragma unroll
+        for (int k = 0; k < 9; ++k) acc[t][k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float bsum = 0.f;
+
+    // zero the column pads once; staging never writes them
+    for (int u = tid; u < CI * ROWS * 2; u += 256) {
+        const int side = u & 1, row = u >> 1;
+        u32x4 z = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4 *>(band + row * WPAD + (side ? 8 + a.W : 0)) = z;
+    }
+
+    const int x8n = a.W / 8;
+    const int kb = RB * a.Wo / 32;   // k-steps per band
+    for (int b = sp; b < a.B; b += a.splits) {
+        const i64 img = (i64)w * a.B + b;
+        for (int y0 = 0; y0 < a.Ho; y0 += RB) {
+            __syncthreads();   // previous band fully consumed
+            for (int u = tid; u < CI * ROWS * x8n; u += 256) {
+                const int x8 = u % x8n, r = (u / x8n) % ROWS, ci = u / (x8n * ROWS);
+                const int iy = y0 - 1 + r;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (ci < a.CIr && iy >= 0 && iy < a.H)
+                    v = *reinterpret_cast<const u32x4 *>(a.inT + ((img * a.CIr + ci) * a.H + iy) * a.W + x8 * 8);
+                *reinterpret_cast<u32x4 *>(band + (ci * ROWS + r) * WPAD + 8 + x8 * 8) = v;
+            }
+            __syncthreads();
+            for (int ks = kq; ks < kb; ks += WK) {
+                const int q = 32 * ks + 8 * g;          // first of this lane's 8 pixels inside the band
+                const int yy = q / a.Wo, x = q % a.Wo;
+                const u32x4 av = *reinterpret_cast<const u32x4 *>(
+                    a.doutT + ((img * CO + mi * 16 + n16) * a.Ho + y0 + yy) * a.Wo + x);
+                bsum += (bf2f((bf16_t)(av.x & 0xffff)) + bf2f((bf16_t)(av.x >> 16))) +
+                        (bf2f((bf16_t)(av.y & 0xffff)) + bf2f((bf16_t)(av.y >> 16))) +
+                        (bf2f((bf16_t)(av.z & 0xffff)) + bf2f((bf16_t)(av.z >> 16))) +
+                        (bf2f((bf16_t)(av.w & 0xffff)) + bf2f((bf16_t)(av.w >> 16)));
+                const bf16x8 afrag = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+                for (int t = 0; t < NTI; ++t) {
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) {
+                        const bf16_t *row = band + ((t * 16 + n16) * ROWS + yy + ky) * WPAD + 8 + x;
+                        const u32x4 d = *reinterpret_cast<const u32x4 *>(row);
+                        const unsigned prev = *reinterpret_cast<const unsigned *>(row - 2);
+                        const unsigned next = *reinterpret_cast<const unsigned *>(row + 8);
+                        u32x4 l, r;
+                        l.x = __builtin_amdgcn_alignbit(d.x, prev, 16);
+                        l.y = __builtin_amdgcn_alignbit(d.y, d.x, 16);
+                        l.z = __builtin_amdgcn_alignbit(d.z, d.y, 16);
+                        l.w = __builtin_amdgcn_alignbit(d.w, d.z, 16);
+                        r.x = l.y;
+                        r.y = l.z;
+                        r.z = l.w;
+                        r.w = __builtin_amdgcn_alignbit(next, d.w, 16);
+                        acc[t][ky * 3 + 0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, __builtin_bit_cast(bf16x8, l),
+                                                                                     acc[t][ky * 3 + 0], 0, 0, 0);
+                        acc[t][ky * 3 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, __builtin_bit_cast(bf16x8, d),
+                                                                                     acc[t][ky * 3 + 1], 0, 0, 0);
+                        acc[t][ky * 3 + 2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, __builtin_bit_cast(bf16x8, r),
+                                                                                     acc[t][ky * 3 + 2], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // fold the pixel-split waves into wave kq == 0 (fixed order), then write this workgroup's partial
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(smem);   // [(WK-1)*WM waves][NTI*9][64 lanes][4]
+    if (WK > 1) {
+        if (kq > 0) {
+            float *dst = red + (size_t)((kq - 1) * WM + mi) * (NTI * 9 * 256);
+#pragma unroll
+            for (int t = 0; t < NTI; ++t)
+#pragma unroll
+                for (int k = 0; k < 9; ++k) *reinterpret_cast<f32x4 *>(dst + ((t * 9 + k) * 64 + lane) * 4) = acc[t][k];
+        }
+        __syncthreads();
+        if (kq == 0)
+            for (int o = 1; o < WK; ++o) {
+                const float *src = red + (size_t)((o - 1) * WM + mi) * (NTI * 9 * 256);
+#pragma unroll
+                for (int t = 0; t < NTI; ++t)
+#pragma unroll
+                    for (int k = 0; k < 9; ++k) acc[t][k] += *reinterpret_cast<const f32x4 *>(src + ((t * 9 + k) * 64 + lane) * 4);
+            }
+        __syncthreads();
+    }
+    float *out = a.part + ((i64)w * a.splits + sp) * psz;
+    if (kq == 0) {
+#pragma unroll
+        for (int t = 0; t < NTI; ++t) {
+            const int ci = t * 16 + n16;
+            if (ci < a.CIr)
+#pragma unroll
+                for (int k = 0; k < 9; ++k)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) out[((mi * 16 + 4 * g + i) * a.CIr + ci) * 9 + k] = acc[t][k][i];
+        }
+    }
+    // bias: sum of every delta element this workgroup saw
+    for (int off = 32; off > 0; off >>= 1) bsum += __shfl_down(bsum, off, 64);
+    if (lane == 0) red[wave] = bsum;
+    __syncthreads();
+    if (tid == 0) out[psz - 1] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// G[w_off + e] = sum over splits of the partials (ascending split), G[b_off] = sum of the bias partials.
+__global__ void __launch_bounds__(256)
+wgrad_reduce_kernel(const float *__restrict__ part, int splits, int psz, float *__restrict__ G, i64 ld, i64 w_off, i64 b_off)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x, w = blockIdx.y;
+    if (e >= psz) return;
+    const float *p = part + (i64)w * splits * psz + e;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += p[(i64)k * psz];
+    G[(i64)w * ld + (e == psz - 1 ? b_off : w_off + e)] = s;
+}
+
+int wgrad_splits(int B) { return B < 8 ? B : 8; }
+
+bool wgrad_mfma_ok(const ConvDesc &c)
+{
+    const int cip = (c.Ci + 15) / 16 * 16;
+    if (c.stride != 1 || !pow2_channels(c.Co) || !pow2_channels(cip)) return false;
+    if (c.Ho % 8 || c.Wo % 8 || c.W > 64) return false;
+    return true;
+}
+
+template <int CI, int CO>
+dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs &a, float *G)
+{
+    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16;
+    size_t shm = (size_t)CI * 10 * (a.W + 16) * sizeof(bf16_t);
+    const size_t red = (size_t)(WK - 1) * WM * NTI * 9 * 256 * sizeof(float);
+    if (red > shm) shm = red;
+    if (shm < 64) shm = 64;
+    hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256), shm,
+                       ctx->stream, a);
+    const int psz = CO * a.CIr * 9 + 1;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((psz + 255) / 256), (unsigned)ctx->n), dim3(256), 0, ctx->stream,
+                       a.part, a.splits, psz, G, ctx->ld, c.w_off, c.b_off);
+    return hip_status(hipGetLastError());
+}
+
 // Can the MFMA kernel produce a tensor of Hd x Wd from a source of width Ws?
 bool tile_ok(int Hd, int Wd, int stride, int ci)
 {
@@ -223,7 +400,11 @@ size_t conv_pack_bytes(const ConvDesc &c, bool dgrad)
     return (size_t)ksteps(ci) * 32 * co * sizeof(bf16_t);
 }
 
-size_t conv_wgrad_partial_bytes(const ConvDesc &, int) { return 0; }
+size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B)
+{
+    if (!wgrad_mfma_ok(c)) return 0;
+    return (size_t)wgrad_splits(B) * ((size_t)c.Co * c.Ci * 9 + 1) * sizeof(float);
+}
 
 dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d)
 {
@@ -272,8 +453,16 @@ dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dou
     return launch_conv<64, 32, 1, 2, true>(ctx, a);
 }
 
-dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *)
+dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials)
 {
+    if (!wgrad_mfma_ok(c) || !in.t || !dout.t || !partials) return conv_weight_grad_generic(ctx, c, B, in, dout, G);
+    WgradMfmaArgs a{};
+    a.inT = in.t; a.doutT = dout.t; a.H = c.H; a.W = c.W; a.Ho = c.Ho; a.Wo = c.Wo; a.B = B; a.CIr = c.Ci;
+    a.splits = wgrad_splits(B); a.part = partials;
+    const int cip = (c.Ci + 15) / 16 * 16;
+    if (cip == 16 && c.Co == 16) return launch_wgrad<16, 16>(ctx, c, a, G);
+    if (cip == 32 && c.Co == 32) return launch_wgrad<32, 32>(ctx, c, a, G);
+    if (cip == 64 && c.Co == 64) return launch_wgrad<64, 64>(ctx, c, a, G);
     return conv_weight_grad_generic(ctx, c, B, in, dout, G);
 }
 
