@@ -197,7 +197,7 @@ struct WgradMfmaArgs {
     float *part;           // [n][splits][CO*CIr*9 + 1]
 };
 
-template <int CI, int CO>
+template <int CI, int CO, int STRIDE>
 __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
 {
     constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16, RB = 8;
@@ -207,7 +207,10 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int mi = wave % WM, kq = wave / WM;
     const int n16 = lane & 15, g = lane >> 4;
-    const int WPAD = a.W + 16, ROWS = RB + 2;
+    // stride 1: one plane per (channel, row), [8 zeros | W | 8 zeros].  stride 2: two planes, the even
+    // and the odd input columns (an output pixel x reads columns 2x-1, 2x, 2x+1 = odd[x-1], even[x], odd[x]).
+    constexpr int PLANES = STRIDE;
+    const int WPAD = a.Wo + 16, ROWS = (RB - 1) * STRIDE + 3;
     const int psz = CO * a.CIr * 9 + 1;
 
     f32x4 acc[NTI][9];
@@ -218,10 +221,10 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
     float bsum = 0.f;
 
     // zero the column pads once; staging never writes them
-    for (int u = tid; u < CI * ROWS * 2; u += 256) {
+    for (int u = tid; u < CI * ROWS * PLANES * 2; u += 256) {
         const int side = u & 1, row = u >> 1;
         u32x4 z = {0u, 0u, 0u, 0u};
-        *reinterpret_cast<u32x4 *>(band + row * WPAD + (side ? 8 + a.W : 0)) = z;
+        *reinterpret_cast<u32x4 *>(band + row * WPAD + (side ? 8 + a.Wo : 0)) = z;
     }
 
     const int x8n = a.W / 8;
@@ -232,11 +235,19 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
             __syncthreads();   // previous band fully consumed
             for (int u = tid; u < CI * ROWS * x8n; u += 256) {
                 const int x8 = u % x8n, r = (u / x8n) % ROWS, ci = u / (x8n * ROWS);
-                const int iy = y0 - 1 + r;
+                const int iy = y0 * STRIDE - 1 + r;
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (ci < a.CIr && iy >= 0 && iy < a.H)
                     v = *reinterpret_cast<const u32x4 *>(a.inT + ((img * a.CIr + ci) * a.H + iy) * a.W + x8 * 8);
-                *reinterpret_cast<u32x4 *>(band + (ci * ROWS + r) * WPAD + 8 + x8 * 8) = v;
+                if (STRIDE == 1) {
+                    *reinterpret_cast<u32x4 *>(band + (ci * ROWS + r) * WPAD + 8 + x8 * 8) = v;
+                } else {
+                    const u32x2 ev = {(v.x & 0xffffu) | (v.y << 16), (v.z & 0xffffu) | (v.w << 16)};
+                    const u32x2 od = {(v.x >> 16) | (v.y & 0xffff0000u), (v.z >> 16) | (v.w & 0xffff0000u)};
+                    bf16_t *base = band + ((ci * ROWS + r) * 2) * WPAD + 8 + x8 * 4;
+                    *reinterpret_cast<u32x2 *>(base) = ev;
+                    *reinterpret_cast<u32x2 *>(base + WPAD) = od;
+                }
             }
             __syncthreads();
             for (int ks = kq; ks < kb; ks += WK) {
@@ -253,19 +264,31 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
                 for (int t = 0; t < NTI; ++t) {
 #pragma unroll
                     for (int ky = 0; ky < 3; ++ky) {
-                        const bf16_t *row = band + ((t * 16 + n16) * ROWS + yy + ky) * WPAD + 8 + x;
-                        const u32x4 d = *reinterpret_cast<const u32x4 *>(row);
-                        const unsigned prev = *reinterpret_cast<const unsigned *>(row - 2);
-                        const unsigned next = *reinterpret_cast<const unsigned *>(row + 8);
-                        u32x4 l, r;
-                        l.x = __builtin_amdgcn_alignbit(d.x, prev, 16);
-                        l.y = __builtin_amdgcn_alignbit(d.y, d.x, 16);
-                        l.z = __builtin_amdgcn_alignbit(d.z, d.y, 16);
-                        l.w = __builtin_amdgcn_alignbit(d.w, d.z, 16);
-                        r.x = l.y;
-                        r.y = l.z;
-                        r.z = l.w;
-                        r.w = __builtin_amdgcn_alignbit(next, d.w, 16);
+                        u32x4 l, d, r;   // the operand for kx = 0, 1, 2
+                        if (STRIDE == 1) {
+                            const bf16_t *row = band + ((t * 16 + n16) * ROWS + yy + ky) * WPAD + 8 + x;
+                            d = *reinterpret_cast<const u32x4 *>(row);
+                            const unsigned prev = *reinterpret_cast<const unsigned *>(row - 2);
+                            const unsigned next = *reinterpret_cast<const unsigned *>(row + 8);
+                            l.x = __builtin_amdgcn_alignbit(d.x, prev, 16);
+                            l.y = __builtin_amdgcn_alignbit(d.y, d.x, 16);
+                            l.z = __builtin_amdgcn_alignbit(d.z, d.y, 16);
+                            l.w = __builtin_amdgcn_alignbit(d.w, d.z, 16);
+                            r.x = l.y;
+                            r.y = l.z;
+                            r.z = l.w;
+                            r.w = __builtin_amdgcn_alignbit(next, d.w, 16);
+                        } else {
+                            const bf16_t *even = band + (((t * 16 + n16) * ROWS + 2 * yy + ky) * 2) * WPAD + 8 + x;
+                            const bf16_t *odd = even + WPAD;
+                            d = *reinterpret_cast<const u32x4 *>(even);
+                            r = *reinterpret_cast<const u32x4 *>(odd);
+                            const unsigned prev = *reinterpret_cast<const unsigned *>(odd - 2);
+                            l.x = __builtin_amdgcn_alignbit(r.x, prev, 16);
+                            l.y = __builtin_amdgcn_alignbit(r.y, r.x, 16);
+                            l.z = __builtin_amdgcn_alignbit(r.z, r.y, 16);
+                            l.w = __builtin_amdgcn_alignbit(r.w, r.z, 16);
+                        }
                         acc[t][ky * 3 + 0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, __builtin_bit_cast(bf16x8, l),
                                                                                      acc[t][ky * 3 + 0], 0, 0, 0);
                         acc[t][ky * 3 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, __builtin_bit_cast(bf16x8, d),
@@ -336,20 +359,21 @@ int wgrad_splits(int B) { return B < 8 ? B : 8; }
 bool wgrad_mfma_ok(const ConvDesc &c)
 {
     const int cip = (c.Ci + 15) / 16 * 16;
-    if (c.stride != 1 || !pow2_channels(c.Co) || !pow2_channels(cip)) return false;
-    if (c.Ho % 8 || c.Wo % 8 || c.W > 64) return false;
-    return true;
+    if (!pow2_channels(c.Co) || !pow2_channels(cip)) return false;
+    if (c.Ho % 8 || c.Wo % 8 || c.W % 8 || c.W > 64) return false;
+    if (c.stride == 1) return cip == c.Co;
+    return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && c.W == 2 * c.Wo && c.H == 2 * c.Ho;
 }
 
-template <int CI, int CO>
+template <int CI, int CO, int STRIDE>
 dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs &a, float *G)
 {
     constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16;
-    size_t shm = (size_t)CI * 10 * (a.W + 16) * sizeof(bf16_t);
+    size_t shm = (size_t)CI * (7 * STRIDE + 3) * STRIDE * (a.Wo + 16) * sizeof(bf16_t);
     const size_t red = (size_t)(WK - 1) * WM * NTI * 9 * 256 * sizeof(float);
     if (red > shm) shm = red;
     if (shm < 64) shm = 64;
-    hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256), shm,
+    hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256), shm,
                        ctx->stream, a);
     const int psz = CO * a.CIr * 9 + 1;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((psz + 255) / 256), (unsigned)ctx->n), dim3(256), 0, ctx->stream,
@@ -365,8 +389,12 @@ bool tile_ok(int Hd, int Wd, int stride, int ci)
     return pr * pc * (ci + 8) * 2 <= 64 * 1024;
 }
 
+// The stem (at most 8 input channels) runs on an image padded to 8 channels (NHWC8).
+bool stem_like(const ConvDesc &c) { return c.Ci <= 8 && c.Co == 16 && c.stride == 1; }
+
 bool fwd_mfma_ok(const ConvDesc &c)
 {
+    if (stem_like(c)) return tile_ok(c.Ho, c.Wo, 1, 8);
     if (!pow2_channels(c.Ci) || !pow2_channels(c.Co)) return false;
     if (c.stride == 1) return c.Ci == c.Co && tile_ok(c.Ho, c.Wo, 1, c.Ci);
     return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && tile_ok(c.Ho, c.Wo, 2, c.Ci);
@@ -374,6 +402,7 @@ bool fwd_mfma_ok(const ConvDesc &c)
 
 bool dgrad_mfma_ok(const ConvDesc &c)
 {
+    if (stem_like(c)) return false;
     if (!pow2_channels(c.Ci) || !pow2_channels(c.Co)) return false;
     if (c.stride == 1) return c.Ci == c.Co && tile_ok(c.H, c.W, 1, c.Co);
     return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && c.H == 2 * c.Ho && c.W == 2 * c.Wo &&
@@ -392,11 +421,55 @@ dpsgd_status launch_conv(dpsgd_ctx *ctx, const ConvMfmaArgs &a)
 
 }  // namespace
 
+namespace {
+// image [n*B][C][H][W] (fp32 or bf16) -> bf16 channel-major copy (fp32 input only) and NHWC8 copy
+template <bool IN_BF16>
+__global__ void __launch_bounds__(256)
+prep_image_kernel(const void *__restrict__ in, int C, int HW, i64 total, bf16_t *__restrict__ chw, bf16_t *__restrict__ nhwc8)
+{
+    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;   // over [img][pixel]
+    if (idx >= total) return;
+    const i64 img = idx / HW;
+    const int px = (int)(idx % HW);
+    bf16_t v[8];
+#pragma unroll
+    for (int ch = 0; ch < 8; ++ch) {
+        v[ch] = 0;
+        if (ch < C) {
+            const i64 src = (img * C + ch) * HW + px;
+            v[ch] = IN_BF16 ? ((const bf16_t *)in)[src] : f2bf(((const float *)in)[src]);
+            if (!IN_BF16 && chw) chw[src] = v[ch];
+        }
+    }
+    if (nhwc8) {
+        u32x4 pk = {(unsigned)v[0] | ((unsigned)v[1] << 16), (unsigned)v[2] | ((unsigned)v[3] << 16),
+                    (unsigned)v[4] | ((unsigned)v[5] << 16), (unsigned)v[6] | ((unsigned)v[7] << 16)};
+        *reinterpret_cast<u32x4 *>(nhwc8 + idx * 8) = pk;
+    }
+}
+}  // namespace
+
+bool conv_stem_uses_mfma(const ConvDesc &c) { return stem_like(c) && fwd_mfma_ok(c) && wgrad_mfma_ok(c); }
+
+dpsgd_status conv_prep_image(dpsgd_ctx *ctx, const ConvDesc &c, int B, const void *image, bool image_is_bf16,
+                             bf16_t *chw_bf16, bf16_t *nhwc8)
+{
+    const i64 total = (i64)ctx->n * B * c.H * c.W;
+    if (c.Ci > 8 && nhwc8) return DPSGD_EUNSUPPORTED;
+    if (image_is_bf16)
+        hipLaunchKernelGGL(prep_image_kernel<true>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, ctx->stream, image,
+                           c.Ci, c.H * c.W, total, chw_bf16, nhwc8);
+    else
+        hipLaunchKernelGGL(prep_image_kernel<false>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, ctx->stream, image,
+                           c.Ci, c.H * c.W, total, chw_bf16, nhwc8);
+    return hip_status(hipGetLastError());
+}
+
 size_t conv_pack_bytes(const ConvDesc &c, bool dgrad)
 {
     const bool ok = dgrad ? dgrad_mfma_ok(c) : fwd_mfma_ok(c);
     if (!ok) return 0;
-    const int ci = dgrad ? c.Co : c.Ci, co = dgrad ? c.Ci : c.Co;
+    const int ci = dgrad ? c.Co : (stem_like(c) ? 8 : c.Ci), co = dgrad ? c.Ci : c.Co;
     return (size_t)ksteps(ci) * 32 * co * sizeof(bf16_t);
 }
 
@@ -409,11 +482,12 @@ size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B)
 dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d)
 {
     if (fwd_mfma_ok(c)) {
-        const int KS = ksteps(c.Ci), per = KS * 32 * c.Co;
+        const int cic = stem_like(c) ? 8 : c.Ci;
+        const int KS = ksteps(cic), per = KS * 32 * c.Co;
         hipLaunchKernelGGL(pack_weights_kernel<false>, dim3((unsigned)((per + 255) / 256), (unsigned)ctx->n), dim3(256), 0,
-                           ctx->stream, X, ctx->ld, c, c.Ci, c.Co, KS, wpack_f);
+                           ctx->stream, X, ctx->ld, c, cic, c.Co, KS, wpack_f);
     }
-    if (dgrad_mfma_ok(c)) {
+    if (!stem_like(c) && dgrad_mfma_ok(c)) {
         const int KS = ksteps(c.Co), per = KS * 32 * c.Ci;
         hipLaunchKernelGGL(pack_weights_kernel<true>, dim3((unsigned)((per + 255) / 256), (unsigned)ctx->n), dim3(256), 0,
                            ctx->stream, X, ctx->ld, c, c.Co, c.Ci, KS, wpack_d);
@@ -428,6 +502,7 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
     ConvMfmaArgs a{};
     a.src = in.p; a.Hs = c.H; a.Ws = c.W; a.wpack = wpack; a.dst = out.p; a.dstT = out.t; a.Hd = c.Ho; a.Wd = c.Wo;
     a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = c.b_off; a.sc = sc; a.act = nullptr;
+    if (stem_like(c)) return launch_conv<8, 16, 1, 1, false>(ctx, a);   // `in` is the image padded to 8 channels
     if (c.stride == 1) {
         if (c.Ci == 16) return launch_conv<16, 16, 1, 1, false>(ctx, a);
         if (c.Ci == 32) return launch_conv<32, 32, 1, 1, false>(ctx, a);
@@ -455,15 +530,21 @@ dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dou
 
 dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials)
 {
-    if (!wgrad_mfma_ok(c) || !in.t || !dout.t || !partials) return conv_weight_grad_generic(ctx, c, B, in, dout, G);
+    if (!wgrad_mfma_ok(c) || !in.t || !dout.t || !partials) {
+        if (!in.p || !dout.p) return DPSGD_EUNSUPPORTED;
+        return conv_weight_grad_generic(ctx, c, B, in, dout, G);
+    }
     WgradMfmaArgs a{};
     a.inT = in.t; a.doutT = dout.t; a.H = c.H; a.W = c.W; a.Ho = c.Ho; a.Wo = c.Wo; a.B = B; a.CIr = c.Ci;
     a.splits = wgrad_splits(B); a.part = partials;
     const int cip = (c.Ci + 15) / 16 * 16;
-    if (cip == 16 && c.Co == 16) return launch_wgrad<16, 16>(ctx, c, a, G);
-    if (cip == 32 && c.Co == 32) return launch_wgrad<32, 32>(ctx, c, a, G);
-    if (cip == 64 && c.Co == 64) return launch_wgrad<64, 64>(ctx, c, a, G);
-    return conv_weight_grad_generic(ctx, c, B, in, dout, G);
+    if (c.stride == 1) {
+        if (cip == 16) return launch_wgrad<16, 16, 1>(ctx, c, a, G);
+        if (cip == 32) return launch_wgrad<32, 32, 1>(ctx, c, a, G);
+        return launch_wgrad<64, 64, 1>(ctx, c, a, G);
+    }
+    if (cip == 16) return launch_wgrad<16, 32, 2>(ctx, c, a, G);
+    return launch_wgrad<32, 64, 2>(ctx, c, a, G);
 }
 
 }  // namespace dpsgd

@@ -299,6 +299,7 @@ struct Workspace {
     Tensor delta[3];                      // rotating delta buffers
     std::vector<bf16_t *> wpack_f, wpack_d;
     bf16_t *image_bf16 = nullptr;         // bf16 copy of an fp32 image (channel-major, as given)
+    bf16_t *image_nhwc8 = nullptr;        // image padded to 8 channels, pixel-major (MFMA stem only)
     float *pool = nullptr, *dpool = nullptr, *logits = nullptr, *partials = nullptr;
     size_t bytes = 0;
 };
@@ -331,6 +332,7 @@ Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPla
         w.delta[i].t = (bf16_t *)take(biggest * 2);
     }
     if (!m.input_is_bf16) w.image_bf16 = (bf16_t *)take(nB * p.convs[0].Ci * p.convs[0].H * p.convs[0].W * 2);
+    if (conv_stem_uses_mfma(p.convs[0])) w.image_nhwc8 = (bf16_t *)take(nB * p.convs[0].H * p.convs[0].W * 8 * 2);
     w.pool = (float *)take(nB * p.C_last * 4);
     w.dpool = (float *)take(nB * p.C_last * 4);
     w.logits = (float *)take(nB * p.classes * 4);
@@ -368,7 +370,16 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         if ((st = conv_pack_weights(ctx, p.convs[q], X, ws.wpack_f[q], ws.wpack_d[q])) != DPSGD_OK) return st;
 
     // ---- forward
-    {
+    const bool stem_mfma = conv_stem_uses_mfma(p.convs[0]);
+    // the image as bf16, channel-major (what the stem's weight gradient contracts over)
+    const bf16_t *image_chw = m.input_is_bf16 ? (const bf16_t *)inputs : ws.image_bf16;
+    if (stem_mfma) {
+        const ConvDesc &c = p.convs[0];
+        if ((st = conv_prep_image(ctx, c, B, inputs, m.input_is_bf16, ws.image_bf16, ws.image_nhwc8)) != DPSGD_OK) return st;
+        Tensor img8;
+        img8.p = ws.image_nhwc8;
+        if ((st = conv_forward(ctx, c, B, img8, X, ws.wpack_f[0], none, ws.out[0])) != DPSGD_OK) return st;
+    } else {
         const ConvDesc &c = p.convs[0];
         const i64 total = nB * c.Ho * c.Wo * c.Co;
         if (m.input_is_bf16)
@@ -406,7 +417,11 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         if ((st = conv_data_grad(ctx, c1, B, du, X, ws.wpack_d[1 + 2 * j], scd, a_of(j).p, dnext)) != DPSGD_OK) return st;
         Tensor t = dv; dv = dnext; dnext = t;
     }
-    {   // stem: weight and bias gradient only
+    if (stem_mfma) {   // stem: weight and bias gradient only
+        Tensor img;
+        img.t = const_cast<bf16_t *>(image_chw);
+        if ((st = conv_weight_grad(ctx, p.convs[0], B, img, dv, G, ws.partials)) != DPSGD_OK) return st;
+    } else {
         const ConvDesc &c = p.convs[0];
         dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)n);
         if (m.input_is_bf16)

@@ -61,6 +61,12 @@ size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B);
 // Rounds one conv's fp32 weights of every worker to bf16 in MFMA operand order (both operands).
 dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d);
 
+// Stem support: whether the first conv runs on MFMA, and the image copies it then needs: a bf16
+// channel-major copy (only made from fp32 images; may be null) and the image padded to 8 channels (NHWC8).
+bool conv_stem_uses_mfma(const ConvDesc &c);
+dpsgd_status conv_prep_image(dpsgd_ctx *ctx, const ConvDesc &c, int B, const void *image, bool image_is_bf16,
+                             bf16_t *chw_bf16, bf16_t *nhwc8);
+
 dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, ShortcutRef sc,
                                   Tensor out);
 dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X,

@@ -90,6 +90,12 @@ def test_resnet_fp32_inputs_and_odd_stride():
     grad_case(cfg, d + 3, bf16_inputs=False)
 
 
+def test_resnet_fp32_inputs_on_the_mfma_path():
+    cfg = shrink(CONFIGS[4], widths=(3, 16, 16, 16, 1, 10), batch=9, n=2)
+    d = synth.model_dim(MODEL_RESNET20, cfg.widths)
+    grad_case(cfg, synth.padded_stride(d), bf16_inputs=False)
+
+
 def test_resnet_config4_shape_two_workers():
     cfg = shrink(CONFIGS[4], n=3)
     d = synth.model_dim(MODEL_RESNET20, cfg.widths)
