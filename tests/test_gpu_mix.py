@@ -159,3 +159,46 @@ def test_multi_step_invariants_on_device():
     assert rel_err(got.mean(0), mean0) < 1e-5
     lam2 = (1 + 2 * np.cos(2 * np.pi / n)) / 3
     assert prev <= oracle.consensus(X) * lam2 ** (2 * 20) * (1 + 1e-3)
+
+
+def _full_size_mix(n, d, topo_b, topo_o, gamma=0.1):
+    """The launch shape bench.py times (in place, consensus on); the oracle checks sampled columns, and the
+    consensus distance chunk by chunk."""
+    ld = (d + 63) // 64 * 64
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(170509056)
+    base = torch.randn(ld, device="cuda", generator=gen)
+    Xd = base + 0.05 * torch.randn(n, ld, device="cuda", generator=gen)
+    Gd = torch.randn(n, ld, device="cuda", generator=gen)
+    rng = np.random.default_rng(3)
+    cols = np.unique(np.concatenate([rng.integers(0, d, 4000), np.arange(0, 300), np.arange(d - 300, d)]))
+    cols_d = torch.from_numpy(cols).cuda()
+    Xs = Xd[:, cols_d].cpu().numpy()
+    Gs = Gd[:, cols_d].cpu().numpy()
+    ref = oracle.mix_step(topo_o, Xs, Gs, np.float32(gamma))
+    cons = torch.zeros(1, device="cuda")
+    print(f"full-size mix n={n} d={d}", flush=True)
+    with B.Dpsgd(n, d, topo_b, gamma, ld=ld) as ctx:
+        ctx.mix_step(Xd, Gd, Xd, cons)
+        torch.cuda.synchronize()
+    got = Xd[:, cols_d].cpu().numpy()
+    assert rel_err(got, ref) < TOL
+    # consensus of the whole output, accumulated by the oracle over column chunks
+    total = 0.0
+    step = 2_000_000
+    for c0 in range(0, d, step):
+        chunk = Xd[:, c0:min(d, c0 + step)].cpu().numpy()
+        total += oracle.consensus(chunk)
+    assert float(cons.item()) == pytest.approx(total, rel=1e-5)
+
+
+def test_full_size_config3_ring():
+    _full_size_mix(64, 29409290, B.Topology.ring(), oracle.ring(64).with_fp32_values())
+
+
+def test_full_size_config3_torus():
+    _full_size_mix(64, 29409290, B.Topology.torus(8, 8), oracle.torus(8, 8).with_fp32_values())
+
+
+def test_full_size_config4_ring():
+    _full_size_mix(112, 268365, B.Topology.ring(), oracle.ring(112).with_fp32_values())
