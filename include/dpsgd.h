@@ -162,6 +162,18 @@ dpsgd_status dpsgd_mix_step(dpsgd_ctx *ctx, const float *X_in, const float *G, f
 dpsgd_status dpsgd_mix_step_swapped(dpsgd_ctx *ctx, const float *X_in, const float *G, float *X_out,
                                     float *consensus);
 
+/* One whole iteration of Algorithm 1 in place: X <- W X - gamma * grad(X), i.e. the result of dpsgd_grad(X -> G)
+ * followed by dpsgd_mix_step(X, G -> X), up to the order of floating-point sums.  Footnote [b] observes that steps 3
+ * and 4 are independent; here they share one pass over X wherever a kernel exists for it: for bf16 MLPs on the ring
+ * the weight gradient of every large layer is formed inside the mix kernel and never written to memory.  All other
+ * cases run the two calls back to back.
+ *   X          device, n x d (stride ld), overwritten by the next iterate
+ *   G_scratch  device, n x d (stride ld), must not overlap X; on return it holds the gradient only of those
+ *              parameters whose update was not fused (contents otherwise unspecified)
+ *   loss, consensus  as in dpsgd_grad and dpsgd_mix_step; either may be NULL */
+dpsgd_status dpsgd_step(dpsgd_ctx *ctx, const dpsgd_model *model, float *X, const dpsgd_batch *batch, float *G_scratch,
+                        float *loss, float *consensus);
+
 /* Algorithm 1 step 7: xbar = (1/n) sum_i X[i].  X device n x d (stride ld); xbar device, d floats. */
 dpsgd_status dpsgd_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
 

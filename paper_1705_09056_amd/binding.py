@@ -21,7 +21,7 @@ MODEL_LSQ, MODEL_SOFTMAX, MODEL_MLP, MODEL_RESNET20 = range(4)
 
 EXPORTS = (
     "dpsgd_topology_build", "dpsgd_model_dim", "dpsgd_create", "dpsgd_destroy", "dpsgd_set_gamma",
-    "dpsgd_set_option", "dpsgd_topology_export", "dpsgd_grad", "dpsgd_mix_step", "dpsgd_mix_step_swapped",
+    "dpsgd_set_option", "dpsgd_topology_export", "dpsgd_grad", "dpsgd_step", "dpsgd_mix_step", "dpsgd_mix_step_swapped",
     "dpsgd_mean", "dpsgd_strerror",
 )
 
@@ -74,6 +74,8 @@ def load():
     L.dpsgd_topology_export.argtypes = [vp, i32p, i32p, f32p, i64p]
     L.dpsgd_grad.restype = C.c_int
     L.dpsgd_grad.argtypes = [vp, C.POINTER(_Model), vp, C.POINTER(_Batch), vp, vp]
+    L.dpsgd_step.restype = C.c_int
+    L.dpsgd_step.argtypes = [vp, C.POINTER(_Model), vp, C.POINTER(_Batch), vp, vp, vp]
     for name in ("dpsgd_mix_step", "dpsgd_mix_step_swapped"):
         getattr(L, name).restype = C.c_int
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp]
@@ -224,7 +226,16 @@ class Dpsgd:
         if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (self.n, self.ld):
             raise ValueError(f"{name} must be a contiguous float32 CUDA tensor of shape ({self.n}, {self.ld})")
 
+    def step(self, model: Model, X, inputs, targets, batch: int, G, loss=None, consensus=None,
+             input_is_bf16: bool = False):
+        """One whole iteration in place (dpsgd_step)."""
+        self._grad_like(self._L.dpsgd_step, "dpsgd_step", model, X, inputs, targets, batch, G, loss, input_is_bf16,
+                        extra=(_ptr(consensus),))
+
     def grad(self, model: Model, X, inputs, targets, batch: int, G, loss=None, input_is_bf16: bool = False):
+        self._grad_like(self._L.dpsgd_grad, "dpsgd_grad", model, X, inputs, targets, batch, G, loss, input_is_bf16)
+
+    def _grad_like(self, fn, name, model, X, inputs, targets, batch, G, loss, input_is_bf16, extra=()):
         self._check_mat(X, "X")
         self._check_mat(G, "G")
         import torch
@@ -239,7 +250,7 @@ class Dpsgd:
             raise ValueError("loss must hold n float32 values")
         m = model._c()
         b = _Batch(C.c_void_p(inputs.data_ptr()), C.c_void_p(targets.data_ptr()), int(batch), 1 if input_is_bf16 else 0)
-        _check(self._L.dpsgd_grad(self._handle, C.byref(m), _ptr(X), C.byref(b), _ptr(G), _ptr(loss)), "dpsgd_grad")
+        _check(fn(self._handle, C.byref(m), _ptr(X), C.byref(b), _ptr(G), _ptr(loss), *extra), name)
 
     def mix_step(self, X_in, G, X_out, consensus=None, swapped: bool = False):
         self._check_mat(X_in, "X_in")

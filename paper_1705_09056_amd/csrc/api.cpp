@@ -337,8 +337,23 @@ dpsgd_status dpsgd_mean(dpsgd_ctx *ctx, const float *X, float *xbar)
     return dpsgd::launch_mean(ctx, X, xbar);
 }
 
+static dpsgd_status grad_or_step(dpsgd_ctx *ctx, const dpsgd_model *model, const float *X, const dpsgd_batch *batch,
+                                 float *G, float *loss, bool step, float *consensus);
+
 dpsgd_status dpsgd_grad(dpsgd_ctx *ctx, const dpsgd_model *model, const float *X, const dpsgd_batch *batch, float *G,
                         float *loss)
+{
+    return grad_or_step(ctx, model, X, batch, G, loss, false, nullptr);
+}
+
+dpsgd_status dpsgd_step(dpsgd_ctx *ctx, const dpsgd_model *model, float *X, const dpsgd_batch *batch, float *G_scratch,
+                        float *loss, float *consensus)
+{
+    return grad_or_step(ctx, model, X, batch, G_scratch, loss, true, consensus);
+}
+
+static dpsgd_status grad_or_step(dpsgd_ctx *ctx, const dpsgd_model *model, const float *X, const dpsgd_batch *batch,
+                                 float *G, float *loss, bool step, float *consensus)
 {
     if (!ctx || !model || !X || !batch || !G) return DPSGD_EINVAL;
     if (!batch->inputs || !batch->targets || batch->batch < 1 || batch->batch > (1 << 20)) return DPSGD_EINVAL;
@@ -366,6 +381,7 @@ dpsgd_status dpsgd_grad(dpsgd_ctx *ctx, const dpsgd_model *model, const float *X
         }
         ctx->ws_model = m;
     }
+    if (step) return dpsgd::launch_step(ctx, m, const_cast<float *>(X), batch->inputs, batch->targets, G, loss, consensus);
     return dpsgd::launch_grad(ctx, m, X, batch->inputs, batch->targets, G, loss);
 }
 

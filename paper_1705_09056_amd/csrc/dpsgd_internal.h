@@ -56,11 +56,17 @@ dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float 
                         bool swapped);
 dpsgd_status launch_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
 int64_t mix_partials_needed(const dpsgd_ctx *ctx);
+dpsgd_status launch_mix_ring_range(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, int64_t col0,
+                                   int64_t ncols, bool cons, int64_t *nparts);
+dpsgd_status launch_consensus_finalize(dpsgd_ctx *ctx, int64_t count, float *consensus);
 
 // ---- grad_*.hip : each returns the workspace it needs and runs on ctx->stream
 size_t grad_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m);
 dpsgd_status launch_grad(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
                          const void *targets, float *G, float *loss);
+// One whole iteration in place (X <- W X - gamma grad(X)); G is scratch.  Fuses what it can.
+dpsgd_status launch_step(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs, const void *targets,
+                         float *G, float *loss, float *consensus);
 
 inline dpsgd_status hip_status(hipError_t e) { return e == hipSuccess ? DPSGD_OK : DPSGD_EDEVICE; }
 

@@ -20,4 +20,15 @@ dpsgd_status launch_grad(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float 
     return launch_grad_f32(ctx, m, X, inputs, targets, G, loss);
 }
 
+dpsgd_status launch_step(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs, const void *targets,
+                         float *G, float *loss, float *consensus)
+{
+    if (is_dense(m) && m.compute_bf16 && ctx->ring_uniform && !ctx->opt_mix_force_csr)
+        return launch_step_mlp_bf16(ctx, m, X, inputs, targets, G, loss, consensus);
+    // everything else: the two calls of the boundary, back to back, in place
+    dpsgd_status st = launch_grad(ctx, m, X, inputs, targets, G, loss);
+    if (st != DPSGD_OK) return st;
+    return launch_mix(ctx, X, G, X, consensus, false);
+}
+
 }  // namespace dpsgd

@@ -18,6 +18,11 @@ size_t mlp_bf16_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m)
 dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
                                   const void *targets, float *G, float *loss);
 
+// One whole iteration in place for bf16 MLPs on a ring: weight gradients of the large layers are formed inside
+// the mix kernel and never written to G.
+dpsgd_status launch_step_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs,
+                                  const void *targets, float *G, float *loss, float *consensus);
+
 size_t resnet_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m);
 dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
                                 const void *targets, float *G, float *loss);

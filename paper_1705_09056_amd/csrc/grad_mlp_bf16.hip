@@ -501,61 +501,165 @@ dpsgd_status dgrad_launch(hipStream_t s, int n, const DgradArgs &a, bool vec)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-}  // namespace
-
-size_t mlp_bf16_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m)
+// gb[o] = sum_b dZ[b][o] from the transposed copy (used when the weight gradient itself is fused away)
+__global__ void __launch_bounds__(256)
+bias_grad_bf16_kernel(const bf16_t *__restrict__ dzt, int O, int Bp, float *__restrict__ G, i64 ld, i64 boff)
 {
-    const size_t n = (size_t)ctx->n, B = (size_t)m.batch, Bp = (size_t)round_up(m.batch, 32);
-    const size_t L = m.widths.size() - 1;
-    size_t bytes = 0;
-    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
-    if (!m.input_is_bf16) bytes += pad(n * B * (size_t)m.widths[0] * 2);
-    bytes += pad(n * (size_t)m.widths[0] * Bp * 2);
-    for (size_t l = 1; l < L; ++l) {
-        bytes += pad(n * B * (size_t)m.widths[l] * 2);      // h
-        bytes += pad(n * (size_t)m.widths[l] * Bp * 2);     // ht
-    }
-    bytes += pad(n * B * (size_t)m.widths[L] * 4);          // logits
-    size_t widest = 0;
-    for (size_t l = 1; l <= L; ++l) widest = widest > (size_t)m.widths[l] ? widest : (size_t)m.widths[l];
-    bytes += 2 * (pad(n * B * widest * 2) + pad(n * widest * Bp * 2));   // dz / dzt, ping-pong
-    return bytes + 256;
+    const int o = blockIdx.x * 256 + threadIdx.x, w = blockIdx.y;
+    if (o >= O) return;
+    const bf16_t *p = dzt + ((i64)w * O + o) * Bp;
+    float s = 0.f;
+    for (int b = 0; b < Bp; ++b) s += bf2f(p[b]);
+    G[(i64)w * ld + boff + o] = s;
 }
 
-dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
-                                  const void *targets, float *G, float *loss)
+// ------------------------------------------------- weight gradient fused into mix + step (ring)
+// X[i][tile] <- w (X[i-1] + X[i] + X[i+1])[tile] - gamma * (dZ_i^T A_i)[tile] for one weight matrix,
+// in place, without the gradient ever reaching HBM (Algorithm 1 steps 3-5 in one pass; footnote [b]:
+// steps 3 and 4 are independent).  A wave owns a 32 x 32 tile of the matrix for ALL workers and
+// walks the ring keeping x_{i-1}, x_i, x_{i+1} in registers in the MFMA accumulator layout; the
+// worker's gradient tile comes from two bf16 MFMAs per 16 minibatch rows on L2-resident operands.
+struct FusedArgs {
+    float *X;
+    i64 ld, woff;
+    const bf16_t *dzt;   // [n][O][Bp]
+    const bf16_t *at;    // [n][K][Bp]
+    int n, K, O, Bp;
+    float w, gamma;
+    double *partials;    // one per wave (CONS only)
+};
+
+template <bool CONS>
+__global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int k0 = blockIdx.x * 128 + wave * 32, o0 = blockIdx.y * 32;
+    const int steps = a.Bp / 16;
+    // element v of this lane: row o0 + (v/4)*8 + half*4 + v%4, column k0 + l32
+    float *xt = a.X + a.woff + (i64)(o0 + half * 4) * a.K + k0 + l32;
+    auto row_off = [&](int v) { return (i64)((v >> 2) * 8 + (v & 3)) * a.K; };
+    const bf16_t *ap = a.dzt + (i64)(o0 + l32) * a.Bp + 8 * half;
+    const bf16_t *bp = a.at + (i64)(k0 + l32) * a.Bp + 8 * half;
+
+    float xm[16], xc[16], xh[16], s1[16], s2[16], sh[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        xm[v] = xt[(i64)(a.n - 1) * a.ld + row_off(v)];
+        xc[v] = xt[row_off(v)];
+        xh[v] = xc[v];
+        s1[v] = 0.f;
+        s2[v] = 0.f;
+        sh[v] = 0.f;
+    }
+    for (int i = 0; i < a.n; ++i) {
+        float xn[16];
+        if (i + 1 < a.n) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) xn[v] = xt[(i64)(i + 1) * a.ld + row_off(v)];
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) xn[v] = xh[v];
+        }
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        const bf16_t *ai = ap + (i64)i * a.O * a.Bp, *bi = bp + (i64)i * a.K * a.Bp;
+        for (int st = 0; st < steps; ++st)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(ai + st * 16), frag(bi + st * 16), acc, 0, 0, 0);
+        float *dst = xt + (i64)i * a.ld;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float mix = a.w * xm[v];
+            mix = a.w * xc[v] + mix;
+            mix = a.w * xn[v] + mix;
+            const float o = mix - a.gamma * acc[v];
+            dst[row_off(v)] = o;
+            if (CONS) {
+                if (i == 0) sh[v] = o;
+                const float e = o - sh[v];
+                s1[v] += e;
+                s2[v] += e * e;
+            }
+            xm[v] = xc[v];
+            xc[v] = xn[v];
+        }
+    }
+    if (CONS) {
+        float m2 = 0.f;
+        const float inv_n = 1.0f / (float)a.n;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m2 += s2[v] - s1[v] * s1[v] * inv_n;
+        double t = (double)m2;
+        for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
+        if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = t;
+    }
+}
+
+}  // namespace
+
+// Workspace layout shared by the size query and the launches.
+namespace {
+struct MlpWs {
+    bf16_t *a0 = nullptr, *at0 = nullptr;
+    std::vector<bf16_t *> h, ht, dzt;   // per layer output l = 1..L: h/ht for hidden layers, dzt for all
+    float *logits = nullptr;
+    bf16_t *dz[2] = {nullptr, nullptr};
+    size_t bytes = 0;
+};
+
+MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base)
+{
+    MlpWs w;
+    const size_t n = (size_t)ctx->n, B = (size_t)m.batch, Bp = (size_t)round_up(m.batch, 32);
+    const int L = (int)m.widths.size() - 1;
+    size_t off = 0;
+    auto take = [&](size_t b) {
+        unsigned char *q = base ? base + off : nullptr;
+        off += (b + 255) / 256 * 256;
+        return q;
+    };
+    if (!m.input_is_bf16) w.a0 = (bf16_t *)take(n * B * (size_t)m.widths[0] * 2);
+    w.at0 = (bf16_t *)take(n * (size_t)m.widths[0] * Bp * 2);
+    w.h.assign(L + 1, nullptr);
+    w.ht.assign(L + 1, nullptr);
+    w.dzt.assign(L + 1, nullptr);
+    size_t widest = 0;
+    for (int l = 1; l <= L; ++l) {
+        if (l < L) {
+            w.h[l] = (bf16_t *)take(n * B * (size_t)m.widths[l] * 2);
+            w.ht[l] = (bf16_t *)take(n * (size_t)m.widths[l] * Bp * 2);
+        }
+        w.dzt[l] = (bf16_t *)take(n * (size_t)m.widths[l] * Bp * 2);
+        widest = widest > (size_t)m.widths[l] ? widest : (size_t)m.widths[l];
+    }
+    w.logits = (float *)take(n * B * (size_t)m.widths[L] * 4);
+    for (int i = 0; i < 2; ++i) w.dz[i] = (bf16_t *)take(n * B * widest * 2);
+    w.bytes = off + 256;
+    return w;
+}
+
+// A layer's weight gradient can be fused into the ring mix when the tiles divide the matrix.
+bool layer_fusable(const dpsgd_ctx *ctx, int K, int O, i64 woff)
+{
+    return ctx->ring_uniform && !ctx->opt_mix_force_csr && (K % 128) == 0 && (O % 32) == 0 && (i64)K * O >= (1 << 20) &&
+           woff >= 0;
+}
+
+dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs, const void *targets,
+                          float *G, float *loss, bool fuse, float *consensus)
 {
     hipStream_t s = ctx->stream;
     const int n = ctx->n, B = m.batch, Bp = round_up(B, 32);
     const int L = (int)m.widths.size() - 1;
     if (n > 65535) return DPSGD_EUNSUPPORTED;
-    unsigned char *ws = (unsigned char *)ctx->ws;
-    auto take = [&](size_t bytes) {
-        unsigned char *p = ws;
-        ws += (bytes + 255) / 256 * 256;
-        return p;
-    };
-    const size_t nB = (size_t)n * B;
+    MlpWs ws = carve(ctx, m, (unsigned char *)ctx->ws);
     std::vector<const bf16_t *> act(L), actt(L);   // act[l]: input of layer l, [n][B][w_l]; actt[l]: [n][w_l][Bp]
-    bf16_t *a0 = nullptr;
-    if (!m.input_is_bf16) a0 = (bf16_t *)take(nB * m.widths[0] * 2);
-    bf16_t *at0 = (bf16_t *)take((size_t)n * m.widths[0] * Bp * 2);
-    act[0] = m.input_is_bf16 ? (const bf16_t *)inputs : a0;
-    actt[0] = at0;
-    std::vector<bf16_t *> h(L, nullptr), ht(L, nullptr);
+    act[0] = m.input_is_bf16 ? (const bf16_t *)inputs : ws.a0;
+    actt[0] = ws.at0;
     for (int l = 1; l < L; ++l) {
-        h[l] = (bf16_t *)take(nB * m.widths[l] * 2);
-        ht[l] = (bf16_t *)take((size_t)n * m.widths[l] * Bp * 2);
-        act[l] = h[l];
-        actt[l] = ht[l];
-    }
-    float *logits = (float *)take(nB * m.widths[L] * 4);
-    size_t widest = 0;
-    for (int l = 1; l <= L; ++l) widest = widest > (size_t)m.widths[l] ? widest : (size_t)m.widths[l];
-    bf16_t *dz[2], *dzt[2];
-    for (int i = 0; i < 2; ++i) {
-        dz[i] = (bf16_t *)take(nB * widest * 2);
-        dzt[i] = (bf16_t *)take((size_t)n * widest * Bp * 2);
+        act[l] = ws.h[l];
+        actt[l] = ws.ht[l];
     }
     std::vector<i64> woff(L), boff(L);
     i64 off = 0;
@@ -568,9 +672,9 @@ dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, con
         const int F = m.widths[0];
         dim3 grid((unsigned)((F + 31) / 32), (unsigned)(Bp / 32), (unsigned)n);
         if (m.input_is_bf16)
-            hipLaunchKernelGGL(prep_input_kernel<true>, grid, dim3(256), 0, s, inputs, a0, at0, B, Bp, F);
+            hipLaunchKernelGGL(prep_input_kernel<true>, grid, dim3(256), 0, s, inputs, ws.a0, ws.at0, B, Bp, F);
         else
-            hipLaunchKernelGGL(prep_input_kernel<false>, grid, dim3(256), 0, s, inputs, a0, at0, B, Bp, F);
+            hipLaunchKernelGGL(prep_input_kernel<false>, grid, dim3(256), 0, s, inputs, ws.a0, ws.at0, B, Bp, F);
     }
     const Tiling t = pick_tiling(B);
     const bool base_ok = aligned16(X) && (ctx->ld % 4) == 0;
@@ -580,7 +684,7 @@ dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, con
         a.act = act[l]; a.X = X; a.ld = ctx->ld; a.woff = woff[l]; a.boff = boff[l];
         a.B = B; a.Bp = Bp; a.K = m.widths[l]; a.O = m.widths[l + 1];
         const bool last = (l == L - 1);
-        if (last) a.z = logits; else { a.h = h[l + 1]; a.ht = ht[l + 1]; }
+        if (last) a.z = ws.logits; else { a.h = ws.h[l + 1]; a.ht = ws.ht[l + 1]; }
         const bool vec = base_ok && (a.K % 8) == 0 && (woff[l] % 4) == 0 && aligned16(act[l]);
         if (t.mt == 1) st = fwd_launch<1, 4, 1>(s, n, a, vec, last);
         else if (t.wm == 1) st = fwd_launch<1, 4, 2>(s, n, a, vec, last);
@@ -589,20 +693,27 @@ dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, con
     if (st != DPSGD_OK) return st;
     const int C = m.widths[L];
     int cur = 0;
-    hipLaunchKernelGGL(softmax_xent_bf16_kernel, dim3((unsigned)n), dim3(256), 0, s, logits, (const int *)targets, B, Bp,
-                       C, dz[cur], dzt[cur], loss);
+    hipLaunchKernelGGL(softmax_xent_bf16_kernel, dim3((unsigned)n), dim3(256), 0, s, ws.logits, (const int *)targets, B, Bp,
+                       C, ws.dz[cur], ws.dzt[L], loss);
+    std::vector<char> fused(L, 0);
     for (int l = L - 1; l >= 0 && st == DPSGD_OK; --l) {
         const int K = m.widths[l], O = m.widths[l + 1];
-        WgradArgs wa{};
-        wa.dzt = dzt[cur]; wa.at = actt[l]; wa.G = G; wa.ld = ctx->ld; wa.woff = woff[l]; wa.boff = boff[l];
-        wa.Bp = Bp; wa.K = K; wa.O = O;
-        dim3 wgrid((unsigned)((K + 255) / 256), (unsigned)((O + 127) / 128), (unsigned)n);
-        hipLaunchKernelGGL(mlp_wgrad_kernel, wgrid, dim3(256), 0, s, wa);
+        fused[l] = fuse && layer_fusable(ctx, K, O, woff[l]);
+        if (fused[l]) {   // only the bias gradient goes to G; the weight gradient is formed inside the mix
+            hipLaunchKernelGGL(bias_grad_bf16_kernel, dim3((unsigned)((O + 255) / 256), (unsigned)n), dim3(256), 0, s,
+                               ws.dzt[l + 1], O, Bp, G, ctx->ld, boff[l]);
+        } else {
+            WgradArgs wa{};
+            wa.dzt = ws.dzt[l + 1]; wa.at = actt[l]; wa.G = G; wa.ld = ctx->ld; wa.woff = woff[l]; wa.boff = boff[l];
+            wa.Bp = Bp; wa.K = K; wa.O = O;
+            dim3 wgrid((unsigned)((K + 255) / 256), (unsigned)((O + 127) / 128), (unsigned)n);
+            hipLaunchKernelGGL(mlp_wgrad_kernel, wgrid, dim3(256), 0, s, wa);
+        }
         st = hip_status(hipGetLastError());
         if (l > 0 && st == DPSGD_OK) {
             DgradArgs da{};
-            da.dz = dz[cur]; da.X = X; da.ld = ctx->ld; da.woff = woff[l]; da.hprev = h[l];
-            da.dzp = dz[cur ^ 1]; da.dzpt = dzt[cur ^ 1];
+            da.dz = ws.dz[cur]; da.X = X; da.ld = ctx->ld; da.woff = woff[l]; da.hprev = ws.h[l];
+            da.dzp = ws.dz[cur ^ 1]; da.dzpt = ws.dzt[l];
             da.B = B; da.Bp = Bp; da.K = K; da.O = O;
             const bool vec = base_ok && (K % 4) == 0 && (O % 8) == 0 && (woff[l] % 4) == 0;
             if (t.mt == 1) st = dgrad_launch<1, 4, 1>(s, n, da, vec);
@@ -611,7 +722,52 @@ dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, con
             cur ^= 1;
         }
     }
+    if (st != DPSGD_OK || !fuse) return st;
+
+    // ---- Algorithm 1 steps 4-5, in place: fused layers first, then the remaining column ranges
+    const bool cons = consensus != nullptr;
+    int64_t nparts = 0;
+    for (int l = 0; l < L && st == DPSGD_OK; ++l) {
+        if (!fused[l]) continue;
+        const int K = m.widths[l], O = m.widths[l + 1];
+        FusedArgs fa{};
+        fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
+        fa.n = n; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->ring_w; fa.gamma = ctx->gamma;
+        fa.partials = ctx->d_partials + nparts;
+        dim3 grid((unsigned)(K / 128), (unsigned)(O / 32));
+        const i64 np = (i64)grid.x * grid.y * 4;
+        if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
+        if (cons) hipLaunchKernelGGL(mlp_fused_ring_kernel<true>, grid, dim3(256), 0, s, fa);
+        else hipLaunchKernelGGL(mlp_fused_ring_kernel<false>, grid, dim3(256), 0, s, fa);
+        if (cons) nparts += np;
+        st = hip_status(hipGetLastError());
+    }
+    // maximal runs of columns that no fused kernel owns
+    i64 run0 = 0;
+    for (int l = 0; l <= L && st == DPSGD_OK; ++l) {
+        const bool boundary = (l == L) || fused[l];
+        if (!boundary) continue;
+        const i64 run1 = (l == L) ? ctx->d : woff[l];
+        if (run1 > run0) st = launch_mix_ring_range(ctx, X, G, X, run0, run1 - run0, cons, &nparts);
+        if (l < L) run0 = boff[l];
+    }
+    if (st == DPSGD_OK && cons) st = launch_consensus_finalize(ctx, nparts, consensus);
     return st;
+}
+}  // namespace
+
+size_t mlp_bf16_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m) { return carve(ctx, m, nullptr).bytes; }
+
+dpsgd_status launch_grad_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float *X, const void *inputs,
+                                  const void *targets, float *G, float *loss)
+{
+    return run_mlp_bf16(ctx, m, const_cast<float *>(X), inputs, targets, G, loss, false, nullptr);
+}
+
+dpsgd_status launch_step_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs,
+                                  const void *targets, float *G, float *loss, float *consensus)
+{
+    return run_mlp_bf16(ctx, m, X, inputs, targets, G, loss, true, consensus);
 }
 
 }  // namespace dpsgd
