@@ -1,14 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the D-PSGD hot path on one MI355X.
 
-A "step" is one synchronous iteration of Algorithm 1 over all n simulated workers:
-dpsgd_grad (step 3) followed by dpsgd_mix_step (steps 4-5, with the consensus distance).  Inputs
-(replicas, a pool of pre-generated minibatches) are resident in HBM before the timed region;
-drawing the minibatches (step 2) is not timed.
+A "step" is one synchronous iteration of Algorithm 1 over all n simulated workers: the minibatch
+gradient of every worker at its own iterate (step 3), the neighbourhood average and the update
+(steps 4-5) and the consensus distance.  Bf16 MLP workloads on the ring run it as dpsgd_step (the
+weight gradient of the large layers is formed inside the mix kernel); everything else, or
+--two-call, runs dpsgd_grad followed by dpsgd_mix_step.  Inputs (replicas, a pool of pre-generated
+minibatches) are resident in HBM before the timed region; drawing the minibatches (step 2) is not
+timed.
 
-Prints ONE JSON line: worker-iterations/s, plus the roofline of the dominant kernel (the fused
-mix+step kernel: 12 bytes per (worker, parameter)) measured with HIP events around every mix
-launch inside the timed region, and the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: worker-iterations/s, plus the roofline of the dominant kernel measured with
+HIP events inside the timed region, on the stream the kernels run on - the fused weight-gradient +
+mix kernel (8 bytes per (worker, weight): X read once, X written once) on the dpsgd_step path, the
+mix+step kernel (12 bytes per (worker, parameter)) on the two-call path - and the CPU oracle timed
+on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -25,7 +30,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per mix launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by what the
 # same counters read for a plain copy of known size (2.0 and 1.0); see profiles/.
-MEASURED_MIX_TRAFFIC = {"mlp3_ring64": 22.76e9}
+MEASURED_TRAFFIC = {("mlp3_ring64", "two-call"): 22.76e9}
 
 
 def parse():
@@ -38,6 +43,7 @@ def parse():
     ap.add_argument("--pool", type=int, default=4, help="distinct minibatches kept in HBM and cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-consensus", action="store_true")
+    ap.add_argument("--two-call", action="store_true", help="dpsgd_grad + dpsgd_mix_step even where dpsgd_step fuses")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (reference for the FETCH_SIZE / WRITE_SIZE "
                          "counters under rocprofv3 --pmc) and exit")
@@ -107,7 +113,7 @@ def main():
 
     from paper_1705_09056_amd import binding as B
     from paper_1705_09056_amd import synth
-    from paper_1705_09056_amd.configs import MODEL_LSQ, by_name
+    from paper_1705_09056_amd.configs import MODEL_MLP, MODEL_SOFTMAX, by_name
 
     cfg = by_name(args.workload)
     K = args.steps or cfg.iters
@@ -135,9 +141,20 @@ def main():
         pool.append((inp_d, torch.from_numpy(tgt).cuda()))
 
     ctx = B.Dpsgd(cfg.n, d, topo, cfg.gamma, ld=ld)
+    # layers whose weight gradient dpsgd_step forms inside the mix kernel (same rule as the library)
+    fused_weights = 0
+    if cfg.bf16 and cfg.model_kind in (MODEL_MLP, MODEL_SOFTMAX) and cfg.topology == "ring" and cfg.n >= 3:
+        for l in range(len(cfg.widths) - 1):
+            w_in, w_out = cfg.widths[l], cfg.widths[l + 1]
+            if w_in % 128 == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
+                fused_weights += w_in * w_out
+    fused = fused_weights > 0 and not args.two_call
 
     def step(k, ev=None):
         inp_d, tgt_d = pool[k % len(pool)]
+        if fused:
+            ctx.step(model, X, inp_d, tgt_d, cfg.batch, G, loss, cons, input_is_bf16=cfg.bf16)
+            return
         ctx.grad(model, X, inp_d, tgt_d, cfg.batch, G, loss, input_is_bf16=cfg.bf16)
         if ev is not None:
             ev[0].record()
@@ -152,6 +169,8 @@ def main():
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
     t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
+    if fused:
+        ctx.set_option("time_fused", 1)
     wall0 = time.perf_counter()
     t_begin.record()
     for k in range(K):
@@ -160,13 +179,22 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     total_ms = t_begin.elapsed_time(t_end)
-    mix_ms = sum(a.elapsed_time(b) for a, b in evs) / K
+    if fused:
+        fused_ms, launches = ctx.read_timing()
+        kernel_name = "mlp_fused_ring_kernel (weight gradient + Algorithm 1 steps 4-5, in place)"
+        launch_ms = fused_ms / launches
+        launch_bytes = 8.0 * cfg.n * fused_weights * K / launches
+        mix_ms = fused_ms / K
+    else:
+        kernel_name = "mix_step (Algorithm 1 steps 4-5 fused)"
+        mix_ms = sum(a.elapsed_time(b) for a, b in evs) / K
+        launch_ms = mix_ms
+        launch_bytes = 12.0 * cfg.n * d
     final_loss = float(loss.mean().item())
     final_cons = None if cons is None else float(cons.item())
     ctx.close()
 
-    mix_bytes = 12.0 * cfg.n * d
-    achieved = mix_bytes / (mix_ms * 1e-3) / 1e9
+    achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
     out = {
         "metric": "worker-iters/sec (grad+mix) at n workers",
         "value": cfg.n * K / (total_ms * 1e-3),
@@ -178,11 +206,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "model_kind": int(cfg.model_kind), "widths": list(cfg.widths), "n": cfg.n,
                    "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "gamma": cfg.gamma,
-                   "minibatch_pool": len(pool), "consensus": cons is not None},
-        "roofline": {"kernel": "mix_step (Algorithm 1 steps 4-5 fused)", "bound": "hbm", "achieved": achieved,
+                   "minibatch_pool": len(pool), "consensus": cons is not None,
+                   "path": "dpsgd_step" if fused else "dpsgd_grad + dpsgd_mix_step"},
+        "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_MIX_TRAFFIC.get(cfg.name),
-                     "algorithmic_bytes_per_launch": mix_bytes, "avg_launch_ms": mix_ms},
+                     "traffic": MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
+                     "algorithmic_bytes_per_launch": launch_bytes, "avg_launch_ms": launch_ms},
         "mix_fraction_of_step": mix_ms / (total_ms / K),
         "wall_s": wall,
         "final_mean_loss": final_loss, "final_consensus": final_cons,

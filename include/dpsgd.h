@@ -129,7 +129,7 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
 /* Launch-shape knobs for measurements; unknown keys give DPSGD_EINVAL.  Defaults are chosen from
  * (n, d).  Keys: "mix_bands" (row bands per workgroup of the ring kernel, 0 = auto),
  * "mix_vec" (floats per lane: 0 = auto, 1, 2 or 4), "mix_force_csr" (1: run the generic CSR
- * kernel even for ring / torus tags). */
+ * kernel even for ring / torus tags), "time_fused" (see dpsgd_read_timing). */
 dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value);
 
 /* CSR of the context's W (host arrays as in dpsgd_topology_build). */
@@ -176,6 +176,11 @@ dpsgd_status dpsgd_step(dpsgd_ctx *ctx, const dpsgd_model *model, float *X, cons
 
 /* Algorithm 1 step 7: xbar = (1/n) sum_i X[i].  X device n x d (stride ld); xbar device, d floats. */
 dpsgd_status dpsgd_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
+
+/* Measurement aid.  With dpsgd_set_option(ctx, "time_fused", 1), dpsgd_step brackets its fused weight-gradient +
+ * mix kernel launches with HIP events on the context's stream.  This call waits for the stream and returns the summed
+ * duration (ms) and the number of bracketed kernel launches since the previous call (at most 8192 steps are kept). */
+dpsgd_status dpsgd_read_timing(dpsgd_ctx *ctx, double *total_ms, int64_t *launches);
 
 /* Static, never NULL. */
 const char *dpsgd_strerror(dpsgd_status status);

@@ -22,7 +22,7 @@ MODEL_LSQ, MODEL_SOFTMAX, MODEL_MLP, MODEL_RESNET20 = range(4)
 EXPORTS = (
     "dpsgd_topology_build", "dpsgd_model_dim", "dpsgd_create", "dpsgd_destroy", "dpsgd_set_gamma",
     "dpsgd_set_option", "dpsgd_topology_export", "dpsgd_grad", "dpsgd_step", "dpsgd_mix_step", "dpsgd_mix_step_swapped",
-    "dpsgd_mean", "dpsgd_strerror",
+    "dpsgd_mean", "dpsgd_read_timing", "dpsgd_strerror",
 )
 
 
@@ -81,6 +81,8 @@ def load():
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp]
     L.dpsgd_mean.restype = C.c_int
     L.dpsgd_mean.argtypes = [vp, vp, vp]
+    L.dpsgd_read_timing.restype = C.c_int
+    L.dpsgd_read_timing.argtypes = [vp, C.POINTER(C.c_double), i64p]
     L.dpsgd_strerror.restype = C.c_char_p
     L.dpsgd_strerror.argtypes = [C.c_int]
     _lib = L
@@ -258,6 +260,12 @@ class Dpsgd:
         self._check_mat(X_out, "X_out")
         fn = self._L.dpsgd_mix_step_swapped if swapped else self._L.dpsgd_mix_step
         _check(fn(self._handle, _ptr(X_in), _ptr(G), _ptr(X_out), _ptr(consensus)), "dpsgd_mix_step")
+
+    def read_timing(self):
+        """(total ms, launches) of the fused kernels bracketed since the last call (option "time_fused")."""
+        ms, cnt = C.c_double(0.0), C.c_int64(0)
+        _check(self._L.dpsgd_read_timing(self._handle, C.byref(ms), C.byref(cnt)), "dpsgd_read_timing")
+        return ms.value, cnt.value
 
     def mean(self, X, xbar):
         self._check_mat(X, "X")

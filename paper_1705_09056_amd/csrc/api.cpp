@@ -267,6 +267,7 @@ dpsgd_status dpsgd_destroy(dpsgd_ctx *ctx)
     (void)hipFree(ctx->d_vals);
     (void)hipFree(ctx->d_partials);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    for (hipEvent_t e2 : ctx->ev) (void)hipEventDestroy(e2);
     delete ctx;
     return dpsgd::hip_status(e);
 }
@@ -290,6 +291,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
         ctx->opt_mix_vec = (int32_t)value;
     } else if (k == "mix_force_csr") {
         ctx->opt_mix_force_csr = value ? 1 : 0;
+    } else if (k == "time_fused") {
+        ctx->opt_time_fused = value ? 1 : 0;
     } else {
         return DPSGD_EINVAL;
     }
@@ -383,6 +386,23 @@ static dpsgd_status grad_or_step(dpsgd_ctx *ctx, const dpsgd_model *model, const
     }
     if (step) return dpsgd::launch_step(ctx, m, const_cast<float *>(X), batch->inputs, batch->targets, G, loss, consensus);
     return dpsgd::launch_grad(ctx, m, X, batch->inputs, batch->targets, G, loss);
+}
+
+dpsgd_status dpsgd_read_timing(dpsgd_ctx *ctx, double *total_ms, int64_t *launches)
+{
+    if (!ctx || !total_ms || !launches) return DPSGD_EINVAL;
+    DPSGD_HIP_TRY(hipStreamSynchronize(ctx->stream));
+    double sum = 0.0;
+    for (int64_t i = 0; i < ctx->ev_pairs; ++i) {
+        float ms = 0.f;
+        DPSGD_HIP_TRY(hipEventElapsedTime(&ms, ctx->ev[2 * i], ctx->ev[2 * i + 1]));
+        sum += (double)ms;
+    }
+    *total_ms = sum;
+    *launches = ctx->ev_launches;
+    ctx->ev_pairs = 0;
+    ctx->ev_launches = 0;
+    return DPSGD_OK;
 }
 
 const char *dpsgd_strerror(dpsgd_status s)

@@ -43,6 +43,11 @@ struct dpsgd_ctx {
     // launch-shape options (0 = auto)
     int32_t opt_mix_bands = 0, opt_mix_vec = 0, opt_mix_force_csr = 0;
 
+    // measurement aid: HIP events around the fused wgrad+mix launches of dpsgd_step ("time_fused")
+    int32_t opt_time_fused = 0;
+    std::vector<hipEvent_t> ev;   // pairs (start, stop)
+    int64_t ev_pairs = 0, ev_launches = 0;
+
     // gradient workspace (activations, bf16 operand copies), owned by the context
     void *ws = nullptr;
     size_t ws_bytes = 0;

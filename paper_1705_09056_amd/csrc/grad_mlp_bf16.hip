@@ -542,24 +542,25 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
     const bf16_t *ap = a.dzt + (i64)(o0 + l32) * a.Bp + 8 * half;
     const bf16_t *bp = a.at + (i64)(k0 + l32) * a.Bp + 8 * half;
 
-    float xm[16], xc[16], xh[16], s1[16], s2[16], sh[16];
+    // xh: worker 0's original tile (the ring's wrap-around, and the shift of the consensus sums);
+    // xn / xf: the tiles of workers i+1 and i+2, fetched one and two steps ahead
+    float xm[16], xc[16], xh[16], xn[16], xf[16], s1[16], s2[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         xm[v] = xt[(i64)(a.n - 1) * a.ld + row_off(v)];
         xc[v] = xt[row_off(v)];
         xh[v] = xc[v];
+        xn[v] = xt[(i64)(1 % a.n) * a.ld + row_off(v)];
         s1[v] = 0.f;
         s2[v] = 0.f;
-        sh[v] = 0.f;
     }
     for (int i = 0; i < a.n; ++i) {
-        float xn[16];
-        if (i + 1 < a.n) {
+        if (i + 2 < a.n) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) xn[v] = xt[(i64)(i + 1) * a.ld + row_off(v)];
+            for (int v = 0; v < 16; ++v) xf[v] = xt[(i64)(i + 2) * a.ld + row_off(v)];
         } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) xn[v] = xh[v];
+            for (int v = 0; v < 16; ++v) xf[v] = xh[v];   // only its use as worker n-1's successor matters
         }
         f32x16 acc;
 #pragma unroll
@@ -570,19 +571,20 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
         float *dst = xt + (i64)i * a.ld;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
+            const float nxt = (i + 1 < a.n) ? xn[v] : xh[v];
             float mix = a.w * xm[v];
             mix = a.w * xc[v] + mix;
-            mix = a.w * xn[v] + mix;
+            mix = a.w * nxt + mix;
             const float o = mix - a.gamma * acc[v];
             dst[row_off(v)] = o;
             if (CONS) {
-                if (i == 0) sh[v] = o;
-                const float e = o - sh[v];
+                const float e = o - xh[v];
                 s1[v] += e;
                 s2[v] += e * e;
             }
             xm[v] = xc[v];
-            xc[v] = xn[v];
+            xc[v] = nxt;
+            xn[v] = xf[v];
         }
     }
     if (CONS) {
@@ -727,8 +729,19 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
     // ---- Algorithm 1 steps 4-5, in place: fused layers first, then the remaining column ranges
     const bool cons = consensus != nullptr;
     int64_t nparts = 0;
+    bool timing = false;
+    if (ctx->opt_time_fused && ctx->ev_pairs < 8192) {   // bracket the fused launches with events
+        while ((int64_t)ctx->ev.size() < 2 * (ctx->ev_pairs + 1)) {
+            hipEvent_t e = nullptr;
+            if (hipEventCreate(&e) != hipSuccess) return DPSGD_EDEVICE;
+            ctx->ev.push_back(e);
+        }
+        timing = true;
+        (void)hipEventRecord(ctx->ev[2 * ctx->ev_pairs], s);
+    }
     for (int l = 0; l < L && st == DPSGD_OK; ++l) {
         if (!fused[l]) continue;
+        if (timing) ctx->ev_launches += 1;
         const int K = m.widths[l], O = m.widths[l + 1];
         FusedArgs fa{};
         fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
@@ -741,6 +754,10 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         else hipLaunchKernelGGL(mlp_fused_ring_kernel<false>, grid, dim3(256), 0, s, fa);
         if (cons) nparts += np;
         st = hip_status(hipGetLastError());
+    }
+    if (timing) {
+        (void)hipEventRecord(ctx->ev[2 * ctx->ev_pairs + 1], s);
+        ctx->ev_pairs += 1;
     }
     // maximal runs of columns that no fused kernel owns
     i64 run0 = 0;
