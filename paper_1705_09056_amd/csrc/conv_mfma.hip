@@ -138,6 +138,30 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
         const int pi = mt * 16 + n16;                  // this lane's pixel as an A-operand row
         const int py = pi / a.Wd, px = pi % a.Wd;
         const bf16_t *pa = patch + ((py * STRIDE) * PC + px * STRIDE) * PP;
+        // this lane's outputs: pixels q0..q0+3 (consecutive x of one row) of channel o, per channel tile
+        const int q0 = mt * 16 + 4 * g;
+        const int y = y0 + q0 / a.Wd, x0 = q0 % a.Wd;
+        // fetch what the epilogue needs (shortcut values, activation signs) before the MFMAs so that
+        // their latency hides behind the arithmetic
+        bf16_t e_sc[NTW][4], e_act[NTW][4];
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) {
+            const int o = (wc * NTW + t) * 16 + n16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int x = x0 + i;
+                e_sc[t][i] = 0;
+                e_act[t][i] = 0;
+                if (!DGRAD) {
+                    if (a.sc.p && o < a.sc.C)
+                        e_sc[t][i] = a.sc.p[((img * a.sc.H + (i64)y * a.sc.S) * a.sc.W + x * a.sc.S) * a.sc.C + o];
+                } else {
+                    if (a.sc.p && (y % a.sc.S) == 0 && (x % a.sc.S) == 0)
+                        e_sc[t][i] = a.sc.p[((img * a.sc.H + y / a.sc.S) * a.sc.W + x / a.sc.S) * a.sc.C + o];
+                    e_act[t][i] = a.act[((img * a.Hd + y) * a.Wd + x) * CO + o];
+                }
+            }
+        }
         f32x4 acc[NTW];
 #pragma unroll
         for (int t = 0; t < NTW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -147,30 +171,21 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 #pragma unroll
             for (int t = 0; t < NTW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wf[s][t], acc[t], 0, 0, 0);
         }
-        // epilogue: this lane holds pixels q0..q0+3 (consecutive x of one row) of channel o
-        const int q0 = mt * 16 + 4 * g;
-        const int y = y0 + q0 / a.Wd, x0 = q0 % a.Wd;
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
             const int o = (wc * NTW + t) * 16 + n16;
             bf16_t r[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int x = x0 + i;
-                float v = acc[t][i];
-                const i64 di = ((img * a.Hd + y) * a.Wd + x) * CO + o;
+                float v = acc[t][i] + bf2f(e_sc[t][i]);
                 if (!DGRAD) {
                     v += bias;
-                    if (a.sc.p && o < a.sc.C)
-                        v += bf2f(a.sc.p[((img * a.sc.H + (i64)y * a.sc.S) * a.sc.W + x * a.sc.S) * a.sc.C + o]);
                     v = v > 0.f ? v : 0.f;
                 } else {
-                    if (a.sc.p && (y % a.sc.S) == 0 && (x % a.sc.S) == 0)
-                        v += bf2f(a.sc.p[((img * a.sc.H + y / a.sc.S) * a.sc.W + x / a.sc.S) * a.sc.C + o]);
-                    v = bf16_positive(a.act[di]) ? v : 0.f;
+                    v = bf16_positive(e_act[t][i]) ? v : 0.f;
                 }
                 r[i] = f2bf(v);
-                a.dst[di] = r[i];
+                a.dst[((img * a.Hd + y) * a.Wd + x0 + i) * CO + o] = r[i];
             }
             u32x2 pk = {(unsigned)r[0] | ((unsigned)r[1] << 16), (unsigned)r[2] | ((unsigned)r[3] << 16)};
             *reinterpret_cast<u32x2 *>(a.dstT + ((img * CO + o) * a.Hd + y) * a.Wd + x0) = pk;
