@@ -64,11 +64,11 @@ struct ConvMfmaArgs {
     int Hs, Ws;
     const bf16_t *wpack;    // [n][KS][CO/16][64][8]
     bf16_t *dst, *dstT;     // NHWC [n*B][Hd][Wd][CO], channel-major [n*B][CO][Hd][Wd]
-    int Hd, Wd, B;
+    int Hd, Wd, lw, B;      // lw = log2(Wd)
     const float *X;         // forward: scalar bias at X[w*ld + b_off]
     i64 ld, b_off;
-    ShortcutRef sc;         // forward: block input; data gradient: delta of the block output
-    const bf16_t *act;      // data gradient: activation whose sign masks the result (same shape as dst)
+    ShortcutRef sc;         // forward: block input; data gradient: delta of the block output (channel-major copy used)
+    const bf16_t *actT;     // data gradient: channel-major activation whose sign masks the result (shape of dst)
 };
 
 template <int CI, int CO, int STRIDE, int DILATE, bool DGRAD>
@@ -76,35 +76,44 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 {
     constexpr int KS = ksteps(CI), NT = CO / 16, WC = wave_cols(CI, CO), NTW = NT / WC, WP = 4 / WC;
     constexpr int PP = CI + 8;   // LDS pixel pitch (bf16 elements)
-    constexpr int TH = 8;
+    constexpr int TH = 8, C8 = CI / 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *patch = reinterpret_cast<bf16_t *>(smem);
     const int band = blockIdx.x, b = blockIdx.y, w = blockIdx.z;
     const i64 img = (i64)w * a.B + b;
     const int y0 = band * TH;
-    const int PR = (TH - 1) * STRIDE + 3, PC = (a.Wd - 1) * STRIDE + 3;
+    const int Wd = a.Wd, lw = a.lw;
+    const int PR = (TH - 1) * STRIDE + 3, PC = (Wd - 1) * STRIDE + 3;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wc = wave % WC, wp = wave / WC;
     const int n16 = lane & 15, g = lane >> 4;
 
-    // stage the source rows (with halo, zeros outside / between dilated pixels)
+    // stage the source rows (with halo, zeros outside / between dilated pixels): a wave per patch row,
+    // a lane per 16-byte unit of the row
     {
-        constexpr int C8 = CI / 8;
-        const int units = PR * PC * C8;
         const bf16_t *src = a.src + img * a.Hs * a.Ws * CI;
-        for (int u = tid; u < units; u += 256) {
-            const int c8 = u % C8, pc = (u / C8) % PC, pr = u / (C8 * PC);
-            int vr = y0 * STRIDE - 1 + pr, vc = pc - 1;
-            bool ok = vr >= 0 && vc >= 0;
+        const int row_units = PC * C8;
+        for (int pr = wave; pr < PR; pr += 4) {
+            int vr = y0 * STRIDE - 1 + pr;
+            bool row_ok = vr >= 0;
             if (DILATE == 2) {
-                ok = ok && !(vr & 1) && !(vc & 1);
+                row_ok = row_ok && !(vr & 1);
                 vr >>= 1;
-                vc >>= 1;
             }
-            ok = ok && vr < a.Hs && vc < a.Ws;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = *reinterpret_cast<const u32x4 *>(src + ((i64)vr * a.Ws + vc) * CI + c8 * 8);
-            *reinterpret_cast<u32x4 *>(patch + (pr * PC + pc) * PP + c8 * 8) = v;
+            row_ok = row_ok && vr < a.Hs;
+            for (int u = lane; u < row_units; u += 64) {
+                const int c8 = u % C8, pc = u / C8;
+                int vc = pc - 1;
+                bool ok = row_ok && vc >= 0;
+                if (DILATE == 2) {
+                    ok = ok && !(vc & 1);
+                    vc >>= 1;
+                }
+                ok = ok && vc < a.Ws;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (ok) v = *reinterpret_cast<const u32x4 *>(src + (vr * a.Ws + vc) * CI + c8 * 8);
+                *reinterpret_cast<u32x4 *>(patch + (pr * PC + pc) * PP + c8 * 8) = v;
+            }
         }
     }
 
@@ -131,34 +140,47 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     }
     __syncthreads();
 
-    const int mtot = TH * a.Wd / 16;
+    const int mtot = (TH << lw) >> 4;
     float bias = 0.f;
     if (!DGRAD) bias = a.X[(i64)w * a.ld + a.b_off];
+    // per-image bases; everything below is 32-bit offsets inside one image
+    bf16_t *dst = a.dst ? a.dst + img * a.Hd * Wd * CO : nullptr;
+    bf16_t *dstT = a.dstT + img * CO * a.Hd * Wd;
+    const bf16_t *actT = DGRAD ? a.actT + img * CO * a.Hd * Wd : nullptr;
+    const bf16_t *scT = a.sc.t ? a.sc.t + img * a.sc.C * a.sc.H * a.sc.W : nullptr;
+    const int scS = a.sc.S;
+
     for (int mt = wp; mt < mtot; mt += WP) {
         const int pi = mt * 16 + n16;                  // this lane's pixel as an A-operand row
-        const int py = pi / a.Wd, px = pi % a.Wd;
+        const int py = pi >> lw, px = pi & (Wd - 1);
         const bf16_t *pa = patch + ((py * STRIDE) * PC + px * STRIDE) * PP;
         // this lane's outputs: pixels q0..q0+3 (consecutive x of one row) of channel o, per channel tile
         const int q0 = mt * 16 + 4 * g;
-        const int y = y0 + q0 / a.Wd, x0 = q0 % a.Wd;
-        // fetch what the epilogue needs (shortcut values, activation signs) before the MFMAs so that
-        // their latency hides behind the arithmetic
-        bf16_t e_sc[NTW][4], e_act[NTW][4];
+        const int y = y0 + (q0 >> lw), x0 = q0 & (Wd - 1);
+        // fetch what the epilogue needs (shortcut values, activation signs; 4 consecutive pixels of one
+        // channel are contiguous in the channel-major copies) before the MFMAs, to hide their latency
+        float e_sc[NTW][4];
+        u32x2 e_act[NTW];
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
             const int o = (wc * NTW + t) * 16 + n16;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int x = x0 + i;
-                e_sc[t][i] = 0;
-                e_act[t][i] = 0;
-                if (!DGRAD) {
-                    if (a.sc.p && o < a.sc.C)
-                        e_sc[t][i] = a.sc.p[((img * a.sc.H + (i64)y * a.sc.S) * a.sc.W + x * a.sc.S) * a.sc.C + o];
-                } else {
-                    if (a.sc.p && (y % a.sc.S) == 0 && (x % a.sc.S) == 0)
-                        e_sc[t][i] = a.sc.p[((img * a.sc.H + y / a.sc.S) * a.sc.W + x / a.sc.S) * a.sc.C + o];
-                    e_act[t][i] = a.act[((img * a.Hd + y) * a.Wd + x) * CO + o];
+            for (int i = 0; i < 4; ++i) e_sc[t][i] = 0.f;
+            e_act[t] = (u32x2){0u, 0u};
+            if (DGRAD) e_act[t] = *reinterpret_cast<const u32x2 *>(actT + (o * a.Hd + y) * Wd + x0);
+            if (scT && o < a.sc.C) {
+                if (scS == 1) {
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(scT + (o * a.sc.H + y) * a.sc.W + x0);
+                    e_sc[t][0] = bf2f((bf16_t)(v.x & 0xffff)); e_sc[t][1] = bf2f((bf16_t)(v.x >> 16));
+                    e_sc[t][2] = bf2f((bf16_t)(v.y & 0xffff)); e_sc[t][3] = bf2f((bf16_t)(v.y >> 16));
+                } else if (!DGRAD) {   // block input at (2y, 2x): every second of 8 consecutive pixels
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(scT + (o * a.sc.H + 2 * y) * a.sc.W + 2 * x0);
+                    e_sc[t][0] = bf2f((bf16_t)(v.x & 0xffff)); e_sc[t][1] = bf2f((bf16_t)(v.y & 0xffff));
+                    e_sc[t][2] = bf2f((bf16_t)(v.z & 0xffff)); e_sc[t][3] = bf2f((bf16_t)(v.w & 0xffff));
+                } else if (!(y & 1)) {   // delta of the block output lands on even pixels only
+                    const unsigned v = *reinterpret_cast<const unsigned *>(scT + (o * a.sc.H + (y >> 1)) * a.sc.W + (x0 >> 1));
+                    e_sc[t][0] = bf2f((bf16_t)(v & 0xffff));
+                    e_sc[t][2] = bf2f((bf16_t)(v >> 16));
                 }
             }
         }
@@ -174,26 +196,35 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
             const int o = (wc * NTW + t) * 16 + n16;
-            bf16_t r[4];
+            const bf16_t am[4] = {(bf16_t)(e_act[t].x & 0xffff), (bf16_t)(e_act[t].x >> 16), (bf16_t)(e_act[t].y & 0xffff),
+                                  (bf16_t)(e_act[t].y >> 16)};
+            float r[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float v = acc[t][i] + bf2f(e_sc[t][i]);
+                float v = acc[t][i] + e_sc[t][i];
                 if (!DGRAD) {
                     v += bias;
                     v = v > 0.f ? v : 0.f;
                 } else {
-                    v = bf16_positive(e_act[t][i]) ? v : 0.f;
+                    v = bf16_positive(am[i]) ? v : 0.f;
                 }
-                r[i] = f2bf(v);
-                a.dst[((img * a.Hd + y) * a.Wd + x0 + i) * CO + o] = r[i];
+                r[i] = v;
             }
-            u32x2 pk = {(unsigned)r[0] | ((unsigned)r[1] << 16), (unsigned)r[2] | ((unsigned)r[3] << 16)};
-            *reinterpret_cast<u32x2 *>(a.dstT + ((img * CO + o) * a.Hd + y) * a.Wd + x0) = pk;
+            const u32x2 pk = {f2bf_pack(r[0], r[1]), f2bf_pack(r[2], r[3])};
+            if (dst) {
+                bf16_t *dp = dst + ((y << lw) + x0) * CO + o;
+                dp[0] = (bf16_t)(pk.x & 0xffff);
+                dp[CO] = (bf16_t)(pk.x >> 16);
+                dp[2 * CO] = (bf16_t)(pk.y & 0xffff);
+                dp[3 * CO] = (bf16_t)(pk.y >> 16);
+            }
+            *reinterpret_cast<u32x2 *>(dstT + ((o * a.Hd + y) << lw) + x0) = pk;
         }
     }
 }
 
 bool pow2_channels(int c) { return c == 16 || c == 32 || c == 64; }
+int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 // ----------------------------------------------------------------------- weight gradient
 // dW[co][ci][tap] = sum over pixels of dout[pixel][co] * in[pixel shifted by tap][ci]: for each tap a
@@ -399,7 +430,7 @@ dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs
 // Can the MFMA kernel produce a tensor of Hd x Wd from a source of width Ws?
 bool tile_ok(int Hd, int Wd, int stride, int ci)
 {
-    if (Hd % 8 || Wd % 8 || Wd > 64) return false;
+    if (Hd % 8 || !(Wd == 8 || Wd == 16 || Wd == 32 || Wd == 64)) return false;
     const size_t pr = 7 * stride + 3, pc = (size_t)(Wd - 1) * stride + 3;
     return pr * pc * (ci + 8) * 2 <= 64 * 1024;
 }
@@ -513,10 +544,11 @@ dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X
 dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, const bf16_t *wpack,
                           ShortcutRef sc, Tensor out)
 {
-    if (!fwd_mfma_ok(c) || !out.t) return conv_forward_generic(ctx, c, B, in, X, sc, out);
+    if (!fwd_mfma_ok(c) || !out.t || (sc.p && !sc.t)) return conv_forward_generic(ctx, c, B, in, X, sc, out);
     ConvMfmaArgs a{};
     a.src = in.p; a.Hs = c.H; a.Ws = c.W; a.wpack = wpack; a.dst = out.p; a.dstT = out.t; a.Hd = c.Ho; a.Wd = c.Wo;
-    a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = c.b_off; a.sc = sc; a.act = nullptr;
+    a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = c.b_off; a.sc = sc; a.actT = nullptr;
+    a.lw = ilog2(a.Wd);
     if (stem_like(c)) return launch_conv<8, 16, 1, 1, false>(ctx, a);   // `in` is the image padded to 8 channels
     if (c.stride == 1) {
         if (c.Ci == 16) return launch_conv<16, 16, 1, 1, false>(ctx, a);
@@ -528,12 +560,14 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
 }
 
 dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X, const bf16_t *wpack_d,
-                            ShortcutRef scd, const bf16_t *act, Tensor din)
+                            ShortcutRef scd, Tensor act, Tensor din)
 {
-    if (!dgrad_mfma_ok(c) || !din.t) return conv_data_grad_generic(ctx, c, B, dout, X, scd, act, din);
+    if (!dgrad_mfma_ok(c) || !din.t || !act.t || (scd.p && !scd.t))
+        return conv_data_grad_generic(ctx, c, B, dout, X, scd, act.p, din);
     ConvMfmaArgs a{};
     a.src = dout.p; a.Hs = c.Ho; a.Ws = c.Wo; a.wpack = wpack_d; a.dst = din.p; a.dstT = din.t; a.Hd = c.H; a.Wd = c.W;
-    a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = 0; a.sc = scd; a.act = act;
+    a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = 0; a.sc = scd; a.actT = act.t;
+    a.lw = ilog2(a.Wd);
     if (c.stride == 1) {
         if (c.Ci == 16) return launch_conv<16, 16, 1, 1, true>(ctx, a);
         if (c.Ci == 32) return launch_conv<32, 32, 1, 1, true>(ctx, a);

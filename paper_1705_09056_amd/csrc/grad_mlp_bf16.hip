@@ -33,12 +33,17 @@ constexpr int KC = 64;        // contraction elements staged per step
 constexpr int PITCH = KC + 8; // LDS row pitch in bf16 elements (144 B: 16 B aligned, spreads banks)
 
 __device__ __forceinline__ bf16_t f2bf(float f)
-{   // round to nearest, ties to even
-    unsigned u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+{   // round to nearest, ties to even (v_cvt_pk_bf16_f32)
+    const __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(unsigned short, h);
 }
-__device__ __forceinline__ unsigned pack2(float a, float b) { return (unsigned)f2bf(a) | ((unsigned)f2bf(b) << 16); }
+__device__ __forceinline__ unsigned pack2(float a, float b)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
 __device__ __forceinline__ bf16x8 frag(const bf16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
 __device__ __forceinline__ bf16x8 zero_frag()

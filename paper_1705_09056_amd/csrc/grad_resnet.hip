@@ -362,7 +362,7 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     const int nconv = (int)p.convs.size();
     auto a_of = [&](int j) { return ws.out[j == 0 ? 0 : 2 * j]; };   // block input/output j
     auto u_of = [&](int j) { return ws.out[1 + 2 * j]; };
-    const ShortcutRef none{nullptr, 0, 0, 0, 1};
+    const ShortcutRef none{nullptr, nullptr, 0, 0, 0, 1};
     dpsgd_status st;
 
     // bf16 operands of the convolutions in the layout the MFMA kernels read (no-op for generic convs)
@@ -392,7 +392,7 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     for (int j = 0; j < p.nblocks; ++j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
         if ((st = conv_forward(ctx, c1, B, a_of(j), X, ws.wpack_f[1 + 2 * j], none, u_of(j))) != DPSGD_OK) return st;
-        const ShortcutRef sc{a_of(j).p, c1.Ci, c1.H, c1.W, c1.stride};
+        const ShortcutRef sc{a_of(j).p, a_of(j).t, c1.Ci, c1.H, c1.W, c1.stride};
         if ((st = conv_forward(ctx, c2, B, u_of(j), X, ws.wpack_f[2 + 2 * j], sc, a_of(j + 1))) != DPSGD_OK) return st;
     }
     const int HWl = p.H_last * p.W_last;
@@ -410,11 +410,11 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
         // conv2: weight and bias gradient from dv and u; du = [u > 0] * dgrad(dv)
         if ((st = conv_weight_grad(ctx, c2, B, u_of(j), dv, G, ws.partials)) != DPSGD_OK) return st;
-        if ((st = conv_data_grad(ctx, c2, B, dv, X, ws.wpack_d[2 + 2 * j], none, u_of(j).p, du)) != DPSGD_OK) return st;
+        if ((st = conv_data_grad(ctx, c2, B, dv, X, ws.wpack_d[2 + 2 * j], none, u_of(j), du)) != DPSGD_OK) return st;
         // conv1: from du and a_j; next dv = [a_j > 0] * (dgrad(du) + shortcut delta)
         if ((st = conv_weight_grad(ctx, c1, B, a_of(j), du, G, ws.partials)) != DPSGD_OK) return st;
-        const ShortcutRef scd{dv.p, c2.Co, c2.Ho, c2.Wo, c1.stride};
-        if ((st = conv_data_grad(ctx, c1, B, du, X, ws.wpack_d[1 + 2 * j], scd, a_of(j).p, dnext)) != DPSGD_OK) return st;
+        const ShortcutRef scd{dv.p, dv.t, c2.Co, c2.Ho, c2.Wo, c1.stride};
+        if ((st = conv_data_grad(ctx, c1, B, du, X, ws.wpack_d[1 + 2 * j], scd, a_of(j), dnext)) != DPSGD_OK) return st;
         Tensor t = dv; dv = dnext; dnext = t;
     }
     if (stem_mfma) {   // stem: weight and bias gradient only

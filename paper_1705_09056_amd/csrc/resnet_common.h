@@ -10,10 +10,16 @@ namespace dpsgd {
 typedef unsigned short bf16_t;
 
 __device__ __forceinline__ bf16_t f2bf(float f)
-{   // round to nearest, ties to even
-    unsigned u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+{   // round to nearest, ties to even (v_cvt_pk_bf16_f32)
+    const __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(unsigned short, h);
+}
+__device__ __forceinline__ unsigned f2bf_pack(float lo, float hi)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
 __device__ __forceinline__ bool bf16_positive(bf16_t h) { return (h & 0x7fffu) != 0 && (h & 0x8000u) == 0; }
@@ -42,7 +48,8 @@ struct Tensor {
 // Forward: the block input added to the block output at (y*S, x*S) for the first C channels.
 // Backward: the delta of the block output added to the block input's delta at multiples of S.
 struct ShortcutRef {
-    const bf16_t *p;
+    const bf16_t *p;   // NHWC
+    const bf16_t *t;   // channel-major copy
     int C, H, W, S;
 };
 
@@ -51,7 +58,7 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
                           ShortcutRef sc, Tensor out);
 // din = round([act > 0] * (conv^T(dout) + shortcut delta)).
 dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X, const bf16_t *wpack_d,
-                            ShortcutRef scd, const bf16_t *act, Tensor din);
+                            ShortcutRef scd, Tensor act, Tensor din);
 // G[w_off..] = dout (*) in, G[b_off] = sum(dout).  partials: scratch of conv_wgrad_partial_bytes(c, B) * n bytes.
 dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials);
 
