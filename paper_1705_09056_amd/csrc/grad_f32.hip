@@ -138,6 +138,58 @@ dpsgd_status gemm_f32(hipStream_t s, int nworkers, const GemmArgs &g)
     return hip_status(hipGetLastError());
 }
 
+// Forward of a layer with few outputs (O <= 16, e.g. the 10 classes): one wave per (worker, sample row); lanes
+// stride over the inputs, every lane keeps O partial sums, a wave reduction finishes them.  The tiled GEMM above
+// would launch only a handful of workgroups for such a shape.
+template <int OMAX, bool VEC>
+__global__ void __launch_bounds__(256)
+linear_fwd_skinny_kernel(const float *__restrict__ act, const float *__restrict__ X, i64 ld, i64 woff, i64 boff, int B, int I,
+                         int O, int relu, float *__restrict__ out)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);   // sample row inside the worker
+    const int w = blockIdx.y;
+    if (row >= B) return;
+    const float *a = act + ((i64)w * B + row) * I;
+    const float *Wg = X + (i64)w * ld + woff;
+    float acc[OMAX];
+#pragma unroll
+    for (int o = 0; o < OMAX; ++o) acc[o] = 0.f;
+    if (VEC) {   // I % 4 == 0 and 16-byte aligned rows: 4 consecutive inputs per lane and step
+#pragma unroll 2
+        for (int k = lane * 4; k < I; k += 256) {
+            const f4 av = *reinterpret_cast<const f4 *>(a + k);
+#pragma unroll
+            for (int o = 0; o < OMAX; ++o)
+                if (o < O) {
+                    const f4 wv = *reinterpret_cast<const f4 *>(Wg + (i64)o * I + k);
+                    acc[o] = av.x * wv.x + acc[o];
+                    acc[o] = av.y * wv.y + acc[o];
+                    acc[o] = av.z * wv.z + acc[o];
+                    acc[o] = av.w * wv.w + acc[o];
+                }
+        }
+    } else {
+        for (int k = lane; k < I; k += 64) {
+            const float av = a[k];
+#pragma unroll
+            for (int o = 0; o < OMAX; ++o)
+                if (o < O) acc[o] = av * Wg[(i64)o * I + k] + acc[o];
+        }
+    }
+#pragma unroll
+    for (int o = 0; o < OMAX; ++o) {
+        float v = acc[o];
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+        if (lane == 0 && o < O) {
+            v += X[(i64)w * ld + boff + o];
+            if (relu) v = v > 0.f ? v : 0.f;
+            out[((i64)w * B + row) * O + o] = v;
+        }
+    }
+}
+
 // gb[w][o] = sum_b dz[w][b][o]
 __global__ void __launch_bounds__(256)
 bias_grad_kernel(const float *__restrict__ dz, int B, int O, float *__restrict__ G, i64 ld, i64 boff)
@@ -247,6 +299,19 @@ dpsgd_status launch_grad_f32(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const fl
         g.C = (float *)act[l + 1]; g.sCw = (i64)B * O; g.sCm = O; g.sCn = 1;
         g.bias = X + boff[l]; g.sBiasw = ctx->ld;
         g.M = B; g.N = O; g.K = I; g.relu = (l < L - 1);
+        if (O <= 16 && I >= 256) {
+            const bool vec = (I % 4) == 0 && (woff[l] % 4) == 0 && (ctx->ld % 4) == 0 &&
+                             (reinterpret_cast<uintptr_t>(X) % 16) == 0 && (reinterpret_cast<uintptr_t>(act[l]) % 16) == 0;
+            dim3 sgrid((unsigned)((B + 3) / 4), (unsigned)n);
+            if (vec)
+                hipLaunchKernelGGL((linear_fwd_skinny_kernel<16, true>), sgrid, dim3(256), 0, s, act[l], X, ctx->ld, woff[l],
+                                   boff[l], B, I, O, g.relu, (float *)act[l + 1]);
+            else
+                hipLaunchKernelGGL((linear_fwd_skinny_kernel<16, false>), sgrid, dim3(256), 0, s, act[l], X, ctx->ld, woff[l],
+                                   boff[l], B, I, O, g.relu, (float *)act[l + 1]);
+            if ((st = hip_status(hipGetLastError())) != DPSGD_OK) return st;
+            continue;
+        }
         if ((st = gemm_f32(s, n, g)) != DPSGD_OK) return st;
     }
     const int C = m.widths[L];
