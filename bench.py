@@ -93,6 +93,52 @@ def cpu_baseline(cfg, seconds_budget=20.0):
     }
 
 
+MFMA_PEAK_TFLOPS = 2500.0   # dense bf16
+
+
+def gradient_roofline(cfg, d, step_ms):
+    """Arithmetic of the gradient (Algorithm 1 step 3) per iteration against the bf16 MFMA peak and against the
+    ceiling its arithmetic intensity allows: a GEMM M x K . K x N counts 2MKN; forward + weight gradient for a first
+    layer, + data gradient for the others.  Minimum HBM bytes: every worker has its own weights, so an MLP weight is
+    read (4 B) for the forward, again for the data gradient (not the first layer) and its fp32 gradient or update is
+    written (4 B), and the minibatch is read twice; the CNN streams each conv's bf16 input and output once per pass (forward, data and weight
+    gradient).  The rate is taken over the whole iteration (gradient + mix), not over the gradient kernels alone."""
+    from paper_1705_09056_amd.configs import MODEL_LSQ, MODEL_RESNET20
+    n, Bw = cfg.n, cfg.batch
+    if cfg.model_kind == MODEL_LSQ:
+        flop, byts = 4.0 * Bw * d * n, 4.0 * Bw * d * n
+    elif cfg.model_kind == MODEL_RESNET20:
+        in_ch, H, Wd, base, blocks, classes = cfg.widths
+        convs = [(in_ch, base, H * Wd, H * Wd)]
+        c, px = base, H * Wd
+        for stage in range(3):
+            for blk in range(blocks):
+                if stage > 0 and blk == 0:
+                    convs.append((c, 2 * c, px, px // 4))
+                    c, px = 2 * c, px // 4
+                else:
+                    convs.append((c, c, px, px))
+                convs.append((c, c, px, px))
+        mac = sum(9 * ci * co * po for ci, co, _, po in convs) + c * classes
+        first = 9 * convs[0][0] * convs[0][1] * convs[0][3]
+        flop = 2.0 * (3 * mac - first) * Bw * n
+        byts = 3.0 * 2.0 * sum(ci * pi + co * po for ci, co, pi, po in convs) * Bw * n
+    else:
+        flop = 0.0
+        byts = 2.0 * (2.0 if cfg.bf16 else 4.0) * Bw * cfg.widths[0] * n   # minibatch: forward and first weight gradient
+        for l in range(len(cfg.widths) - 1):
+            w = cfg.widths[l] * cfg.widths[l + 1]
+            flop += (4.0 if l == 0 else 6.0) * Bw * w * n
+            byts += (8.0 if l == 0 else 12.0) * w * n
+    peak = MFMA_PEAK_TFLOPS if cfg.bf16 else 157.3
+    achieved = flop / (step_ms * 1e-3) / 1e12
+    ceiling = min(1.0, (flop / byts) / (peak * 1e12 / (HBM_PEAK_GBS * 1e9)))
+    return {"flop_per_step": flop, "min_hbm_bytes_per_step": byts, "achieved_tflops": achieved,
+            "peak_tflops": peak, "peak_kind": "bf16 MFMA" if cfg.bf16 else "fp32 vector",
+            "frac_of_peak": achieved / peak, "intensity_ceiling_frac": ceiling,
+            "frac_of_ceiling": achieved / peak / ceiling, "timed_over": "whole iteration (gradient + mix)"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -213,6 +259,7 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
                      "algorithmic_bytes_per_launch": launch_bytes, "avg_launch_ms": launch_ms},
+        "gradient": gradient_roofline(cfg, d, total_ms / K),
         "mix_fraction_of_step": mix_ms / (total_ms / K),
         "wall_s": wall,
         "final_mean_loss": final_loss, "final_consensus": final_cons,

@@ -52,9 +52,19 @@ __device__ __forceinline__ bf16x8 zero_frag()
     return __builtin_bit_cast(bf16x8, z);
 }
 
+// Transposed operand copies ("T copies": minibatch index fastest) are stored in MFMA fragment order so
+// that a wave fetches one operand of v_mfma_f32_32x32x16_bf16 as 1 KB of consecutive memory: rows
+// (features) in groups of 32, samples in groups of 16; inside a group first the half (samples 0-7,
+// 8-15), then the row, then the 8 samples.  Per worker a copy holds round_up(rows, 32) * Bp elements.
+__device__ __forceinline__ i64 tfrag_off(int r, int b, int Bp)
+{
+    return ((i64)(r >> 5) * (Bp >> 4) + (b >> 4)) * 512 + ((b >> 3) & 1) * 256 + (r & 31) * 8 + (b & 7);
+}
+__device__ __forceinline__ i64 tfrag_worker(int w, int rows, int Bp) { return (i64)w * ((rows + 31) / 32 * 32) * Bp; }
+
 // ------------------------------------------------------------------ input preparation
 // in: [n*B][F] fp32 or bf16 -> a [n][B][F] bf16 (only when the input is fp32) and
-// at [n][F][Bp] bf16 (transposed, zero padded).  32x32 tiles through LDS.
+// at = its T copy (zero padded samples).  32x32 tiles through LDS.
 template <bool IN_BF16>
 __global__ void __launch_bounds__(256)
 prep_input_kernel(const void *__restrict__ in, bf16_t *__restrict__ a, bf16_t *__restrict__ at, int B, int Bp, int F)
@@ -73,9 +83,17 @@ prep_input_kernel(const void *__restrict__ in, bf16_t *__restrict__ a, bf16_t *_
         tile[r][tx] = v;
     }
     __syncthreads();
-    for (int r = ty; r < 32; r += 8) {
-        const int f = f0 + r, b = b0 + tx;
-        if (f < F && b < Bp) at[((i64)w * F + f) * Bp + b] = tile[tx][r];
+    if (threadIdx.x < 128) {   // one 16-byte chunk (8 samples of one feature) per thread
+        const int r = threadIdx.x & 31, c = threadIdx.x >> 5;
+        const int f = f0 + r, b = b0 + 8 * c;
+        if (f < F) {
+            unsigned short e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = tile[8 * c + j][r];
+            u32x4 pk = {e[0] | ((unsigned)e[1] << 16), e[2] | ((unsigned)e[3] << 16), e[4] | ((unsigned)e[5] << 16),
+                        e[6] | ((unsigned)e[7] << 16)};
+            *reinterpret_cast<u32x4 *>(at + tfrag_worker(w, F, Bp) + tfrag_off(f, b, Bp)) = pk;
+        }
     }
 }
 
@@ -86,7 +104,7 @@ struct FwdArgs {
     i64 ld, woff, boff;
     int B, Bp, K, O;
     bf16_t *h;             // [n][B][O]   (hidden layers)
-    bf16_t *ht;            // [n][O][Bp]  (hidden layers)
+    bf16_t *ht;            // T copy of h (hidden layers)
     float *z;              // [n][B][O]   (last layer, fp32 logits)
 };
 
@@ -219,7 +237,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
                 }
                 if (bb < g.Bp) {
                     u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
-                    *reinterpret_cast<u32x2 *>(g.ht + ((i64)w * g.O + o) * g.Bp + bb) = p;
+                    *reinterpret_cast<u32x2 *>(g.ht + tfrag_worker(w, g.O, g.Bp) + tfrag_off(o, bb, g.Bp)) = p;
                 }
             }
         }
@@ -227,7 +245,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
 }
 
 // ------------------------------------------------------------- softmax cross-entropy
-// z fp32 [n][B][C] -> dz bf16 [n][B][C], dzt bf16 [n][C][Bp] (zero padded), loss[n].
+// z fp32 [n][B][C] -> dz bf16 [n][B][C], dzt = its T copy (zero padded samples), loss[n].
 __global__ void __launch_bounds__(256)
 softmax_xent_bf16_kernel(const float *__restrict__ z, const int *__restrict__ labels, int B, int Bp, int C,
                          bf16_t *__restrict__ dz, bf16_t *__restrict__ dzt, float *__restrict__ loss)
@@ -238,7 +256,7 @@ softmax_xent_bf16_kernel(const float *__restrict__ z, const int *__restrict__ la
     float local = 0.f;
     for (int b = threadIdx.x; b < Bp; b += 256) {
         if (b >= B) {
-            for (int c = 0; c < C; ++c) dzt[((i64)w * C + c) * Bp + b] = 0;
+            for (int c = 0; c < C; ++c) dzt[tfrag_worker(w, C, Bp) + tfrag_off(c, b, Bp)] = 0;
             continue;
         }
         const float *zb = z + ((i64)w * B + b) * C;
@@ -253,7 +271,7 @@ softmax_xent_bf16_kernel(const float *__restrict__ z, const int *__restrict__ la
         for (int c = 0; c < C; ++c) {
             const bf16_t v = f2bf((expf(zb[c] - lse) - (c == lab ? 1.f : 0.f)) * invB);
             dz[((i64)w * B + b) * C + c] = v;
-            dzt[((i64)w * C + c) * Bp + b] = v;
+            dzt[tfrag_worker(w, C, Bp) + tfrag_off(c, b, Bp)] = v;
         }
     }
     red[threadIdx.x] = local;
@@ -267,8 +285,8 @@ softmax_xent_bf16_kernel(const float *__restrict__ z, const int *__restrict__ la
 
 // ----------------------------------------------------------------------- weight gradient
 struct WgradArgs {
-    const bf16_t *dzt;   // [n][O][Bp]
-    const bf16_t *at;    // [n][K][Bp]
+    const bf16_t *dzt;   // T copy of dZ [n][B][O]
+    const bf16_t *at;    // T copy of A  [n][B][K]
     float *G;
     i64 ld, woff, boff;
     int Bp, K, O;
@@ -284,8 +302,9 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g)
     if (o_base >= g.O) return;
     const int o = o_base + l32;            // row this lane feeds into the A operand
     const bool o_ok = o < g.O;
-    const bf16_t *Ap = g.dzt + ((i64)w * g.O + (o_ok ? o : 0)) * g.Bp + 8 * half;
     const int steps = g.Bp / 16;
+    // fragment (32-row group, step st) of a T copy: 512 elements, this lane's 8 at 8 * lane
+    const bf16_t *Ap = g.dzt + tfrag_worker(w, g.O, g.Bp) + (i64)(o_base >> 5) * steps * 512 + lane * 8;
     float *Gw = g.G + (i64)w * g.ld + g.woff;
 
     if (blockIdx.x == 0) {   // bias gradient: gb[o] = sum_b dZ[b][o]
@@ -293,7 +312,7 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g)
         if (o_ok)
             for (int st = 0; st < steps; ++st)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) s += bf2f(Ap[st * 16 + j]);
+                for (int j = 0; j < 8; ++j) s += bf2f(Ap[st * 512 + j]);
         s += __shfl_down(s, 32, 64);
         if (half == 0 && o_ok) g.G[(i64)w * g.ld + g.boff + o] = s;
     }
@@ -303,13 +322,13 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g)
         if (k_base >= g.K) break;
         const int k = k_base + l32;
         const bool k_ok = k < g.K;
-        const bf16_t *Bp_ = g.at + ((i64)w * g.K + (k_ok ? k : 0)) * g.Bp + 8 * half;
+        const bf16_t *Bp_ = g.at + tfrag_worker(w, g.K, g.Bp) + (i64)(k_base >> 5) * steps * 512 + lane * 8;
         f32x16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.f;
         for (int st = 0; st < steps; ++st) {
-            const bf16x8 a = o_ok ? frag(Ap + st * 16) : zero_frag();
-            const bf16x8 b = k_ok ? frag(Bp_ + st * 16) : zero_frag();
+            const bf16x8 a = o_ok ? frag(Ap + st * 512) : zero_frag();
+            const bf16x8 b = k_ok ? frag(Bp_ + st * 512) : zero_frag();
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
         }
         if (k_ok) {
@@ -329,7 +348,7 @@ struct DgradArgs {
     i64 ld, woff;
     const bf16_t *hprev;  // [n][B][K] post-ReLU activations of the layer below (mask)
     bf16_t *dzp;          // [n][B][K]
-    bf16_t *dzpt;         // [n][K][Bp]
+    bf16_t *dzpt;         // T copy of dzp
     int B, Bp, K, O;
 };
 
@@ -464,7 +483,7 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
             }
             if (bb < g.Bp) {
                 u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
-                *reinterpret_cast<u32x2 *>(g.dzpt + ((i64)w * g.K + k) * g.Bp + bb) = p;
+                *reinterpret_cast<u32x2 *>(g.dzpt + tfrag_worker(w, g.K, g.Bp) + tfrag_off(k, bb, g.Bp)) = p;
             }
         }
     }
@@ -512,9 +531,13 @@ bias_grad_bf16_kernel(const bf16_t *__restrict__ dzt, int O, int Bp, float *__re
 {
     const int o = blockIdx.x * 256 + threadIdx.x, w = blockIdx.y;
     if (o >= O) return;
-    const bf16_t *p = dzt + ((i64)w * O + o) * Bp;
+    const bf16_t *p = dzt + tfrag_worker(w, O, Bp);
     float s = 0.f;
-    for (int b = 0; b < Bp; ++b) s += bf2f(p[b]);
+    for (int b = 0; b < Bp; b += 8) {
+        const bf16_t *q = p + tfrag_off(o, b, Bp);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += bf2f(q[j]);
+    }
     G[(i64)w * ld + boff + o] = s;
 }
 
@@ -527,8 +550,8 @@ bias_grad_bf16_kernel(const bf16_t *__restrict__ dzt, int O, int Bp, float *__re
 struct FusedArgs {
     float *X;
     i64 ld, woff;
-    const bf16_t *dzt;   // [n][O][Bp]
-    const bf16_t *at;    // [n][K][Bp]
+    const bf16_t *dzt;   // T copy of dZ [n][B][O]
+    const bf16_t *at;    // T copy of A  [n][B][K]
     int n, K, O, Bp;
     float w, gamma;
     double *partials;    // one per wave (CONS only)
@@ -544,8 +567,8 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
     // element v of this lane: row o0 + (v/4)*8 + half*4 + v%4, column k0 + l32
     float *xt = a.X + a.woff + (i64)(o0 + half * 4) * a.K + k0 + l32;
     auto row_off = [&](int v) { return (i64)((v >> 2) * 8 + (v & 3)) * a.K; };
-    const bf16_t *ap = a.dzt + (i64)(o0 + l32) * a.Bp + 8 * half;
-    const bf16_t *bp = a.at + (i64)(k0 + l32) * a.Bp + 8 * half;
+    const bf16_t *ap = a.dzt + (i64)(o0 >> 5) * steps * 512 + lane * 8;
+    const bf16_t *bp = a.at + (i64)(k0 >> 5) * steps * 512 + lane * 8;
 
     // xh: worker 0's original tile (the ring's wrap-around, and the shift of the consensus sums);
     // xn / xf: the tiles of workers i+1 and i+2, fetched one and two steps ahead
@@ -572,7 +595,7 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
         for (int v = 0; v < 16; ++v) acc[v] = 0.f;
         const bf16_t *ai = ap + (i64)i * a.O * a.Bp, *bi = bp + (i64)i * a.K * a.Bp;
         for (int st = 0; st < steps; ++st)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(ai + st * 16), frag(bi + st * 16), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(ai + st * 512), frag(bi + st * 512), acc, 0, 0, 0);
         float *dst = xt + (i64)i * a.ld;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -626,8 +649,9 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
         off += (b + 255) / 256 * 256;
         return q;
     };
+    auto r32 = [](int rows) { return (size_t)((rows + 31) / 32 * 32); };   // rows of a T copy
     if (!m.input_is_bf16) w.a0 = (bf16_t *)take(n * B * (size_t)m.widths[0] * 2);
-    w.at0 = (bf16_t *)take(n * (size_t)m.widths[0] * Bp * 2);
+    w.at0 = (bf16_t *)take(n * r32(m.widths[0]) * Bp * 2);
     w.h.assign(L + 1, nullptr);
     w.ht.assign(L + 1, nullptr);
     w.dzt.assign(L + 1, nullptr);
@@ -635,9 +659,9 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
     for (int l = 1; l <= L; ++l) {
         if (l < L) {
             w.h[l] = (bf16_t *)take(n * B * (size_t)m.widths[l] * 2);
-            w.ht[l] = (bf16_t *)take(n * (size_t)m.widths[l] * Bp * 2);
+            w.ht[l] = (bf16_t *)take(n * r32(m.widths[l]) * Bp * 2);
         }
-        w.dzt[l] = (bf16_t *)take(n * (size_t)m.widths[l] * Bp * 2);
+        w.dzt[l] = (bf16_t *)take(n * r32(m.widths[l]) * Bp * 2);
         widest = widest > (size_t)m.widths[l] ? widest : (size_t)m.widths[l];
     }
     w.logits = (float *)take(n * B * (size_t)m.widths[L] * 4);
