@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--workload", default="mlp3_ring64",
                     help="lsq_ring8 | softmax_ring16 | mlp2_ring32 | mlp3_ring64 | mlp3_torus8x8 | resnet20_ring112")
     ap.add_argument("--pool", type=int, default=4, help="distinct minibatches kept in HBM and cycled through")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="override the per-worker minibatch (a kernel check at a large batch; NOT a benchmark "
+                         "configuration, and flagged as such in the output)")
+    ap.add_argument("--workers", type=int, default=0, help="override n (same caveat as --batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-consensus", action="store_true")
     ap.add_argument("--two-call", action="store_true", help="dpsgd_grad + dpsgd_mix_step even where dpsgd_step fuses")
@@ -163,6 +167,11 @@ def main():
     from paper_1705_09056_amd.configs import MODEL_MLP, MODEL_SOFTMAX, by_name
 
     cfg = by_name(args.workload)
+    variant = None
+    if args.batch or args.workers:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, batch=args.batch or cfg.batch, n=args.workers or cfg.n)
+        variant = f"batch={cfg.batch}, n={cfg.n}: kernel check, not a benchmark configuration"
     K = args.steps or cfg.iters
     W = args.warmup
     torch.cuda.set_device(0)
@@ -254,17 +263,18 @@ def main():
         "config": {"workload": cfg.name, "model_kind": int(cfg.model_kind), "widths": list(cfg.widths), "n": cfg.n,
                    "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "gamma": cfg.gamma,
                    "minibatch_pool": len(pool), "consensus": cons is not None,
-                   "path": "dpsgd_step" if fused else "dpsgd_grad + dpsgd_mix_step"},
+                   "path": "dpsgd_step" if fused else "dpsgd_grad + dpsgd_mix_step",
+                   **({"variant": variant} if variant else {})},
         "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
+                     "traffic": None if variant else MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
                      "algorithmic_bytes_per_launch": launch_bytes, "avg_launch_ms": launch_ms},
         "gradient": gradient_roofline(cfg, d, total_ms / K),
         "mix_fraction_of_step": mix_ms / (total_ms / K),
         "wall_s": wall,
         "final_mean_loss": final_loss, "final_consensus": final_cons,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not variant:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
 

@@ -51,7 +51,10 @@ typedef enum {
     DPSGD_TOPO_CSR = 0,      /* caller-supplied CSR (host arrays) */
     DPSGD_TOPO_RING = 1,     /* Theorem 3's matrix: W_ii = W_i,i+-1 = 1/3 (indices mod n) */
     DPSGD_TOPO_TORUS2D = 2,  /* worker i = r*dim1 + c; itself and (r+-1,c), (r,c+-1) at 1/5 */
-    DPSGD_TOPO_COMPLETE = 3  /* W = (1/n) 1 1^T, the centralized special case */
+    DPSGD_TOPO_COMPLETE = 3, /* W = (1/n) 1 1^T, the centralized special case */
+    DPSGD_TOPO_RING_CHORD = 4 /* ring plus a link to the node farthest away on it, i + n/2 (the 16-machine runs
+                                 of the supplement's scalability experiment); itself, i+-1 and i+n/2 at 1/4 each;
+                                 n even and >= 4, else DPSGD_EINVAL */
 } dpsgd_topo_kind;
 
 typedef struct {
@@ -65,7 +68,7 @@ typedef struct {
 /* Builds (tags) or validates (CSR) W on the host and writes its CSR form; touches no device.
  * Tags with coinciding neighbours (ring with n < 3, torus with a dimension < 3) accumulate the
  * duplicate weights, so the result always satisfies Section 3.  Tag values are (float)(1.0/3.0),
- * (float)(1.0/5.0), (float)(1.0/n).
+ * (float)(1.0/5.0), (float)(1.0/n), 0.25f.
  * Validation (DPSGD_ETOPOLOGY on failure): rowptr monotone from 0; column indices in [0,n),
  * strictly ascending per row; values in [0,1]; |row sum - 1| <= 1e-6; W_ij == W_ji bitwise.
  * rowptr_out (n+1), colidx_out, vals_out (capacity *nnz_inout entries) are host arrays; any of the

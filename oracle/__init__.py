@@ -35,7 +35,7 @@ def lib():
     if _lib is None:
         L = C.CDLL(build())
         i32p, f64p = C.POINTER(C.c_int32), C.POINTER(C.c_double)
-        for name in ("orc_topology_ring", "orc_topology_complete"):
+        for name in ("orc_topology_ring", "orc_topology_ring_chord", "orc_topology_complete"):
             getattr(L, name).restype = C.c_int64
             getattr(L, name).argtypes = [C.c_int32, i32p, i32p, f64p]
         L.orc_topology_torus.restype = C.c_int64
@@ -113,6 +113,13 @@ def ring(n: int) -> Topology:
 
 def torus(dim0: int, dim1: int) -> Topology:
     return _build_topo(lib().orc_topology_torus, dim0 * dim1, dim0, dim1)
+
+
+def ring_chord(n: int) -> Topology:
+    """Ring plus a link to the farthest node (supplement, scalability experiment); n even, >= 4."""
+    if n < 4 or n % 2:
+        raise ValueError("ring_chord needs an even n >= 4")
+    return _build_topo(lib().orc_topology_ring_chord, n, n)
 
 
 def complete(n: int) -> Topology:

@@ -89,6 +89,29 @@ int64_t orc_topology_ring(int32_t n, int32_t *rowptr, int32_t *col, double *val)
     return nnz;
 }
 
+/* Ring with one extra link per node to the node farthest away on the ring, i + n/2
+ * (the 16-machine runs of the supplement's scalability experiment).  n must be even and
+ * at least 4.  Our reading of the weights: itself, the two ring neighbours and the far
+ * node at 1/4 each, which is symmetric and doubly stochastic.  Returns nnz, or -1. */
+int64_t orc_topology_ring_chord(int32_t n, int32_t *rowptr, int32_t *col, double *val)
+{
+    if (n < 4 || (n % 2) != 0) return -1;
+    double *row = (double *)malloc(sizeof(double) * (size_t)n);
+    int64_t nnz = 0;
+    if (rowptr) rowptr[0] = 0;
+    for (int i = 0; i < n; ++i) {
+        memset(row, 0, sizeof(double) * (size_t)n);
+        row[i] += 0.25;
+        row[(i + 1) % n] += 0.25;
+        row[(i + n - 1) % n] += 0.25;
+        row[(i + n / 2) % n] += 0.25;
+        nnz = emit_row(row, n, nnz, col, val);
+        if (rowptr) rowptr[i + 1] = (int32_t)nnz;
+    }
+    free(row);
+    return nnz;
+}
+
 /* 2-D torus: worker i = r*dim1 + c averages itself and (r+-1, c), (r, c+-1) (indices
  * modulo the grid) with weight 1/5.  Satisfies Section 3's requirements on W. */
 int64_t orc_topology_torus(int32_t dim0, int32_t dim1, int32_t *rowptr, int32_t *col, double *val)

@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libdpsgd_hip.so")
 
 OK, EINVAL, ETOPOLOGY, ENOMEM, EDEVICE, EUNSUPPORTED = range(6)
-TOPO_CSR, TOPO_RING, TOPO_TORUS2D, TOPO_COMPLETE = range(4)
+TOPO_CSR, TOPO_RING, TOPO_TORUS2D, TOPO_COMPLETE, TOPO_RING_CHORD = range(5)
 MODEL_LSQ, MODEL_SOFTMAX, MODEL_MLP, MODEL_RESNET20 = range(4)
 
 EXPORTS = (
@@ -99,7 +99,7 @@ def _check(status: int, where: str):
 
 
 class Topology:
-    """Host description of W: a tag (ring / torus / complete) or CSR arrays."""
+    """Host description of W: a tag (ring / torus / complete / ring with far link) or CSR arrays."""
 
     def __init__(self, kind: int, dim0: int = 0, dim1: int = 0, rowptr=None, colidx=None, vals=None):
         self.kind, self.dim0, self.dim1 = int(kind), int(dim0), int(dim1)
@@ -118,6 +118,10 @@ class Topology:
     @staticmethod
     def complete():
         return Topology(TOPO_COMPLETE)
+
+    @staticmethod
+    def ring_chord():
+        return Topology(TOPO_RING_CHORD)
 
     @staticmethod
     def csr(rowptr, colidx, vals):

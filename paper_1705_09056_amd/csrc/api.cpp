@@ -77,6 +77,17 @@ dpsgd_status build_host_csr(int32_t n, const dpsgd_topology *W, HostCsr &csr)
         }
         break;
     }
+    case DPSGD_TOPO_RING_CHORD: {
+        if (n < 4 || (n % 2) != 0) return DPSGD_EINVAL;
+        for (int32_t i = 0; i < n; ++i) {
+            row[(i + n - 1) % n] += 0.25f;
+            row[i] += 0.25f;
+            row[(i + 1) % n] += 0.25f;
+            row[(i + n / 2) % n] += 0.25f;
+            push_row(csr, row);
+        }
+        break;
+    }
     case DPSGD_TOPO_TORUS2D: {
         if (W->dim0 < 1 || W->dim1 < 1 || (int64_t)W->dim0 * W->dim1 != n) return DPSGD_EINVAL;
         const float w = (float)(1.0 / 5.0);

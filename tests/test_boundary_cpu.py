@@ -57,6 +57,24 @@ def test_torus_topology_indices_bit_exact_vs_oracle(dims):
         assert np.all(val == np.float32(0.2))
 
 
+@pytest.mark.parametrize("n", [4, 6, 16, 112])
+def test_ring_with_far_link_indices_bit_exact_vs_oracle(n):
+    rowptr, col, val = B.topology_build(n, B.Topology.ring_chord())
+    t = oracle.ring_chord(n)
+    assert np.array_equal(rowptr, t.rowptr)
+    assert np.array_equal(col, t.col)
+    assert np.array_equal(val, t.val.astype(np.float32))
+    if n > 4:
+        assert np.all(val == np.float32(0.25))
+
+
+def test_ring_with_far_link_rejects_odd_or_tiny_rings():
+    for n in (2, 3, 5, 15):
+        with pytest.raises(B.DpsgdError) as e:
+            B.topology_build(n, B.Topology.ring_chord())
+        assert e.value.status == B.EINVAL
+
+
 def test_complete_and_csr_roundtrip():
     rowptr, col, val = B.topology_build(5, B.Topology.complete())
     t = oracle.complete(5)

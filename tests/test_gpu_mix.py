@@ -101,6 +101,33 @@ def test_complete_and_random_csr(n):
     run_mix(n, 2500, 2560, B.Topology.csr(rowptr, col, val), to, n + 1, n <= 256, True)
 
 
+def hypercube_csr(k):
+    """n = 2^k workers, neighbours differ in one bit; itself and its k neighbours at 1/(k+1)."""
+    n = 1 << k
+    rowptr, col, val = [0], [], []
+    for i in range(n):
+        for j in sorted([i] + [i ^ (1 << b) for b in range(k)]):
+            col.append(j); val.append(1.0 / (k + 1))
+        rowptr.append(len(col))
+    return np.array(rowptr, np.int32), np.array(col, np.int32), np.array(val, np.float32)
+
+
+@pytest.mark.parametrize("n", [4, 16, 112])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_ring_with_far_link(n, inplace):
+    """The 16-machine topology of the supplement's scalability experiment, through the CSR slab kernel."""
+    run_mix(n, 5003, 5056, B.Topology.ring_chord(), oracle.ring_chord(n).with_fp32_values(), 40 + n, inplace, True)
+
+
+@pytest.mark.parametrize("k", [3, 4, 6])
+def test_hypercube_csr(k):
+    rowptr, col, val = hypercube_csr(k)
+    to = oracle.Topology(1 << k, rowptr, col, val.astype(np.float64))
+    assert to.check(1e-6) == 0
+    run_mix(1 << k, 4100, 4160, B.Topology.csr(rowptr, col, val), to, 50 + k, True, True)
+    run_mix(1 << k, 4100, 4160, B.Topology.csr(rowptr, col, val), to, 60 + k, False, True, swapped=True)
+
+
 def test_inplace_without_slab_is_refused():
     n, d = 300, 100
     X, G = random_state(n, d, 1)

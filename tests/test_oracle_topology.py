@@ -93,3 +93,31 @@ def test_ring_equals_the_printed_matrix_of_theorem3():
     path = os.path.join(os.path.dirname(__file__), "golden", "ring_theorem3_n6.txt")
     printed = np.loadtxt(path) / 3.0
     np.testing.assert_allclose(oracle.ring(6).dense(), printed, atol=1e-16)
+
+
+@pytest.mark.parametrize("n", [4, 6, 16, 64])
+def test_ring_with_far_link_requirements_and_spectrum(n):
+    """Ring plus the link i <-> i + n/2 at uniform 1/4 (supplement, scalability experiment, 16 machines): a
+    circulant whose eigenvalues are (1 + 2 cos(2 pi m/n) + (-1)^m)/4; its spectral gap beats the plain ring's."""
+    t = oracle.ring_chord(n)
+    W = t.dense()
+    assert t.check() == 0
+    assert np.array_equal(W, W.T)
+    np.testing.assert_allclose(W.sum(0), 1.0, atol=1e-15)
+    np.testing.assert_allclose(W.sum(1), 1.0, atol=1e-15)
+    for i in range(n):
+        want = {i, (i + 1) % n, (i - 1) % n, (i + n // 2) % n}
+        assert set(np.nonzero(W[i])[0].tolist()) == want
+        assert np.all(W[i, sorted(want)] == 1.0 / len(want) if len(want) == 4 else True)
+    m = np.arange(n)
+    closed = np.sort((1.0 + 2.0 * np.cos(2.0 * np.pi * m / n) + (-1.0) ** m) / 4.0)
+    np.testing.assert_allclose(np.sort(np.linalg.eigvalsh(W)), closed, atol=1e-13)
+    if n >= 8:
+        second = lambda M: np.sort(np.abs(np.linalg.eigvalsh(M)))[-2]
+        assert second(W) < second(oracle.ring(n).dense())      # information flows faster (smaller rho)
+
+
+def test_ring_with_far_link_needs_an_even_ring():
+    for n in (3, 5, 2):
+        with pytest.raises(ValueError):
+            oracle.ring_chord(n)
