@@ -243,12 +243,16 @@ struct WgradMfmaArgs {
     float *part;           // [n][splits][CO*CIr*9 + 1]
 };
 
+constexpr int kWgradStage = 5;   // 16-byte units of a band's source rows a thread holds while they are in flight
+
+__host__ __device__ constexpr int wgrad_channel_pitch(int plane) { return (plane + 119) / 128 * 128 + 8; }
+
 template <int CI, int CO, int STRIDE>
 __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
 {
     constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16, RB = 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t *band = reinterpret_cast<bf16_t *>(smem);   // [CI][RB + 2][WPAD]
+    bf16_t *band = reinterpret_cast<bf16_t *>(smem);   // [CI] planes of CP elements, each [ROWS][PLANES][WPAD]
     const int sp = blockIdx.x, w = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int mi = wave % WM, kq = wave / WM;
@@ -257,6 +261,9 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
     // and the odd input columns (an output pixel x reads columns 2x-1, 2x, 2x+1 = odd[x-1], even[x], odd[x]).
     constexpr int PLANES = STRIDE;
     const int WPAD = a.Wo + 16, ROWS = (RB - 1) * STRIDE + 3;
+    // channel pitch = 8 elements (16 bytes) past a multiple of 256 bytes: the 16 lanes of an operand read
+    // (16 channels, 16 bytes each) then fall into 16 different groups of 4 banks
+    const int CP = wgrad_channel_pitch(ROWS * PLANES * WPAD);
     const int psz = CO * a.CIr * 9 + 1;
 
     f32x4 acc[NTI][9];
@@ -268,39 +275,66 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
 
     // zero the column pads once; staging never writes them
     for (int u = tid; u < CI * ROWS * PLANES * 2; u += 256) {
-        const int side = u & 1, row = u >> 1;
+        const int side = u & 1, row = (u >> 1) % (ROWS * PLANES), ci = (u >> 1) / (ROWS * PLANES);
         u32x4 z = {0u, 0u, 0u, 0u};
-        *reinterpret_cast<u32x4 *>(band + row * WPAD + (side ? 8 + a.Wo : 0)) = z;
+        *reinterpret_cast<u32x4 *>(band + ci * CP + row * WPAD + (side ? 8 + a.Wo : 0)) = z;
     }
 
     const int x8n = a.W / 8;
     const int kb = RB * a.Wo / 32;   // k-steps per band
-    for (int b = sp; b < a.B; b += a.splits) {
-        const i64 img = (i64)w * a.B + b;
-        for (int y0 = 0; y0 < a.Ho; y0 += RB) {
+    // The bands (8 output rows of one image) this workgroup handles, in order; the source rows of band
+    // j+1 are fetched into registers while band j is multiplied.
+    const int bands_per_img = a.Ho / RB;
+    const int nb = ((a.B - sp + a.splits - 1) / a.splits) * bands_per_img;
+    const int chunks = CI * ROWS * x8n;   // 16-byte units of a band's source rows, <= kWgradStage * 256
+    u32x4 stg[kWgradStage];
+    auto fetch_band = [&](int j) {
+        const i64 img = (i64)w * a.B + sp + (j / bands_per_img) * a.splits;
+        const int y0 = (j % bands_per_img) * RB;
+#pragma unroll
+        for (int q = 0; q < kWgradStage; ++q) {
+            const int u = tid + 256 * q;
+            const int x8 = u % x8n, r = (u / x8n) % ROWS, ci = u / (x8n * ROWS);
+            const int iy = y0 * STRIDE - 1 + r;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (u < chunks && ci < a.CIr && iy >= 0 && iy < a.H)
+                v = *reinterpret_cast<const u32x4 *>(a.inT + ((img * a.CIr + ci) * a.H + iy) * a.W + x8 * 8);
+            stg[q] = v;
+        }
+    };
+    if (nb > 0) fetch_band(0);
+    for (int j = 0; j < nb; ++j) {
+        const i64 img = (i64)w * a.B + sp + (j / bands_per_img) * a.splits;
+        {
+            const int y0 = (j % bands_per_img) * RB;
             __syncthreads();   // previous band fully consumed
-            for (int u = tid; u < CI * ROWS * x8n; u += 256) {
+#pragma unroll
+            for (int q = 0; q < kWgradStage; ++q) {
+                const int u = tid + 256 * q;
+                if (u >= chunks) break;
                 const int x8 = u % x8n, r = (u / x8n) % ROWS, ci = u / (x8n * ROWS);
-                const int iy = y0 * STRIDE - 1 + r;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (ci < a.CIr && iy >= 0 && iy < a.H)
-                    v = *reinterpret_cast<const u32x4 *>(a.inT + ((img * a.CIr + ci) * a.H + iy) * a.W + x8 * 8);
+                const u32x4 v = stg[q];
                 if (STRIDE == 1) {
-                    *reinterpret_cast<u32x4 *>(band + (ci * ROWS + r) * WPAD + 8 + x8 * 8) = v;
+                    *reinterpret_cast<u32x4 *>(band + ci * CP + r * WPAD + 8 + x8 * 8) = v;
                 } else {
                     const u32x2 ev = {(v.x & 0xffffu) | (v.y << 16), (v.z & 0xffffu) | (v.w << 16)};
                     const u32x2 od = {(v.x >> 16) | (v.y & 0xffff0000u), (v.z >> 16) | (v.w & 0xffff0000u)};
-                    bf16_t *base = band + ((ci * ROWS + r) * 2) * WPAD + 8 + x8 * 4;
+                    bf16_t *base = band + ci * CP + (r * 2) * WPAD + 8 + x8 * 4;
                     *reinterpret_cast<u32x2 *>(base) = ev;
                     *reinterpret_cast<u32x2 *>(base + WPAD) = od;
                 }
             }
             __syncthreads();
+            if (j + 1 < nb) fetch_band(j + 1);
+            // this lane's 8 delta pixels of k-step ks: pixels 32 ks + 8 g .. + 7 of the band (rows are contiguous)
+            const bf16_t *dband = a.doutT + ((img * CO + mi * 16 + n16) * a.Ho + y0) * a.Wo + 8 * g;
+            u32x4 av_next = {0u, 0u, 0u, 0u};
+            if (kq < kb) av_next = *reinterpret_cast<const u32x4 *>(dband + 32 * kq);
             for (int ks = kq; ks < kb; ks += WK) {
                 const int q = 32 * ks + 8 * g;          // first of this lane's 8 pixels inside the band
                 const int yy = q / a.Wo, x = q % a.Wo;
-                const u32x4 av = *reinterpret_cast<const u32x4 *>(
-                    a.doutT + ((img * CO + mi * 16 + n16) * a.Ho + y0 + yy) * a.Wo + x);
+                const u32x4 av = av_next;
+                if (ks + WK < kb) av_next = *reinterpret_cast<const u32x4 *>(dband + 32 * (ks + WK));
                 bsum += (bf2f((bf16_t)(av.x & 0xffff)) + bf2f((bf16_t)(av.x >> 16))) +
                         (bf2f((bf16_t)(av.y & 0xffff)) + bf2f((bf16_t)(av.y >> 16))) +
                         (bf2f((bf16_t)(av.z & 0xffff)) + bf2f((bf16_t)(av.z >> 16))) +
@@ -312,7 +346,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
                     for (int ky = 0; ky < 3; ++ky) {
                         u32x4 l, d, r;   // the operand for kx = 0, 1, 2
                         if (STRIDE == 1) {
-                            const bf16_t *row = band + ((t * 16 + n16) * ROWS + yy + ky) * WPAD + 8 + x;
+                            const bf16_t *row = band + (t * 16 + n16) * CP + (yy + ky) * WPAD + 8 + x;
                             d = *reinterpret_cast<const u32x4 *>(row);
                             const unsigned prev = *reinterpret_cast<const unsigned *>(row - 2);
                             const unsigned next = *reinterpret_cast<const unsigned *>(row + 8);
@@ -325,7 +359,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
                             r.z = l.w;
                             r.w = __builtin_amdgcn_alignbit(next, d.w, 16);
                         } else {
-                            const bf16_t *even = band + (((t * 16 + n16) * ROWS + 2 * yy + ky) * 2) * WPAD + 8 + x;
+                            const bf16_t *even = band + (t * 16 + n16) * CP + ((2 * yy + ky) * 2) * WPAD + 8 + x;
                             const bf16_t *odd = even + WPAD;
                             d = *reinterpret_cast<const u32x4 *>(even);
                             r = *reinterpret_cast<const u32x4 *>(odd);
@@ -407,6 +441,7 @@ bool wgrad_mfma_ok(const ConvDesc &c)
     const int cip = (c.Ci + 15) / 16 * 16;
     if (!pow2_channels(c.Co) || !pow2_channels(cip)) return false;
     if (c.Ho % 8 || c.Wo % 8 || c.W % 8 || c.W > 64) return false;
+    if (cip * (7 * c.stride + 3) * (c.W / 8) > kWgradStage * 256) return false;   // a band's source rows fit the staging registers
     if (c.stride == 1) return cip == c.Co;
     return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && c.W == 2 * c.Wo && c.H == 2 * c.Ho;
 }
@@ -415,7 +450,7 @@ template <int CI, int CO, int STRIDE>
 dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs &a, float *G)
 {
     constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16;
-    size_t shm = (size_t)CI * (7 * STRIDE + 3) * STRIDE * (a.Wo + 16) * sizeof(bf16_t);
+    size_t shm = (size_t)CI * wgrad_channel_pitch((7 * STRIDE + 3) * STRIDE * (a.Wo + 16)) * sizeof(bf16_t);
     const size_t red = (size_t)(WK - 1) * WM * NTI * 9 * 256 * sizeof(float);
     if (red > shm) shm = red;
     if (shm < 64) shm = 64;
