@@ -243,19 +243,27 @@ struct WgradMfmaArgs {
     float *part;           // [n][splits][CO*CIr*9 + 1]
 };
 
-constexpr int kWgradStage = 5;   // 16-byte units of a band's source rows a thread holds while they are in flight
+// 16-byte units of a band's source rows a thread holds while they are in flight (10 rows at stride 1, 17 at stride 2)
+__host__ __device__ constexpr int wgrad_stage(int stride) { return stride == 1 ? 3 : 5; }
 
 __host__ __device__ constexpr int wgrad_channel_pitch(int plane) { return (plane + 119) / 128 * 128 + 8; }
 
+// With 64 x 64 channels a wave that kept all four input-channel tiles would need 144 accumulator
+// registers (one wave per SIMD); two groups of four waves split them instead.
+constexpr int wgrad_wave_groups(int ci, int co) { return (ci >= 64 && co >= 64) ? 2 : 1; }
+
 template <int CI, int CO, int STRIDE>
-__global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
+__global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4 : 2)) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
 {
-    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16, RB = 8;
+    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, RB = 8;
+    constexpr int WT = wgrad_wave_groups(CI, CO), NTI = CI / 16 / WT, NT = 256 * WT;
+    constexpr int kWgradStage = wgrad_stage(STRIDE);
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *band = reinterpret_cast<bf16_t *>(smem);   // [CI] planes of CP elements, each [ROWS][PLANES][WPAD]
     const int sp = blockIdx.x, w = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int mi = wave % WM, kq = wave / WM;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, th = tid >> 8;
+    const int mi = wave % WM, kq = wave / WM;   // output-channel tile, share of the k-steps
+    const int t0 = th * NTI;                    // first input-channel tile of this wave
     const int n16 = lane & 15, g = lane >> 4;
     // stride 1: one plane per (channel, row), [8 zeros | W | 8 zeros].  stride 2: two planes, the even
     // and the odd input columns (an output pixel x reads columns 2x-1, 2x, 2x+1 = odd[x-1], even[x], odd[x]).
@@ -274,7 +282,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
     float bsum = 0.f;
 
     // zero the column pads once; staging never writes them
-    for (int u = tid; u < CI * ROWS * PLANES * 2; u += 256) {
+    for (int u = tid; u < CI * ROWS * PLANES * 2; u += NT) {
         const int side = u & 1, row = (u >> 1) % (ROWS * PLANES), ci = (u >> 1) / (ROWS * PLANES);
         u32x4 z = {0u, 0u, 0u, 0u};
         *reinterpret_cast<u32x4 *>(band + ci * CP + row * WPAD + (side ? 8 + a.Wo : 0)) = z;
@@ -293,7 +301,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
         const int y0 = (j % bands_per_img) * RB;
 #pragma unroll
         for (int q = 0; q < kWgradStage; ++q) {
-            const int u = tid + 256 * q;
+            const int u = tid + NT * q;
             const int x8 = u % x8n, r = (u / x8n) % ROWS, ci = u / (x8n * ROWS);
             const int iy = y0 * STRIDE - 1 + r;
             u32x4 v = {0u, 0u, 0u, 0u};
@@ -310,7 +318,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
             __syncthreads();   // previous band fully consumed
 #pragma unroll
             for (int q = 0; q < kWgradStage; ++q) {
-                const int u = tid + 256 * q;
+                const int u = tid + NT * q;
                 if (u >= chunks) break;
                 const int x8 = u % x8n, r = (u / x8n) % ROWS, ci = u / (x8n * ROWS);
                 const u32x4 v = stg[q];
@@ -335,10 +343,11 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
                 const int yy = q / a.Wo, x = q % a.Wo;
                 const u32x4 av = av_next;
                 if (ks + WK < kb) av_next = *reinterpret_cast<const u32x4 *>(dband + 32 * (ks + WK));
-                bsum += (bf2f((bf16_t)(av.x & 0xffff)) + bf2f((bf16_t)(av.x >> 16))) +
-                        (bf2f((bf16_t)(av.y & 0xffff)) + bf2f((bf16_t)(av.y >> 16))) +
-                        (bf2f((bf16_t)(av.z & 0xffff)) + bf2f((bf16_t)(av.z >> 16))) +
-                        (bf2f((bf16_t)(av.w & 0xffff)) + bf2f((bf16_t)(av.w >> 16)));
+                if (th == 0)
+                    bsum += (bf2f((bf16_t)(av.x & 0xffff)) + bf2f((bf16_t)(av.x >> 16))) +
+                            (bf2f((bf16_t)(av.y & 0xffff)) + bf2f((bf16_t)(av.y >> 16))) +
+                            (bf2f((bf16_t)(av.z & 0xffff)) + bf2f((bf16_t)(av.z >> 16))) +
+                            (bf2f((bf16_t)(av.w & 0xffff)) + bf2f((bf16_t)(av.w >> 16)));
                 const bf16x8 afrag = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
                 for (int t = 0; t < NTI; ++t) {
@@ -346,7 +355,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
                     for (int ky = 0; ky < 3; ++ky) {
                         u32x4 l, d, r;   // the operand for kx = 0, 1, 2
                         if (STRIDE == 1) {
-                            const bf16_t *row = band + (t * 16 + n16) * CP + (yy + ky) * WPAD + 8 + x;
+                            const bf16_t *row = band + ((t0 + t) * 16 + n16) * CP + (yy + ky) * WPAD + 8 + x;
                             d = *reinterpret_cast<const u32x4 *>(row);
                             const unsigned prev = *reinterpret_cast<const unsigned *>(row - 2);
                             const unsigned next = *reinterpret_cast<const unsigned *>(row + 8);
@@ -359,7 +368,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
                             r.z = l.w;
                             r.w = __builtin_amdgcn_alignbit(next, d.w, 16);
                         } else {
-                            const bf16_t *even = band + (t * 16 + n16) * CP + ((2 * yy + ky) * 2) * WPAD + 8 + x;
+                            const bf16_t *even = band + ((t0 + t) * 16 + n16) * CP + ((2 * yy + ky) * 2) * WPAD + 8 + x;
                             const bf16_t *odd = even + WPAD;
                             d = *reinterpret_cast<const u32x4 *>(even);
                             r = *reinterpret_cast<const u32x4 *>(odd);
@@ -407,7 +416,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
     if (kq == 0) {
 #pragma unroll
         for (int t = 0; t < NTI; ++t) {
-            const int ci = t * 16 + n16;
+            const int ci = (t0 + t) * 16 + n16;
             if (ci < a.CIr)
 #pragma unroll
                 for (int k = 0; k < 9; ++k)
@@ -417,7 +426,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
     }
     // bias: sum of every delta element this workgroup saw
     for (int off = 32; off > 0; off >>= 1) bsum += __shfl_down(bsum, off, 64);
-    if (lane == 0) red[wave] = bsum;
+    if (lane == 0 && th == 0) red[wave] = bsum;
     __syncthreads();
     if (tid == 0) out[psz - 1] = (red[0] + red[1]) + (red[2] + red[3]);
 }
@@ -441,7 +450,7 @@ bool wgrad_mfma_ok(const ConvDesc &c)
     const int cip = (c.Ci + 15) / 16 * 16;
     if (!pow2_channels(c.Co) || !pow2_channels(cip)) return false;
     if (c.Ho % 8 || c.Wo % 8 || c.W % 8 || c.W > 64) return false;
-    if (cip * (7 * c.stride + 3) * (c.W / 8) > kWgradStage * 256) return false;   // a band's source rows fit the staging registers
+    if (cip * (7 * c.stride + 3) * (c.W / 8) > wgrad_stage(c.stride) * 256) return false;   // a band's source rows fit the staging registers
     if (c.stride == 1) return cip == c.Co;
     return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && c.W == 2 * c.Wo && c.H == 2 * c.Ho;
 }
@@ -449,12 +458,12 @@ bool wgrad_mfma_ok(const ConvDesc &c)
 template <int CI, int CO, int STRIDE>
 dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs &a, float *G)
 {
-    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, NTI = CI / 16;
+    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, WT = wgrad_wave_groups(CI, CO), NTI = CI / 16 / WT;
     size_t shm = (size_t)CI * wgrad_channel_pitch((7 * STRIDE + 3) * STRIDE * (a.Wo + 16)) * sizeof(bf16_t);
     const size_t red = (size_t)(WK - 1) * WM * NTI * 9 * 256 * sizeof(float);
     if (red > shm) shm = red;
     if (shm < 64) shm = 64;
-    hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256), shm,
+    hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256 * WT), shm,
                        ctx->stream, a);
     const int psz = CO * a.CIr * 9 + 1;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((psz + 255) / 256), (unsigned)ctx->n), dim3(256), 0, ctx->stream,
