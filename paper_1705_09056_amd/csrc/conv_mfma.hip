@@ -443,7 +443,14 @@ wgrad_reduce_kernel(const float *__restrict__ part, int splits, int psz, float *
     G[(i64)w * ld + (e == psz - 1 ? b_off : w_off + e)] = s;
 }
 
-int wgrad_splits(int B) { return B < 8 ? B : 8; }
+// Workgroups that share one worker's minibatch (each writes a partial sum of the whole weight gradient): few when
+// the gradient is large (the partials are HBM traffic), more when the source rows of a band are many.
+int wgrad_splits(int B, int co, int stride)
+{
+    int m = co >= 64 ? 2 : (co >= 32 ? 4 : 8);
+    if (stride == 2 && m < 8) m *= 2;
+    return B < m ? B : m;
+}
 
 bool wgrad_mfma_ok(const ConvDesc &c)
 {
@@ -566,7 +573,7 @@ size_t conv_pack_bytes(const ConvDesc &c, bool dgrad)
 size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B)
 {
     if (!wgrad_mfma_ok(c)) return 0;
-    return (size_t)wgrad_splits(B) * ((size_t)c.Co * c.Ci * 9 + 1) * sizeof(float);
+    return (size_t)wgrad_splits(B, c.Co, c.stride) * ((size_t)c.Co * c.Ci * 9 + 1) * sizeof(float);
 }
 
 dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d)
@@ -629,7 +636,7 @@ dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor i
     }
     WgradMfmaArgs a{};
     a.inT = in.t; a.doutT = dout.t; a.H = c.H; a.W = c.W; a.Ho = c.Ho; a.Wo = c.Wo; a.B = B; a.CIr = c.Ci;
-    a.splits = wgrad_splits(B); a.part = partials;
+    a.splits = wgrad_splits(B, c.Co, c.stride); a.part = partials;
     const int cip = (c.Ci + 15) / 16 * 16;
     if (c.stride == 1) {
         if (cip == 16) return launch_wgrad<16, 16, 1>(ctx, c, a, G);
