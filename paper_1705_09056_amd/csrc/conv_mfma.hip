@@ -5,14 +5,15 @@
 // Forward and data gradient share one kernel: out(y,x,o) = sum_{tap,c} P(y*S+ky-1, x*S+kx-1, c) *
 // Weff[o][c][tap], where P is the source tensor (zero outside; for the data gradient of a stride-2
 // conv the delta with zeros inserted between its pixels) and Weff the conv's weights (for the data
-// gradient: channels transposed, taps reversed).  A workgroup owns 8 output rows of one image: it
-// stages the (8-1)*S+3 source rows with their halo in LDS (NHWC, pixel pitch padded by 16 bytes so
-// that 16 lanes reading 16 bytes each spread over all banks), keeps its slice of the packed weights
-// in registers for the whole tile, and issues v_mfma_f32_16x16x32_bf16: A = 16 consecutive output
-// pixels x 32 contraction values (8 channels of one tap per lane, one 16-byte LDS read), B = 32 x
-// 16 output channels.  Accumulator register i of lane l is (pixel 4*(l/16)+i, channel l%16), so a
-// lane writes 4 consecutive pixels of one channel: one 8-byte store into the channel-major copy,
-// four 2-byte stores into the NHWC tensor.
+// gradient: channels transposed, taps reversed).  Tensors are channel-major in memory; a workgroup
+// owns 8 output rows of one image: it stages the (8-1)*S+3 source rows with their halo in LDS
+// pixel-major (the transposition happens on the way in: a thread fetches 8 pixels of two channels
+// and writes 8 channel pairs; pixel pitch padded by 16 bytes so that 16 lanes reading 16 bytes each
+// spread over all banks), keeps its slice of the packed weights in registers for the whole tile, and
+// issues v_mfma_f32_16x16x32_bf16: A = 16 consecutive output pixels x 32 contraction values (8
+// channels of one tap per lane, one 16-byte LDS read), B = 32 x 16 output channels.  Accumulator
+// register i of lane l is (pixel 4*(l/16)+i, channel l%16), so a lane writes 4 consecutive pixels
+// of one channel with one 8-byte store.
 #include "resnet_common.h"
 
 namespace dpsgd {
@@ -60,15 +61,15 @@ pack_weights_kernel(const float *__restrict__ X, i64 ld, ConvDesc c, int CI, int
 
 // --------------------------------------------------------------- forward / data gradient
 struct ConvMfmaArgs {
-    const bf16_t *src;      // NHWC [n*B][Hs][Ws][CI]
+    const bf16_t *src;      // [n*B][CI][Hs][Ws]; CI == 8 (stem): the image, pixel-major [n*B][Hs][Ws][8]
     int Hs, Ws;
     const bf16_t *wpack;    // [n][KS][CO/16][64][8]
-    bf16_t *dst, *dstT;     // NHWC [n*B][Hd][Wd][CO], channel-major [n*B][CO][Hd][Wd]
+    bf16_t *dstT;           // [n*B][CO][Hd][Wd]
     int Hd, Wd, lw, B;      // lw = log2(Wd)
     const float *X;         // forward: scalar bias at X[w*ld + b_off]
     i64 ld, b_off;
-    ShortcutRef sc;         // forward: block input; data gradient: delta of the block output (channel-major copy used)
-    const bf16_t *actT;     // data gradient: channel-major activation whose sign masks the result (shape of dst)
+    ShortcutRef sc;         // forward: block input; data gradient: delta of the block output
+    const bf16_t *actT;     // data gradient: activation whose sign masks the result (shape of dst)
 };
 
 template <int CI, int CO, int STRIDE, int DILATE, bool DGRAD>
@@ -76,7 +77,7 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 {
     constexpr int KS = ksteps(CI), NT = CO / 16, WC = wave_cols(CI, CO), NTW = NT / WC, WP = 4 / WC;
     constexpr int PP = CI + 8;   // LDS pixel pitch (bf16 elements)
-    constexpr int TH = 8, C8 = CI / 8;
+    constexpr int TH = 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *patch = reinterpret_cast<bf16_t *>(smem);
     const int band = blockIdx.x, b = blockIdx.y, w = blockIdx.z;
@@ -88,32 +89,77 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     const int wc = wave % WC, wp = wave / WC;
     const int n16 = lane & 15, g = lane >> 4;
 
-    // stage the source rows (with halo, zeros outside / between dilated pixels): a wave per patch row,
-    // a lane per 16-byte unit of the row
-    {
+    // stage the source rows (with halo, zeros outside / between dilated pixels)
+    if (CI == 8) {   // pixel-major image: a wave per patch row, a lane per pixel (16 bytes)
         const bf16_t *src = a.src + img * a.Hs * a.Ws * CI;
-        const int row_units = PC * C8;
         for (int pr = wave; pr < PR; pr += 4) {
-            int vr = y0 * STRIDE - 1 + pr;
-            bool row_ok = vr >= 0;
+            const int vr = y0 * STRIDE - 1 + pr;
+            const bool row_ok = vr >= 0 && vr < a.Hs;
+            for (int pc = lane; pc < PC; pc += 64) {
+                const int vc = pc - 1;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (row_ok && vc >= 0 && vc < a.Ws) v = *reinterpret_cast<const u32x4 *>(src + (vr * a.Ws + vc) * CI);
+                *reinterpret_cast<u32x4 *>(patch + (pr * PC + pc) * PP) = v;
+            }
+        }
+    } else {
+        // channel-major source: a task = (channel pair j, patch row pr, 8 source pixels xc); the thread
+        // fetches the 8 pixels of both channels (16 bytes each) and writes 8 channel pairs
+        constexpr int CP2 = CI / 2, FT = 4;   // FT tasks per thread are in flight at once
+        const bf16_t *src = a.src + img * CI * a.Hs * a.Ws;
+        const int x8n = a.Ws >> 3, plane = a.Hs * a.Ws;
+        const int ntask = CP2 * x8n * PR;
+        u32x4 fa[FT], fb[FT];
+        auto decode = [&](int task, int &j, int &pr, int &xc, int &vr) {
+            j = task % CP2;
+            const int rest = task / CP2;
+            xc = rest % x8n;
+            pr = rest / x8n;
+            vr = y0 * STRIDE - 1 + pr;
+            bool ok = task < ntask && vr >= 0;
             if (DILATE == 2) {
-                row_ok = row_ok && !(vr & 1);
+                ok = ok && !(vr & 1);
                 vr >>= 1;
             }
-            row_ok = row_ok && vr < a.Hs;
-            for (int u = lane; u < row_units; u += 64) {
-                const int c8 = u % C8, pc = u / C8;
-                int vc = pc - 1;
-                bool ok = row_ok && vc >= 0;
-                if (DILATE == 2) {
-                    ok = ok && !(vc & 1);
-                    vc >>= 1;
+            return ok && vr < a.Hs;
+        };
+        auto issue = [&](int round) {
+#pragma unroll
+            for (int q = 0; q < FT; ++q) {
+                int j, pr, xc, vr;
+                fa[q] = (u32x4){0u, 0u, 0u, 0u};
+                fb[q] = fa[q];
+                if (decode(tid + 256 * (round * FT + q), j, pr, xc, vr)) {
+                    const bf16_t *p = src + (2 * j) * plane + vr * a.Ws + 8 * xc;
+                    fa[q] = *reinterpret_cast<const u32x4 *>(p);
+                    fb[q] = *reinterpret_cast<const u32x4 *>(p + plane);
                 }
-                ok = ok && vc < a.Ws;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (ok) v = *reinterpret_cast<const u32x4 *>(src + (vr * a.Ws + vc) * CI + c8 * 8);
-                *reinterpret_cast<u32x4 *>(patch + (pr * PC + pc) * PP + c8 * 8) = v;
             }
+        };
+        auto commit = [&](int round) {
+#pragma unroll
+            for (int q = 0; q < FT; ++q) {
+                int j, pr, xc, vr;
+                if (!decode(tid + 256 * (round * FT + q), j, pr, xc, vr)) continue;
+                // source pixel 8 xc + i sits at patch column (8 xc + i) * DILATE + 1
+                unsigned *dst = reinterpret_cast<unsigned *>(patch + (pr * PC + 8 * xc * DILATE + 1) * PP + 2 * j);
+                constexpr int step = DILATE * PP / 2;   // dwords between consecutive source pixels
+                const unsigned lo[4] = {fa[q].x, fa[q].y, fa[q].z, fa[q].w}, hi[4] = {fb[q].x, fb[q].y, fb[q].z, fb[q].w};
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    dst[(2 * h) * step] = (lo[h] & 0xffffu) | (hi[h] << 16);
+                    dst[(2 * h + 1) * step] = (lo[h] >> 16) | (hi[h] & 0xffff0000u);
+                }
+            }
+        };
+        issue(0);
+        const int units = PR * PC * PP / 8;   // zero everything a task will not write
+        for (int u = tid; u < units; u += 256) *reinterpret_cast<u32x4 *>(patch + u * 8) = (u32x4){0u, 0u, 0u, 0u};
+        __syncthreads();
+        commit(0);
+        for (int round = 1; round * FT * 256 < ntask; ++round) {
+            issue(round);
+            commit(round);
         }
     }
 
@@ -144,7 +190,6 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     float bias = 0.f;
     if (!DGRAD) bias = a.X[(i64)w * a.ld + a.b_off];
     // per-image bases; everything below is 32-bit offsets inside one image
-    bf16_t *dst = a.dst ? a.dst + img * a.Hd * Wd * CO : nullptr;
     bf16_t *dstT = a.dstT + img * CO * a.Hd * Wd;
     const bf16_t *actT = DGRAD ? a.actT + img * CO * a.Hd * Wd : nullptr;
     const bf16_t *scT = a.sc.t ? a.sc.t + img * a.sc.C * a.sc.H * a.sc.W : nullptr;
@@ -211,13 +256,6 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
                 r[i] = v;
             }
             const u32x2 pk = {f2bf_pack(r[0], r[1]), f2bf_pack(r[2], r[3])};
-            if (dst) {
-                bf16_t *dp = dst + ((y << lw) + x0) * CO + o;
-                dp[0] = (bf16_t)(pk.x & 0xffff);
-                dp[CO] = (bf16_t)(pk.x >> 16);
-                dp[2 * CO] = (bf16_t)(pk.y & 0xffff);
-                dp[3 * CO] = (bf16_t)(pk.y >> 16);
-            }
             *reinterpret_cast<u32x2 *>(dstT + ((o * a.Hd + y) << lw) + x0) = pk;
         }
     }
@@ -492,7 +530,7 @@ bool stem_like(const ConvDesc &c) { return c.Ci <= 8 && c.Co == 16 && c.stride =
 bool fwd_mfma_ok(const ConvDesc &c)
 {
     if (stem_like(c)) return tile_ok(c.Ho, c.Wo, 1, 8);
-    if (!pow2_channels(c.Ci) || !pow2_channels(c.Co)) return false;
+    if (!pow2_channels(c.Ci) || !pow2_channels(c.Co) || (c.W % 8) != 0) return false;   // source rows in 16-byte units
     if (c.stride == 1) return c.Ci == c.Co && tile_ok(c.Ho, c.Wo, 1, c.Ci);
     return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && tile_ok(c.Ho, c.Wo, 2, c.Ci);
 }
@@ -500,7 +538,7 @@ bool fwd_mfma_ok(const ConvDesc &c)
 bool dgrad_mfma_ok(const ConvDesc &c)
 {
     if (stem_like(c)) return false;
-    if (!pow2_channels(c.Ci) || !pow2_channels(c.Co)) return false;
+    if (!pow2_channels(c.Ci) || !pow2_channels(c.Co) || (c.Wo % 8) != 0) return false;
     if (c.stride == 1) return c.Ci == c.Co && tile_ok(c.H, c.W, 1, c.Co);
     return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && c.H == 2 * c.Ho && c.W == 2 * c.Wo &&
            tile_ok(c.H, c.W, 1, c.Co);
@@ -595,9 +633,9 @@ dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X
 dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, const bf16_t *wpack,
                           ShortcutRef sc, Tensor out)
 {
-    if (!fwd_mfma_ok(c) || !out.t || (sc.p && !sc.t)) return conv_forward_generic(ctx, c, B, in, X, sc, out);
+    if (!fwd_mfma_ok(c)) return conv_forward_generic(ctx, c, B, in, X, sc, out);
     ConvMfmaArgs a{};
-    a.src = in.p; a.Hs = c.H; a.Ws = c.W; a.wpack = wpack; a.dst = out.p; a.dstT = out.t; a.Hd = c.Ho; a.Wd = c.Wo;
+    a.src = in.t; a.Hs = c.H; a.Ws = c.W; a.wpack = wpack; a.dstT = out.t; a.Hd = c.Ho; a.Wd = c.Wo;
     a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = c.b_off; a.sc = sc; a.actT = nullptr;
     a.lw = ilog2(a.Wd);
     if (stem_like(c)) return launch_conv<8, 16, 1, 1, false>(ctx, a);   // `in` is the image padded to 8 channels
@@ -613,10 +651,9 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
 dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X, const bf16_t *wpack_d,
                             ShortcutRef scd, Tensor act, Tensor din)
 {
-    if (!dgrad_mfma_ok(c) || !din.t || !act.t || (scd.p && !scd.t))
-        return conv_data_grad_generic(ctx, c, B, dout, X, scd, act.p, din);
+    if (!dgrad_mfma_ok(c)) return conv_data_grad_generic(ctx, c, B, dout, X, scd, act, din);
     ConvMfmaArgs a{};
-    a.src = dout.p; a.Hs = c.Ho; a.Ws = c.Wo; a.wpack = wpack_d; a.dst = din.p; a.dstT = din.t; a.Hd = c.H; a.Wd = c.W;
+    a.src = dout.t; a.Hs = c.Ho; a.Ws = c.Wo; a.wpack = wpack_d; a.dstT = din.t; a.Hd = c.H; a.Wd = c.W;
     a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = 0; a.sc = scd; a.actT = act.t;
     a.lw = ilog2(a.Wd);
     if (c.stride == 1) {
@@ -630,10 +667,7 @@ dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dou
 
 dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials)
 {
-    if (!wgrad_mfma_ok(c) || !in.t || !dout.t || !partials) {
-        if (!in.p || !dout.p) return DPSGD_EUNSUPPORTED;
-        return conv_weight_grad_generic(ctx, c, B, in, dout, G);
-    }
+    if (!wgrad_mfma_ok(c) || !partials) return conv_weight_grad_generic(ctx, c, B, in, dout, G);
     WgradMfmaArgs a{};
     a.inT = in.t; a.doutT = dout.t; a.H = c.H; a.W = c.W; a.Ho = c.Ho; a.Wo = c.Wo; a.B = B; a.CIr = c.Ci;
     a.splits = wgrad_splits(B, c.Co, c.stride); a.part = partials;

@@ -5,7 +5,8 @@
 //
 // Arithmetic: the image, every conv weight, every stored activation (after its ReLU) and every
 // delta entering a convolution are bf16 (round to nearest even); sums are fp32; biases, pooling
-// and the fully connected layer are fp32.  Activations and deltas are NHWC bf16 in the workspace.
+// and the fully connected layer are fp32.  Activations and deltas are channel-major bf16
+// ([n][B][C][H][W]) in the workspace.
 //
 // This file holds the shape-generic kernels (any channel count, image size, stride): one thread
 // per output element for forward and data gradient, one workgroup per (worker, c_out, c_in) for
@@ -20,19 +21,18 @@ namespace {
 typedef long long i64;
 
 // ------------------------------------------------------------------------------ forward
-// IN_MODE 0: NHWC bf16 activation; 1: NCHW bf16 image; 2: NCHW fp32 image (rounded on load).
-template <int IN_MODE>
+// IN_FP32: the source is the fp32 image (rounded on load), else a bf16 tensor; both channel-major.
+template <bool IN_FP32>
 __global__ void __launch_bounds__(256)
 conv_fwd_generic_kernel(const void *__restrict__ in, const float *__restrict__ X, i64 ld, ConvDesc c, int B, i64 total,
-                        const bf16_t *__restrict__ sc, int scC, int scH, int scW, int scS, bf16_t *__restrict__ out,
-                        bf16_t *__restrict__ outT)
+                        const bf16_t *__restrict__ sc, int scC, int scH, int scW, int scS, bf16_t *__restrict__ out)
 {
-    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
+    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;   // over [w][b][co][y][x]
     if (idx >= total) return;
-    const int co = (int)(idx % c.Co);
-    i64 t = idx / c.Co;
+    i64 t = idx;
     const int x = (int)(t % c.Wo); t /= c.Wo;
     const int y = (int)(t % c.Ho); t /= c.Ho;
+    const int co = (int)(t % c.Co); t /= c.Co;
     const int b = (int)(t % B);
     const int w = (int)(t / B);
     const float *Wg = X + (i64)w * ld + c.w_off + (i64)co * c.Ci * 9;
@@ -44,37 +44,31 @@ conv_fwd_generic_kernel(const void *__restrict__ in, const float *__restrict__ X
             for (int kx = 0; kx < 3; ++kx) {
                 const int ix = x * c.stride + kx - 1;
                 if (ix < 0 || ix >= c.W) continue;
-                float v;
-                if (IN_MODE == 0)
-                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.H + iy) * c.W + ix) * c.Ci + ci]);
-                else if (IN_MODE == 1)
-                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]);
-                else
-                    v = bf2f(f2bf(((const float *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]));
+                const i64 src = ((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix;
+                const float v = IN_FP32 ? bf2f(f2bf(((const float *)in)[src])) : bf2f(((const bf16_t *)in)[src]);
                 acc = v * bf2f(f2bf(Wg[(ci * 3 + ky) * 3 + kx])) + acc;
             }
         }
     float v = acc + X[(i64)w * ld + c.b_off];
-    if (sc && co < scC) v += bf2f(sc[((((i64)w * B + b) * scH + y * scS) * scW + x * scS) * scC + co]);
+    if (sc && co < scC) v += bf2f(sc[((((i64)w * B + b) * scC + co) * scH + y * scS) * scW + x * scS]);
     v = v > 0.f ? v : 0.f;
     out[idx] = f2bf(v);
-    if (outT) outT[((((i64)w * B + b) * c.Co + co) * c.Ho + y) * c.Wo + x] = f2bf(v);   // channel-major copy
 }
 
 // ------------------------------------------------------------------------ data gradient
-// din[w][b][iy][ix][ci] = round( [act > 0] * ( sum_{co,ky,kx} dout[oy][ox][co] w[co][ci][ky][kx]
+// din[w][b][ci][iy][ix] = round( [act > 0] * ( sum_{co,ky,kx} dout[co][oy][ox] w[co][ci][ky][kx]
 //                                              + shortcut delta ) ),  oy = (iy + 1 - ky)/stride.
 __global__ void __launch_bounds__(256)
 conv_dgrad_generic_kernel(const bf16_t *__restrict__ dout, const float *__restrict__ X, i64 ld, ConvDesc c, int B,
                           i64 total, const bf16_t *__restrict__ scd, int scC, int scH, int scW, int scS,
-                          const bf16_t *__restrict__ act, bf16_t *__restrict__ din, bf16_t *__restrict__ dinT)
+                          const bf16_t *__restrict__ act, bf16_t *__restrict__ din)
 {
-    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
+    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;   // over [w][b][ci][iy][ix]
     if (idx >= total) return;
-    const int ci = (int)(idx % c.Ci);
-    i64 t = idx / c.Ci;
+    i64 t = idx;
     const int ix = (int)(t % c.W); t /= c.W;
     const int iy = (int)(t % c.H); t /= c.H;
+    const int ci = (int)(t % c.Ci); t /= c.Ci;
     const int b = (int)(t % B);
     const int w = (int)(t / B);
     const float *Wg = X + (i64)w * ld + c.w_off;
@@ -89,21 +83,20 @@ conv_dgrad_generic_kernel(const bf16_t *__restrict__ dout, const float *__restri
             if (tx < 0 || tx % c.stride) continue;
             const int ox = tx / c.stride;
             if (ox >= c.Wo) continue;
-            const bf16_t *dp = dout + ((((i64)w * B + b) * c.Ho + oy) * c.Wo + ox) * c.Co;
+            const bf16_t *dp = dout + ((i64)w * B + b) * c.Co * c.Ho * c.Wo + (i64)oy * c.Wo + ox;
             for (int co = 0; co < c.Co; ++co)
-                acc = bf2f(dp[co]) * bf2f(f2bf(Wg[(((i64)co * c.Ci + ci) * 3 + ky) * 3 + kx])) + acc;
+                acc = bf2f(dp[(i64)co * c.Ho * c.Wo]) * bf2f(f2bf(Wg[(((i64)co * c.Ci + ci) * 3 + ky) * 3 + kx])) + acc;
         }
     }
     if (scd && (iy % scS) == 0 && (ix % scS) == 0 && iy / scS < scH && ix / scS < scW)
-        acc += bf2f(scd[((((i64)w * B + b) * scH + iy / scS) * scW + ix / scS) * scC + ci]);
+        acc += bf2f(scd[((((i64)w * B + b) * scC + ci) * scH + iy / scS) * scW + ix / scS]);
     const bool pos = bf16_positive(act[idx]);
     din[idx] = f2bf(pos ? acc : 0.f);
-    if (dinT) dinT[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix] = f2bf(pos ? acc : 0.f);
 }
 
 // ---------------------------------------------------------------------- weight gradient
 // One workgroup per (c_in, c_out, worker): 9 tap sums over all (b, y, x), fixed-order reduction.
-template <int IN_MODE>
+template <bool IN_FP32>
 __global__ void __launch_bounds__(256)
 conv_wgrad_generic_kernel(const void *__restrict__ in, const bf16_t *__restrict__ dout, ConvDesc c, int B,
                           float *__restrict__ G, i64 ld)
@@ -116,7 +109,7 @@ conv_wgrad_generic_kernel(const void *__restrict__ in, const bf16_t *__restrict_
     const int npix = B * c.Ho * c.Wo;
     for (int p = threadIdx.x; p < npix; p += 256) {
         const int x = p % c.Wo, y = (p / c.Wo) % c.Ho, b = p / (c.Wo * c.Ho);
-        const float go = bf2f(dout[((i64)w * npix + p) * c.Co + co]);
+        const float go = bf2f(dout[((((i64)w * B + b) * c.Co + co) * c.Ho + y) * c.Wo + x]);
         if (go == 0.f) continue;
 #pragma unroll
         for (int ky = 0; ky < 3; ++ky) {
@@ -126,13 +119,8 @@ conv_wgrad_generic_kernel(const void *__restrict__ in, const bf16_t *__restrict_
             for (int kx = 0; kx < 3; ++kx) {
                 const int ix = x * c.stride + kx - 1;
                 if (ix < 0 || ix >= c.W) continue;
-                float v;
-                if (IN_MODE == 0)
-                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.H + iy) * c.W + ix) * c.Ci + ci]);
-                else if (IN_MODE == 1)
-                    v = bf2f(((const bf16_t *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]);
-                else
-                    v = bf2f(f2bf(((const float *)in)[((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix]));
+                const i64 src = ((((i64)w * B + b) * c.Ci + ci) * c.H + iy) * c.W + ix;
+                const float v = IN_FP32 ? bf2f(f2bf(((const float *)in)[src])) : bf2f(((const bf16_t *)in)[src]);
                 acc[ky * 3 + kx] = go * v + acc[ky * 3 + kx];
             }
         }
@@ -173,7 +161,7 @@ sum_delta_kernel(const bf16_t *__restrict__ d, i64 count, float *__restrict__ G,
 }
 
 // ------------------------------------------------------------ head: pool, FC, loss, FC grads
-// One workgroup per worker.  a: [B][HW][C] bf16.  pool / dpool: [n][B][C] fp32, z: [n][B][K] fp32.
+// One workgroup per worker.  a: [B][C][HW] bf16.  pool / dpool: [n][B][C] fp32, z: [n][B][K] fp32.
 __global__ void __launch_bounds__(256)
 head_kernel(const bf16_t *__restrict__ a, const float *__restrict__ X, i64 ld, i64 fcw_off, i64 fcb_off, int B, int HW,
             int C, int K, const int *__restrict__ labels, float *__restrict__ pool, float *__restrict__ z,
@@ -186,9 +174,9 @@ head_kernel(const bf16_t *__restrict__ a, const float *__restrict__ X, i64 ld, i
     const float inv_hw = 1.0f / (float)HW;
     for (int e = tid; e < B * C; e += 256) {
         const int b = e / C, ch = e % C;
-        const bf16_t *p = a + (((i64)w * B + b) * HW) * C + ch;
+        const bf16_t *p = a + (((i64)w * B + b) * C + ch) * HW;
         float s = 0.f;
-        for (int t = 0; t < HW; ++t) s += bf2f(p[(i64)t * C]);
+        for (int t = 0; t < HW; ++t) s += bf2f(p[t]);
         pw[e] = s * inv_hw;
     }
     __syncthreads();
@@ -239,19 +227,13 @@ head_kernel(const bf16_t *__restrict__ a, const float *__restrict__ X, i64 ld, i
     }
 }
 
-// dv[w][b][t][c] = round([a > 0] * dpool[w][b][c])   (dpool already divided by H*W)
+// dv[w][b][c][t] = round([a > 0] * dpool[w][b][c])   (dpool already divided by H*W)
 __global__ void __launch_bounds__(256)
-pool_bwd_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dpool, int HW, int C, i64 total,
-                bf16_t *__restrict__ dv, bf16_t *__restrict__ dvT)
+pool_bwd_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dpool, int HW, i64 total, bf16_t *__restrict__ dv)
 {
-    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;
+    const i64 idx = (i64)blockIdx.x * 256 + threadIdx.x;   // over [w*b][c][t]
     if (idx >= total) return;
-    const int ch = (int)(idx % C);
-    const int t = (int)((idx / C) % HW);
-    const i64 wb = idx / ((i64)HW * C);
-    const bf16_t v = bf16_positive(a[idx]) ? f2bf(dpool[wb * C + ch]) : (bf16_t)0;
-    dv[idx] = v;
-    if (dvT) dvT[(wb * C + ch) * HW + t] = v;
+    dv[idx] = bf16_positive(a[idx]) ? f2bf(dpool[idx / HW]) : (bf16_t)0;
 }
 
 unsigned blocks_for(i64 total) { return (unsigned)((total + 255) / 256); }
@@ -318,7 +300,6 @@ Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPla
     for (const ConvDesc &c : p.convs) {
         const size_t e = nB * c.Ho * c.Wo * c.Co;
         Tensor t;
-        t.p = (bf16_t *)take(e * 2);
         t.t = (bf16_t *)take(e * 2);
         w.out.push_back(t);
         biggest = e > biggest ? e : biggest;
@@ -327,10 +308,7 @@ Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPla
         const size_t pb = conv_wgrad_partial_bytes(c, m.batch) * ctx->n;
         part = pb > part ? pb : part;
     }
-    for (int i = 0; i < 3; ++i) {
-        w.delta[i].p = (bf16_t *)take(biggest * 2);
-        w.delta[i].t = (bf16_t *)take(biggest * 2);
-    }
+    for (int i = 0; i < 3; ++i) w.delta[i].t = (bf16_t *)take(biggest * 2);
     if (!m.input_is_bf16) w.image_bf16 = (bf16_t *)take(nB * p.convs[0].Ci * p.convs[0].H * p.convs[0].W * 2);
     if (conv_stem_uses_mfma(p.convs[0])) w.image_nhwc8 = (bf16_t *)take(nB * p.convs[0].H * p.convs[0].W * 8 * 2);
     w.pool = (float *)take(nB * p.C_last * 4);
@@ -362,7 +340,7 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     const int nconv = (int)p.convs.size();
     auto a_of = [&](int j) { return ws.out[j == 0 ? 0 : 2 * j]; };   // block input/output j
     auto u_of = [&](int j) { return ws.out[1 + 2 * j]; };
-    const ShortcutRef none{nullptr, nullptr, 0, 0, 0, 1};
+    const ShortcutRef none{nullptr, 0, 0, 0, 1};
     dpsgd_status st;
 
     // bf16 operands of the convolutions in the layout the MFMA kernels read (no-op for generic convs)
@@ -377,34 +355,34 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         const ConvDesc &c = p.convs[0];
         if ((st = conv_prep_image(ctx, c, B, inputs, m.input_is_bf16, ws.image_bf16, ws.image_nhwc8)) != DPSGD_OK) return st;
         Tensor img8;
-        img8.p = ws.image_nhwc8;
+        img8.t = ws.image_nhwc8;
         if ((st = conv_forward(ctx, c, B, img8, X, ws.wpack_f[0], none, ws.out[0])) != DPSGD_OK) return st;
     } else {
         const ConvDesc &c = p.convs[0];
         const i64 total = nB * c.Ho * c.Wo * c.Co;
         if (m.input_is_bf16)
-            hipLaunchKernelGGL(conv_fwd_generic_kernel<1>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld, c,
-                               B, total, nullptr, 0, 0, 0, 1, ws.out[0].p, ws.out[0].t);
+            hipLaunchKernelGGL(conv_fwd_generic_kernel<false>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld,
+                               c, B, total, nullptr, 0, 0, 0, 1, ws.out[0].t);
         else
-            hipLaunchKernelGGL(conv_fwd_generic_kernel<2>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld, c,
-                               B, total, nullptr, 0, 0, 0, 1, ws.out[0].p, ws.out[0].t);
+            hipLaunchKernelGGL(conv_fwd_generic_kernel<true>, dim3(blocks_for(total)), dim3(256), 0, s, inputs, X, ctx->ld,
+                               c, B, total, nullptr, 0, 0, 0, 1, ws.out[0].t);
     }
     for (int j = 0; j < p.nblocks; ++j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
         if ((st = conv_forward(ctx, c1, B, a_of(j), X, ws.wpack_f[1 + 2 * j], none, u_of(j))) != DPSGD_OK) return st;
-        const ShortcutRef sc{a_of(j).p, a_of(j).t, c1.Ci, c1.H, c1.W, c1.stride};
+        const ShortcutRef sc{a_of(j).t, c1.Ci, c1.H, c1.W, c1.stride};
         if ((st = conv_forward(ctx, c2, B, u_of(j), X, ws.wpack_f[2 + 2 * j], sc, a_of(j + 1))) != DPSGD_OK) return st;
     }
     const int HWl = p.H_last * p.W_last;
-    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, a_of(p.nblocks).p, X, ctx->ld, p.fcw_off, p.fcb_off,
+    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, a_of(p.nblocks).t, X, ctx->ld, p.fcw_off, p.fcb_off,
                        B, HWl, p.C_last, p.classes, (const int *)targets, ws.pool, ws.logits, ws.dpool, G, loss);
 
     // ---- backward
     Tensor dv = ws.delta[0], du = ws.delta[1], dnext = ws.delta[2];
     {
         const i64 total = nB * HWl * p.C_last;
-        hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks).p, ws.dpool, HWl,
-                           p.C_last, total, dv.p, dv.t);
+        hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks).t, ws.dpool, HWl,
+                           total, dv.t);
     }
     for (int j = p.nblocks - 1; j >= 0; --j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
@@ -413,7 +391,7 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         if ((st = conv_data_grad(ctx, c2, B, dv, X, ws.wpack_d[2 + 2 * j], none, u_of(j), du)) != DPSGD_OK) return st;
         // conv1: from du and a_j; next dv = [a_j > 0] * (dgrad(du) + shortcut delta)
         if ((st = conv_weight_grad(ctx, c1, B, a_of(j), du, G, ws.partials)) != DPSGD_OK) return st;
-        const ShortcutRef scd{dv.p, dv.t, c2.Co, c2.Ho, c2.Wo, c1.stride};
+        const ShortcutRef scd{dv.t, c2.Co, c2.Ho, c2.Wo, c1.stride};
         if ((st = conv_data_grad(ctx, c1, B, du, X, ws.wpack_d[1 + 2 * j], scd, a_of(j), dnext)) != DPSGD_OK) return st;
         Tensor t = dv; dv = dnext; dnext = t;
     }
@@ -425,10 +403,10 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         const ConvDesc &c = p.convs[0];
         dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)n);
         if (m.input_is_bf16)
-            hipLaunchKernelGGL(conv_wgrad_generic_kernel<1>, grid, dim3(256), 0, s, inputs, dv.p, c, B, G, ctx->ld);
+            hipLaunchKernelGGL(conv_wgrad_generic_kernel<false>, grid, dim3(256), 0, s, inputs, dv.t, c, B, G, ctx->ld);
         else
-            hipLaunchKernelGGL(conv_wgrad_generic_kernel<2>, grid, dim3(256), 0, s, inputs, dv.p, c, B, G, ctx->ld);
-        hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)n), dim3(1024), 0, s, dv.p, (i64)B * c.Ho * c.Wo * c.Co, G,
+            hipLaunchKernelGGL(conv_wgrad_generic_kernel<true>, grid, dim3(256), 0, s, inputs, dv.t, c, B, G, ctx->ld);
+        hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)n), dim3(1024), 0, s, dv.t, (i64)B * c.Ho * c.Wo * c.Co, G,
                            ctx->ld, c.b_off);
     }
     return hip_status(hipGetLastError());
@@ -439,25 +417,25 @@ dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tens
                                   Tensor out)
 {
     const i64 total = (i64)ctx->n * B * c.Ho * c.Wo * c.Co;
-    hipLaunchKernelGGL(conv_fwd_generic_kernel<0>, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, in.p, X, ctx->ld, c,
-                       B, total, sc.p, sc.C, sc.H, sc.W, sc.S, out.p, out.t);
+    hipLaunchKernelGGL(conv_fwd_generic_kernel<false>, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, in.t, X, ctx->ld,
+                       c, B, total, sc.t, sc.C, sc.H, sc.W, sc.S, out.t);
     return hip_status(hipGetLastError());
 }
 
 dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X,
-                                    ShortcutRef scd, const bf16_t *act, Tensor din)
+                                    ShortcutRef scd, Tensor act, Tensor din)
 {
     const i64 total = (i64)ctx->n * B * c.H * c.W * c.Ci;
-    hipLaunchKernelGGL(conv_dgrad_generic_kernel, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, dout.p, X, ctx->ld, c,
-                       B, total, scd.p, scd.C, scd.H, scd.W, scd.S, act, din.p, din.t);
+    hipLaunchKernelGGL(conv_dgrad_generic_kernel, dim3(blocks_for(total)), dim3(256), 0, ctx->stream, dout.t, X, ctx->ld, c,
+                       B, total, scd.t, scd.C, scd.H, scd.W, scd.S, act.t, din.t);
     return hip_status(hipGetLastError());
 }
 
 dpsgd_status conv_weight_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G)
 {
     dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)ctx->n);
-    hipLaunchKernelGGL(conv_wgrad_generic_kernel<0>, grid, dim3(256), 0, ctx->stream, in.p, dout.p, c, B, G, ctx->ld);
-    hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)ctx->n), dim3(1024), 0, ctx->stream, dout.p,
+    hipLaunchKernelGGL(conv_wgrad_generic_kernel<false>, grid, dim3(256), 0, ctx->stream, in.t, dout.t, c, B, G, ctx->ld);
+    hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)ctx->n), dim3(1024), 0, ctx->stream, dout.t,
                        (i64)B * c.Ho * c.Wo * c.Co, G, ctx->ld, c.b_off);
     return hip_status(hipGetLastError());
 }

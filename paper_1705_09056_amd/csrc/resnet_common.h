@@ -39,21 +39,22 @@ struct ResnetPlan {
 
 ResnetPlan make_resnet_plan(const dpsgd_model_desc &m);
 
-// An activation or delta tensor: NHWC bf16 [n][B][H][W][C] and its channel-major copy
-// [n][B][C][H][W] (the weight gradient contracts over pixels and wants them contiguous).
+// An activation or delta tensor: bf16, channel-major [n][B][C][H][W].  The weight gradient contracts
+// over pixels and reads them contiguously; forward and data gradient contract over channels and
+// transpose their source rows on the way into LDS; epilogues read and write 4 consecutive pixels
+// of one channel.
 struct Tensor {
-    bf16_t *p = nullptr;
     bf16_t *t = nullptr;
 };
 // Forward: the block input added to the block output at (y*S, x*S) for the first C channels.
 // Backward: the delta of the block output added to the block input's delta at multiples of S.
 struct ShortcutRef {
-    const bf16_t *p;   // NHWC
-    const bf16_t *t;   // channel-major copy
+    const bf16_t *t;
     int C, H, W, S;
 };
 
 // out = round(ReLU(conv(in) + bias + shortcut)).  wpack: this conv's packed bf16 weights (see conv_pack_weights).
+// For the stem on MFMA (conv_stem_uses_mfma) `in` is the image padded to 8 channels, pixel-major.
 dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, const bf16_t *wpack,
                           ShortcutRef sc, Tensor out);
 // din = round([act > 0] * (conv^T(dout) + shortcut delta)).
@@ -77,7 +78,7 @@ dpsgd_status conv_prep_image(dpsgd_ctx *ctx, const ConvDesc &c, int B, const voi
 dpsgd_status conv_forward_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, const float *X, ShortcutRef sc,
                                   Tensor out);
 dpsgd_status conv_data_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X,
-                                    ShortcutRef scd, const bf16_t *act, Tensor din);
+                                    ShortcutRef scd, Tensor act, Tensor din);
 dpsgd_status conv_weight_grad_generic(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G);
 
 }  // namespace dpsgd
