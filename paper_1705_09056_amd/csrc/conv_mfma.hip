@@ -38,25 +38,50 @@ constexpr int wave_cols(int ci, int co)
 // wpack[w][s][t][lane][j] = Weff[o = 16 t + lane%16][c][tap], contraction index 32 s + 8 (lane/16) + j
 // = tap * CI + c (CI = contraction channels rounded up to 8); zero beyond tap 8 or channel c_real.
 // DGRAD: Weff[o = c_in][c = c_out][tap] = W[c_out][c_in][8 - tap].
-template <bool DGRAD>
-__global__ void __launch_bounds__(256)
-pack_weights_kernel(const float *__restrict__ X, i64 ld, ConvDesc c, int CI, int CO, int KS, bf16_t *__restrict__ wpack)
+// One launch packs every conv of the network (both operands): the jobs travel in the kernel arguments.
+struct PackJob {
+    long long w_off;    // the conv's weights inside a worker's parameter vector
+    bf16_t *dst;        // [n][per_worker]
+    int Ci, Co;         // the conv's real channel counts
+    int CI, CO, KS;     // contraction channels (padded), output channels, k-steps of the packed operand
+    int dgrad;
+    int block0;         // first blockIdx.x of this job
+};
+constexpr int kMaxPackJobs = 64;
+struct PackTable {
+    PackJob job[kMaxPackJobs];
+    int njobs;
+};
+
+__global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restrict__ X, i64 ld, PackTable tbl)
 {
-    const int w = blockIdx.y;
-    const int per_worker = KS * (CO / 16) * 64 * 8;
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= per_worker) return;
-    const int j = e & 7, lane = (e >> 3) & 63, st = e >> 9;
-    const int t = st % (CO / 16), s = st / (CO / 16);
-    const int kk = 32 * s + 8 * (lane >> 4) + j;
-    const int tap = kk / CI, ch = kk % CI, o = 16 * t + (lane & 15);
-    float v = 0.f;
-    const int c_real = DGRAD ? c.Co : c.Ci, o_real = DGRAD ? c.Ci : c.Co;
-    if (tap < 9 && ch < c_real && o < o_real) {
-        const float *Wg = X + (i64)w * ld + c.w_off;
-        v = DGRAD ? Wg[((i64)ch * c.Ci + o) * 9 + (8 - tap)] : Wg[((i64)o * c.Ci + ch) * 9 + tap];
+    // the job of this workgroup: last one whose first block is <= blockIdx.x (bisection over uniform values)
+    int lo = 0, hi = tbl.njobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int)blockIdx.x >= tbl.job[mid].block0) lo = mid; else hi = mid - 1;
     }
-    wpack[(i64)w * per_worker + e] = f2bf(v);
+    const PackJob &jb = tbl.job[lo];
+    const int w = blockIdx.y;
+    const int groups = jb.KS * (jb.CO / 16) * 64;            // 16-byte units (one lane's 8 values) per worker
+    const int u = ((int)blockIdx.x - jb.block0) * 256 + threadIdx.x;
+    if (u >= groups) return;
+    const int lane = u & 63, st = u >> 6;
+    const int t = st % (jb.CO / 16), s = st / (jb.CO / 16);
+    const int o = 16 * t + (lane & 15);
+    const int c_real = jb.dgrad ? jb.Co : jb.Ci, o_real = jb.dgrad ? jb.Ci : jb.Co;
+    const float *Wg = X + (i64)w * ld + jb.w_off;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int kk = 32 * s + 8 * (lane >> 4) + j;
+        const int tap = kk / jb.CI, ch = kk % jb.CI;
+        v[j] = 0.f;
+        if (tap < 9 && ch < c_real && o < o_real)
+            v[j] = jb.dgrad ? Wg[((i64)ch * jb.Ci + o) * 9 + (8 - tap)] : Wg[((i64)o * jb.Ci + ch) * 9 + tap];
+    }
+    const u32x4 pk = {f2bf_pack(v[0], v[1]), f2bf_pack(v[2], v[3]), f2bf_pack(v[4], v[5]), f2bf_pack(v[6], v[7])};
+    *reinterpret_cast<u32x4 *>(jb.dst + ((i64)w * groups + u) * 8) = pk;
 }
 
 // --------------------------------------------------------------- forward / data gradient
@@ -614,19 +639,31 @@ size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B)
     return (size_t)wgrad_splits(B, c.Co, c.stride) * ((size_t)c.Co * c.Ci * 9 + 1) * sizeof(float);
 }
 
-dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d)
+dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const std::vector<ConvDesc> &convs, const float *X,
+                               const std::vector<bf16_t *> &wpack_f, const std::vector<bf16_t *> &wpack_d)
 {
-    if (fwd_mfma_ok(c)) {
-        const int cic = stem_like(c) ? 8 : c.Ci;
-        const int KS = ksteps(cic), per = KS * 32 * c.Co;
-        hipLaunchKernelGGL(pack_weights_kernel<false>, dim3((unsigned)((per + 255) / 256), (unsigned)ctx->n), dim3(256), 0,
-                           ctx->stream, X, ctx->ld, c, cic, c.Co, KS, wpack_f);
+    PackTable tbl{};
+    int blocks = 0;
+    auto flush = [&]() {
+        if (tbl.njobs > 0)
+            hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)blocks, (unsigned)ctx->n), dim3(256), 0, ctx->stream, X,
+                               ctx->ld, tbl);
+        tbl.njobs = 0;
+        blocks = 0;
+    };
+    auto add = [&](const ConvDesc &c, int CI, int CO, bool dgrad, bf16_t *dst) {
+        if (tbl.njobs == kMaxPackJobs) flush();
+        PackJob &jb = tbl.job[tbl.njobs++];
+        jb.w_off = c.w_off; jb.dst = dst; jb.Ci = c.Ci; jb.Co = c.Co; jb.CI = CI; jb.CO = CO; jb.KS = ksteps(CI);
+        jb.dgrad = dgrad ? 1 : 0; jb.block0 = blocks;
+        blocks += (jb.KS * 4 * CO + 255) / 256;   // KS * (CO / 16) * 64 units of 16 bytes
+    };
+    for (size_t q = 0; q < convs.size(); ++q) {
+        const ConvDesc &c = convs[q];
+        if (fwd_mfma_ok(c)) add(c, stem_like(c) ? 8 : c.Ci, c.Co, false, wpack_f[q]);
+        if (!stem_like(c) && dgrad_mfma_ok(c)) add(c, c.Co, c.Ci, true, wpack_d[q]);
     }
-    if (!stem_like(c) && dgrad_mfma_ok(c)) {
-        const int KS = ksteps(c.Co), per = KS * 32 * c.Ci;
-        hipLaunchKernelGGL(pack_weights_kernel<true>, dim3((unsigned)((per + 255) / 256), (unsigned)ctx->n), dim3(256), 0,
-                           ctx->stream, X, ctx->ld, c, c.Co, c.Ci, KS, wpack_d);
-    }
+    flush();
     return hip_status(hipGetLastError());
 }
 

@@ -337,15 +337,13 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     for (const ConvDesc &c : p.convs)
         if (c.Ho < 1 || c.Wo < 1 || c.Ci > 65535 || c.Co > 65535) return DPSGD_EUNSUPPORTED;
     Workspace ws = carve(ctx, m, p, (unsigned char *)ctx->ws);
-    const int nconv = (int)p.convs.size();
     auto a_of = [&](int j) { return ws.out[j == 0 ? 0 : 2 * j]; };   // block input/output j
     auto u_of = [&](int j) { return ws.out[1 + 2 * j]; };
     const ShortcutRef none{nullptr, 0, 0, 0, 1};
     dpsgd_status st;
 
     // bf16 operands of the convolutions in the layout the MFMA kernels read (no-op for generic convs)
-    for (int q = 0; q < nconv; ++q)
-        if ((st = conv_pack_weights(ctx, p.convs[q], X, ws.wpack_f[q], ws.wpack_d[q])) != DPSGD_OK) return st;
+    if ((st = conv_pack_weights(ctx, p.convs, X, ws.wpack_f, ws.wpack_d)) != DPSGD_OK) return st;
 
     // ---- forward
     const bool stem_mfma = conv_stem_uses_mfma(p.convs[0]);

@@ -66,8 +66,10 @@ dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor i
 // Bytes per worker of the packed weights of one conv (forward operand, or data-gradient operand).
 size_t conv_pack_bytes(const ConvDesc &c, bool dgrad);
 size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B);
-// Rounds one conv's fp32 weights of every worker to bf16 in MFMA operand order (both operands).
-dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const ConvDesc &c, const float *X, bf16_t *wpack_f, bf16_t *wpack_d);
+// Rounds the fp32 weights of every conv and worker to bf16 in MFMA operand order (forward and data-gradient
+// operands, wpack_f[q] / wpack_d[q] for convs[q]; nothing is written for convs the MFMA kernels do not take).
+dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const std::vector<ConvDesc> &convs, const float *X,
+                               const std::vector<bf16_t *> &wpack_f, const std::vector<bf16_t *> &wpack_d);
 
 // Stem support: whether the first conv runs on MFMA, and the image copies it then needs: a bf16
 // channel-major copy (only made from fp32 images; may be null) and the image padded to 8 channels (NHWC8).
