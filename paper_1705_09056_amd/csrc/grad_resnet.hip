@@ -161,25 +161,39 @@ sum_delta_kernel(const bf16_t *__restrict__ d, i64 count, float *__restrict__ G,
 }
 
 // ------------------------------------------------------------ head: pool, FC, loss, FC grads
-// One workgroup per worker.  a: [B][C][HW] bf16.  pool / dpool: [n][B][C] fp32, z: [n][B][K] fp32.
+// Global average pool: a [n*B*C][HW] bf16 -> pool [n*B*C] fp32, one thread per (image, channel), pixels in order.
 __global__ void __launch_bounds__(256)
-head_kernel(const bf16_t *__restrict__ a, const float *__restrict__ X, i64 ld, i64 fcw_off, i64 fcb_off, int B, int HW,
-            int C, int K, const int *__restrict__ labels, float *__restrict__ pool, float *__restrict__ z,
+pool_fwd_kernel(const bf16_t *__restrict__ a, int HW, i64 total, float *__restrict__ pool)
+{
+    const i64 e = (i64)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const bf16_t *p = a + e * HW;
+    float s = 0.f;
+    int t = 0;
+    if ((HW & 7) == 0)
+        for (; t < HW; t += 8) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(p + t);
+            s += bf2f((bf16_t)(v.x & 0xffff)); s += bf2f((bf16_t)(v.x >> 16));
+            s += bf2f((bf16_t)(v.y & 0xffff)); s += bf2f((bf16_t)(v.y >> 16));
+            s += bf2f((bf16_t)(v.z & 0xffff)); s += bf2f((bf16_t)(v.z >> 16));
+            s += bf2f((bf16_t)(v.w & 0xffff)); s += bf2f((bf16_t)(v.w >> 16));
+        }
+    for (; t < HW; ++t) s += bf2f(p[t]);
+    pool[e] = s * (1.0f / (float)HW);
+}
+
+// One workgroup per worker.  pool / dpool: [n][B][C] fp32, z: [n][B][K] fp32.
+__global__ void __launch_bounds__(256)
+head_kernel(const float *__restrict__ X, i64 ld, i64 fcw_off, i64 fcb_off, int B, int HW, int C, int K,
+            const int *__restrict__ labels, const float *__restrict__ pool, float *__restrict__ z,
             float *__restrict__ dpool, float *__restrict__ G, float *__restrict__ loss)
 {
     __shared__ float red[256];
     const int w = blockIdx.x, tid = threadIdx.x;
     const float *fw = X + (i64)w * ld + fcw_off, *fb = X + (i64)w * ld + fcb_off;
-    float *pw = pool + (i64)w * B * C, *zw = z + (i64)w * B * K, *dpw = dpool + (i64)w * B * C;
+    const float *pw = pool + (i64)w * B * C;
+    float *zw = z + (i64)w * B * K, *dpw = dpool + (i64)w * B * C;
     const float inv_hw = 1.0f / (float)HW;
-    for (int e = tid; e < B * C; e += 256) {
-        const int b = e / C, ch = e % C;
-        const bf16_t *p = a + (((i64)w * B + b) * C + ch) * HW;
-        float s = 0.f;
-        for (int t = 0; t < HW; ++t) s += bf2f(p[t]);
-        pw[e] = s * inv_hw;
-    }
-    __syncthreads();
     for (int e = tid; e < B * K; e += 256) {
         const int b = e / K, o = e % K;
         float s = fb[o];
@@ -372,8 +386,10 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         if ((st = conv_forward(ctx, c2, B, u_of(j), X, ws.wpack_f[2 + 2 * j], sc, a_of(j + 1))) != DPSGD_OK) return st;
     }
     const int HWl = p.H_last * p.W_last;
-    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, a_of(p.nblocks).t, X, ctx->ld, p.fcw_off, p.fcb_off,
-                       B, HWl, p.C_last, p.classes, (const int *)targets, ws.pool, ws.logits, ws.dpool, G, loss);
+    hipLaunchKernelGGL(pool_fwd_kernel, dim3(blocks_for(nB * p.C_last)), dim3(256), 0, s, a_of(p.nblocks).t, HWl,
+                       nB * p.C_last, ws.pool);
+    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, X, ctx->ld, p.fcw_off, p.fcb_off, B, HWl, p.C_last,
+                       p.classes, (const int *)targets, ws.pool, ws.logits, ws.dpool, G, loss);
 
     // ---- backward
     Tensor dv = ws.delta[0], du = ws.delta[1], dnext = ws.delta[2];
