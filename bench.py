@@ -90,8 +90,12 @@ def cpu_baseline(cfg, seconds_budget=20.0):
     t_mix = (time.perf_counter() - t0) * (d / dcols)
     # m workers ran on min(m, threads) cores at once; all n workers need n/m such rounds
     t_iter = t_grad * (cfg.n / m) + t_mix
+    # each thread took ceil(m / threads) workers in turn, so one worker's gradient costs one core about this long
+    per_worker = t_grad / (-(-m // max(1, min(threads, m))))
+    t_iter_1 = per_worker * cfg.n + t_mix
     return {
         "value": cfg.n / t_iter, "unit": "worker-iters/s", "cores": int(min(threads, m)), "kind": "oracle",
+        "single_thread_estimate": cfg.n / t_iter_1,
         "sample": f"gradient of {m} of {cfg.n} workers (one minibatch each, OpenMP over workers, {t_grad:.2f} s) "
                   f"scaled by n/{m}; mix+step on {dcols} of {d} columns (single thread, scaled to d)",
     }
