@@ -97,6 +97,35 @@ prep_input_kernel(const void *__restrict__ in, bf16_t *__restrict__ a, bf16_t *_
     }
 }
 
+// The same for bf16 inputs whose rows are 16-byte aligned (F % 8 == 0): 64 features x 32 samples per
+// workgroup, 16-byte loads (8 features of a sample) and 16-byte stores (8 samples of a feature).
+__global__ void __launch_bounds__(256)
+prep_input_vec_kernel(const bf16_t *__restrict__ in, bf16_t *__restrict__ at, int B, int Bp, int F)
+{
+    __shared__ bf16_t tile[32][72];   // [sample][feature], pitch 144 bytes
+    const int w = blockIdx.z, b0 = blockIdx.y * 32, f0 = blockIdx.x * 64;
+    {
+        const int r = threadIdx.x >> 3, c8 = threadIdx.x & 7;   // sample row, group of 8 features
+        const int b = b0 + r, f = f0 + 8 * c8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (b < B && f < F) v = *reinterpret_cast<const u32x4 *>(in + ((i64)w * B + b) * F + f);
+        *reinterpret_cast<u32x4 *>(&tile[r][8 * c8]) = v;
+    }
+    __syncthreads();
+    {
+        const int r = threadIdx.x & 63, c = threadIdx.x >> 6;   // feature, group of 8 samples
+        const int f = f0 + r, b = b0 + 8 * c;
+        if (f < F) {
+            unsigned short e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = tile[8 * c + j][r];
+            u32x4 pk = {e[0] | ((unsigned)e[1] << 16), e[2] | ((unsigned)e[3] << 16), e[4] | ((unsigned)e[5] << 16),
+                        e[6] | ((unsigned)e[7] << 16)};
+            *reinterpret_cast<u32x4 *>(at + tfrag_worker(w, F, Bp) + tfrag_off(f, b, Bp)) = pk;
+        }
+    }
+}
+
 // --------------------------------------------------------------------------- forward
 struct FwdArgs {
     const bf16_t *act;     // [n][B][K]
@@ -244,6 +273,52 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
     }
 }
 
+// Class layer (at most 32 outputs): the tile above would be 3/4 padding and one workgroup per worker
+// would walk the whole contraction alone.  Here a workgroup owns 32 samples of one worker and its 8
+// waves split K; operands come straight from global memory (activations bf16, weights fp32 rounded
+// in registers), the partial tiles meet in LDS.  grid (ceil(B / 32), n), block 512.  K % 16 == 0.
+__global__ void __launch_bounds__(512) mlp_fwd_last_kernel(FwdArgs g)
+{
+    constexpr int NW = 8;
+    __shared__ float red[NW][16][64];
+    const int w = blockIdx.y, b0 = blockIdx.x * 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int b = b0 + l32, o = l32;
+    const bool b_ok = b < g.B, o_ok = o < g.O;
+    const bf16_t *ap = g.act + ((i64)w * g.B + (b_ok ? b : 0)) * g.K + 8 * half;
+    const float *wp = g.X + (i64)w * g.ld + g.woff + (i64)(o_ok ? o : 0) * g.K + 8 * half;
+    const int steps = g.K / 16;
+    const int s0 = (int)((i64)steps * wave / NW), s1 = (int)((i64)steps * (wave + 1) / NW);
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (int st = s0; st < s1; ++st) {
+        bf16x8 av = zero_frag(), bv = zero_frag();
+        if (b_ok) av = frag(ap + st * 16);
+        if (o_ok) {
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(wp + st * 16);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(wp + st * 16 + 4);
+            const u32x4 pk = {pack2(lo.x, lo.y), pack2(lo.z, lo.w), pack2(hi.x, hi.y), pack2(hi.z, hi.w)};
+            bv = __builtin_bit_cast(bf16x8, pk);
+        }
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[v];
+    __syncthreads();
+    // element v of lane l: sample b0 + (v/4)*8 + (l/32)*4 + v%4, output l%32; 16 x 64 elements over 512 threads
+    for (int e = threadIdx.x; e < 16 * 64; e += 512) {
+        const int v = e >> 6, l = e & 63;
+        const int bb = b0 + (v >> 2) * 8 + (l >> 5) * 4 + (v & 3), oo = l & 31;
+        if (bb >= g.B || oo >= g.O) continue;
+        float sum = 0.f;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) sum += red[q][v][l];
+        g.z[((i64)w * g.B + bb) * g.O + oo] = sum + g.X[(i64)w * g.ld + g.boff + oo];
+    }
+}
+
 // ------------------------------------------------------------- softmax cross-entropy
 // z fp32 [n][B][C] -> dz bf16 [n][B][C], dzt = its T copy (zero padded samples), loss[n].
 __global__ void __launch_bounds__(256)
@@ -293,12 +368,15 @@ struct WgradArgs {
 };
 
 // grid (ceil(K / 256), ceil(O / 128), n); wave = 32 rows o, walks 8 tiles of 32 columns k.
+// SKINNY (few outputs, e.g. the class layer): grid (ceil(K / 128), ceil(O / 32), n); the four waves
+// share the 32 rows o and take one tile of 32 columns k each.
+template <bool SKINNY>
 __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g)
 {
     const int w = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int o_base = blockIdx.y * 128 + wave * 32;
+    const int o_base = SKINNY ? blockIdx.y * 32 : blockIdx.y * 128 + wave * 32;
     if (o_base >= g.O) return;
     const int o = o_base + l32;            // row this lane feeds into the A operand
     const bool o_ok = o < g.O;
@@ -307,7 +385,7 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g)
     const bf16_t *Ap = g.dzt + tfrag_worker(w, g.O, g.Bp) + (i64)(o_base >> 5) * steps * 512 + lane * 8;
     float *Gw = g.G + (i64)w * g.ld + g.woff;
 
-    if (blockIdx.x == 0) {   // bias gradient: gb[o] = sum_b dZ[b][o]
+    if (blockIdx.x == 0 && (!SKINNY || wave == 0)) {   // bias gradient: gb[o] = sum_b dZ[b][o]
         float s = 0.f;
         if (o_ok)
             for (int st = 0; st < steps; ++st)
@@ -317,8 +395,8 @@ __global__ void __launch_bounds__(256) mlp_wgrad_kernel(WgradArgs g)
         if (half == 0 && o_ok) g.G[(i64)w * g.ld + g.boff + o] = s;
     }
 
-    for (int t = 0; t < 8; ++t) {
-        const int k_base = blockIdx.x * 256 + t * 32;
+    for (int t = 0; t < (SKINNY ? 1 : 8); ++t) {
+        const int k_base = SKINNY ? blockIdx.x * 128 + wave * 32 : blockIdx.x * 256 + t * 32;
         if (k_base >= g.K) break;
         const int k = k_base + l32;
         const bool k_ok = k < g.K;
@@ -702,7 +780,10 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
     {   // bf16 copy (if needed) and transposed copy of the inputs
         const int F = m.widths[0];
         dim3 grid((unsigned)((F + 31) / 32), (unsigned)(Bp / 32), (unsigned)n);
-        if (m.input_is_bf16)
+        if (m.input_is_bf16 && (F % 8) == 0 && aligned16(inputs))
+            hipLaunchKernelGGL(prep_input_vec_kernel, dim3((unsigned)((F + 63) / 64), (unsigned)(Bp / 32), (unsigned)n),
+                               dim3(256), 0, s, (const bf16_t *)inputs, ws.at0, B, Bp, F);
+        else if (m.input_is_bf16)
             hipLaunchKernelGGL(prep_input_kernel<true>, grid, dim3(256), 0, s, inputs, ws.a0, ws.at0, B, Bp, F);
         else
             hipLaunchKernelGGL(prep_input_kernel<false>, grid, dim3(256), 0, s, inputs, ws.a0, ws.at0, B, Bp, F);
@@ -717,7 +798,10 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         const bool last = (l == L - 1);
         if (last) a.z = ws.logits; else { a.h = ws.h[l + 1]; a.ht = ws.ht[l + 1]; }
         const bool vec = base_ok && (a.K % 8) == 0 && (woff[l] % 4) == 0 && aligned16(act[l]);
-        if (t.mt == 1) st = fwd_launch<1, 4, 1>(s, n, a, vec, last);
+        if (last && vec && a.O <= 32 && (a.K % 16) == 0 && a.K >= 256) {
+            hipLaunchKernelGGL(mlp_fwd_last_kernel, dim3((unsigned)((B + 31) / 32), (unsigned)n), dim3(512), 0, s, a);
+            st = hip_status(hipGetLastError());
+        } else if (t.mt == 1) st = fwd_launch<1, 4, 1>(s, n, a, vec, last);
         else if (t.wm == 1) st = fwd_launch<1, 4, 2>(s, n, a, vec, last);
         else st = fwd_launch<2, 2, 2>(s, n, a, vec, last);
     }
@@ -737,8 +821,13 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             WgradArgs wa{};
             wa.dzt = ws.dzt[l + 1]; wa.at = actt[l]; wa.G = G; wa.ld = ctx->ld; wa.woff = woff[l]; wa.boff = boff[l];
             wa.Bp = Bp; wa.K = K; wa.O = O;
-            dim3 wgrid((unsigned)((K + 255) / 256), (unsigned)((O + 127) / 128), (unsigned)n);
-            hipLaunchKernelGGL(mlp_wgrad_kernel, wgrid, dim3(256), 0, s, wa);
+            if (O <= 32) {
+                dim3 wgrid((unsigned)((K + 127) / 128), (unsigned)((O + 31) / 32), (unsigned)n);
+                hipLaunchKernelGGL(mlp_wgrad_kernel<true>, wgrid, dim3(256), 0, s, wa);
+            } else {
+                dim3 wgrid((unsigned)((K + 255) / 256), (unsigned)((O + 127) / 128), (unsigned)n);
+                hipLaunchKernelGGL(mlp_wgrad_kernel<false>, wgrid, dim3(256), 0, s, wa);
+            }
         }
         st = hip_status(hipGetLastError());
         if (l > 0 && st == DPSGD_OK) {
