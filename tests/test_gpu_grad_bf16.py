@@ -57,6 +57,9 @@ def grad_case(cfg, ld, k=0, spread=0.3, bf16_inputs=True, extra_bias=0.0):
     ((512, 4096, 10), 32, 2),          # a full-width 4096 hidden layer
     ((256, 128, 10), 64, 2),           # the 64-row tiling
     ((256, 128, 64, 10), 130, 2),      # more than one row block
+    ((64, 272, 7), 37, 3),             # class layer on the split-contraction kernel, ragged minibatch
+    ((128, 256, 32), 33, 2),           # 32 outputs: the widest class layer that kernel takes
+    ((128, 256, 33), 33, 2),           # 33 outputs: back on the general tile
 ])
 def test_mlp_bf16_aligned(widths, batch, n):
     cfg = shrink(CONFIGS[2], widths=widths, batch=batch, n=n)
