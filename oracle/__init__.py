@@ -47,6 +47,9 @@ def lib():
         for name in ("orc_mix_step", "orc_mix_step_swapped"):
             getattr(L, name).restype = None
             getattr(L, name).argtypes = [C.c_int32, C.c_int64, i32p, i32p, f64p, f64p, f64p, C.c_double, f64p]
+        L.orc_mix_step_momentum.restype = None
+        L.orc_mix_step_momentum.argtypes = [C.c_int32, C.c_int64, i32p, i32p, f64p, f64p, f64p, f64p, C.c_double,
+                                            C.c_double, f64p, f64p]
         L.orc_mean.restype = None
         L.orc_mean.argtypes = [C.c_int32, C.c_int64, f64p, f64p]
         L.orc_consensus.restype = C.c_double
@@ -136,6 +139,20 @@ def mix_step(topo: Topology, X, G, gamma: float, swapped: bool = False) -> np.nd
     fn(n, d, _i32(topo.rowptr)[1], _i32(topo.col)[1], _f64(topo.val)[1], Xp, Gp, float(gamma),
        Xn.ctypes.data_as(C.POINTER(C.c_double)))
     return Xn
+
+
+def mix_step_momentum(topo: Topology, X, G, V, gamma: float, mu: float):
+    """Heavy-ball variant of Algorithm 1 steps 4-5: returns (X_next, V_next)."""
+    X, Xp = _f64(X)
+    G, Gp = _f64(G)
+    V, Vp = _f64(V)
+    n, d = X.shape
+    assert n == topo.n and G.shape == X.shape and V.shape == X.shape
+    Xn, Vn = np.empty_like(X), np.empty_like(X)
+    lib().orc_mix_step_momentum(n, d, _i32(topo.rowptr)[1], _i32(topo.col)[1], _f64(topo.val)[1], Xp, Gp, Vp,
+                                float(gamma), float(mu), Xn.ctypes.data_as(C.POINTER(C.c_double)),
+                                Vn.ctypes.data_as(C.POINTER(C.c_double)))
+    return Xn, Vn
 
 
 def mean(X) -> np.ndarray:

@@ -216,6 +216,24 @@ void orc_mix_step_swapped(int32_t n, int64_t d, const int32_t *rowptr, const int
         }
 }
 
+/* Momentum variant of steps 4-5 (Section 5.3 runs D-PSGD with learning rate 0.1 and
+ * momentum 0.9 and does not say where the momentum enters; the reading taken is the
+ * plain heavy-ball update of the local gradient, averaging untouched):
+ *   Vn[i] = mu V[i] + G[i],   Xn[i] = sum_j W_ij X[j] - gamma Vn[i]. */
+void orc_mix_step_momentum(int32_t n, int64_t d, const int32_t *rowptr, const int32_t *col, const double *val,
+                           const double *X, const double *G, const double *V, double gamma, double mu, double *Xn,
+                           double *Vn)
+{
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            size_t e = (size_t)i * d + c;
+            double half = 0.0;
+            for (int p = rowptr[i]; p < rowptr[i + 1]; ++p) half += val[p] * X[(size_t)col[p] * d + c];
+            Vn[e] = mu * V[e] + G[e];
+            Xn[e] = half - gamma * Vn[e];
+        }
+}
+
 /* Algorithm 1 step 7: (1/n) sum_i x_i. */
 void orc_mean(int32_t n, int64_t d, const double *X, double *xbar)
 {

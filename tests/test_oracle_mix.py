@@ -119,3 +119,62 @@ def test_mean_and_consensus_brute_force():
     brute = sum(np.sum((xbar - X[i]) ** 2) for i in range(13)) / 13
     assert oracle.consensus(X) == pytest.approx(brute, rel=1e-14)
     assert oracle.consensus(np.tile(xbar, (13, 1))) < 1e-28
+
+
+# ------------------------------------------------------------------ momentum variant (Section 5.3: momentum 0.9)
+def test_momentum_zero_is_the_plain_step():
+    rng = np.random.default_rng(21)
+    topo = oracle.ring(7)
+    X, G, V = rng.standard_normal((3, 7, 13))
+    Xn, Vn = oracle.mix_step_momentum(topo, X, G, V, 0.1, 0.0)
+    assert np.array_equal(Xn, oracle.mix_step(topo, X, G, 0.1))
+    assert np.array_equal(Vn, G)
+
+
+def test_momentum_heavy_ball_identity_over_three_steps():
+    """Eliminating V: X_{k+1} - W X_k = mu (X_k - W X_{k-1}) - gamma G_k, checked with a dense W product."""
+    rng = np.random.default_rng(22)
+    topo = oracle.torus(3, 4)
+    W = topo.dense()
+    gamma, mu = 0.05, 0.9
+    X = [rng.standard_normal((12, 9))]
+    V = np.zeros((12, 9))
+    Gs = [rng.standard_normal((12, 9)) for _ in range(4)]
+    for k in range(4):
+        Xn, V = oracle.mix_step_momentum(topo, X[-1], Gs[k], V, gamma, mu)
+        X.append(Xn)
+    np.testing.assert_allclose(X[1], W @ X[0] - gamma * Gs[0], atol=1e-14)          # V_0 = 0
+    for k in range(1, 4):
+        lhs = X[k + 1] - W @ X[k]
+        rhs = mu * (X[k] - W @ X[k - 1]) - gamma * Gs[k]
+        np.testing.assert_allclose(lhs, rhs, atol=1e-13)
+
+
+def test_momentum_node_average_follows_textbook_heavy_ball():
+    """1^T W = 1^T, so the node average obeys vbar' = mu vbar + gbar, xbar' = xbar - gamma vbar'."""
+    rng = np.random.default_rng(23)
+    topo = oracle.ring_chord(8)
+    X, G, V = rng.standard_normal((3, 8, 11))
+    Xn, Vn = oracle.mix_step_momentum(topo, X, G, V, 0.07, 0.8)
+    vbar = 0.8 * V.mean(0) + G.mean(0)
+    np.testing.assert_allclose(Vn.mean(0), vbar, atol=1e-14)
+    np.testing.assert_allclose(Xn.mean(0), X.mean(0) - 0.07 * vbar, atol=1e-14)
+
+
+def test_momentum_on_a_quadratic_matches_the_mode_recurrence():
+    """Complete graph, identical workers, f(x) = lambda x^2 / 2 per coordinate: each coordinate follows the 2 x 2
+    linear recurrence (x, v) -> (x - gamma (mu v + lambda x), mu v + lambda x), evaluated here by a matrix power."""
+    n, K = 5, 25
+    lam = np.array([0.3, 1.0, 2.5, 7.0])
+    gamma, mu = 0.1, 0.9
+    topo = oracle.complete(n)
+    X = np.tile(np.array([1.0, -2.0, 0.5, 3.0]), (n, 1))
+    V = np.zeros_like(X)
+    for _ in range(K):
+        X, V = oracle.mix_step_momentum(topo, X, lam * X, V, gamma, mu)
+    for c, l in enumerate(lam):
+        M = np.array([[1.0 - gamma * l, -gamma * mu], [l, mu]])
+        x0 = np.array([[1.0, -2.0, 0.5, 3.0][c], 0.0])
+        want = np.linalg.matrix_power(M, K) @ x0
+        np.testing.assert_allclose(X[:, c], want[0], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(V[:, c], want[1], rtol=1e-12, atol=1e-14)
