@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-consensus", action="store_true")
     ap.add_argument("--two-call", action="store_true", help="dpsgd_grad + dpsgd_mix_step even where dpsgd_step fuses")
+    ap.add_argument("--momentum", type=float, default=0.0,
+                    help="run the heavy-ball variant dpsgd_mix_step_momentum with this mu (two-call path; a variant "
+                         "of the benchmark, flagged in the output)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (reference for the FETCH_SIZE / WRITE_SIZE "
                          "counters under rocprofv3 --pmc) and exit")
@@ -208,7 +211,10 @@ def main():
             w_in, w_out = cfg.widths[l], cfg.widths[l + 1]
             if w_in % 128 == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
                 fused_weights += w_in * w_out
-    fused = fused_weights > 0 and not args.two_call
+    fused = fused_weights > 0 and not args.two_call and not args.momentum
+    Vel = torch.zeros_like(X) if args.momentum else None
+    if args.momentum:
+        variant = (variant + "; " if variant else "") + f"heavy-ball momentum {args.momentum} (not the benchmark's update)"
 
     def step(k, ev=None):
         inp_d, tgt_d = pool[k % len(pool)]
@@ -218,7 +224,10 @@ def main():
         ctx.grad(model, X, inp_d, tgt_d, cfg.batch, G, loss, input_is_bf16=cfg.bf16)
         if ev is not None:
             ev[0].record()
-        ctx.mix_step(X, G, X, cons)
+        if Vel is not None:
+            ctx.mix_step_momentum(X, G, Vel, args.momentum, X, cons)
+        else:
+            ctx.mix_step(X, G, X, cons)
         if ev is not None:
             ev[1].record()
 
@@ -249,7 +258,7 @@ def main():
         kernel_name = "mix_step (Algorithm 1 steps 4-5 fused)"
         mix_ms = sum(a.elapsed_time(b) for a, b in evs) / K
         launch_ms = mix_ms
-        launch_bytes = 12.0 * cfg.n * d
+        launch_bytes = (20.0 if Vel is not None else 12.0) * cfg.n * d
     final_loss = float(loss.mean().item())
     final_cons = None if cons is None else float(cons.item())
     ctx.close()
@@ -267,7 +276,8 @@ def main():
         "config": {"workload": cfg.name, "model_kind": int(cfg.model_kind), "widths": list(cfg.widths), "n": cfg.n,
                    "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "gamma": cfg.gamma,
                    "minibatch_pool": len(pool), "consensus": cons is not None,
-                   "path": "dpsgd_step" if fused else "dpsgd_grad + dpsgd_mix_step",
+                   "path": "dpsgd_step" if fused else ("dpsgd_grad + dpsgd_mix_step_momentum" if Vel is not None
+                                                           else "dpsgd_grad + dpsgd_mix_step"),
                    **({"variant": variant} if variant else {})},
         "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

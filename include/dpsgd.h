@@ -165,6 +165,18 @@ dpsgd_status dpsgd_mix_step(dpsgd_ctx *ctx, const float *X_in, const float *G, f
 dpsgd_status dpsgd_mix_step_swapped(dpsgd_ctx *ctx, const float *X_in, const float *G, float *X_out,
                                     float *consensus);
 
+/* Heavy-ball variant of steps 4 and 5.  Section 5.3 runs D-PSGD with learning rate 0.1 and momentum 0.9 without
+ * saying where the momentum enters; the reading taken is the plain momentum update of the local gradient, the
+ * averaging untouched:
+ *   V[i]     <- mu * V[i] + G[i]                      (in place)
+ *   X_out[i]  = sum_j W_ij X_in[j] - gamma * V[i]
+ *   V        device, n x d (stride ld), read and written once; must not overlap X_in, X_out or G
+ *   mu       in [0, 1); mu = 0 gives dpsgd_mix_step (and V = G)
+ * Other arguments, in-place rule and consensus as in dpsgd_mix_step.  20 bytes per (worker, parameter).
+ * DPSGD_EINVAL for a mu outside [0, 1) or overlapping buffers. */
+dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const float *G, float *V, float mu,
+                                     float *X_out, float *consensus);
+
 /* One whole iteration of Algorithm 1 in place: X <- W X - gamma * grad(X), i.e. the result of dpsgd_grad(X -> G)
  * followed by dpsgd_mix_step(X, G -> X), up to the order of floating-point sums.  Footnote [b] observes that steps 3
  * and 4 are independent; here they share one pass over X wherever a kernel exists for it: for bf16 MLPs on the ring

@@ -22,7 +22,7 @@ MODEL_LSQ, MODEL_SOFTMAX, MODEL_MLP, MODEL_RESNET20 = range(4)
 EXPORTS = (
     "dpsgd_topology_build", "dpsgd_model_dim", "dpsgd_create", "dpsgd_destroy", "dpsgd_set_gamma",
     "dpsgd_set_option", "dpsgd_topology_export", "dpsgd_grad", "dpsgd_step", "dpsgd_mix_step", "dpsgd_mix_step_swapped",
-    "dpsgd_mean", "dpsgd_read_timing", "dpsgd_strerror",
+    "dpsgd_mix_step_momentum", "dpsgd_mean", "dpsgd_read_timing", "dpsgd_strerror",
 )
 
 
@@ -79,6 +79,8 @@ def load():
     for name in ("dpsgd_mix_step", "dpsgd_mix_step_swapped"):
         getattr(L, name).restype = C.c_int
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp]
+    L.dpsgd_mix_step_momentum.restype = C.c_int
+    L.dpsgd_mix_step_momentum.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp]
     L.dpsgd_mean.restype = C.c_int
     L.dpsgd_mean.argtypes = [vp, vp, vp]
     L.dpsgd_read_timing.restype = C.c_int
@@ -264,6 +266,13 @@ class Dpsgd:
         self._check_mat(X_out, "X_out")
         fn = self._L.dpsgd_mix_step_swapped if swapped else self._L.dpsgd_mix_step
         _check(fn(self._handle, _ptr(X_in), _ptr(G), _ptr(X_out), _ptr(consensus)), "dpsgd_mix_step")
+
+    def mix_step_momentum(self, X_in, G, V, mu: float, X_out, consensus=None):
+        """V <- mu V + G (in place); X_out = W X_in - gamma V."""
+        for t, name in ((X_in, "X_in"), (G, "G"), (V, "V"), (X_out, "X_out")):
+            self._check_mat(t, name)
+        _check(self._L.dpsgd_mix_step_momentum(self._handle, _ptr(X_in), _ptr(G), _ptr(V), C.c_float(mu), _ptr(X_out),
+                                               _ptr(consensus)), "dpsgd_mix_step_momentum")
 
     def read_timing(self):
         """(total ms, launches) of the fused kernels bracketed since the last call (option "time_fused")."""

@@ -345,6 +345,18 @@ dpsgd_status dpsgd_mix_step_swapped(dpsgd_ctx *ctx, const float *X_in, const flo
     return mix_common(ctx, X_in, G, X_out, consensus, true);
 }
 
+dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const float *G, float *V, float mu, float *X_out,
+                                     float *consensus)
+{
+    if (!ctx || !X_in || !G || !V || !X_out) return DPSGD_EINVAL;
+    if (!(mu >= 0.f && mu < 1.f)) return DPSGD_EINVAL;
+    const size_t bytes = (size_t)ctx->n * (size_t)ctx->ld * sizeof(float);
+    if (overlaps(G, X_out, bytes) || overlaps(V, X_out, bytes) || overlaps(V, X_in, bytes) || overlaps(V, G, bytes))
+        return DPSGD_EINVAL;
+    if (X_out != X_in && overlaps(X_in, X_out, bytes)) return DPSGD_EINVAL;
+    return dpsgd::launch_mix(ctx, X_in, G, X_out, consensus, false, V, mu);
+}
+
 dpsgd_status dpsgd_mean(dpsgd_ctx *ctx, const float *X, float *xbar)
 {
     if (!ctx || !X || !xbar) return DPSGD_EINVAL;

@@ -57,8 +57,9 @@ struct dpsgd_ctx {
 namespace dpsgd {
 
 // ---- mix.hip
+// Vel != NULL: heavy-ball variant (Vel <- mu Vel + G is the step direction); not with swapped.
 dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, float *consensus,
-                        bool swapped);
+                        bool swapped, float *Vel = nullptr, float mu = 0.f);
 dpsgd_status launch_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
 int64_t mix_partials_needed(const dpsgd_ctx *ctx);
 dpsgd_status launch_mix_ring_range(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, int64_t col0,

@@ -114,10 +114,11 @@ __device__ __forceinline__ void combine_bands(ColStats<V> &st, float *lds, int b
 // ------------------------------------------------------------------------------- ring
 // grid.x = column groups of 64*V columns; block = 64 * bands threads; wave b owns rows
 // [b*rpb, min(n,(b+1)*rpb)).
-template <int V, int U, bool CONS>
+// MOM: heavy-ball variant, the step uses v = mu * Vel + g and Vel is overwritten with it.
+template <int V, int U, bool CONS, bool MOM>
 __global__ void __launch_bounds__(512)
 mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld, float w,
-                float gamma, int bands, int rpb, double *__restrict__ partials)
+                float gamma, int bands, int rpb, double *__restrict__ partials, float *__restrict__ Vel, float mu)
 {
     typedef typename VecT<V>::type vec;
     extern __shared__ float lds[];
@@ -159,29 +160,47 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
         const int rlast = r1 - 1;
         const float *xp = xin + (i64)(row + 1) * ld;
         const float *gp = gin + (i64)row * ld;
+        float *vp = MOM ? Vel + c0 + (i64)row * ld : nullptr;
         float *op = xout + (i64)row * ld;
+        // the gradient the step uses: g itself, or the updated velocity (written back)
+        auto step_dir = [&](vec g, float *vdst) {
+            if (MOM) {
+                g = mu * vload<V>(vdst) + g;
+                vstore<V>(vdst, g);
+            }
+            return g;
+        };
         for (; row + U <= rlast; row += U) {
-            vec xs[U], gs[U];
+            vec xs[U], gs[U], vs[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 gs[u] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gp + (i64)u * ld));
+                if (MOM) vs[u] = vload<V>(vp + (i64)u * ld);
                 xs[u] = vload<V>(xp + (i64)u * ld);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) form(xs[u], gs[u], op + (i64)u * ld);
+            for (int u = 0; u < U; ++u) {
+                if (MOM) {
+                    gs[u] = mu * vs[u] + gs[u];
+                    vstore<V>(vp + (i64)u * ld, gs[u]);
+                }
+                form(xs[u], gs[u], op + (i64)u * ld);
+            }
             xp += (i64)U * ld;
             gp += (i64)U * ld;
+            if (MOM) vp += (i64)U * ld;
             op += (i64)U * ld;
         }
         for (; row < rlast; ++row) {
-            vec g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gp));
+            vec g = step_dir(__builtin_nontemporal_load(reinterpret_cast<const vec *>(gp)), vp);
             vec xn = vload<V>(xp);
             form(xn, g, op);
             xp += ld;
             gp += ld;
+            if (MOM) vp += ld;
             op += ld;
         }
-        form(xhalo, __builtin_nontemporal_load(reinterpret_cast<const vec *>(gp)), op);
+        form(xhalo, step_dir(__builtin_nontemporal_load(reinterpret_cast<const vec *>(gp)), vp), op);
     }
     if (CONS) {
         combine_bands<V>(st, lds, band, lane, bands);
@@ -195,11 +214,12 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
 // ------------------------------------------------------------------------ CSR via LDS slab
 // grid.x = column groups of 64*V columns; block = 64 * RG threads; lane = column vector,
 // wave = row group (rows rg, rg+RG, ...).  Dynamic LDS: n * 64 * V floats (+ stats region).
+// Vel != NULL (not with SWAPPED): heavy-ball variant, as in the ring kernel.
 template <int V, bool CONS, bool SWAPPED>
 __global__ void __launch_bounds__(1024)
 mix_csr_slab_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld,
                     const int *__restrict__ rowptr, const int *__restrict__ colidx, const float *__restrict__ vals,
-                    float gamma, int rgroups, double *__restrict__ partials)
+                    float gamma, int rgroups, double *__restrict__ partials, float *__restrict__ Vel, float mu)
 {
     typedef typename VecT<V>::type vec;
     extern __shared__ float lds[];
@@ -242,8 +262,14 @@ mix_csr_slab_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
             if (CONS) st.add(o);
         };
         auto gload = [&](int row) {
-            return SWAPPED ? (vec)(0.f)
-                           : __builtin_nontemporal_load(reinterpret_cast<const vec *>(gin + (i64)row * ld));
+            if (SWAPPED) return (vec)(0.f);
+            vec g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(gin + (i64)row * ld));
+            if (Vel) {
+                float *vdst = Vel + c0 + (i64)row * ld;
+                g = mu * vload<V>(vdst) + g;
+                vstore<V>(vdst, g);
+            }
+            return g;
         };
         int row = rg;
         for (; row + 3 * rgroups < n; row += 4 * rgroups) {
@@ -271,7 +297,7 @@ template <bool SWAPPED>
 __global__ void __launch_bounds__(256)
 mix_csr_gather_kernel(const float *__restrict__ Xin, const float *__restrict__ G, float *__restrict__ Xout, int n,
                       i64 ncols, i64 ld, const int *__restrict__ rowptr, const int *__restrict__ colidx,
-                      const float *__restrict__ vals, float gamma)
+                      const float *__restrict__ vals, float gamma, float *__restrict__ Vel, float mu)
 {
     const i64 c = (i64)blockIdx.x * 256 + threadIdx.x;
     const int row = blockIdx.y;
@@ -283,7 +309,16 @@ mix_csr_gather_kernel(const float *__restrict__ Xin, const float *__restrict__ G
         if (SWAPPED) x -= gamma * G[j * ld + c];
         acc = vals[p] * x + acc;
     }
-    Xout[(i64)row * ld + c] = SWAPPED ? acc : acc - gamma * G[(i64)row * ld + c];
+    if (SWAPPED) {
+        Xout[(i64)row * ld + c] = acc;
+        return;
+    }
+    float g = G[(i64)row * ld + c];
+    if (Vel) {
+        g = mu * Vel[(i64)row * ld + c] + g;
+        Vel[(i64)row * ld + c] = g;
+    }
+    Xout[(i64)row * ld + c] = acc - gamma * g;
 }
 
 // ---------------------------------------------------------------- column statistics / mean
@@ -430,7 +465,7 @@ size_t stats_lds_bytes(int bands, int vec) { return bands > 1 ? (size_t)bands * 
 
 template <int V>
 dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols,
-                         bool cons, double *partials, i64 *nparts)
+                         bool cons, double *partials, i64 *nparts, float *Vel = nullptr, float mu = 0.f)
 {
     const i64 groups = groups_for(ncols, V);
     const int bands = pick_bands(ctx, groups);
@@ -439,12 +474,15 @@ dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float
     dim3 grid((unsigned)groups), block(64u * (unsigned)used);
     if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
     const size_t shm = cons ? stats_lds_bytes(used, V) : 0;
-    if (cons)
-        hipLaunchKernelGGL((mix_ring_kernel<V, 4, true>), grid, block, shm, ctx->stream, Xin + col0, G + col0,
-                           Xout + col0, ctx->n, ncols, ctx->ld, ctx->ring_w, ctx->gamma, used, rpb, partials);
-    else
-        hipLaunchKernelGGL((mix_ring_kernel<V, 4, false>), grid, block, shm, ctx->stream, Xin + col0, G + col0,
-                           Xout + col0, ctx->n, ncols, ctx->ld, ctx->ring_w, ctx->gamma, used, rpb, partials);
+    float *vel = Vel ? Vel + col0 : nullptr;
+#define DPSGD_RING(CONS, MOM)                                                                                        \
+    hipLaunchKernelGGL((mix_ring_kernel<V, 4, CONS, MOM>), grid, block, shm, ctx->stream, Xin + col0, G + col0,      \
+                       Xout + col0, ctx->n, ncols, ctx->ld, ctx->ring_w, ctx->gamma, used, rpb, partials, vel, mu)
+    if (cons && vel) DPSGD_RING(true, true);
+    else if (cons) DPSGD_RING(true, false);
+    else if (vel) DPSGD_RING(false, true);
+    else DPSGD_RING(false, false);
+#undef DPSGD_RING
     *nparts = groups;
     return hip_status(hipGetLastError());
 }
@@ -453,8 +491,9 @@ constexpr size_t kSlabLdsBudget = 64 * 1024;
 
 template <int V, bool SWAPPED>
 dpsgd_status slab_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols,
-                         bool cons, double *partials, i64 *nparts)
+                         bool cons, double *partials, i64 *nparts, float *Vel = nullptr, float mu = 0.f)
 {
+    float *vel = Vel ? Vel + col0 : nullptr;
     const i64 groups = groups_for(ncols, V);
     if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
     int rgroups = ctx->n < 4 ? ctx->n : 4;
@@ -465,11 +504,11 @@ dpsgd_status slab_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float
     if (cons)
         hipLaunchKernelGGL((mix_csr_slab_kernel<V, true, SWAPPED>), grid, block, shm, ctx->stream, Xin + col0,
                            G + col0, Xout + col0, ctx->n, ncols, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals,
-                           ctx->gamma, rgroups, partials);
+                           ctx->gamma, rgroups, partials, vel, mu);
     else
         hipLaunchKernelGGL((mix_csr_slab_kernel<V, false, SWAPPED>), grid, block, shm, ctx->stream, Xin + col0,
                            G + col0, Xout + col0, ctx->n, ncols, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals,
-                           ctx->gamma, rgroups, partials);
+                           ctx->gamma, rgroups, partials, vel, mu);
     *nparts = groups;
     return hip_status(hipGetLastError());
 }
@@ -535,23 +574,25 @@ int64_t mix_partials_needed(const dpsgd_ctx *ctx)
     return groups_for(ctx->d, 1) + 8 + kStage1Blocks;
 }
 
-dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, float *consensus, bool swapped)
+dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, float *consensus, bool swapped,
+                        float *Vel, float mu)
 {
+    if (Vel && swapped) return DPSGD_EUNSUPPORTED;
     const bool cons = consensus != nullptr;
     const bool ring = ctx->ring_uniform && !ctx->opt_mix_force_csr && !swapped;
     i64 n1 = 0, n2 = 0;
     dpsgd_status st = DPSGD_OK;
 
     if (ring) {
-        const int vec = pick_vec(ctx, {Xin, G, Xout}, 4);
+        const int vec = pick_vec(ctx, {Xin, G, Xout, Vel ? Vel : Xin}, 4);
         const Plan p = make_plan(ctx, vec);
         if (p.bulk_cols) {
-            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1);
-            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1);
-            else st = ring_launch<1>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1);
+            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu);
+            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu);
+            else st = ring_launch<1>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu);
         }
         if (st == DPSGD_OK && p.tail_cols)
-            st = ring_launch<1>(ctx, Xin, G, Xout, p.bulk_cols, p.tail_cols, cons, ctx->d_partials + n1, &n2);
+            st = ring_launch<1>(ctx, Xin, G, Xout, p.bulk_cols, p.tail_cols, cons, ctx->d_partials + n1, &n2, Vel, mu);
         if (st != DPSGD_OK) return st;
         return cons ? finalize_consensus(ctx, n1 + n2, consensus) : DPSGD_OK;
     }
@@ -560,11 +601,11 @@ dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float 
     int cap = 4;
     while (cap >= 1 && (size_t)ctx->n * 64 * cap * sizeof(float) > kSlabLdsBudget) cap >>= 1;
     if (cap >= 1) {
-        const int vec = pick_vec(ctx, {Xin, G, Xout}, cap);
+        const int vec = pick_vec(ctx, {Xin, G, Xout, Vel ? Vel : Xin}, cap);
         const Plan p = make_plan(ctx, vec);
 #define DPSGD_SLAB(V, C0, NC, PART, NP)                                                              \
     (swapped ? slab_launch<V, true>(ctx, Xin, G, Xout, C0, NC, cons, PART, NP)                       \
-             : slab_launch<V, false>(ctx, Xin, G, Xout, C0, NC, cons, PART, NP))
+             : slab_launch<V, false>(ctx, Xin, G, Xout, C0, NC, cons, PART, NP, Vel, mu))
         if (p.bulk_cols) {
             if (vec == 4) st = DPSGD_SLAB(4, 0, p.bulk_cols, ctx->d_partials, &n1);
             else if (vec == 2) st = DPSGD_SLAB(2, 0, p.bulk_cols, ctx->d_partials, &n1);
@@ -583,10 +624,10 @@ dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float 
     dim3 grid((unsigned)gx, (unsigned)ctx->n);
     if (swapped)
         hipLaunchKernelGGL(mix_csr_gather_kernel<true>, grid, dim3(256), 0, ctx->stream, Xin, G, Xout, ctx->n, ctx->d,
-                           ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma);
+                           ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma, nullptr, 0.f);
     else
         hipLaunchKernelGGL(mix_csr_gather_kernel<false>, grid, dim3(256), 0, ctx->stream, Xin, G, Xout, ctx->n,
-                           ctx->d, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma);
+                           ctx->d, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma, Vel, mu);
     st = hip_status(hipGetLastError());
     if (st != DPSGD_OK) return st;
     return cons ? consensus_of(ctx, Xout, consensus) : DPSGD_OK;

@@ -229,3 +229,69 @@ def test_full_size_config3_torus():
 
 def test_full_size_config4_ring():
     _full_size_mix(112, 268365, B.Topology.ring(), oracle.ring(112).with_fp32_values())
+
+
+# ------------------------------------------------------------------ momentum variant (dpsgd_mix_step_momentum)
+def run_momentum(n, d, ld, topo_b, topo_o, seed, inplace, mu=0.9, gamma=0.05, steps=3, options=()):
+    rng = np.random.default_rng(seed)
+    X, _ = random_state(n, d, seed)
+    V = np.zeros((n, d), np.float32)
+    Xo, Vo = X.astype(np.float64), V.astype(np.float64)
+    Xd, Vd = to_dev(X, ld), to_dev(V, ld)
+    cd = torch.zeros(1, device="cuda")
+    print(f"momentum n={n} d={d} ld={ld} inplace={inplace} mu={mu}", flush=True)
+    with B.Dpsgd(n, d, topo_b, gamma, ld=ld) as ctx:
+        for k, v in options:
+            ctx.set_option(k, v)
+        for k in range(steps):
+            G = rng.standard_normal((n, d)).astype(np.float32)
+            Xo, Vo = oracle.mix_step_momentum(topo_o, Xo, G, Vo, np.float32(gamma), np.float32(mu))
+            Gd = to_dev(G, ld)
+            out = Xd if inplace else torch.full_like(Xd, 777.0)
+            ctx.mix_step_momentum(Xd, Gd, Vd, mu, out, cd)
+            torch.cuda.synchronize()
+            Xd = out
+            assert rel_err(from_dev(Xd, d), Xo) < TOL
+            assert rel_err(from_dev(Vd, d), Vo) < TOL
+            assert np.array_equal(from_dev(Gd, d), G.astype(np.float64))
+            assert float(cd.item()) == pytest.approx(oracle.consensus(Xo), rel=1e-4)
+
+
+@pytest.mark.parametrize("n,d,ld", [(8, 1003, 1024), (16, 30730, 30784), (5, 70001, 70002), (33, 5, 5)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_momentum_ring(n, d, ld, inplace):
+    run_momentum(n, d, ld, B.Topology.ring(), oracle.ring(n).with_fp32_values(), 70 + n, inplace)
+
+
+def test_momentum_torus_ring_chord_and_gather():
+    run_momentum(12, 3001, 3008, B.Topology.torus(3, 4), oracle.torus(3, 4).with_fp32_values(), 81, True)
+    run_momentum(16, 3001, 3001, B.Topology.ring_chord(), oracle.ring_chord(16).with_fp32_values(), 82, True, mu=0.5)
+    run_momentum(300, 700, 704, B.Topology.complete(), oracle.complete(300).with_fp32_values(), 83, False)
+
+
+def test_momentum_zero_equals_plain_step_bitwise():
+    n, d, ld = 16, 9000, 9024
+    X, G = random_state(n, d, 91)
+    Xd, Gd = to_dev(X, ld), to_dev(G, ld)
+    Vd = to_dev(np.ones((n, d), np.float32), ld)
+    a, b = torch.full_like(Xd, 777.0), torch.full_like(Xd, 777.0)
+    with B.Dpsgd(n, d, B.Topology.ring(), 0.05, ld=ld) as ctx:
+        ctx.mix_step(Xd, Gd, a)
+        ctx.mix_step_momentum(Xd, Gd, Vd, 0.0, b)
+        torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    assert np.array_equal(from_dev(Vd, d), G.astype(np.float64))
+
+
+def test_momentum_rejects_bad_arguments():
+    n, d = 8, 100
+    X, G = random_state(n, d, 92)
+    Xd, Gd, Vd = to_dev(X), to_dev(G), to_dev(np.zeros((n, d), np.float32))
+    with B.Dpsgd(n, d, B.Topology.ring(), 0.05) as ctx:
+        for mu in (1.0, -0.1, float("nan")):
+            with pytest.raises(B.DpsgdError) as e:
+                ctx.mix_step_momentum(Xd, Gd, Vd, mu, Xd)
+            assert e.value.status == B.EINVAL
+        with pytest.raises(B.DpsgdError) as e:
+            ctx.mix_step_momentum(Xd, Gd, Gd, 0.9, Xd)      # V aliases G
+        assert e.value.status == B.EINVAL
