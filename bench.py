@@ -259,6 +259,16 @@ def main():
         mix_ms = sum(a.elapsed_time(b) for a, b in evs) / K
         launch_ms = mix_ms
         launch_bytes = (20.0 if Vel is not None else 12.0) * cfg.n * d
+    # Algorithm 1 step 7 (run once after the K iterations): the node average, read-only, 4 n d bytes
+    xbar = torch.empty(d, device="cuda")
+    m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ctx.mean(X, xbar)
+    m0.record()
+    for _ in range(3):
+        ctx.mean(X, xbar)
+    m1.record()
+    torch.cuda.synchronize()
+    mean_ms = m0.elapsed_time(m1) / 3
     final_loss = float(loss.mean().item())
     final_cons = None if cons is None else float(cons.item())
     ctx.close()
@@ -284,6 +294,9 @@ def main():
                      "traffic": None if variant else MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
                      "algorithmic_bytes_per_launch": launch_bytes, "avg_launch_ms": launch_ms},
         "gradient": gradient_roofline(cfg, d, total_ms / K),
+        "mean": {"kernel": "dpsgd_mean (Algorithm 1 step 7)", "ms": mean_ms, "algorithmic_bytes": 4.0 * cfg.n * d,
+                 "achieved": 4.0 * cfg.n * d / (mean_ms * 1e-3) / 1e9, "unit": "GB/s",
+                 "frac": 4.0 * cfg.n * d / (mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "mix_fraction_of_step": mix_ms / (total_ms / K),
         "wall_s": wall,
         "final_mean_loss": final_loss, "final_consensus": final_cons,
