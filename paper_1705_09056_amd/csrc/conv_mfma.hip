@@ -12,8 +12,9 @@
 // spread over all banks), keeps its slice of the packed weights in registers for the whole tile, and
 // issues v_mfma_f32_16x16x32_bf16: A = 16 consecutive output pixels x 32 contraction values (8
 // channels of one tap per lane, one 16-byte LDS read), B = 32 x 16 output channels.  Accumulator
-// register i of lane l is (pixel 4*(l/16)+i, channel l%16), so a lane writes 4 consecutive pixels
-// of one channel with one 8-byte store.
+// register i of lane l is (MFMA row 4*(l/16)+i, channel l%16); two tiles are taken together with
+// their rows mapped to pixels so that a lane ends up with 8 consecutive pixels of one channel:
+// 16-byte loads and stores in the epilogue.
 #include "resnet_common.h"
 
 namespace dpsgd {
@@ -211,7 +212,7 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     }
     __syncthreads();
 
-    const int mtot = (TH << lw) >> 4;
+    const int npair = (TH << lw) >> 5;   // pairs of M tiles = groups of 32 consecutive pixels of the band
     float bias = 0.f;
     if (!DGRAD) bias = a.X[(i64)w * a.ld + a.b_off];
     // per-image bases; everything below is 32-bit offsets inside one image
@@ -220,68 +221,87 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     const bf16_t *scT = a.sc.t ? a.sc.t + img * a.sc.C * a.sc.H * a.sc.W : nullptr;
     const int scS = a.sc.S;
 
-    for (int mt = wp; mt < mtot; mt += WP) {
-        const int pi = mt * 16 + n16;                  // this lane's pixel as an A-operand row
-        const int py = pi >> lw, px = pi & (Wd - 1);
-        const bf16_t *pa = patch + ((py * STRIDE) * PC + px * STRIDE) * PP;
-        // this lane's outputs: pixels q0..q0+3 (consecutive x of one row) of channel o, per channel tile
-        const int q0 = mt * 16 + 4 * g;
+    // A wave takes two M tiles at a time and maps MFMA row r of tile tt to pixel 8 (r / 4) + 4 tt + r % 4 of
+    // the group: accumulator register i of lane (n16, g) is then pixel 8 g + 4 tt + i, so the lane owns 8
+    // consecutive pixels of channel n16 = 16 contiguous bytes of every channel-major tensor it touches.
+    for (int mp = wp; mp < npair; mp += WP) {
+        const bf16_t *pa[2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const int pi = mp * 32 + 8 * (n16 >> 2) + 4 * tt + (n16 & 3);   // this lane's pixel as an A-operand row
+            const int py = pi >> lw, px = pi & (Wd - 1);
+            pa[tt] = patch + ((py * STRIDE) * PC + px * STRIDE) * PP;
+        }
+        const int q0 = mp * 32 + 8 * g;                     // first of this lane's 8 output pixels (one row: Wd >= 8)
         const int y = y0 + (q0 >> lw), x0 = q0 & (Wd - 1);
-        // fetch what the epilogue needs (shortcut values, activation signs; 4 consecutive pixels of one
-        // channel are contiguous in the channel-major copies) before the MFMAs, to hide their latency
-        float e_sc[NTW][4];
-        u32x2 e_act[NTW];
+        // fetch what the epilogue needs (shortcut values, activation signs) before the MFMAs, to hide their latency
+        float e_sc[NTW][8];
+        u32x4 e_act[NTW];
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
             const int o = (wc * NTW + t) * 16 + n16;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) e_sc[t][i] = 0.f;
-            e_act[t] = (u32x2){0u, 0u};
-            if (DGRAD) e_act[t] = *reinterpret_cast<const u32x2 *>(actT + (o * a.Hd + y) * Wd + x0);
+            for (int i = 0; i < 8; ++i) e_sc[t][i] = 0.f;
+            e_act[t] = (u32x4){0u, 0u, 0u, 0u};
+            if (DGRAD) e_act[t] = *reinterpret_cast<const u32x4 *>(actT + (o * a.Hd + y) * Wd + x0);
             if (scT && o < a.sc.C) {
                 if (scS == 1) {
-                    const u32x2 v = *reinterpret_cast<const u32x2 *>(scT + (o * a.sc.H + y) * a.sc.W + x0);
-                    e_sc[t][0] = bf2f((bf16_t)(v.x & 0xffff)); e_sc[t][1] = bf2f((bf16_t)(v.x >> 16));
-                    e_sc[t][2] = bf2f((bf16_t)(v.y & 0xffff)); e_sc[t][3] = bf2f((bf16_t)(v.y >> 16));
-                } else if (!DGRAD) {   // block input at (2y, 2x): every second of 8 consecutive pixels
-                    const u32x4 v = *reinterpret_cast<const u32x4 *>(scT + (o * a.sc.H + 2 * y) * a.sc.W + 2 * x0);
-                    e_sc[t][0] = bf2f((bf16_t)(v.x & 0xffff)); e_sc[t][1] = bf2f((bf16_t)(v.y & 0xffff));
-                    e_sc[t][2] = bf2f((bf16_t)(v.z & 0xffff)); e_sc[t][3] = bf2f((bf16_t)(v.w & 0xffff));
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(scT + (o * a.sc.H + y) * a.sc.W + x0);
+                    const unsigned d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int h = 0; h < 4; ++h) {
+                        e_sc[t][2 * h] = bf2f((bf16_t)(d[h] & 0xffff));
+                        e_sc[t][2 * h + 1] = bf2f((bf16_t)(d[h] >> 16));
+                    }
+                } else if (!DGRAD) {   // block input at (2y, 2x): every second of 16 consecutive pixels
+                    const bf16_t *sp = scT + (o * a.sc.H + 2 * y) * a.sc.W + 2 * x0;
+                    const u32x4 v0 = *reinterpret_cast<const u32x4 *>(sp), v1 = *reinterpret_cast<const u32x4 *>(sp + 8);
+                    const unsigned d[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) e_sc[t][i] = bf2f((bf16_t)(d[i] & 0xffff));
                 } else if (!(y & 1)) {   // delta of the block output lands on even pixels only
-                    const unsigned v = *reinterpret_cast<const unsigned *>(scT + (o * a.sc.H + (y >> 1)) * a.sc.W + (x0 >> 1));
-                    e_sc[t][0] = bf2f((bf16_t)(v & 0xffff));
-                    e_sc[t][2] = bf2f((bf16_t)(v >> 16));
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(scT + (o * a.sc.H + (y >> 1)) * a.sc.W + (x0 >> 1));
+                    e_sc[t][0] = bf2f((bf16_t)(v.x & 0xffff));
+                    e_sc[t][2] = bf2f((bf16_t)(v.x >> 16));
+                    e_sc[t][4] = bf2f((bf16_t)(v.y & 0xffff));
+                    e_sc[t][6] = bf2f((bf16_t)(v.y >> 16));
                 }
             }
         }
-        f32x4 acc[NTW];
+        f32x4 acc[2][NTW];
 #pragma unroll
-        for (int t = 0; t < NTW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int t = 0; t < NTW; ++t) acc[tt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const bf16x8 av = *reinterpret_cast<const bf16x8 *>(pa + koff[s]);
 #pragma unroll
-            for (int t = 0; t < NTW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wf[s][t], acc[t], 0, 0, 0);
+            for (int tt = 0; tt < 2; ++tt) {
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(pa[tt] + koff[s]);
+#pragma unroll
+                for (int t = 0; t < NTW; ++t)
+                    acc[tt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wf[s][t], acc[tt][t], 0, 0, 0);
+            }
         }
 #pragma unroll
         for (int t = 0; t < NTW; ++t) {
             const int o = (wc * NTW + t) * 16 + n16;
-            const bf16_t am[4] = {(bf16_t)(e_act[t].x & 0xffff), (bf16_t)(e_act[t].x >> 16), (bf16_t)(e_act[t].y & 0xffff),
-                                  (bf16_t)(e_act[t].y >> 16)};
-            float r[4];
+            const unsigned ad[4] = {e_act[t].x, e_act[t].y, e_act[t].z, e_act[t].w};
+            float r[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float v = acc[t][i] + e_sc[t][i];
+            for (int i = 0; i < 8; ++i) {
+                float v = acc[i >> 2][t][i & 3] + e_sc[t][i];
                 if (!DGRAD) {
                     v += bias;
                     v = v > 0.f ? v : 0.f;
                 } else {
-                    v = bf16_positive(am[i]) ? v : 0.f;
+                    const bf16_t am = (bf16_t)((i & 1) ? (ad[i >> 1] >> 16) : (ad[i >> 1] & 0xffff));
+                    v = bf16_positive(am) ? v : 0.f;
                 }
                 r[i] = v;
             }
-            const u32x2 pk = {f2bf_pack(r[0], r[1]), f2bf_pack(r[2], r[3])};
-            *reinterpret_cast<u32x2 *>(dstT + ((o * a.Hd + y) << lw) + x0) = pk;
+            const u32x4 pk = {f2bf_pack(r[0], r[1]), f2bf_pack(r[2], r[3]), f2bf_pack(r[4], r[5]), f2bf_pack(r[6], r[7])};
+            *reinterpret_cast<u32x4 *>(dstT + ((o * a.Hd + y) << lw) + x0) = pk;
         }
     }
 }
