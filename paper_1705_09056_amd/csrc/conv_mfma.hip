@@ -323,7 +323,7 @@ struct WgradMfmaArgs {
     const bf16_t *inT;     // [n*B][CIr][H][W]
     const bf16_t *doutT;   // [n*B][CO][Ho][Wo]
     int H, W, Ho, Wo, B, CIr, splits;
-    float *part;           // [n][splits][CO*CIr*9 + 1]
+    float *part;           // [n][splits][(CO/16)*(CI/16)*9*256 + 1], accumulator order
 };
 
 // 16-byte units of a band's source rows a thread holds while they are in flight (10 rows at stride 1, 17 at stride 2)
@@ -355,7 +355,8 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
     // channel pitch = 8 elements (16 bytes) past a multiple of 256 bytes: the 16 lanes of an operand read
     // (16 channels, 16 bytes each) then fall into 16 different groups of 4 banks
     const int CP = wgrad_channel_pitch(ROWS * PLANES * WPAD);
-    const int psz = CO * a.CIr * 9 + 1;
+    // a partial result in accumulator order: [co tile][ci tile][tap][lane][4] floats, then the bias sum
+    constexpr int psz = (CO / 16) * (CI / 16) * 9 * 256 + 1;
 
     f32x4 acc[NTI][9];
 #pragma unroll
@@ -496,16 +497,12 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
         __syncthreads();
     }
     float *out = a.part + ((i64)w * a.splits + sp) * psz;
-    if (kq == 0) {
+    if (kq == 0) {   // 16-byte stores, 1 KB per wave and tap; wgrad_reduce_kernel puts the elements in their places
 #pragma unroll
-        for (int t = 0; t < NTI; ++t) {
-            const int ci = (t0 + t) * 16 + n16;
-            if (ci < a.CIr)
+        for (int t = 0; t < NTI; ++t)
 #pragma unroll
-                for (int k = 0; k < 9; ++k)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) out[((mi * 16 + 4 * g + i) * a.CIr + ci) * 9 + k] = acc[t][k][i];
-        }
+            for (int k = 0; k < 9; ++k)
+                *reinterpret_cast<f32x4 *>(out + (((mi * (CI / 16) + t0 + t) * 9 + k) * 64 + lane) * 4) = acc[t][k];
     }
     // bias: sum of every delta element this workgroup saw
     for (int off = 32; off > 0; off >>= 1) bsum += __shfl_down(bsum, off, 64);
@@ -514,16 +511,46 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
     if (tid == 0) out[psz - 1] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// G[w_off + e] = sum over splits of the partials (ascending split), G[b_off] = sum of the bias partials.
+// G[w_off + ...] = sum over splits of the partials (ascending split), G[b_off] = sum of the bias partials.
+// grid (tiles + 1, n), block 256: block T sums the (co tile, ci tile) pair T, reading along the accumulator
+// order (consecutive threads, consecutive floats), turns the tile into G's [c_out][c_in][tap] order in LDS and
+// writes 16 runs of up to 144 consecutive floats; the last block adds the bias partials.
 __global__ void __launch_bounds__(256)
-wgrad_reduce_kernel(const float *__restrict__ part, int splits, int psz, float *__restrict__ G, i64 ld, i64 w_off, i64 b_off)
+wgrad_reduce_kernel(const float *__restrict__ part, int splits, int psz, int ci_tiles, int CIr, float *__restrict__ G, i64 ld,
+                    i64 w_off, i64 b_off)
 {
-    const int e = blockIdx.x * 256 + threadIdx.x, w = blockIdx.y;
-    if (e >= psz) return;
-    const float *p = part + (i64)w * splits * psz + e;
-    float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += p[(i64)k * psz];
-    G[(i64)w * ld + (e == psz - 1 ? b_off : w_off + e)] = s;
+    __shared__ float tile[16 * 16 * 9];
+    const int T = blockIdx.x, w = blockIdx.y, tid = threadIdx.x;
+    const float *p = part + (i64)w * splits * psz;
+    if (T == (int)gridDim.x - 1) {
+        if (tid == 0) {
+            float s = 0.f;
+            for (int k = 0; k < splits; ++k) s += p[(i64)k * psz + psz - 1];
+            G[(i64)w * ld + b_off] = s;
+        }
+        return;
+    }
+    {   // element tid of the tile's 256 per tap: lane tid / 4 (c_in = lane % 16, row group lane / 16), register tid % 4
+        const int lane = tid >> 2, i = tid & 3;
+        const int ol = 4 * (lane >> 4) + i, cl = lane & 15;
+        float s[9];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) s[k] = 0.f;
+        for (int sp = 0; sp < splits; ++sp) {
+            const float *q = p + (i64)sp * psz + (i64)T * 9 * 256 + tid;
+#pragma unroll
+            for (int k = 0; k < 9; ++k) s[k] += q[k * 256];
+        }
+#pragma unroll
+        for (int k = 0; k < 9; ++k) tile[(ol * 16 + cl) * 9 + k] = s[k];
+    }
+    __syncthreads();
+    const int o0 = (T / ci_tiles) * 16, c0 = (T % ci_tiles) * 16;
+    const int run = (CIr - c0 < 16 ? CIr - c0 : 16) * 9;   // floats of one c_out row that exist
+    for (int e = tid; e < 16 * 144; e += 256) {
+        const int ol = e / 144, r = e % 144;
+        if (r < run) G[(i64)w * ld + w_off + ((i64)(o0 + ol) * CIr + c0) * 9 + r] = tile[e];
+    }
 }
 
 // Workgroups that share one worker's minibatch (each writes a partial sum of the whole weight gradient): few when
@@ -555,9 +582,9 @@ dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs
     if (shm < 64) shm = 64;
     hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256 * WT), shm,
                        ctx->stream, a);
-    const int psz = CO * a.CIr * 9 + 1;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((psz + 255) / 256), (unsigned)ctx->n), dim3(256), 0, ctx->stream,
-                       a.part, a.splits, psz, G, ctx->ld, c.w_off, c.b_off);
+    constexpr int tiles = (CO / 16) * (CI / 16), psz = tiles * 9 * 256 + 1;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)(tiles + 1), (unsigned)ctx->n), dim3(256), 0, ctx->stream, a.part,
+                       a.splits, psz, CI / 16, a.CIr, G, ctx->ld, c.w_off, c.b_off);
     return hip_status(hipGetLastError());
 }
 
@@ -656,7 +683,8 @@ size_t conv_pack_bytes(const ConvDesc &c, bool dgrad)
 size_t conv_wgrad_partial_bytes(const ConvDesc &c, int B)
 {
     if (!wgrad_mfma_ok(c)) return 0;
-    return (size_t)wgrad_splits(B, c.Co, c.stride) * ((size_t)c.Co * c.Ci * 9 + 1) * sizeof(float);
+    const size_t cip = (size_t)(c.Ci + 15) / 16 * 16;   // partials are stored per 16 x 16 tile of (c_out, padded c_in)
+    return (size_t)wgrad_splits(B, c.Co, c.stride) * ((size_t)c.Co * cip * 9 + 1) * sizeof(float);
 }
 
 dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const std::vector<ConvDesc> &convs, const float *X,
