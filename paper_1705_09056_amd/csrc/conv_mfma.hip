@@ -54,8 +54,15 @@ struct PackTable {
     int njobs;
 };
 
+// A workgroup packs one tile of 16 outputs of one job and worker.  The fp32 weights it needs are runs of
+// consecutive floats (forward: the 16 rows W[o][.][.], one run; data gradient: for every c_out the 16 x 9 floats
+// W[c_out][ci0 .. ci0+15][.]): they are read coalesced, rounded to bf16 into LDS, and the operand is composed from
+// LDS and written as 16-byte units.
+constexpr int kPackLds = 64 * 16 * 9;   // bf16 elements: 16 outputs x 64 contraction channels x 9 taps
+
 __global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restrict__ X, i64 ld, PackTable tbl)
 {
+    __shared__ bf16_t tile[kPackLds];
     // the job of this workgroup: last one whose first block is <= blockIdx.x (bisection over uniform values)
     int lo = 0, hi = tbl.njobs - 1;
     while (lo < hi) {
@@ -63,26 +70,51 @@ __global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restri
         if ((int)blockIdx.x >= tbl.job[mid].block0) lo = mid; else hi = mid - 1;
     }
     const PackJob &jb = tbl.job[lo];
-    const int w = blockIdx.y;
-    const int groups = jb.KS * (jb.CO / 16) * 64;            // 16-byte units (one lane's 8 values) per worker
-    const int u = ((int)blockIdx.x - jb.block0) * 256 + threadIdx.x;
-    if (u >= groups) return;
-    const int lane = u & 63, st = u >> 6;
-    const int t = st % (jb.CO / 16), s = st / (jb.CO / 16);
-    const int o = 16 * t + (lane & 15);
-    const int c_real = jb.dgrad ? jb.Co : jb.Ci, o_real = jb.dgrad ? jb.Ci : jb.Co;
+    const int w = blockIdx.y, t = (int)blockIdx.x - jb.block0, tid = threadIdx.x;
+    const int NT = jb.CO / 16;
     const float *Wg = X + (i64)w * ld + jb.w_off;
-    float v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int kk = 32 * s + 8 * (lane >> 4) + j;
-        const int tap = kk / jb.CI, ch = kk % jb.CI;
-        v[j] = 0.f;
-        if (tap < 9 && ch < c_real && o < o_real)
-            v[j] = jb.dgrad ? Wg[((i64)ch * jb.Ci + o) * 9 + (8 - tap)] : Wg[((i64)o * jb.Ci + ch) * 9 + tap];
+    const int row9 = jb.Ci * 9;   // floats of one c_out row of W
+    // rows x len floats, row r at Wg[base + r * row9]; in LDS row r at tile[r * len]
+    int rows, len, base;
+    if (!jb.dgrad) {   // outputs are c_out 16 t .. 16 t + 15: their rows are adjacent
+        rows = jb.Co - 16 * t < 16 ? jb.Co - 16 * t : 16;
+        len = row9;
+        base = 16 * t * row9;
+    } else {           // outputs are c_in 16 t .. 16 t + 15: 16 x 9 floats of every c_out row
+        rows = jb.Co;
+        len = (jb.Ci - 16 * t < 16 ? jb.Ci - 16 * t : 16) * 9;
+        base = 16 * t * 9;
     }
-    const u32x4 pk = {f2bf_pack(v[0], v[1]), f2bf_pack(v[2], v[3]), f2bf_pack(v[4], v[5]), f2bf_pack(v[6], v[7])};
-    *reinterpret_cast<u32x4 *>(jb.dst + ((i64)w * groups + u) * 8) = pk;
+    if (!jb.dgrad) {
+        for (int e = tid; e < rows * len; e += 256) tile[e] = f2bf(Wg[base + e]);   // one run
+    } else {
+        for (int r = tid >> 6; r < rows; r += 4)
+            for (int c = tid & 63; c < len; c += 64) tile[r * len + c] = f2bf(Wg[base + (i64)r * row9 + c]);
+    }
+    __syncthreads();
+    const int lg = 31 - __builtin_clz(jb.CI);   // CI is 8, 16, 32 or 64
+    const int groups = jb.KS * 64;   // 16-byte units of this tile
+    bf16_t *dst = jb.dst + (i64)w * (jb.KS * NT * 512);
+    for (int u = tid; u < groups; u += 256) {
+        const int lane = u & 63, s = u >> 6, ol = lane & 15;
+        unsigned short v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int kk = 32 * s + 8 * (lane >> 4) + j;
+            const int tap = kk >> lg, ch = kk & (jb.CI - 1);
+            v[j] = 0;
+            if (tap < 9) {
+                if (!jb.dgrad) {
+                    if (ch < jb.Ci && ol < rows) v[j] = tile[ol * len + ch * 9 + tap];
+                } else {
+                    if (ch < jb.Co && ol * 9 < len) v[j] = tile[ch * len + ol * 9 + (8 - tap)];
+                }
+            }
+        }
+        const u32x4 pk = {v[0] | ((unsigned)v[1] << 16), v[2] | ((unsigned)v[3] << 16), v[4] | ((unsigned)v[5] << 16),
+                          v[6] | ((unsigned)v[7] << 16)};
+        *reinterpret_cast<u32x4 *>(dst + ((i64)(s * NT + t) * 64 + lane) * 8) = pk;
+    }
 }
 
 // --------------------------------------------------------------- forward / data gradient
@@ -704,7 +736,7 @@ dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const std::vector<ConvDesc> &conv
         PackJob &jb = tbl.job[tbl.njobs++];
         jb.w_off = c.w_off; jb.dst = dst; jb.Ci = c.Ci; jb.Co = c.Co; jb.CI = CI; jb.CO = CO; jb.KS = ksteps(CI);
         jb.dgrad = dgrad ? 1 : 0; jb.block0 = blocks;
-        blocks += (jb.KS * 4 * CO + 255) / 256;   // KS * (CO / 16) * 64 units of 16 bytes
+        blocks += CO / 16;   // one workgroup per tile of 16 outputs
     };
     for (size_t q = 0; q < convs.size(); ++q) {
         const ConvDesc &c = convs[q];
