@@ -109,3 +109,43 @@ def test_step_config3_full_size_one_worker():
     e = rel_err(got - rows[7], want - rows[7])
     print(f"  worker 7 update vs oracle: {e:.3e}", flush=True)
     assert e < TIGHT
+
+
+def test_step_short_trajectory_with_gamma_schedule():
+    """Ten iterations of dpsgd_step on its own trajectory, fresh minibatches, gamma lowered half way
+    (dpsgd_set_gamma): strict single-step gate from the oracle's X_k at every iteration, loose gate on the
+    free-running iterates, and the node-average recursion of the proof of Theorem 1 on the device data."""
+    cfg = shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=6, iters=10)
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    ld = synth.padded_stride(d)
+    topo_o = oracle_topo_for(cfg)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    Xo = synth.make_replicas(cfg).astype(np.float64)
+    Xfree = to_dev(Xo, ld)
+    G = torch.full_like(Xfree, 777.0)
+    loss = torch.zeros(cfg.n, device="cuda")
+    with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+        for k in range(cfg.iters):
+            gamma = cfg.gamma if k < 5 else cfg.gamma / 10
+            ctx.set_gamma(gamma)
+            inp, tgt = synth.make_batch(cfg, k)
+            inp_d, tgt_d = bf16_dev(inp), torch.from_numpy(tgt).cuda()
+            Xn, Gref, _ = oracle.iteration(cfg.model_kind, cfg.widths, topo_o, np.float32(gamma), Xo, inp, tgt,
+                                           bf16_operands=True)
+            # single step from the oracle's X_k (rounded to fp32, as the device holds it)
+            Xs = to_dev(Xo, ld)
+            ctx.step(model, Xs, inp_d, tgt_d, cfg.batch, G, loss, None, input_is_bf16=True)
+            # free-running
+            before = from_dev(Xfree, d)
+            ctx.step(model, Xfree, inp_d, tgt_d, cfg.batch, G, loss, None, input_is_bf16=True)
+            torch.cuda.synchronize()
+            e1 = rel_err(from_dev(Xs, d) - Xo, Xn - Xo)
+            after = from_dev(Xfree, d)
+            ef = rel_err(after, Xn)
+            print(f"  k={k} gamma={gamma:g}: single-step update {e1:.3e}, free-running X {ef:.3e}", flush=True)
+            assert e1 < TIGHT
+            assert ef < TOL
+            # the step moved the node average by -gamma * (mean gradient): |mean(after) - mean(before)| is O(gamma)
+            drift = np.abs(after.mean(0) - before.mean(0)).max()
+            assert drift < 50 * gamma
+            Xo = Xn
