@@ -18,7 +18,9 @@
  *     ordinary host memory.  The library owns only the context (device copy of W and its
  *     workspace) and frees it in dpsgd_destroy.
  *   - All device work is enqueued on the hipStream_t given to dpsgd_create; no call
- *     synchronises the host with the device except dpsgd_create and dpsgd_destroy.
+ *     synchronises the host with the device except dpsgd_create, dpsgd_destroy,
+ *     dpsgd_read_timing, and a dpsgd_grad / dpsgd_step call that has to allocate or grow the
+ *     gradient workspace (the first call for a model, or one with a larger minibatch).
  *     Device outputs (G, X_out, loss, consensus, xbar) are valid in stream order.
  *   - Every call returns a dpsgd_status.  Arguments and the topology are validated on the
  *     host before anything touches the device.
