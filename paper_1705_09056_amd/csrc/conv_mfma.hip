@@ -128,6 +128,8 @@ struct ConvMfmaArgs {
     i64 ld, b_off;
     ShortcutRef sc;         // forward: block input; data gradient: delta of the block output
     const bf16_t *actT;     // data gradient: activation whose sign masks the result (shape of dst)
+    const unsigned char *sign_in;   // data gradient: the same signs as a bitmap (1 bit per element), or null
+    unsigned char *sign_out;        // forward: bitmap of the output's signs, or null
 };
 
 template <int CI, int CO, int STRIDE, int DILATE, bool DGRAD>
@@ -143,6 +145,7 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     const int y0 = band * TH;
     const int Wd = a.Wd, lw = a.lw;
     const int PR = (TH - 1) * STRIDE + 3, PC = (Wd - 1) * STRIDE + 3;
+    unsigned char *sign_lds = smem + PR * PC * PP * (int)sizeof(bf16_t);   // forward: CO * Wd bytes behind the patch
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wc = wave % WC, wp = wave / WC;
     const int n16 = lane & 15, g = lane >> 4;
@@ -250,6 +253,11 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     // per-image bases; everything below is 32-bit offsets inside one image
     bf16_t *dstT = a.dstT + img * CO * a.Hd * Wd;
     const bf16_t *actT = DGRAD ? a.actT + img * CO * a.Hd * Wd : nullptr;
+    // sign bitmaps are stored per band of 8 rows, [image][band][channel][Wd bytes], so that a workgroup reads
+    // or writes CO * Wd consecutive bytes that no other workgroup shares a cache line with
+    const i64 sign_base = (img * (a.Hd / TH) + band) * (CO * Wd);
+    const unsigned char *signi = (DGRAD && a.sign_in) ? a.sign_in + sign_base : nullptr;
+    unsigned char *signo = (!DGRAD && a.sign_out) ? a.sign_out + sign_base : nullptr;
     const bf16_t *scT = a.sc.t ? a.sc.t + img * a.sc.C * a.sc.H * a.sc.W : nullptr;
     const int scS = a.sc.S;
 
@@ -275,7 +283,10 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 #pragma unroll
             for (int i = 0; i < 8; ++i) e_sc[t][i] = 0.f;
             e_act[t] = (u32x4){0u, 0u, 0u, 0u};
-            if (DGRAD) e_act[t] = *reinterpret_cast<const u32x4 *>(actT + (o * a.Hd + y) * Wd + x0);
+            if (DGRAD) {   // the lane's 8 pixels are one byte of the bitmap
+                if (signi) e_act[t].x = signi[o * Wd + (q0 >> 3)];
+                else e_act[t] = *reinterpret_cast<const u32x4 *>(actT + (o * a.Hd + y) * Wd + x0);
+            }
             if (scT && o < a.sc.C) {
                 if (scS == 1) {
                     const u32x4 v = *reinterpret_cast<const u32x4 *>(scT + (o * a.sc.H + y) * a.sc.W + x0);
@@ -328,13 +339,31 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
                     v = v > 0.f ? v : 0.f;
                 } else {
                     const bf16_t am = (bf16_t)((i & 1) ? (ad[i >> 1] >> 16) : (ad[i >> 1] & 0xffff));
-                    v = bf16_positive(am) ? v : 0.f;
+                    const bool pos = signi ? ((ad[0] >> i) & 1u) != 0 : bf16_positive(am);
+                    v = pos ? v : 0.f;
                 }
                 r[i] = v;
             }
             const u32x4 pk = {f2bf_pack(r[0], r[1]), f2bf_pack(r[2], r[3]), f2bf_pack(r[4], r[5]), f2bf_pack(r[6], r[7])};
             *reinterpret_cast<u32x4 *>(dstT + ((o * a.Hd + y) << lw) + x0) = pk;
+            if (!DGRAD && signo) {
+                // from the stored bf16 values, so that both masks agree bit for bit; after the ReLU a value is
+                // positive exactly when its bf16 pattern is not zero
+                const unsigned pw[4] = {pk.x, pk.y, pk.z, pk.w};
+                unsigned bits = 0;
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    bits |= (pw[h] & 0xffffu) ? (1u << (2 * h)) : 0u;
+                    bits |= (pw[h] >> 16) ? (2u << (2 * h)) : 0u;
+                }
+                sign_lds[o * Wd + (q0 >> 3)] = (unsigned char)bits;
+            }
         }
+    }
+    if (!DGRAD && signo) {   // the band's bitmap (CO * Wd bytes) leaves as 16-byte units: a few requests per workgroup
+        __syncthreads();
+        for (int u = tid; u < CO * Wd / 16; u += 256)
+            *reinterpret_cast<u32x4 *>(signo + 16 * u) = *reinterpret_cast<const u32x4 *>(sign_lds + 16 * u);
     }
 }
 
@@ -625,7 +654,7 @@ bool tile_ok(int Hd, int Wd, int stride, int ci)
 {
     if (Hd % 8 || !(Wd == 8 || Wd == 16 || Wd == 32 || Wd == 64)) return false;
     const size_t pr = 7 * stride + 3, pc = (size_t)(Wd - 1) * stride + 3;
-    return pr * pc * (ci + 8) * 2 <= 64 * 1024;
+    return pr * pc * (ci + 8) * 2 + 64 * 64 <= 64 * 1024;   // patch + the band's sign bitmap (at most 64 channels x 64 bytes)
 }
 
 // The stem (at most 8 input channels) runs on an image padded to 8 channels (NHWC8).
@@ -652,7 +681,7 @@ template <int CI, int CO, int STRIDE, int DILATE, bool DGRAD>
 dpsgd_status launch_conv(dpsgd_ctx *ctx, const ConvMfmaArgs &a)
 {
     const size_t pr = 7 * STRIDE + 3, pc = (size_t)(a.Wd - 1) * STRIDE + 3;
-    const size_t shm = pr * pc * (CI + 8) * sizeof(bf16_t);
+    const size_t shm = pr * pc * (CI + 8) * sizeof(bf16_t) + (DGRAD ? 0 : (size_t)CO * a.Wd);
     dim3 grid((unsigned)(a.Hd / 8), (unsigned)a.B, (unsigned)ctx->n);
     hipLaunchKernelGGL((conv3x3_mfma_kernel<CI, CO, STRIDE, DILATE, DGRAD>), grid, dim3(256), shm, ctx->stream, a);
     return hip_status(hipGetLastError());
@@ -689,6 +718,11 @@ prep_image_kernel(const void *__restrict__ in, int C, int HW, i64 total, bf16_t 
 }  // namespace
 
 bool conv_stem_uses_mfma(const ConvDesc &c) { return stem_like(c) && fwd_mfma_ok(c) && wgrad_mfma_ok(c); }
+
+bool conv_forward_writes_sign(const ConvDesc &c, bool is_stem)
+{
+    return is_stem ? conv_stem_uses_mfma(c) : (!stem_like(c) && fwd_mfma_ok(c));
+}
 
 dpsgd_status conv_prep_image(dpsgd_ctx *ctx, const ConvDesc &c, int B, const void *image, bool image_is_bf16,
                              bf16_t *chw_bf16, bf16_t *nhwc8)
@@ -754,6 +788,7 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
     ConvMfmaArgs a{};
     a.src = in.t; a.Hs = c.H; a.Ws = c.W; a.wpack = wpack; a.dstT = out.t; a.Hd = c.Ho; a.Wd = c.Wo;
     a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = c.b_off; a.sc = sc; a.actT = nullptr;
+    a.sign_in = nullptr; a.sign_out = out.sign;
     a.lw = ilog2(a.Wd);
     if (stem_like(c)) return launch_conv<8, 16, 1, 1, false>(ctx, a);   // `in` is the image padded to 8 channels
     if (c.stride == 1) {
@@ -772,6 +807,7 @@ dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dou
     ConvMfmaArgs a{};
     a.src = dout.t; a.Hs = c.Ho; a.Ws = c.Wo; a.wpack = wpack_d; a.dstT = din.t; a.Hd = c.H; a.Wd = c.W;
     a.B = B; a.X = X; a.ld = ctx->ld; a.b_off = 0; a.sc = scd; a.actT = act.t;
+    a.sign_in = act.sign; a.sign_out = nullptr;
     a.lw = ilog2(a.Wd);
     if (c.stride == 1) {
         if (c.Ci == 16) return launch_conv<16, 16, 1, 1, true>(ctx, a);

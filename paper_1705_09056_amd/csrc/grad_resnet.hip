@@ -315,6 +315,7 @@ Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPla
         const size_t e = nB * c.Ho * c.Wo * c.Co;
         Tensor t;
         t.t = (bf16_t *)take(e * 2);
+        if (conv_forward_writes_sign(c, w.out.empty())) t.sign = (unsigned char *)take(e / 8);
         w.out.push_back(t);
         biggest = e > biggest ? e : biggest;
         w.wpack_f.push_back((bf16_t *)take(conv_pack_bytes(c, false) * ctx->n));

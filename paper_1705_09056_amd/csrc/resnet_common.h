@@ -43,8 +43,12 @@ ResnetPlan make_resnet_plan(const dpsgd_model_desc &m);
 // over pixels and reads them contiguously; forward and data gradient contract over channels and
 // transpose their source rows on the way into LDS; epilogues read and write 4 consecutive pixels
 // of one channel.
+// `sign` (may be null): one bit per element of an activation, stored per band of 8 rows:
+// [n][B][H / 8][C][8 rows][W / 8] bytes, bit i of a byte = pixel 8 k + i of that row is positive.  The MFMA forward kernel writes it next to the activation and the MFMA data gradient reads
+// it as its ReLU mask instead of the 16 times larger activation.
 struct Tensor {
     bf16_t *t = nullptr;
+    unsigned char *sign = nullptr;
 };
 // Forward: the block input added to the block output at (y*S, x*S) for the first C channels.
 // Backward: the delta of the block output added to the block input's delta at multiples of S.
@@ -74,6 +78,8 @@ dpsgd_status conv_pack_weights(dpsgd_ctx *ctx, const std::vector<ConvDesc> &conv
 // Stem support: whether the first conv runs on MFMA, and the image copies it then needs: a bf16
 // channel-major copy (only made from fp32 images; may be null) and the image padded to 8 channels (NHWC8).
 bool conv_stem_uses_mfma(const ConvDesc &c);
+// Whether conv_forward fills out.sign for this conv (the stem counts only when it runs on MFMA).
+bool conv_forward_writes_sign(const ConvDesc &c, bool is_stem);
 dpsgd_status conv_prep_image(dpsgd_ctx *ctx, const ConvDesc &c, int B, const void *image, bool image_is_bf16,
                              bf16_t *chw_bf16, bf16_t *nhwc8);
 
