@@ -58,6 +58,17 @@ def parse():
     return ap.parse_args()
 
 
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, seconds_budget=20.0):
     """The oracle as it stands, on this machine's host cores, on a bounded sample of the workload:
     the gradient of `m` workers (OpenMP over workers) and the mix+step on a column sample, scaled to
@@ -98,7 +109,7 @@ def cpu_baseline(cfg, seconds_budget=20.0):
     t_iter_1 = per_worker * cfg.n + t_mix
     return {
         "value": cfg.n / t_iter, "unit": "worker-iters/s", "cores": int(min(threads, m)), "kind": "oracle",
-        "single_thread_estimate": cfg.n / t_iter_1,
+        "single_thread_estimate": cfg.n / t_iter_1, "cpu_model": _cpu_model(),
         "sample": f"gradient of {m} of {cfg.n} workers (one minibatch each, OpenMP over workers, {t_grad:.2f} s) "
                   f"scaled by n/{m}; mix+step on {dcols} of {d} columns (single thread, scaled to d)",
     }
