@@ -241,6 +241,10 @@ dpsgd_status dpsgd_create(dpsgd_ctx **out, int32_t n, int64_t d, int64_t ld, con
         ctx->ring_uniform = true;
         ctx->ring_w = ctx->vals[0];
     }
+    if (W->kind == DPSGD_TOPO_TORUS2D && W->dim0 >= 3 && W->dim1 >= 3) {
+        ctx->torus_uniform = true;
+        ctx->torus_w = ctx->vals[0];
+    }
 
     // ---- device side
     const size_t nnz = ctx->colidx.size();

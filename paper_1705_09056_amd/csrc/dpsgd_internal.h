@@ -35,6 +35,8 @@ struct dpsgd_ctx {
     float *d_vals = nullptr;
     bool ring_uniform = false;   // Theorem 3's ring with n >= 3: three equal weights per row
     float ring_w = 0.f;
+    bool torus_uniform = false;  // 2-D torus with both dimensions >= 3: five equal weights per row
+    float torus_w = 0.f;
 
     // per-workgroup partial sums of the consensus distance
     double *d_partials = nullptr;
@@ -62,8 +64,8 @@ dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float 
                         bool swapped, float *Vel = nullptr, float mu = 0.f);
 dpsgd_status launch_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
 int64_t mix_partials_needed(const dpsgd_ctx *ctx);
-dpsgd_status launch_mix_ring_range(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, int64_t col0,
-                                   int64_t ncols, bool cons, int64_t *nparts);
+dpsgd_status launch_mix_range(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, int64_t col0,
+                              int64_t ncols, bool cons, int64_t *nparts);
 dpsgd_status launch_consensus_finalize(dpsgd_ctx *ctx, int64_t count, float *consensus);
 
 // ---- grad_*.hip : each returns the workspace it needs and runs on ctx->stream

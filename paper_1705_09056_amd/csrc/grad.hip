@@ -23,7 +23,7 @@ dpsgd_status launch_grad(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float 
 dpsgd_status launch_step(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs, const void *targets,
                          float *G, float *loss, float *consensus)
 {
-    if (is_dense(m) && m.compute_bf16 && ctx->ring_uniform && !ctx->opt_mix_force_csr)
+    if (is_dense(m) && m.compute_bf16 && (ctx->ring_uniform || ctx->torus_uniform) && !ctx->opt_mix_force_csr)
         return launch_step_mlp_bf16(ctx, m, X, inputs, targets, G, loss, consensus);
     // everything else: the two calls of the boundary, back to back, in place
     dpsgd_status st = launch_grad(ctx, m, X, inputs, targets, G, loss);

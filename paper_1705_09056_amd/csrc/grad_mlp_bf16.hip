@@ -704,6 +704,110 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
     }
 }
 
+// ------------------------------------------- the same fusion on a 2-D torus with 8 columns
+// Worker (r, c) = r * 8 + c averages itself, (r +- 1, c) and (r, c +- 1) with weight w (indices modulo the grid).
+// A wave owns a 16 x 16 tile of the weight matrix for ALL workers and walks the grid row by row with the
+// original tiles of grid rows r - 1, r, r + 1 in registers (plus grid row 0, which the last row wraps to, and
+// the row being fetched ahead): 5 x 8 tiles of 4 registers.  The gradient tile of a worker is one
+// v_mfma_f32_16x16x32_bf16 per 32 minibatch rows.  The four waves of a workgroup take adjacent 16-column tiles,
+// so that together they touch 256 consecutive bytes of a row.  grid (K / 64, O / 16), block 256.
+struct FusedTorusArgs {
+    float *X;
+    i64 ld, woff;
+    const bf16_t *dzt;   // T copy of dZ [n][B][O]
+    const bf16_t *at;    // T copy of A  [n][B][K]
+    int R, K, O, Bp;     // R grid rows (n = 8 R)
+    float w, gamma;
+    double *partials;    // one per wave (CONS only)
+};
+
+template <bool CONS>
+__global__ void __launch_bounds__(256) mlp_fused_torus8_kernel(FusedTorusArgs a)
+{
+    constexpr int C = 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n16 = lane & 15, q = lane >> 4;
+    const int k0 = blockIdx.x * 64 + wave * 16, o0 = blockIdx.y * 16;
+    // element i of this lane: row o0 + 4 q + i, column k0 + n16
+    float *xt = a.X + a.woff + (i64)(o0 + 4 * q) * a.K + k0 + n16;
+    auto load_tile = [&](int worker) {
+        const float *p = xt + (i64)worker * a.ld;
+        f32x4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = p[(i64)i * a.K];
+        return v;
+    };
+    // operands in fragment order (tfrag_off): rows in groups of 32, samples in groups of 16 split into halves of 8;
+    // this lane needs row (tile row + n16) and the 8 samples 32 s + 8 q .. + 7
+    const int steps = a.Bp / 32;
+    const i64 op_step = 1024;   // two groups of 16 samples
+    auto op_off = [&](int row) {
+        return ((i64)(row >> 5) * (a.Bp >> 4) + (q >> 1)) * 512 + (q & 1) * 256 + (row & 31) * 8;
+    };
+    const bf16_t *ap = a.dzt + op_off(o0 + n16);
+    const bf16_t *bp = a.at + op_off(k0 + n16);
+    const i64 a_worker = (i64)a.O * a.Bp, b_worker = (i64)a.K * a.Bp;
+
+    f32x4 first[C], prev[C], cur[C], next[C], ahead[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        first[c] = load_tile(c);
+        prev[c] = load_tile((a.R - 1) * C + c);
+        next[c] = load_tile(C + c);
+        cur[c] = first[c];
+    }
+    const f32x4 shift = first[0];
+    f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < a.R; ++r) {
+        if (r + 2 < a.R) {   // all of grid row r + 2 is in flight while row r is worked on
+#pragma unroll
+            for (int c = 0; c < C; ++c) ahead[c] = load_tile((r + 2) * C + c);
+        } else {
+#pragma unroll
+            for (int c = 0; c < C; ++c) ahead[c] = first[c];   // grid row R - 1 wraps to row 0
+        }
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int worker = r * C + c;
+            const bf16_t *ai = ap + worker * a_worker, *bi = bp + worker * b_worker;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int st = 0; st < steps; ++st)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ai + st * op_step), frag(bi + st * op_step), acc, 0, 0, 0);
+            float *dst = xt + (i64)worker * a.ld;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float m = a.w * prev[c][i];
+                m = a.w * cur[(c + C - 1) % C][i] + m;
+                m = a.w * cur[c][i] + m;
+                m = a.w * cur[(c + 1) % C][i] + m;
+                m = a.w * next[c][i] + m;
+                const float o = m - a.gamma * acc[i];
+                dst[(i64)i * a.K] = o;
+                if (CONS) {
+                    const float e = o - shift[i];
+                    s1[i] += e;
+                    s2[i] += e * e;
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            prev[c] = cur[c];
+            cur[c] = next[c];
+            next[c] = ahead[c];
+        }
+    }
+    if (CONS) {
+        const float inv_n = 1.0f / (float)(a.R * C);
+        float m2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m2 += s2[i] - s1[i] * s1[i] * inv_n;
+        double t = (double)m2;
+        for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
+        if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = t;
+    }
+}
+
 }  // namespace
 
 // Workspace layout shared by the size query and the launches.
@@ -748,11 +852,16 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
     return w;
 }
 
-// A layer's weight gradient can be fused into the ring mix when the tiles divide the matrix.
+// A layer's weight gradient can be fused into the mix when a kernel exists for the topology (Theorem 3's ring; a
+// torus with 8 columns) and its tiles divide the matrix.
+bool torus8(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 == 8 && ctx->dim0 >= 3; }
+
 bool layer_fusable(const dpsgd_ctx *ctx, int K, int O, i64 woff)
 {
-    return ctx->ring_uniform && !ctx->opt_mix_force_csr && (K % 128) == 0 && (O % 32) == 0 && (i64)K * O >= (1 << 20) &&
-           woff >= 0;
+    if (ctx->opt_mix_force_csr || woff < 0 || (i64)K * O < (1 << 20)) return false;
+    if (ctx->ring_uniform) return (K % 128) == 0 && (O % 32) == 0;
+    if (torus8(ctx)) return (K % 64) == 0 && (O % 32) == 0;   // 16 x 16 tiles; T copies are padded per 32 rows
+    return false;
 }
 
 dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs, const void *targets,
@@ -861,15 +970,28 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         if (!fused[l]) continue;
         if (timing) ctx->ev_launches += 1;
         const int K = m.widths[l], O = m.widths[l + 1];
-        FusedArgs fa{};
-        fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
-        fa.n = n; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->ring_w; fa.gamma = ctx->gamma;
-        fa.partials = ctx->d_partials + nparts;
-        dim3 grid((unsigned)(K / 128), (unsigned)(O / 32));
-        const i64 np = (i64)grid.x * grid.y * 4;
-        if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
-        if (cons) hipLaunchKernelGGL(mlp_fused_ring_kernel<true>, grid, dim3(256), 0, s, fa);
-        else hipLaunchKernelGGL(mlp_fused_ring_kernel<false>, grid, dim3(256), 0, s, fa);
+        i64 np = 0;
+        if (ctx->ring_uniform) {
+            FusedArgs fa{};
+            fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
+            fa.n = n; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->ring_w; fa.gamma = ctx->gamma;
+            fa.partials = ctx->d_partials + nparts;
+            dim3 grid((unsigned)(K / 128), (unsigned)(O / 32));
+            np = (i64)grid.x * grid.y * 4;
+            if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
+            if (cons) hipLaunchKernelGGL(mlp_fused_ring_kernel<true>, grid, dim3(256), 0, s, fa);
+            else hipLaunchKernelGGL(mlp_fused_ring_kernel<false>, grid, dim3(256), 0, s, fa);
+        } else {
+            FusedTorusArgs fa{};
+            fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
+            fa.R = ctx->dim0; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->torus_w; fa.gamma = ctx->gamma;
+            fa.partials = ctx->d_partials + nparts;
+            dim3 grid((unsigned)(K / 64), (unsigned)(O / 16));
+            np = (i64)grid.x * grid.y * 4;
+            if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
+            if (cons) hipLaunchKernelGGL(mlp_fused_torus8_kernel<true>, grid, dim3(256), 0, s, fa);
+            else hipLaunchKernelGGL(mlp_fused_torus8_kernel<false>, grid, dim3(256), 0, s, fa);
+        }
         if (cons) nparts += np;
         st = hip_status(hipGetLastError());
     }
@@ -883,7 +1005,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         const bool boundary = (l == L) || fused[l];
         if (!boundary) continue;
         const i64 run1 = (l == L) ? ctx->d : woff[l];
-        if (run1 > run0) st = launch_mix_ring_range(ctx, X, G, X, run0, run1 - run0, cons, &nparts);
+        if (run1 > run0) st = launch_mix_range(ctx, X, G, X, run0, run1 - run0, cons, &nparts);
         if (l < L) run0 = boff[l];
     }
     if (st == DPSGD_OK && cons) st = launch_consensus_finalize(ctx, nparts, consensus);

@@ -633,14 +633,20 @@ dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float 
     return cons ? consensus_of(ctx, Xout, consensus) : DPSGD_OK;
 }
 
-// Ring mix + step restricted to the columns [col0, col0 + ncols): used when other kernels own the
-// remaining columns.  Consensus partials are appended at d_partials[*nparts ...] and *nparts advanced.
-dpsgd_status launch_mix_ring_range(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, int64_t col0,
-                                   int64_t ncols, bool cons, int64_t *nparts)
+// Mix + step restricted to the columns [col0, col0 + ncols), in place or out of place: used when other kernels
+// own the remaining columns.  Ring walk for Theorem 3's ring, the LDS-slab kernel for any other W whose n rows
+// fit a slab.  Consensus partials are appended at d_partials[*nparts ...] and *nparts advanced.
+dpsgd_status launch_mix_range(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, int64_t col0,
+                              int64_t ncols, bool cons, int64_t *nparts)
 {
-    if (!ctx->ring_uniform) return DPSGD_EUNSUPPORTED;
     if (ncols <= 0) return DPSGD_OK;
-    int vec = 4;
+    const bool ring = ctx->ring_uniform && !ctx->opt_mix_force_csr;
+    int cap = 4;
+    if (!ring) {
+        while (cap >= 1 && (size_t)ctx->n * 64 * cap * sizeof(float) > kSlabLdsBudget) cap >>= 1;
+        if (cap < 1) return DPSGD_EUNSUPPORTED;
+    }
+    int vec = cap;
     while (vec > 1) {
         const bool ok = (ctx->ld % vec) == 0 && aligned(Xin + col0, 4u * vec) && aligned(G + col0, 4u * vec) &&
                         aligned(Xout + col0, 4u * vec) && ncols >= vec;
@@ -648,16 +654,25 @@ dpsgd_status launch_mix_ring_range(dpsgd_ctx *ctx, const float *Xin, const float
         vec >>= 1;
     }
     const i64 bulk = ncols - ncols % vec, tail = ncols - bulk;
-    if (*nparts + groups_for(bulk, vec) + 2 > ctx->partials_cap - kStage1Blocks) return DPSGD_EINVAL;
+    if (*nparts + groups_for(bulk, vec) + groups_for(tail, 1) + 2 > ctx->partials_cap - kStage1Blocks) return DPSGD_EINVAL;
     i64 n1 = 0, n2 = 0;
     dpsgd_status st = DPSGD_OK;
     double *part = ctx->d_partials + *nparts;
-    if (bulk) {
-        if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
-        else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
-        else st = ring_launch<1>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+    if (ring) {
+        if (bulk) {
+            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+            else st = ring_launch<1>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+        }
+        if (st == DPSGD_OK && tail) st = ring_launch<1>(ctx, Xin, G, Xout, col0 + bulk, tail, cons, part + n1, &n2);
+    } else {
+        if (bulk) {
+            if (vec == 4) st = slab_launch<4, false>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+            else if (vec == 2) st = slab_launch<2, false>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+            else st = slab_launch<1, false>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+        }
+        if (st == DPSGD_OK && tail) st = slab_launch<1, false>(ctx, Xin, G, Xout, col0 + bulk, tail, cons, part + n1, &n2);
     }
-    if (st == DPSGD_OK && tail) st = ring_launch<1>(ctx, Xin, G, Xout, col0 + bulk, tail, cons, part + n1, &n2);
     if (cons) *nparts += n1 + n2;
     return st;
 }

@@ -65,8 +65,19 @@ def test_step_mlp_bf16_ring(widths, batch, n):
     step_case(shrink(CONFIGS[2], widths=widths, batch=batch, n=n))
 
 
+@pytest.mark.parametrize("dims,widths,batch", [
+    ((3, 8), (1024, 1024, 10), 32),          # smallest grid the fused torus kernel takes
+    ((8, 8), (1024, 1024, 1024, 10), 32),    # the benchmark's 8 x 8 grid, two fused layers
+    ((5, 8), (2048, 512, 10), 96),           # odd number of grid rows, three 32-sample steps
+])
+def test_step_mlp_bf16_torus_with_8_columns(dims, widths, batch):
+    """Weight gradient formed inside the torus mix kernel (grid rows walked with three rows of tiles in registers)."""
+    step_case(shrink(CONFIG3_TORUS, widths=widths, batch=batch, n=dims[0] * dims[1], torus_dims=dims))
+
+
 def test_step_falls_back_on_torus_and_fp32():
-    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=12, torus_dims=(3, 4)))
+    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=12, torus_dims=(3, 4)))   # 4 columns: no fused kernel
+    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1000, 10), batch=32, n=24, torus_dims=(3, 8)))   # 1000 outputs: tiles do not divide
     step_case(shrink(CONFIGS[1], widths=(300, 10), batch=16, n=6), bf16=False)
     step_case(shrink(CONFIGS[0], widths=(64,), batch=32, n=8), bf16=False, spread=1.0)
 
