@@ -82,10 +82,13 @@ def test_step_falls_back_on_torus_and_fp32():
     step_case(shrink(CONFIGS[0], widths=(64,), batch=32, n=8), bf16=False, spread=1.0)
 
 
-def test_step_config3_full_size_one_worker():
-    """The launch shape bench.py times.  The oracle forms worker 7's next iterate from its own gradient and the
-    rows of its two ring neighbours; the two-call sequence on the GPU checks every element."""
-    cfg = CONFIGS[3]
+@pytest.mark.parametrize("topology", ["ring", "torus"])
+def test_step_config3_full_size_one_worker(topology):
+    """The launch shape bench.py times.  The oracle forms one worker's next iterate from its own gradient and the
+    rows of its neighbours (ring: worker 7 and workers 6, 8; 8 x 8 torus: worker 27 = (3, 3) and workers 19, 26,
+    28, 35); the two-call sequence on the GPU checks every element."""
+    cfg = CONFIGS[3] if topology == "ring" else CONFIG3_TORUS
+    me, nbrs = (7, (6, 8)) if topology == "ring" else (27, (19, 26, 28, 35))
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = synth.padded_stride(d)
     x0 = synth.make_x0(cfg)
@@ -93,7 +96,7 @@ def test_step_config3_full_size_one_worker():
     Xa = torch.zeros(cfg.n, ld, device="cuda")
     Xa[:, :d] = torch.from_numpy(x0).cuda()
     rows = {}
-    for i in (6, 7, 8):
+    for i in (me,) + nbrs:
         xi = x0 + np.float32(0.3) * np.maximum(np.abs(x0), np.float32(0.02)) * rng.standard_normal(d, dtype=np.float32)
         rows[i] = xi
         Xa[i, :d] = torch.from_numpy(xi).cuda()
@@ -103,7 +106,7 @@ def test_step_config3_full_size_one_worker():
     G = torch.zeros_like(Xa)
     model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
     ca, cb = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
-    with B.Dpsgd(cfg.n, d, B.Topology.ring(), cfg.gamma, ld=ld) as ctx:
+    with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
         ctx.step(model, Xa, inp_d, tgt_d, cfg.batch, G, None, ca, input_is_bf16=True)
         ctx.grad(model, Xb, inp_d, tgt_d, cfg.batch, G, None, input_is_bf16=True)
         ctx.mix_step(Xb, G, Xb, cb)
@@ -113,12 +116,12 @@ def test_step_config3_full_size_one_worker():
           flush=True)
     assert diff < 1e-5
     assert float(ca) == pytest.approx(float(cb), rel=1e-4)
-    _, g7 = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[7], inp[7], tgt[7], bf16_operands=True)
-    w = np.float64(np.float32(1.0 / 3.0))
-    want = w * (rows[6].astype(np.float64) + rows[7] + rows[8]) - np.float64(np.float32(cfg.gamma)) * g7
-    got = Xa[7, :d].cpu().numpy().astype(np.float64)
-    e = rel_err(got - rows[7], want - rows[7])
-    print(f"  worker 7 update vs oracle: {e:.3e}", flush=True)
+    _, gme = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[me], inp[me], tgt[me], bf16_operands=True)
+    w = np.float64(np.float32(1.0 / (1 + len(nbrs))))
+    want = w * sum(rows[i].astype(np.float64) for i in (me,) + nbrs) - np.float64(np.float32(cfg.gamma)) * gme
+    got = Xa[me, :d].cpu().numpy().astype(np.float64)
+    e = rel_err(got - rows[me], want - rows[me])
+    print(f"  worker {me} update vs oracle: {e:.3e}", flush=True)
     assert e < TIGHT
 
 
