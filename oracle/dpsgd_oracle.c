@@ -6,11 +6,14 @@
  * leg may call it.  The product path never does.
  *
  * What is computed (paper passages each function follows):
- *   - weight matrix W of a ring (Theorem 3's matrix), a 2-D torus and the
- *     complete graph; checks of Section 3's requirements (entries in [0,1],
- *     symmetric, rows sum to one);
+ *   - weight matrix W of a ring (Theorem 3's matrix), of the ring with a link to
+ *     the farthest node (supplement, scalability experiment), of a 2-D torus and
+ *     of the complete graph; checks of Section 3's requirements (entries in
+ *     [0,1], symmetric, rows sum to one);
  *   - Algorithm 1 steps 4-5 in the global form of Section 3,
  *       X_{k+1} = W X_k - gamma * dF(X_k; xi_k)       (rows = workers; W = W^T);
+ *     its reordering of footnote [c], and the heavy-ball variant (Section 5.3
+ *     runs with momentum 0.9);
  *   - Algorithm 1 step 7, the node average;
  *   - the consensus distance M_k of the proof of Theorem 1 (eq. 10 and 13),
  *       M = (1/n) sum_i || mean_j x_j - x_i ||^2;
@@ -22,7 +25,8 @@
  * Pins (tests marked "not gpu"): circulant spectra of the ring/torus W, dense
  * W^k powers, the node-average recursion and the unrolled recursion from the
  * proof of Theorem 1, the complete-graph reduction to minibatch SGD, the
- * closed-form affine map on a quadratic objective, central finite differences
+ * closed-form affine map on a quadratic objective, the two-term recurrence and
+ * the 2x2 mode recurrence of the heavy-ball variant, central finite differences
  * and PyTorch-CPU autograd (fp64) on small instances of every model.
  * Values from the paper's experiments: parity unpinned (the paper prints no
  * iterate, loss or gradient of a reproducible instance).
