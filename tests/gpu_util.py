@@ -36,10 +36,17 @@ def topo_for(cfg):
         return B.Topology.ring()
     if cfg.topology == "torus":
         return B.Topology.torus(*cfg.torus_dims)
+    if cfg.topology == "ring_chord":
+        return B.Topology.ring_chord()
     raise ValueError(cfg.topology)
 
 
 def oracle_topo_for(cfg):
     import oracle
-    t = oracle.ring(cfg.n) if cfg.topology == "ring" else oracle.torus(*cfg.torus_dims)
+    if cfg.topology == "ring":
+        t = oracle.ring(cfg.n)
+    elif cfg.topology == "torus":
+        t = oracle.torus(*cfg.torus_dims)
+    else:
+        t = oracle.ring_chord(cfg.n)
     return t.with_fp32_values()

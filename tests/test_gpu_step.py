@@ -75,9 +75,10 @@ def test_step_mlp_bf16_torus_with_8_columns(dims, widths, batch):
     step_case(shrink(CONFIG3_TORUS, widths=widths, batch=batch, n=dims[0] * dims[1], torus_dims=dims))
 
 
-def test_step_falls_back_on_torus_and_fp32():
+def test_step_falls_back_on_other_topologies_and_fp32():
     step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=12, torus_dims=(3, 4)))   # 4 columns: no fused kernel
     step_case(shrink(CONFIG3_TORUS, widths=(1024, 1000, 10), batch=32, n=24, torus_dims=(3, 8)))   # 1000 outputs: tiles do not divide
+    step_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=8, topology="ring_chord"))     # CSR topology
     step_case(shrink(CONFIGS[1], widths=(300, 10), batch=16, n=6), bf16=False)
     step_case(shrink(CONFIGS[0], widths=(64,), batch=32, n=8), bf16=False, spread=1.0)
 
