@@ -134,7 +134,9 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
 /* Launch-shape knobs for measurements; unknown keys give DPSGD_EINVAL.  Defaults are chosen from
  * (n, d).  Keys: "mix_bands" (row bands per workgroup of the ring kernel, 0 = auto),
  * "mix_vec" (floats per lane: 0 = auto, 1, 2 or 4), "mix_force_csr" (1: run the generic CSR
- * kernel even for ring / torus tags), "time_fused" (see dpsgd_read_timing). */
+ * kernel even for ring / torus tags), "torus_window" (1: dpsgd_step on a torus with 8 columns uses the kernel
+ * that keeps three grid rows of tiles in one wave's registers instead of one wave per grid column),
+ * "time_fused" (see dpsgd_read_timing). */
 dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value);
 
 /* CSR of the context's W (host arrays as in dpsgd_topology_build). */

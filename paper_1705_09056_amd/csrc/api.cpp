@@ -306,6 +306,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
         ctx->opt_mix_vec = (int32_t)value;
     } else if (k == "mix_force_csr") {
         ctx->opt_mix_force_csr = value ? 1 : 0;
+    } else if (k == "torus_window") {
+        ctx->opt_torus_window = value ? 1 : 0;
     } else if (k == "time_fused") {
         ctx->opt_time_fused = value ? 1 : 0;
     } else {

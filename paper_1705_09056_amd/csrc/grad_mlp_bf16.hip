@@ -808,6 +808,162 @@ __global__ void __launch_bounds__(256) mlp_fused_torus8_kernel(FusedTorusArgs a)
     }
 }
 
+// ---------------------------------------- torus fusion, one wave per grid column (C <= 8 columns)
+// A workgroup owns one 16 x 32 tile (outputs x inputs) of the weight matrix for ALL workers; wave c takes grid
+// column c and walks down it like the ring kernel walks the ring: the tiles of workers (r-1, c), (r, c),
+// (r+1, c) stay in its registers.  The row neighbours (r, c-1) and (r, c+1) belong to the neighbouring waves: at
+// every grid row each wave publishes its original tile in LDS (two buffers, one workgroup barrier per grid row).
+// The gradient tile is two v_mfma_f32_16x16x32_bf16 per 32 minibatch rows, one for the even and one for the odd
+// input columns, so that a lane owns two adjacent columns of four rows: every access is 8 bytes per lane and 16
+// lanes cover a 128-byte line.  8 registers per tile keep the kernel at 4 waves per SIMD.
+// grid (K / 32, O / 16), block 64 C, dynamic LDS 2 * C * 2 KB.
+struct FusedTorusColArgs {
+    float *X;
+    i64 ld, woff;
+    const bf16_t *dzt;   // T copy of dZ [n][B][O]
+    const bf16_t *at;    // T copy of A  [n][B][K]
+    int R, C, K, O, Bp;  // grid rows and columns (n = R C)
+    float w, gamma;
+    double *partials;    // one per workgroup (CONS only)
+};
+
+template <bool CONS>
+__global__ void __launch_bounds__(512) mlp_fused_torus_cols_kernel(FusedTorusColArgs a)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    f32x4 *tiles = reinterpret_cast<f32x4 *>(smem);   // [2][C][2][64]: a tile as 2 groups of 4 registers
+    const int lane = threadIdx.x & 63, c = threadIdx.x >> 6;
+    const int n16 = lane & 15, q = lane >> 4;
+    const int C = a.C, R = a.R;
+    const int k0 = blockIdx.x * 32, o0 = blockIdx.y * 16;
+    const int steps = a.Bp / 32;
+    // registers 2 i + j of this lane: row o0 + 4 q + i, column k0 + 2 n16 + j
+    float *xt = a.X + a.woff + (i64)(o0 + 4 * q) * a.K + k0 + 2 * n16;
+    // operands in fragment order (tfrag_off): this lane's row and its samples 32 s + 8 q .. + 7
+    auto op_off = [&](int row) {
+        return ((i64)(row >> 5) * (a.Bp >> 4) + (q >> 1)) * 512 + (q & 1) * 256 + (row & 31) * 8;
+    };
+    const bf16_t *ap = a.dzt + op_off(o0 + n16);            // A: 16 outputs
+    const bf16_t *be = a.at + op_off(k0 + 2 * n16);         // B of the even columns
+    const bf16_t *bo = a.at + op_off(k0 + 2 * n16 + 1);     // B of the odd columns
+    const int cl = (c + C - 1) % C, cr = (c + 1) % C;
+
+    float up[8], cur[8], down[8], first[8], ahead[8], shift[8], s1[8], s2[8];
+    auto load_tile = [&](float *dst, int r) {
+        const float *p = xt + (i64)(r * C + c) * a.ld;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x2 v = *reinterpret_cast<const f32x2 *>(p + (i64)i * a.K);
+            dst[2 * i] = v.x;
+            dst[2 * i + 1] = v.y;
+        }
+    };
+    load_tile(up, R - 1);
+    load_tile(cur, 0);
+    load_tile(down, 1);
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        first[v] = cur[v];
+        s1[v] = 0.f;
+        s2[v] = 0.f;
+        shift[v] = 0.f;
+    }
+    // the operands of the first 32 samples of the next worker are fetched one grid row ahead
+    bf16x8 af0 = frag(ap + (i64)c * a.O * a.Bp), be0 = frag(be + (i64)c * a.K * a.Bp), bo0 = frag(bo + (i64)c * a.K * a.Bp);
+    for (int r = 0; r < R; ++r) {
+        f32x4 *mine = tiles + ((r & 1) * C + c) * 128;
+        mine[lane] = (f32x4){cur[0], cur[1], cur[2], cur[3]};
+        mine[64 + lane] = (f32x4){cur[4], cur[5], cur[6], cur[7]};
+        __syncthreads();
+        if (r + 2 < R) load_tile(ahead, r + 2);
+        else {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) ahead[v] = first[v];   // the last grid row wraps to row 0
+        }
+        const int worker = r * C + c;
+        f32x4 acc_e = {0.f, 0.f, 0.f, 0.f}, acc_o = {0.f, 0.f, 0.f, 0.f};
+        const i64 aw = (i64)worker * a.O * a.Bp, bw = (i64)worker * a.K * a.Bp;
+        acc_e = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af0, be0, acc_e, 0, 0, 0);
+        acc_o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af0, bo0, acc_o, 0, 0, 0);
+        if (r + 1 < R) {
+            const i64 an = aw + (i64)C * a.O * a.Bp, bn = bw + (i64)C * a.K * a.Bp;
+            af0 = frag(ap + an);
+            be0 = frag(be + bn);
+            bo0 = frag(bo + bn);
+        }
+        for (int st = 1; st < steps; ++st) {
+            const bf16x8 af = frag(ap + aw + st * 1024);
+            acc_e = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, frag(be + bw + st * 1024), acc_e, 0, 0, 0);
+            acc_o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, frag(bo + bw + st * 1024), acc_o, 0, 0, 0);
+        }
+        const f32x4 *lt = tiles + ((r & 1) * C + cl) * 128, *rt = tiles + ((r & 1) * C + cr) * 128;
+        if (CONS && r == 0) {   // the shift of the consensus sums: worker 0's original tile, the same for every wave
+            const f32x4 z0 = tiles[lane], z1 = tiles[64 + lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                shift[i] = z0[i];
+                shift[4 + i] = z1[i];
+            }
+        }
+        float *dst = xt + (i64)worker * a.ld;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const f32x4 lv = lt[h * 64 + lane], rv = rt[h * 64 + lane];
+            float o4[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int v = 4 * h + e;          // register 2 i + j with i = v / 2, j = v % 2
+                float m = a.w * up[v];
+                m = a.w * lv[e] + m;
+                m = a.w * cur[v] + m;
+                m = a.w * rv[e] + m;
+                m = a.w * down[v] + m;
+                const float g = (v & 1) ? acc_o[v >> 1] : acc_e[v >> 1];
+                const float o = m - a.gamma * g;
+                o4[e] = o;
+                if (CONS) {
+                    const float d = o - shift[v];
+                    s1[v] += d;
+                    s2[v] += d * d;
+                }
+                up[v] = cur[v];
+                cur[v] = down[v];
+                down[v] = ahead[v];
+            }
+            *reinterpret_cast<f32x2 *>(dst + (i64)(2 * h) * a.K) = (f32x2){o4[0], o4[1]};
+            *reinterpret_cast<f32x2 *>(dst + (i64)(2 * h + 1) * a.K) = (f32x2){o4[2], o4[3]};
+        }
+    }
+    if (CONS) {
+        // per element: sums over the C waves first (s1 enters squared), then over the tile
+        __syncthreads();
+        float *red = reinterpret_cast<float *>(smem);   // [C][2][8][64]
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            red[((c * 2 + 0) * 8 + v) * 64 + lane] = s1[v];
+            red[((c * 2 + 1) * 8 + v) * 64 + lane] = s2[v];
+        }
+        __syncthreads();
+        if (c == 0) {
+            const float inv_n = 1.0f / (float)(R * C);
+            float m2 = 0.f;
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                float t1 = 0.f, t2 = 0.f;
+                for (int w2 = 0; w2 < C; ++w2) {
+                    t1 += red[((w2 * 2 + 0) * 8 + v) * 64 + lane];
+                    t2 += red[((w2 * 2 + 1) * 8 + v) * 64 + lane];
+                }
+                m2 += t2 - t1 * t1 * inv_n;
+            }
+            double t = (double)m2;
+            for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
+            if (lane == 0) a.partials[(i64)blockIdx.y * gridDim.x + blockIdx.x] = t;
+        }
+    }
+}
+
 }  // namespace
 
 // Workspace layout shared by the size query and the launches.
@@ -855,12 +1011,14 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
 // A layer's weight gradient can be fused into the mix when a kernel exists for the topology (Theorem 3's ring; a
 // torus with 8 columns) and its tiles divide the matrix.
 bool torus8(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 == 8 && ctx->dim0 >= 3; }
+bool torus_cols(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 >= 3 && ctx->dim1 <= 8 && ctx->dim0 >= 3; }
 
 bool layer_fusable(const dpsgd_ctx *ctx, int K, int O, i64 woff)
 {
     if (ctx->opt_mix_force_csr || woff < 0 || (i64)K * O < (1 << 20)) return false;
     if (ctx->ring_uniform) return (K % 128) == 0 && (O % 32) == 0;
-    if (torus8(ctx)) return (K % 64) == 0 && (O % 32) == 0;   // 16 x 16 tiles; T copies are padded per 32 rows
+    if (ctx->opt_torus_window && torus8(ctx)) return (K % 64) == 0 && (O % 32) == 0;   // 16 x 16 tiles
+    if (torus_cols(ctx)) return (K % 32) == 0 && (O % 32) == 0 && (woff % 2) == 0 && (ctx->ld % 2) == 0;   // 8-byte accesses
     return false;
 }
 
@@ -922,7 +1080,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
     std::vector<char> fused(L, 0);
     for (int l = L - 1; l >= 0 && st == DPSGD_OK; --l) {
         const int K = m.widths[l], O = m.widths[l + 1];
-        fused[l] = fuse && layer_fusable(ctx, K, O, woff[l]);
+        fused[l] = fuse && layer_fusable(ctx, K, O, woff[l]) && (ctx->ring_uniform || (reinterpret_cast<uintptr_t>(X) & 7) == 0);
         if (fused[l]) {   // only the bias gradient goes to G; the weight gradient is formed inside the mix
             hipLaunchKernelGGL(bias_grad_bf16_kernel, dim3((unsigned)((O + 255) / 256), (unsigned)n), dim3(256), 0, s,
                                ws.dzt[l + 1], O, Bp, G, ctx->ld, boff[l]);
@@ -981,6 +1139,17 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
             if (cons) hipLaunchKernelGGL(mlp_fused_ring_kernel<true>, grid, dim3(256), 0, s, fa);
             else hipLaunchKernelGGL(mlp_fused_ring_kernel<false>, grid, dim3(256), 0, s, fa);
+        } else if (!ctx->opt_torus_window || !torus8(ctx)) {
+            FusedTorusColArgs fa{};
+            fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
+            fa.R = ctx->dim0; fa.C = ctx->dim1; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->torus_w; fa.gamma = ctx->gamma;
+            fa.partials = ctx->d_partials + nparts;
+            dim3 grid((unsigned)(K / 32), (unsigned)(O / 16));
+            np = (i64)grid.x * grid.y;
+            if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
+            const size_t shm = (size_t)2 * fa.C * 2048;
+            if (cons) hipLaunchKernelGGL(mlp_fused_torus_cols_kernel<true>, grid, dim3(64u * fa.C), shm, s, fa);
+            else hipLaunchKernelGGL(mlp_fused_torus_cols_kernel<false>, grid, dim3(64u * fa.C), shm, s, fa);
         } else {
             FusedTorusArgs fa{};
             fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
