@@ -218,11 +218,11 @@ def main():
     # layers whose weight gradient dpsgd_step forms inside the mix kernel (same rule as the library)
     fused_weights = 0
     ring_ok = cfg.topology == "ring" and cfg.n >= 3
-    torus_ok = cfg.topology == "torus" and cfg.torus_dims[1] == 8 and cfg.torus_dims[0] >= 3
+    torus_ok = cfg.topology == "torus" and 3 <= cfg.torus_dims[1] <= 8 and cfg.torus_dims[0] >= 3
     if cfg.bf16 and cfg.model_kind in (MODEL_MLP, MODEL_SOFTMAX) and (ring_ok or torus_ok):
         for l in range(len(cfg.widths) - 1):
             w_in, w_out = cfg.widths[l], cfg.widths[l + 1]
-            if w_in % (128 if ring_ok else 64) == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
+            if w_in % (128 if ring_ok else 32) == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
                 fused_weights += w_in * w_out
     fused = fused_weights > 0 and not args.two_call and not args.momentum
     Vel = torch.zeros_like(X) if args.momentum else None
@@ -263,7 +263,7 @@ def main():
     total_ms = t_begin.elapsed_time(t_end)
     if fused:
         fused_ms, launches = ctx.read_timing()
-        kernel_name = ("mlp_fused_ring_kernel" if ring_ok else "mlp_fused_torus8_kernel") + \
+        kernel_name = ("mlp_fused_ring_kernel" if ring_ok else "mlp_fused_torus_cols_kernel") + \
             " (weight gradient + Algorithm 1 steps 4-5, in place)"
         launch_ms = fused_ms / launches
         launch_bytes = 8.0 * cfg.n * fused_weights * K / launches

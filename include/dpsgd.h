@@ -184,7 +184,7 @@ dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const fl
 /* One whole iteration of Algorithm 1 in place: X <- W X - gamma * grad(X), i.e. the result of dpsgd_grad(X -> G)
  * followed by dpsgd_mix_step(X, G -> X), up to the order of floating-point sums.  Footnote [b] observes that steps 3
  * and 4 are independent; here they share one pass over X wherever a kernel exists for it: for bf16 MLPs on the ring
- * (DPSGD_TOPO_RING) and on a torus with 8 columns (DPSGD_TOPO_TORUS2D, dim1 == 8) the weight gradient of every large
+ * (DPSGD_TOPO_RING) and on a torus with 3 to 8 columns (DPSGD_TOPO_TORUS2D, 3 <= dim1 <= 8, dim0 >= 3) the weight gradient of every large
  * layer is formed inside the mix kernel and never written to memory.  All other
  * cases run the two calls back to back.
  *   X          device, n x d (stride ld), overwritten by the next iterate

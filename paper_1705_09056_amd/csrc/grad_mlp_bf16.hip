@@ -1009,7 +1009,7 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
 }
 
 // A layer's weight gradient can be fused into the mix when a kernel exists for the topology (Theorem 3's ring; a
-// torus with 8 columns) and its tiles divide the matrix.
+// torus with 3 to 8 columns and at least 3 grid rows) and its tiles divide the matrix.
 bool torus8(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 == 8 && ctx->dim0 >= 3; }
 bool torus_cols(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 >= 3 && ctx->dim1 <= 8 && ctx->dim0 >= 3; }
 

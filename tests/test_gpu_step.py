@@ -18,7 +18,7 @@ TOL = 2e-2
 TIGHT = 2e-3
 
 
-def step_case(cfg, bf16=True, spread=0.3):
+def step_case(cfg, bf16=True, spread=0.3, options=()):
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = synth.padded_stride(d)
     X = synth.make_replicas(cfg, spread=spread)
@@ -35,6 +35,8 @@ def step_case(cfg, bf16=True, spread=0.3):
     ca, cb = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
     print(f"step {cfg.name} widths={cfg.widths} n={cfg.n} B={cfg.batch} topo={cfg.topology}", flush=True)
     with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+        for key, value in options:
+            ctx.set_option(key, value)
         ctx.step(model, Xa, inp_d, tgt_d, cfg.batch, Ga, la, ca, input_is_bf16=bf16)
         ctx.grad(model, Xb, inp_d, tgt_d, cfg.batch, Gb, lb, input_is_bf16=bf16)
         ctx.mix_step(Xb, Gb, Xb, cb)
@@ -66,17 +68,34 @@ def test_step_mlp_bf16_ring(widths, batch, n):
 
 
 @pytest.mark.parametrize("dims,widths,batch", [
-    ((3, 8), (1024, 1024, 10), 32),          # smallest grid the fused torus kernel takes
+    ((3, 8), (1024, 1024, 10), 32),          # smallest number of grid rows
     ((8, 8), (1024, 1024, 1024, 10), 32),    # the benchmark's 8 x 8 grid, two fused layers
     ((5, 8), (2048, 512, 10), 96),           # odd number of grid rows, three 32-sample steps
+    ((3, 3), (1024, 1024, 10), 32),          # smallest grid: every neighbour is also a wrap-around
+    ((4, 5), (1056, 1024, 10), 40),          # 5 columns; inputs a multiple of 32 but not of 64; ragged minibatch
+    ((6, 4), (1024, 1056, 64, 10), 32),      # 4 columns, 33 output tiles
+    ((3, 7), (2048, 544, 10), 64),           # 7 columns
 ])
-def test_step_mlp_bf16_torus_with_8_columns(dims, widths, batch):
-    """Weight gradient formed inside the torus mix kernel (grid rows walked with three rows of tiles in registers)."""
+def test_step_mlp_bf16_torus(dims, widths, batch):
+    """Weight gradient formed inside the torus mix kernel: one wave per grid column, grid rows walked with three
+    rows of tiles in registers, row neighbours exchanged through LDS."""
     step_case(shrink(CONFIG3_TORUS, widths=widths, batch=batch, n=dims[0] * dims[1], torus_dims=dims))
 
 
+@pytest.mark.parametrize("dims,widths,batch", [
+    ((3, 8), (1024, 1024, 10), 32),
+    ((8, 8), (1024, 1024, 1024, 10), 32),
+    ((5, 8), (2048, 512, 10), 96),
+])
+def test_step_mlp_bf16_torus_register_window_option(dims, widths, batch):
+    """The alternative kernel for 8 columns (one wave holds all eight columns' tiles of three grid rows)."""
+    step_case(shrink(CONFIG3_TORUS, widths=widths, batch=batch, n=dims[0] * dims[1], torus_dims=dims),
+              options=(("torus_window", 1),))
+
+
 def test_step_falls_back_on_other_topologies_and_fp32():
-    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=12, torus_dims=(3, 4)))   # 4 columns: no fused kernel
+    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=27, torus_dims=(3, 9)))   # 9 columns: no fused kernel
+    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=16, torus_dims=(2, 8)))   # 2 grid rows: neighbours coincide
     step_case(shrink(CONFIG3_TORUS, widths=(1024, 1000, 10), batch=32, n=24, torus_dims=(3, 8)))   # 1000 outputs: tiles do not divide
     step_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=8, topology="ring_chord"))     # CSR topology
     step_case(shrink(CONFIGS[1], widths=(300, 10), batch=16, n=6), bf16=False)
