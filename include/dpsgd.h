@@ -22,6 +22,10 @@
  *     dpsgd_read_timing, and a dpsgd_grad / dpsgd_step call that has to allocate or grow the
  *     gradient workspace (the first call for a model, or one with a larger minibatch).
  *     Device outputs (G, X_out, loss, consensus, xbar) are valid in stream order.
+ *   - HIP graphs: once a dpsgd_grad / dpsgd_step call for a model and minibatch size has run, later calls for it
+ *     (and every mix, mean and consensus call) only enqueue kernels: no allocation, no memset, no host wait.  A caller
+ *     may record them into a HIP graph on the context's stream.  Scalars are kernel arguments: a recorded call keeps the
+ *     gamma, mu and pointers it was recorded with.  The "time_fused" option records events and must be off.
  *   - Every call returns a dpsgd_status.  Arguments and the topology are validated on the
  *     host before anything touches the device.
  *   - One context must not be used from two threads at once; calls that share a context and a
