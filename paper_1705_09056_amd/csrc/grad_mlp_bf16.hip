@@ -650,7 +650,7 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
 
     // xh: worker 0's original tile (the ring's wrap-around, and the shift of the consensus sums);
     // xn / xf: the tiles of workers i+1 and i+2, fetched one and two steps ahead
-    float xm[16], xc[16], xh[16], xn[16], xf[16], s1[16], s2[16];
+    float xm[16], xc[16], xh[16], xn[16], xf[16], s1[16], s2[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         xm[v] = xt[(i64)(a.n - 1) * a.ld + row_off(v)];
@@ -658,46 +658,65 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
         xh[v] = xc[v];
         xn[v] = xt[(i64)(1 % a.n) * a.ld + row_off(v)];
         s1[v] = 0.f;
-        s2[v] = 0.f;
     }
+    // The operands of a worker's first 32 minibatch rows (the minibatch is padded to a multiple of 32, so there
+    // are always two steps) are fetched while the previous worker is computed; issued before the tile of worker
+    // i + 2, they can be waited for without waiting for that tile.  Both fetches are unconditional (clamped
+    // to the last worker, whose values are then not used) so that the wait counts stay exact.
+    bf16x8 pa0 = frag(ap), pb0 = frag(bp), pa1 = frag(ap + 512), pb1 = frag(bp + 512);
     for (int i = 0; i < a.n; ++i) {
-        if (i + 2 < a.n) {
+        {
+            const float *src = xt + (i64)(i + 2 < a.n ? i + 2 : a.n - 1) * a.ld;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) xf[v] = xt[(i64)(i + 2) * a.ld + row_off(v)];
-        } else {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) xf[v] = xh[v];   // only its use as worker n-1's successor matters
+            for (int v = 0; v < 16; ++v) xf[v] = src[row_off(v)];
         }
         f32x16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.f;
         const bf16_t *ai = ap + (i64)i * a.O * a.Bp, *bi = bp + (i64)i * a.K * a.Bp;
-        for (int st = 0; st < steps; ++st)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(ai + st * 512), frag(bi + st * 512), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa0, pb0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa1, pb1, acc, 0, 0, 0);
+        for (int st = 2; st < steps; st += 2) {
+            pa0 = frag(ai + st * 512);
+            pb0 = frag(bi + st * 512);
+            pa1 = frag(ai + st * 512 + 512);
+            pb1 = frag(bi + st * 512 + 512);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa0, pb0, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa1, pb1, acc, 0, 0, 0);
+        }
+        {
+            const int nw = i + 1 < a.n ? i + 1 : i;
+            const bf16_t *an = ap + (i64)nw * a.O * a.Bp, *bn = bp + (i64)nw * a.K * a.Bp;
+            pa0 = frag(an);
+            pb0 = frag(bn);
+            pa1 = frag(an + 512);
+            pb1 = frag(bn + 512);
+        }
+        const bool last = i + 1 == a.n;
         float *dst = xt + (i64)i * a.ld;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const float nxt = (i + 1 < a.n) ? xn[v] : xh[v];
+            const float nxt = last ? xh[v] : xn[v];   // the ring closes on worker 0's original tile
             float mix = a.w * xm[v];
             mix = a.w * xc[v] + mix;
             mix = a.w * nxt + mix;
             const float o = mix - a.gamma * acc[v];
             dst[row_off(v)] = o;
-            if (CONS) {
+            if (CONS) {   // per element the sum of (x - shift); the squares need no per-element sum
                 const float e = o - xh[v];
                 s1[v] += e;
-                s2[v] += e * e;
+                s2[v & 3] += e * e;
             }
             xm[v] = xc[v];
             xc[v] = nxt;
-            xn[v] = xf[v];
+            xn[v] = xf[v];   // (a clamped fetch is never used: worker n-1's successor is taken from xh)
         }
     }
     if (CONS) {
-        float m2 = 0.f;
+        float m2 = (s2[0] + s2[1]) + (s2[2] + s2[3]);
         const float inv_n = 1.0f / (float)a.n;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) m2 += s2[v] - s1[v] * s1[v] * inv_n;
+        for (int v = 0; v < 16; ++v) m2 -= s1[v] * s1[v] * inv_n;
         double t = (double)m2;
         for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
         if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = t;
