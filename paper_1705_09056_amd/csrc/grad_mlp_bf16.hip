@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
             if (o < g.O) {
                 const float *p = Wg + (i64)o * g.K + k;
                 if (VEC) {
-                    if (k < g.K) v = *reinterpret_cast<const f32x4 *>(p);
+                    if (k < g.K) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
                 } else {
                     if (k < g.K) v.x = p[0];
                     if (k + 1 < g.K) v.y = p[1];
@@ -459,7 +459,7 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
             if (o < g.O) {
                 const float *p = Wg + (i64)o * g.K + k;
                 if (VEC) {
-                    if (k < g.K) v = *reinterpret_cast<const f32x4 *>(p);
+                    if (k < g.K) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
                 } else {
                     if (k < g.K) v.x = p[0];
                     if (k + 1 < g.K) v.y = p[1];
@@ -661,14 +661,17 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
     }
     // The operands of a worker's first 32 minibatch rows (the minibatch is padded to a multiple of 32, so there
     // are always two steps) are fetched while the previous worker is computed; issued before the tile of worker
-    // i + 2, they can be waited for without waiting for that tile.  Both fetches are unconditional (clamped
-    // to the last worker, whose values are then not used) so that the wait counts stay exact.
+    // i + 2, they can be waited for without waiting for that tile.  Both fetches are unconditional so that the
+    // wait counts stay exact: past the last worker the tile fetch reads one cached line of the operand array
+    // instead (values never used), the operand fetch repeats the last worker's.
     bf16x8 pa0 = frag(ap), pb0 = frag(bp), pa1 = frag(ap + 512), pb1 = frag(bp + 512);
     for (int i = 0; i < a.n; ++i) {
         {
-            const float *src = xt + (i64)(i + 2 < a.n ? i + 2 : a.n - 1) * a.ld;
+            const bool far = i + 2 < a.n;
+            const float *src = far ? xt + (i64)(i + 2) * a.ld : reinterpret_cast<const float *>(a.dzt) + lane;
+            const i64 rs = far ? (i64)a.K : 0;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) xf[v] = src[row_off(v)];
+            for (int v = 0; v < 16; ++v) xf[v] = __builtin_nontemporal_load(src + ((v >> 2) * 8 + (v & 3)) * rs);
         }
         f32x16 acc;
 #pragma unroll
@@ -701,7 +704,7 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
             mix = a.w * xc[v] + mix;
             mix = a.w * nxt + mix;
             const float o = mix - a.gamma * acc[v];
-            dst[row_off(v)] = o;
+            __builtin_nontemporal_store(o, dst + row_off(v));
             if (CONS) {   // per element the sum of (x - shift); the squares need no per-element sum
                 const float e = o - xh[v];
                 s1[v] += e;
@@ -873,7 +876,7 @@ __global__ void __launch_bounds__(512) mlp_fused_torus_cols_kernel(FusedTorusCol
         const float *p = xt + (i64)(r * C + c) * a.ld;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const f32x2 v = *reinterpret_cast<const f32x2 *>(p + (i64)i * a.K);
+            const f32x2 v = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p + (i64)i * a.K));
             dst[2 * i] = v.x;
             dst[2 * i + 1] = v.y;
         }
@@ -950,8 +953,8 @@ __global__ void __launch_bounds__(512) mlp_fused_torus_cols_kernel(FusedTorusCol
                 cur[v] = down[v];
                 down[v] = ahead[v];
             }
-            *reinterpret_cast<f32x2 *>(dst + (i64)(2 * h) * a.K) = (f32x2){o4[0], o4[1]};
-            *reinterpret_cast<f32x2 *>(dst + (i64)(2 * h + 1) * a.K) = (f32x2){o4[2], o4[3]};
+            __builtin_nontemporal_store((f32x2){o4[0], o4[1]}, reinterpret_cast<f32x2 *>(dst + (i64)(2 * h) * a.K));
+            __builtin_nontemporal_store((f32x2){o4[2], o4[3]}, reinterpret_cast<f32x2 *>(dst + (i64)(2 * h + 1) * a.K));
         }
     }
     if (CONS) {
