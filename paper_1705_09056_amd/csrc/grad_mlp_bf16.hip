@@ -62,6 +62,21 @@ __device__ __forceinline__ i64 tfrag_off(int r, int b, int Bp)
 }
 __device__ __forceinline__ i64 tfrag_worker(int w, int rows, int Bp) { return (i64)w * ((rows + 31) / 32 * 32) * Bp; }
 
+// Workgroups are dealt to the 8 XCDs round-robin by linear id and every XCD has its own L2.  For a grid
+// (tiles, 1, n) with n a multiple of 8 the ids are renumbered so that all tiles of a worker run on one XCD and
+// the worker's activation (or delta) matrix is fetched into one L2 instead of eight.
+__device__ __forceinline__ void worker_tile_on_one_xcd(int &tile, int &w)
+{
+    tile = blockIdx.x;
+    w = blockIdx.z;
+    if (gridDim.y == 1 && (gridDim.z & 7) == 0) {
+        const unsigned id = blockIdx.x + gridDim.x * blockIdx.z;
+        const unsigned xcd = id & 7, slot = id >> 3;
+        w = (int)((slot / gridDim.x) * 8 + xcd);
+        tile = (int)(slot % gridDim.x);
+    }
+}
+
 // ------------------------------------------------------------------ input preparation
 // in: [n*B][F] fp32 or bf16 -> a [n][B][F] bf16 (only when the input is fp32) and
 // at = its T copy (zero padded samples).  32x32 tiles through LDS.
@@ -147,7 +162,9 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *Wt = reinterpret_cast<bf16_t *>(smem);          // [2][TO][PITCH]
     bf16_t *At = Wt + 2 * TO * PITCH;                        // [2][MBLK][PITCH]
-    const int w = blockIdx.z, o0 = blockIdx.x * TO, b0 = blockIdx.y * MBLK;
+    int w, tile;
+    worker_tile_on_one_xcd(tile, w);
+    const int o0 = tile * TO, b0 = blockIdx.y * MBLK;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, half = lane >> 5;
@@ -216,13 +233,17 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
 
+    // Workgroups start their walk over the contraction at different chunks: started together at chunk 0 they
+    // would all read the same column range of W at the same time, rows a multiple of 4 KB apart.
     const int nchunks = (g.K + KC - 1) / KC;
-    fetch(0);
+    const int start = (int)((unsigned)(tile * 5 + w * 3) % (unsigned)nchunks);
+    auto chunk_k = [&](int c) { const int cc = c + start; return (cc >= nchunks ? cc - nchunks : cc) * KC; };
+    fetch(chunk_k(0));
     stage(0);
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
-        if (c + 1 < nchunks) fetch((c + 1) * KC);
+        if (c + 1 < nchunks) fetch(chunk_k(c + 1));
         const bf16_t *Wb = Wt + buf * TO * PITCH + (wn * 32 + l32) * PITCH + 8 * half;
         const bf16_t *Ab = At + buf * MBLK * PITCH + (wm * MT * 32 + l32) * PITCH + 8 * half;
 #pragma unroll
@@ -441,7 +462,9 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
     constexpr int WP = TK + 8;                               // pitch of the W tile (bf16 elements)
     bf16_t *Wt = reinterpret_cast<bf16_t *>(smem);          // [2][KC o][WP]    as in memory: rows o, k contiguous
     bf16_t *Dt = Wt + 2 * KC * WP;                           // [2][MBLK][PITCH] rows b, o contiguous
-    const int w = blockIdx.z, kt0 = blockIdx.x * TK, b0 = blockIdx.y * MBLK;
+    int w, tile;
+    worker_tile_on_one_xcd(tile, w);
+    const int kt0 = tile * TK, b0 = blockIdx.y * MBLK;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, half = lane >> 5;
