@@ -140,7 +140,18 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
     constexpr int TH = 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *patch = reinterpret_cast<bf16_t *>(smem);
-    const int band = blockIdx.x, b = blockIdx.y, w = blockIdx.z;
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id and every XCD has its own L2: with n a multiple
+    // of 8 the ids are renumbered so that all workgroups of a worker run on one XCD and its packed weights are
+    // fetched into one L2 instead of eight.
+    int band = blockIdx.x, b = blockIdx.y, w = blockIdx.z;
+    if ((gridDim.z & 7) == 0) {
+        const unsigned per = gridDim.x * gridDim.y;
+        const unsigned id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+        const unsigned xcd = id & 7, slot = id >> 3, within = slot % per;
+        w = (int)((slot / per) * 8 + xcd);
+        band = (int)(within % gridDim.x);
+        b = (int)(within / gridDim.x);
+    }
     const i64 img = (i64)w * a.B + b;
     const int y0 = band * TH;
     const int Wd = a.Wd, lw = a.lw;
