@@ -294,6 +294,152 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
     }
 }
 
+// Minibatches of at most 32 rows: the same product with a [64 outputs][128 k] weight tile, so that a row of the
+// tile is 512 consecutive bytes of W (256-byte pieces of rows 12-16 KB apart stream ~10 % slower from HBM).  The
+// four waves are 2 output tiles x 2 halves of each 128-wide chunk of the contraction; the two halves meet in LDS
+// at the end.  grid (ceil(O / 64), ceil(B / 32), n), block 256.
+constexpr int KC2 = 128;
+constexpr int PITCH2 = KC2 + 8;
+
+template <bool VEC, bool LAST>
+__global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
+{
+    constexpr int TO = 64, MBLK = 32;
+    constexpr int WQ = TO * KC2 / 4 / 256;    // float4 units of the W tile per thread (8)
+    constexpr int AQ = MBLK * KC2 / 8 / 256;  // 16-byte units of the A tile per thread (2)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *Wt = reinterpret_cast<bf16_t *>(smem);          // [2][TO][PITCH2]
+    bf16_t *At = Wt + 2 * TO * PITCH2;                       // [2][MBLK][PITCH2]
+    int w, tile;
+    worker_tile_on_one_xcd(tile, w);
+    const int o0 = tile * TO, b0 = blockIdx.y * MBLK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave & 1, wk = wave >> 1;
+    const int l32 = lane & 31, half = lane >> 5;
+    const float *Wg = g.X + (i64)w * g.ld + g.woff;
+    const bf16_t *Ag = g.act + (i64)w * g.B * g.K;
+
+    f32x4 wreg[WQ];
+    u32x4 areg[AQ];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
+            const int o = o0 + row, k = k0 + kq;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (o < g.O) {
+                const float *p = Wg + (i64)o * g.K + k;
+                if (VEC) {
+                    if (k < g.K) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+                } else {
+                    if (k < g.K) v.x = p[0];
+                    if (k + 1 < g.K) v.y = p[1];
+                    if (k + 2 < g.K) v.z = p[2];
+                    if (k + 3 < g.K) v.w = p[3];
+                }
+            }
+            wreg[q] = v;
+        }
+#pragma unroll
+        for (int q = 0; q < AQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 8;
+            const int b = b0 + row, k = k0 + kq;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (b < g.B) {
+                const bf16_t *p = Ag + (i64)b * g.K + k;
+                if (VEC) {
+                    if (k < g.K) v = *reinterpret_cast<const u32x4 *>(p);
+                } else {
+                    unsigned short e[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) e[i] = (k + i < g.K) ? p[i] : (unsigned short)0;
+                    v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
+                    v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
+                }
+            }
+            areg[q] = v;
+        }
+    };
+    auto stage = [&](int buf) {
+        bf16_t *Wb = Wt + buf * TO * PITCH2, *Ab = At + buf * MBLK * PITCH2;
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
+            u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
+            *reinterpret_cast<u32x2 *>(Wb + row * PITCH2 + kq) = p;
+        }
+#pragma unroll
+        for (int q = 0; q < AQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 8;
+            *reinterpret_cast<u32x4 *>(Ab + row * PITCH2 + kq) = areg[q];
+        }
+    };
+
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+
+    // staggered start, as in mlp_fwd_kernel
+    const int nchunks = (g.K + KC2 - 1) / KC2;
+    const int start = (int)((unsigned)(tile * 5 + w * 3) % (unsigned)nchunks);
+    auto chunk_k = [&](int c) { const int cc = c + start; return (cc >= nchunks ? cc - nchunks : cc) * KC2; };
+    fetch(chunk_k(0));
+    stage(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) fetch(chunk_k(c + 1));
+        const bf16_t *Wb = Wt + buf * TO * PITCH2 + (wn * 32 + l32) * PITCH2 + wk * (KC2 / 2) + 8 * half;
+        const bf16_t *Ab = At + buf * MBLK * PITCH2 + l32 * PITCH2 + wk * (KC2 / 2) + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < KC2 / 32; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Ab + ks * 16), frag(Wb + ks * 16), acc, 0, 0, 0);
+        if (c + 1 < nchunks) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // the upper halves hand their sums to the lower ones (the staging buffers are free after the last barrier)
+    float *red = reinterpret_cast<float *>(smem);   // [2 output tiles][16][64]
+    if (wk == 1) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[(wn * 16 + v) * 64 + lane] = acc[v];
+    }
+    __syncthreads();
+    if (wk == 1) return;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] += red[(wn * 16 + v) * 64 + lane];
+
+    // epilogue: lane owns output column o, 16 rows
+    const int o = o0 + wn * 32 + l32;
+    if (o >= g.O) return;
+    const float bias = g.X[(i64)w * g.ld + g.boff + o];
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) {
+        const int bb = b0 + grp * 8 + half * 4;   // 4 consecutive rows bb..bb+3
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[i] = acc[grp * 4 + i] + bias;
+            if (!LAST) v[i] = v[i] > 0.f ? v[i] : 0.f;
+        }
+        if (LAST) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (bb + i < g.B) g.z[((i64)w * g.B + bb + i) * g.O + o] = v[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (bb + i < g.B) g.h[((i64)w * g.B + bb + i) * g.O + o] = f2bf(v[i]);
+                else v[i] = 0.f;
+            }
+            if (bb < g.Bp) {
+                u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
+                *reinterpret_cast<u32x2 *>(g.ht + tfrag_worker(w, g.O, g.Bp) + tfrag_off(o, bb, g.Bp)) = p;
+            }
+        }
+    }
+}
+
 // Class layer (at most 32 outputs): the tile above would be 3/4 padding and one workgroup per worker
 // would walk the whole contraction alone.  Here a workgroup owns 32 samples of one worker and its 8
 // waves split K; operands come straight from global memory (activations bf16, weights fp32 rounded
@@ -610,6 +756,17 @@ dpsgd_status fwd_launch(hipStream_t s, int n, const FwdArgs &a, bool vec, bool l
     else if (vec) hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, true, false>), grid, dim3(256), shm, s, a);
     else if (last) hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, false, true>), grid, dim3(256), shm, s, a);
     else hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, false, false>), grid, dim3(256), shm, s, a);
+    return hip_status(hipGetLastError());
+}
+
+dpsgd_status fwd_ksplit_launch(hipStream_t s, int n, const FwdArgs &a, bool vec, bool last)
+{
+    dim3 grid((unsigned)((a.O + 63) / 64), (unsigned)((a.B + 31) / 32), (unsigned)n);
+    const size_t shm = (size_t)2 * (64 + 32) * PITCH2 * sizeof(bf16_t);
+    if (vec && last) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<true, true>), grid, dim3(256), shm, s, a);
+    else if (vec) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<true, false>), grid, dim3(256), shm, s, a);
+    else if (last) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<false, true>), grid, dim3(256), shm, s, a);
+    else hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<false, false>), grid, dim3(256), shm, s, a);
     return hip_status(hipGetLastError());
 }
 
@@ -1113,7 +1270,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         if (last && vec && a.O <= 32 && (a.K % 16) == 0 && a.K >= 256) {
             hipLaunchKernelGGL(mlp_fwd_last_kernel, dim3((unsigned)((B + 31) / 32), (unsigned)n), dim3(512), 0, s, a);
             st = hip_status(hipGetLastError());
-        } else if (t.mt == 1) st = fwd_launch<1, 4, 1>(s, n, a, vec, last);
+        } else if (t.mt == 1) st = fwd_ksplit_launch(s, n, a, vec, last);
         else if (t.wm == 1) st = fwd_launch<1, 4, 2>(s, n, a, vec, last);
         else st = fwd_launch<2, 2, 2>(s, n, a, vec, last);
     }
