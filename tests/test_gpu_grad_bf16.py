@@ -68,7 +68,9 @@ def test_mlp_bf16_aligned(widths, batch, n):
 
 
 @pytest.mark.parametrize("widths,batch,n", [((100, 70, 33, 5), 37, 4), ((96, 50, 10), 24, 3), ((33, 7, 3), 1, 2),
-                                             ((130, 260, 9), 70, 2)])
+                                             ((130, 260, 9), 70, 2),
+                                             ((200, 150, 70, 10), 20, 8),    # 8 workers: tiles renumbered per XCD
+                                             ((136, 72, 10), 64, 16)])
 def test_mlp_bf16_ragged(widths, batch, n):
     cfg = shrink(CONFIGS[2], widths=widths, batch=batch, n=n)
     d = synth.model_dim(MODEL_MLP, widths)
