@@ -343,7 +343,7 @@ column_stats_kernel(const float *__restrict__ X, int n, i64 ncols, i64 ld, int b
         const float *x = X + c0;
 #pragma unroll 4
         for (int row = r0; row < r1; ++row) {
-            vec v = vload<V>(x + (i64)row * ld);
+            vec v = __builtin_nontemporal_load(reinterpret_cast<const vec *>(x + (i64)row * ld));
             if (MEAN) sum += v;
             if (CONS) st.add(v);
         }
