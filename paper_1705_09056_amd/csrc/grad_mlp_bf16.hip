@@ -1029,16 +1029,18 @@ struct FusedTorusColArgs {
     double *partials;    // one per workgroup (CONS only)
 };
 
-template <bool CONS>
-__global__ void __launch_bounds__(512) mlp_fused_torus_cols_kernel(FusedTorusColArgs a)
+template <bool CONS, int KT>
+__global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTorusColArgs a)
 {
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    f32x4 *tiles = reinterpret_cast<f32x4 *>(smem);   // [2][C][2][64]: a tile as 2 groups of 4 registers
-    const int lane = threadIdx.x & 63, c = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n16 = lane & 15, q = lane >> 4;
     const int C = a.C, R = a.R;
-    const int k0 = blockIdx.x * 32, o0 = blockIdx.y * 16;
+    // KT groups of C waves sit side by side along the inputs: per worker the workgroup touches 16 rows x KT x 128 B
+    const int c = wave % C, kt = wave / C;
+    f32x4 *tiles = reinterpret_cast<f32x4 *>(smem) + kt * (2 * C * 128);   // per group [2][C][2][64]: a tile as 2 groups of 4 registers
+    const int k0 = (blockIdx.x * KT + kt) * 32, o0 = blockIdx.y * 16;
     const int steps = a.Bp / 32;
     // registers 2 i + j of this lane: row o0 + 4 q + i, column k0 + 2 n16 + j
     float *xt = a.X + a.woff + (i64)(o0 + 4 * q) * a.K + k0 + 2 * n16;
@@ -1138,9 +1140,9 @@ __global__ void __launch_bounds__(512) mlp_fused_torus_cols_kernel(FusedTorusCol
         }
     }
     if (CONS) {
-        // per element: sums over the C waves first (s1 enters squared), then over the tile
+        // per element: sums over the C waves of a group first (s1 enters squared), then over the tile
         __syncthreads();
-        float *red = reinterpret_cast<float *>(smem);   // [C][2][8][64]
+        float *red = reinterpret_cast<float *>(smem) + kt * (C * 1024);   // per group [C][2][8][64]
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
             red[((c * 2 + 0) * 8 + v) * 64 + lane] = s1[v];
@@ -1161,7 +1163,7 @@ __global__ void __launch_bounds__(512) mlp_fused_torus_cols_kernel(FusedTorusCol
             }
             double t = (double)m2;
             for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
-            if (lane == 0) a.partials[(i64)blockIdx.y * gridDim.x + blockIdx.x] = t;
+            if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * KT + kt] = t;
         }
     }
 }
@@ -1346,12 +1348,19 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
             fa.R = ctx->dim0; fa.C = ctx->dim1; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->torus_w; fa.gamma = ctx->gamma;
             fa.partials = ctx->d_partials + nparts;
-            dim3 grid((unsigned)(K / 32), (unsigned)(O / 16));
-            np = (i64)grid.x * grid.y;
+            // two groups of waves side by side (256-byte row segments) when the inputs divide
+            const int kt = (K % 64) == 0 ? 2 : 1;
+            dim3 grid((unsigned)(K / (32 * kt)), (unsigned)(O / 16));
+            np = (i64)grid.x * grid.y * kt;
             if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
-            const size_t shm = (size_t)2 * fa.C * 2048;
-            if (cons) hipLaunchKernelGGL(mlp_fused_torus_cols_kernel<true>, grid, dim3(64u * fa.C), shm, s, fa);
-            else hipLaunchKernelGGL(mlp_fused_torus_cols_kernel<false>, grid, dim3(64u * fa.C), shm, s, fa);
+            const size_t shm = (size_t)2 * fa.C * 2048 * kt;
+            if (kt == 2) {
+                if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 2>), grid, dim3(128u * fa.C), shm, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 2>), grid, dim3(128u * fa.C), shm, s, fa);
+            } else {
+                if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 1>), grid, dim3(64u * fa.C), shm, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 1>), grid, dim3(64u * fa.C), shm, s, fa);
+            }
         } else {
             FusedTorusArgs fa{};
             fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
