@@ -1018,7 +1018,8 @@ __global__ void __launch_bounds__(256) mlp_fused_torus8_kernel(FusedTorusArgs a)
 // The gradient tile is two v_mfma_f32_16x16x32_bf16 per 32 minibatch rows, one for the even and one for the odd
 // input columns, so that a lane owns two adjacent columns of four rows: every access is 8 bytes per lane and 16
 // lanes cover a 128-byte line.  8 registers per tile keep the kernel at 4 waves per SIMD.
-// grid (K / 32, O / 16), block 64 C, dynamic LDS 2 * C * 2 KB.
+// KT such groups of C waves sit side by side along the inputs (KT x 128-byte row segments per workgroup).
+// grid (K / (32 KT), O / 16), block 64 C KT, dynamic LDS KT * 2 * C * 2 KB.
 struct FusedTorusColArgs {
     float *X;
     i64 ld, woff;
