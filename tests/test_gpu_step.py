@@ -183,3 +183,40 @@ def test_step_short_trajectory_with_gamma_schedule():
             drift = np.abs(after.mean(0) - before.mean(0)).max()
             assert drift < 50 * gamma
             Xo = Xn
+
+
+def test_two_contexts_on_two_streams_do_not_share_state():
+    """Two contexts (different topologies, own workspaces) enqueue interleaved on two streams; each result equals
+    the one the same context gives alone."""
+    cfg_a = shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=6)
+    cfg_b = shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=64, n=12, torus_dims=(3, 4))
+    results = {}
+    for interleaved in (False, True):
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        state = []
+        for cfg, st in zip((cfg_a, cfg_b), streams):
+            d = synth.model_dim(cfg.model_kind, cfg.widths)
+            ld = synth.padded_stride(d)
+            inp, tgt = synth.make_batch(cfg, 0)
+            with torch.cuda.stream(st):
+                X = to_dev(synth.make_replicas(cfg), ld)
+                G = torch.zeros_like(X)
+                cons = torch.zeros(1, device="cuda")
+                inp_d, tgt_d = bf16_dev(inp), torch.from_numpy(tgt).cuda()
+                ctx = B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld, stream=st)
+            state.append((cfg, st, X, G, cons, inp_d, tgt_d, ctx, d))
+        torch.cuda.synchronize()
+        model = B.Model(cfg_a.model_kind, cfg_a.widths, compute_bf16=True)
+        order = [0, 1, 0, 1, 0, 1] if interleaved else [0, 0, 0, 1, 1, 1]
+        for which in order:
+            cfg, st, X, G, cons, inp_d, tgt_d, ctx, d = state[which]
+            ctx.step(model, X, inp_d, tgt_d, cfg.batch, G, None, cons, input_is_bf16=True)
+            if not interleaved:
+                st.synchronize()
+        torch.cuda.synchronize()
+        results[interleaved] = [(from_dev(s[2], s[8]), float(s[4])) for s in state]
+        for s in state:
+            s[7].close()
+    for (xa, ca), (xb, cb) in zip(results[False], results[True]):
+        assert np.array_equal(xa, xb)
+        assert ca == cb
