@@ -18,9 +18,9 @@ TOL = 2e-2
 TIGHT = 2e-3
 
 
-def step_case(cfg, bf16=True, spread=0.3, options=()):
+def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0):
     d = synth.model_dim(cfg.model_kind, cfg.widths)
-    ld = synth.padded_stride(d)
+    ld = ld or synth.padded_stride(d)
     X = synth.make_replicas(cfg, spread=spread)
     inp, tgt = synth.make_batch(cfg, 0)
     topo_o = oracle_topo_for(cfg)
@@ -100,6 +100,14 @@ def test_step_falls_back_on_other_topologies_and_fp32():
     step_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=8, topology="ring_chord"))     # CSR topology
     step_case(shrink(CONFIGS[1], widths=(300, 10), batch=16, n=6), bf16=False)
     step_case(shrink(CONFIGS[0], widths=(64,), batch=32, n=8), bf16=False, spread=1.0)
+
+
+def test_step_with_odd_row_stride():
+    """Row stride d + 1: rows are only 4-byte aligned.  The ring kernel still fuses (4-byte accesses); the torus
+    kernel needs 8-byte aligned rows and hands over to the two calls."""
+    for cfg in (shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=5),
+                shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=12, torus_dims=(3, 4))):
+        step_case(cfg, ld=synth.model_dim(cfg.model_kind, cfg.widths) + 1)
 
 
 @pytest.mark.parametrize("topology", ["ring", "torus"])
