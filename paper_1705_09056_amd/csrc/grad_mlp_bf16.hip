@@ -152,6 +152,39 @@ struct FwdArgs {
     float *z;              // [n][B][O]   (last layer, fp32 logits)
 };
 
+// Epilogue of one 32 x 32 accumulator tile of the forward product: lane owns output column o and the 16 rows
+// bt + (v/4)*8 + half*4 + v%4.  Adds the bias; hidden layers: ReLU, bf16 activation in [b][o] order and in the
+// T copy (zero padded samples); last layer: fp32 logits.
+template <bool LAST>
+__device__ __forceinline__ void fwd_store_tile(const FwdArgs &g, int w, int o, int bt, int half, float bias, const f32x16 &acc)
+{
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) {
+        const int bb = bt + grp * 8 + half * 4;   // 4 consecutive rows bb..bb+3
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[i] = acc[grp * 4 + i] + bias;
+            if (!LAST) v[i] = v[i] > 0.f ? v[i] : 0.f;
+        }
+        if (LAST) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (bb + i < g.B) g.z[((i64)w * g.B + bb + i) * g.O + o] = v[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (bb + i < g.B) g.h[((i64)w * g.B + bb + i) * g.O + o] = f2bf(v[i]);
+                else v[i] = 0.f;
+            }
+            if (bb < g.Bp) {
+                u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
+                *reinterpret_cast<u32x2 *>(g.ht + tfrag_worker(w, g.O, g.Bp) + tfrag_off(o, bb, g.Bp)) = p;
+            }
+        }
+    }
+}
+
 // grid (ceil(O / (32 WN)), ceil(B / (32 WM MT)), n), block 256 = WM x WN waves.
 template <int WM, int WN, int MT, bool VEC, bool LAST>
 __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
@@ -264,34 +297,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
     if (o >= g.O) return;
     const float bias = g.X[(i64)w * g.ld + g.boff + o];
 #pragma unroll
-    for (int m = 0; m < MT; ++m) {
-        const int bt = b0 + (wm * MT + m) * 32;
-#pragma unroll
-        for (int grp = 0; grp < 4; ++grp) {
-            const int bb = bt + grp * 8 + half * 4;   // 4 consecutive rows bb..bb+3
-            float v[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[i] = acc[m][grp * 4 + i] + bias;
-                if (!LAST) v[i] = v[i] > 0.f ? v[i] : 0.f;
-            }
-            if (LAST) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (bb + i < g.B) g.z[((i64)w * g.B + bb + i) * g.O + o] = v[i];
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (bb + i < g.B) g.h[((i64)w * g.B + bb + i) * g.O + o] = f2bf(v[i]);
-                    else v[i] = 0.f;
-                }
-                if (bb < g.Bp) {
-                    u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
-                    *reinterpret_cast<u32x2 *>(g.ht + tfrag_worker(w, g.O, g.Bp) + tfrag_off(o, bb, g.Bp)) = p;
-                }
-            }
-        }
-    }
+    for (int m = 0; m < MT; ++m) fwd_store_tile<LAST>(g, w, o, b0 + (wm * MT + m) * 32, half, bias, acc[m]);
 }
 
 // Minibatches of at most 32 rows: the same product with a [64 outputs][128 k] weight tile, so that a row of the
@@ -412,32 +418,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
     // epilogue: lane owns output column o, 16 rows
     const int o = o0 + wn * 32 + l32;
     if (o >= g.O) return;
-    const float bias = g.X[(i64)w * g.ld + g.boff + o];
-#pragma unroll
-    for (int grp = 0; grp < 4; ++grp) {
-        const int bb = b0 + grp * 8 + half * 4;   // 4 consecutive rows bb..bb+3
-        float v[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[i] = acc[grp * 4 + i] + bias;
-            if (!LAST) v[i] = v[i] > 0.f ? v[i] : 0.f;
-        }
-        if (LAST) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (bb + i < g.B) g.z[((i64)w * g.B + bb + i) * g.O + o] = v[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (bb + i < g.B) g.h[((i64)w * g.B + bb + i) * g.O + o] = f2bf(v[i]);
-                else v[i] = 0.f;
-            }
-            if (bb < g.Bp) {
-                u32x2 p = {pack2(v[0], v[1]), pack2(v[2], v[3])};
-                *reinterpret_cast<u32x2 *>(g.ht + tfrag_worker(w, g.O, g.Bp) + tfrag_off(o, bb, g.Bp)) = p;
-            }
-        }
-    }
+    fwd_store_tile<LAST>(g, w, o, b0, half, g.X[(i64)w * g.ld + g.boff + o], acc);
 }
 
 // Class layer (at most 32 outputs): the tile above would be 3/4 padding and one workgroup per worker
