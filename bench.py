@@ -53,6 +53,10 @@ def parse():
     ap.add_argument("--momentum", type=float, default=0.0,
                     help="run the heavy-ball variant dpsgd_mix_step_momentum with this mu (two-call path; a variant "
                          "of the benchmark, flagged in the output)")
+    ap.add_argument("--shadow", action="store_true",
+                    help="dpsgd_step with the bf16_shadow option: the fused kernel leaves the bf16 rounding of the new "
+                         "hidden-layer weights for the next iteration's forward and data gradient (same results; the "
+                         "caller must not touch X between iterations, which this loop does not)")
     ap.add_argument("--graph", action="store_true",
                     help="after the eager pass, record the K iterations into one HIP graph and report the timed "
                          "replay of it as the value (pays where the iteration is launch-bound: the small workloads)")
@@ -221,8 +225,11 @@ def main():
         pool.append((inp_d, torch.from_numpy(tgt).cuda()))
 
     ctx = B.Dpsgd(cfg.n, d, topo, cfg.gamma, ld=ld)
+    if args.shadow:
+        ctx.set_option("bf16_shadow", 1)
     # layers whose weight gradient dpsgd_step forms inside the mix kernel (same rule as the library)
     fused_weights = 0
+    shadow_weights = 0   # of those, the hidden-layer weights whose bf16 copy the fused kernel also writes (--shadow)
     ring_ok = cfg.topology == "ring" and cfg.n >= 3
     torus_ok = cfg.topology == "torus" and 3 <= cfg.torus_dims[1] <= 8 and cfg.torus_dims[0] >= 3
     if cfg.bf16 and cfg.model_kind in (MODEL_MLP, MODEL_SOFTMAX) and (ring_ok or torus_ok):
@@ -230,6 +237,8 @@ def main():
             w_in, w_out = cfg.widths[l], cfg.widths[l + 1]
             if w_in % (128 if ring_ok else 32) == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
                 fused_weights += w_in * w_out
+                if args.shadow and ring_ok and l >= 1:
+                    shadow_weights += w_in * w_out
     fused = fused_weights > 0 and not args.two_call and not args.momentum
     Vel = torch.zeros_like(X) if args.momentum else None
     if args.momentum:
@@ -272,7 +281,7 @@ def main():
         kernel_name = ("mlp_fused_ring_kernel" if ring_ok else "mlp_fused_torus_cols_kernel") + \
             " (weight gradient + Algorithm 1 steps 4-5, in place)"
         launch_ms = fused_ms / launches
-        launch_bytes = 8.0 * cfg.n * fused_weights * K / launches
+        launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / launches
         mix_ms = fused_ms / K
     else:
         kernel_name = "mix_step (Algorithm 1 steps 4-5 fused)"
@@ -329,10 +338,12 @@ def main():
                                                            else "dpsgd_grad + dpsgd_mix_step"),
                    **({"launch": f"one HIP graph of {K} iterations, one replay timed",
                        "eager_ms_per_step": eager_ms / K} if graph_ms is not None else {}),
+                   **({"bf16_shadow": True} if args.shadow else {}),
                    **({"variant": variant} if variant else {})},
         "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if variant else MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
+                     "traffic": None if (variant or args.shadow) else
+                     MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
                      "algorithmic_bytes_per_launch": launch_bytes, "avg_launch_ms": launch_ms},
         "gradient": gradient_roofline(cfg, d, total_ms / K),
         "mean": {"kernel": "dpsgd_mean (Algorithm 1 step 7)", "ms": mean_ms, "algorithmic_bytes": 4.0 * cfg.n * d,

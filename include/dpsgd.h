@@ -140,6 +140,12 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * "mix_vec" (floats per lane: 0 = auto, 1, 2 or 4), "mix_force_csr" (1: run the generic CSR
  * kernel even for ring / torus tags), "torus_window" (1: dpsgd_step on a torus with 8 columns uses the kernel
  * that keeps three grid rows of tiles in one wave's registers instead of one wave per grid column),
+ * "bf16_shadow" (1: dpsgd_step on the ring also leaves the bf16 rounding of the new hidden-layer weights of a bf16 MLP
+ * in a buffer of the context, and the next dpsgd_step on the same X and model reads them instead of the fp32
+ * weights in its forward and data-gradient kernels: the same values, half the bytes.  The caller promises that
+ * between two dpsgd_step calls nobody else writes X; every dpsgd_mix_step* call, a change of this option, another
+ * X or model, and calls recorded under stream capture drop the copy.  Costs 2 bytes per hidden-layer weight and
+ * worker of device memory),
  * "time_fused" (see dpsgd_read_timing). */
 dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value);
 

@@ -282,6 +282,7 @@ dpsgd_status dpsgd_destroy(dpsgd_ctx *ctx)
     (void)hipFree(ctx->d_vals);
     (void)hipFree(ctx->d_partials);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->shadow) (void)hipFree(ctx->shadow);
     for (hipEvent_t e2 : ctx->ev) (void)hipEventDestroy(e2);
     delete ctx;
     return dpsgd::hip_status(e);
@@ -308,6 +309,9 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
         ctx->opt_mix_force_csr = value ? 1 : 0;
     } else if (k == "torus_window") {
         ctx->opt_torus_window = value ? 1 : 0;
+    } else if (k == "bf16_shadow") {
+        ctx->opt_bf16_shadow = value ? 1 : 0;
+        ctx->shadow_valid = false;
     } else if (k == "time_fused") {
         ctx->opt_time_fused = value ? 1 : 0;
     } else {
@@ -337,6 +341,7 @@ static dpsgd_status mix_common(dpsgd_ctx *ctx, const float *X_in, const float *G
     // G must be distinct from the output; X_out is either X_in itself or a disjoint buffer
     if (overlaps(G, X_out, bytes)) return DPSGD_EINVAL;
     if (X_out != X_in && overlaps(X_in, X_out, bytes)) return DPSGD_EINVAL;
+    ctx->shadow_valid = false;   // X_out may be the matrix the bf16 copy belongs to
     return dpsgd::launch_mix(ctx, X_in, G, X_out, consensus, swapped);
 }
 
@@ -360,6 +365,7 @@ dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const fl
     if (overlaps(G, X_out, bytes) || overlaps(V, X_out, bytes) || overlaps(V, X_in, bytes) || overlaps(V, G, bytes))
         return DPSGD_EINVAL;
     if (X_out != X_in && overlaps(X_in, X_out, bytes)) return DPSGD_EINVAL;
+    ctx->shadow_valid = false;   // X_out may be the matrix the bf16 copy belongs to
     return dpsgd::launch_mix(ctx, X_in, G, X_out, consensus, false, V, mu);
 }
 

@@ -51,6 +51,17 @@ struct dpsgd_ctx {
     std::vector<hipEvent_t> ev;   // pairs (start, stop)
     int64_t ev_pairs = 0, ev_launches = 0;
 
+    // "bf16_shadow": dpsgd_step's fused kernel also leaves the bf16 rounding of the new hidden-layer weights here,
+    // and the next dpsgd_step on the same X reads them (2 B instead of 4 B per weight in the forward and the data
+    // gradient).  Valid only from one dpsgd_step to the next on the same X and model; everything else clears it.
+    int32_t opt_bf16_shadow = 0;
+    void *shadow = nullptr;
+    size_t shadow_bytes = 0;
+    bool shadow_valid = false;
+    const float *shadow_X = nullptr;
+    dpsgd_model_desc shadow_model;
+    std::vector<int64_t> shadow_off;   // per layer: element offset of its [n][O][K] block, or -1
+
     // gradient workspace (activations, bf16 operand copies), owned by the context
     void *ws = nullptr;
     size_t ws_bytes = 0;

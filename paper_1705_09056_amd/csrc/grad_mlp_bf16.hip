@@ -62,6 +62,11 @@ __device__ __forceinline__ i64 tfrag_off(int r, int b, int Bp)
 }
 __device__ __forceinline__ i64 tfrag_worker(int w, int rows, int Bp) { return (i64)w * ((rows + 31) / 32 * 32) * Bp; }
 
+// The bf16 weight copy of a layer ("bf16_shadow") is stored per worker in 32 x 32 tiles, [O/32][K/32][32][32]: the
+// fused kernel writes a wave's tile as 2 KB of consecutive memory (whole cache lines per store instruction), and
+// the forward / data-gradient kernels read the tiles of their [64][128] blocks as runs of 8 KB.
+__device__ __forceinline__ i64 shadow_tile(int o, int k, int K) { return ((i64)(o >> 5) * (K >> 5) + (k >> 5)) * 1024; }
+
 // Workgroups are dealt to the 8 XCDs round-robin by linear id and every XCD has its own L2.  For a grid
 // (tiles, 1, n) with n a multiple of 8 the ids are renumbered so that all tiles of a worker run on one XCD and
 // the worker's activation (or delta) matrix is fetched into one L2 instead of eight.
@@ -150,6 +155,7 @@ struct FwdArgs {
     bf16_t *h;             // [n][B][O]   (hidden layers)
     bf16_t *ht;            // T copy of h (hidden layers)
     float *z;              // [n][B][O]   (last layer, fp32 logits)
+    const bf16_t *wb;      // bf16 copy of the weights (32 x 32 tiles, see shadow_tile) left by the previous fused step, or null
 };
 
 // Epilogue of one 32 x 32 accumulator tile of the forward product: lane owns output column o and the 16 rows
@@ -307,11 +313,12 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
 constexpr int KC2 = 128;
 constexpr int PITCH2 = KC2 + 8;
 
-template <bool VEC, bool LAST>
+template <bool VEC, bool LAST, bool WB16>
 __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
 {
     constexpr int TO = 64, MBLK = 32;
     constexpr int WQ = TO * KC2 / 4 / 256;    // float4 units of the W tile per thread (8)
+    constexpr int BQ = TO * KC2 / 8 / 256;    // 16-byte units of a bf16 W tile per thread (4)
     constexpr int AQ = MBLK * KC2 / 8 / 256;  // 16-byte units of the A tile per thread (2)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *Wt = reinterpret_cast<bf16_t *>(smem);          // [2][TO][PITCH2]
@@ -323,13 +330,33 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
     const int wn = wave & 1, wk = wave >> 1;
     const int l32 = lane & 31, half = lane >> 5;
     const float *Wg = g.X + (i64)w * g.ld + g.woff;
+    const bf16_t *Wb16 = WB16 ? g.wb + (i64)w * g.O * g.K : nullptr;
     const bf16_t *Ag = g.act + (i64)w * g.B * g.K;
 
-    f32x4 wreg[WQ];
+    f32x4 wreg[WB16 ? 1 : WQ];
+    u32x4 breg0[WB16 ? BQ : 1];
     u32x4 areg[AQ];
-    auto fetch = [&](int k0) {
+    // already rounded weights: 8 tiles of 2 KB (O % 64 == 0 and K % 128 == 0 hold), 128 threads per tile
+    auto fetch_w16 = [&](int k0, u32x4 (&br)[WB16 ? BQ : 1]) {
 #pragma unroll
-        for (int q = 0; q < WQ; ++q) {
+        for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
+            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
+            br[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
+                Wb16 + shadow_tile(o0 + (t >> 2) * 32, k0 + (t & 3) * 32, g.K) + within * 8));
+        }
+    };
+    auto stage_w16 = [&](int buf, const u32x4 (&br)[WB16 ? BQ : 1]) {
+        bf16_t *Wb = Wt + buf * TO * PITCH2;
+#pragma unroll
+        for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
+            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
+            const int row = (t >> 2) * 32 + (within >> 2), kq = (t & 3) * 32 + (within & 3) * 8;
+            *reinterpret_cast<u32x4 *>(Wb + row * PITCH2 + kq) = br[q];
+        }
+    };
+    auto fetch_w32 = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
             const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
             const int o = o0 + row, k = k0 + kq;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
@@ -346,6 +373,17 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
             }
             wreg[q] = v;
         }
+    };
+    auto stage_w32 = [&](int buf) {
+        bf16_t *Wb = Wt + buf * TO * PITCH2;
+#pragma unroll
+        for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
+            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
+            u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
+            *reinterpret_cast<u32x2 *>(Wb + row * PITCH2 + kq) = p;
+        }
+    };
+    auto fetch_a = [&](int k0) {
 #pragma unroll
         for (int q = 0; q < AQ; ++q) {
             const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 8;
@@ -366,14 +404,8 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
             areg[q] = v;
         }
     };
-    auto stage = [&](int buf) {
-        bf16_t *Wb = Wt + buf * TO * PITCH2, *Ab = At + buf * MBLK * PITCH2;
-#pragma unroll
-        for (int q = 0; q < WQ; ++q) {
-            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
-            u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
-            *reinterpret_cast<u32x2 *>(Wb + row * PITCH2 + kq) = p;
-        }
+    auto stage_a = [&](int buf) {
+        bf16_t *Ab = At + buf * MBLK * PITCH2;
 #pragma unroll
         for (int q = 0; q < AQ; ++q) {
             const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 8;
@@ -389,18 +421,35 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
     const int nchunks = (g.K + KC2 - 1) / KC2;
     const int start = (int)((unsigned)(tile * 5 + w * 3) % (unsigned)nchunks);
     auto chunk_k = [&](int c) { const int cc = c + start; return (cc >= nchunks ? cc - nchunks : cc) * KC2; };
-    fetch(chunk_k(0));
-    stage(0);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < nchunks) fetch(chunk_k(c + 1));
+    auto multiply = [&](int buf) {
         const bf16_t *Wb = Wt + buf * TO * PITCH2 + (wn * 32 + l32) * PITCH2 + wk * (KC2 / 2) + 8 * half;
         const bf16_t *Ab = At + buf * MBLK * PITCH2 + l32 * PITCH2 + wk * (KC2 / 2) + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < KC2 / 32; ++ks)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Ab + ks * 16), frag(Wb + ks * 16), acc, 0, 0, 0);
-        if (c + 1 < nchunks) stage(buf ^ 1);
+    };
+    // (fetching the half-size bf16 chunks two ahead, to keep as many bytes in flight as with fp32 weights, was measured
+    // and is slower: 400 against 387 us)
+    fetch_w16(chunk_k(0), breg0);
+    fetch_w32(chunk_k(0));
+    fetch_a(chunk_k(0));
+    stage_w16(0, breg0);
+    stage_w32(0);
+    stage_a(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) {
+            fetch_w16(chunk_k(c + 1), breg0);
+            fetch_w32(chunk_k(c + 1));
+            fetch_a(chunk_k(c + 1));
+        }
+        multiply(buf);
+        if (c + 1 < nchunks) {
+            stage_w16(buf ^ 1, breg0);
+            stage_w32(buf ^ 1);
+            stage_a(buf ^ 1);
+        }
         __syncthreads();
     }
 
@@ -576,14 +625,16 @@ struct DgradArgs {
     bf16_t *dzp;          // [n][B][K]
     bf16_t *dzpt;         // T copy of dzp
     int B, Bp, K, O;
+    const bf16_t *wb;     // bf16 copy of the weights (32 x 32 tiles, see shadow_tile) left by the previous fused step, or null
 };
 
 // grid (ceil(K / (32 WN)), ceil(B / (32 WM MT)), n), block 256.
-template <int WM, int WN, int MT, bool VEC>
+template <int WM, int WN, int MT, bool VEC, bool WB16 = false>
 __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
 {
     constexpr int TK = 32 * WN, MBLK = 32 * WM * MT;
     constexpr int WQ = TK / 16;     // float4 units of the [64 o][TK k] W tile per thread
+    constexpr int BQ = TK / 32;     // 16-byte units of the bf16 W tile per thread
     constexpr int DQ = MBLK / 32;   // 16-byte units of the dZ tile per thread
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int WP = TK + 8;                               // pitch of the W tile (bf16 elements)
@@ -596,13 +647,34 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, half = lane >> 5;
     const float *Wg = g.X + (i64)w * g.ld + g.woff;
+    const bf16_t *Wb16 = WB16 ? g.wb + (i64)w * g.O * g.K : nullptr;
     const bf16_t *Dg = g.dz + (i64)w * g.B * g.O;
 
-    f32x4 wreg[WQ];
+    f32x4 wreg[WB16 ? 1 : WQ];
+    u32x4 breg0[WB16 ? BQ : 1];
     u32x4 dreg[DQ];
+    // already rounded weights: 2 x TK / 32 tiles of 2 KB (O % 64 == 0 and K % TK == 0 hold), 128 threads per tile
+    auto fetch_w16 = [&](int oc, u32x4 (&br)[WB16 ? BQ : 1]) {
+#pragma unroll
+        for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
+            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
+            br[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
+                Wb16 + shadow_tile(oc + (t / (TK / 32)) * 32, kt0 + (t % (TK / 32)) * 32, g.K) + within * 8));
+        }
+    };
+    auto stage_w16 = [&](int buf, const u32x4 (&br)[WB16 ? BQ : 1]) {
+        bf16_t *Wb = Wt + buf * KC * WP;
+#pragma unroll
+        for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
+            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
+            const int orow = (t / (TK / 32)) * 32 + (within >> 2), kq = (t % (TK / 32)) * 32 + (within & 3) * 8;
+            *reinterpret_cast<u32x4 *>(Wb + orow * WP + kq) = br[q];
+        }
+    };
+    // fp32 weights (unless the bf16 copy is used) and the delta tile
     auto fetch = [&](int oc) {
 #pragma unroll
-        for (int q = 0; q < WQ; ++q) {
+        for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
             const int u = tid + 256 * q, orow = u / (TK / 4), kq = (u % (TK / 4)) * 4;
             const int o = oc + orow, k = kt0 + kq;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
@@ -642,7 +714,7 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
     auto stage = [&](int buf) {
         bf16_t *Wb = Wt + buf * KC * WP, *Db = Dt + buf * MBLK * PITCH;
 #pragma unroll
-        for (int q = 0; q < WQ; ++q) {
+        for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
             const int u = tid + 256 * q, orow = u / (TK / 4), kq = (u % (TK / 4)) * 4;
             u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
             *reinterpret_cast<u32x2 *>(Wb + orow * WP + kq) = p;
@@ -661,12 +733,7 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
         for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
 
     const int nchunks = (g.O + KC - 1) / KC;
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < nchunks) fetch((c + 1) * KC);
+    auto multiply = [&](int buf) {
         // B operand: column k of the tile, 8 consecutive o (the transpose happens in these reads:
         // consecutive lanes read consecutive k of one LDS row)
         const bf16_t *Wb = Wt + buf * KC * WP + (8 * half) * WP + wn * 32 + l32;
@@ -685,7 +752,23 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
                 acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aa, bw, acc[m], 0, 0, 0);
             }
         }
-        if (c + 1 < nchunks) stage(buf ^ 1);
+    };
+    fetch_w16(0, breg0);
+    fetch(0);
+    stage_w16(0, breg0);
+    stage(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) {
+            fetch_w16((c + 1) * KC, breg0);
+            fetch((c + 1) * KC);
+        }
+        multiply(buf);
+        if (c + 1 < nchunks) {
+            stage_w16(buf ^ 1, breg0);
+            stage(buf ^ 1);
+        }
         __syncthreads();
     }
 
@@ -744,10 +827,12 @@ dpsgd_status fwd_ksplit_launch(hipStream_t s, int n, const FwdArgs &a, bool vec,
 {
     dim3 grid((unsigned)((a.O + 63) / 64), (unsigned)((a.B + 31) / 32), (unsigned)n);
     const size_t shm = (size_t)2 * (64 + 32) * PITCH2 * sizeof(bf16_t);
-    if (vec && last) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<true, true>), grid, dim3(256), shm, s, a);
-    else if (vec) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<true, false>), grid, dim3(256), shm, s, a);
-    else if (last) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<false, true>), grid, dim3(256), shm, s, a);
-    else hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<false, false>), grid, dim3(256), shm, s, a);
+    if (a.wb && vec && !last && (a.O % 64) == 0 && (a.K % 128) == 0)
+        hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<true, false, true>), grid, dim3(256), shm, s, a);
+    else if (vec && last) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<true, true, false>), grid, dim3(256), shm, s, a);
+    else if (vec) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<true, false, false>), grid, dim3(256), shm, s, a);
+    else if (last) hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<false, true, false>), grid, dim3(256), shm, s, a);
+    else hipLaunchKernelGGL((mlp_fwd_ksplit_kernel<false, false, false>), grid, dim3(256), shm, s, a);
     return hip_status(hipGetLastError());
 }
 
@@ -757,7 +842,9 @@ dpsgd_status dgrad_launch(hipStream_t s, int n, const DgradArgs &a, bool vec)
     constexpr int TK = 32 * WN, MBLK = 32 * WM * MT;
     dim3 grid((unsigned)((a.K + TK - 1) / TK), (unsigned)((a.B + MBLK - 1) / MBLK), (unsigned)n);
     const size_t shm = (size_t)2 * (KC * (TK + 8) + MBLK * PITCH) * sizeof(bf16_t);
-    if (vec) hipLaunchKernelGGL((mlp_dgrad_kernel<WM, WN, MT, true>), grid, dim3(256), shm, s, a);
+    if (a.wb && vec && (a.O % KC) == 0 && (a.K % TK) == 0)
+        hipLaunchKernelGGL((mlp_dgrad_kernel<WM, WN, MT, true, true>), grid, dim3(256), shm, s, a);
+    else if (vec) hipLaunchKernelGGL((mlp_dgrad_kernel<WM, WN, MT, true>), grid, dim3(256), shm, s, a);
     else hipLaunchKernelGGL((mlp_dgrad_kernel<WM, WN, MT, false>), grid, dim3(256), shm, s, a);
     return hip_status(hipGetLastError());
 }
@@ -794,10 +881,11 @@ struct FusedArgs {
     int n, K, O, Bp;
     float w, gamma;
     double *partials;    // one per wave (CONS only)
+    bf16_t *shadow;      // SHADOW: [n][O/32][K/32][32][32] bf16, receives the rounding of the new weights
 };
 
-template <bool CONS>
-__global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
+template <bool CONS, bool SHADOW>
+__global__ void __launch_bounds__(256, 3) mlp_fused_ring_kernel(FusedArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -826,6 +914,9 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
     // wait counts stay exact: past the last worker the tile fetch reads one cached line of the operand array
     // instead (values never used), the operand fetch repeats the last worker's.
     bf16x8 pa0 = frag(ap), pb0 = frag(bp), pa1 = frag(ap + 512), pb1 = frag(bp + 512);
+    // SHADOW: byte offset of this lane's pair of columns inside the wave's 32 x 32 bf16 tile; the odd lane writes one
+    // row further down than the even lane
+    const unsigned shadow_lane = (unsigned)(((half * 4 + (l32 & 1)) * 32 + (l32 & ~1)) * 2);
     for (int i = 0; i < a.n; ++i) {
         {
             const bool far = i + 2 < a.n;
@@ -858,6 +949,12 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
         }
         const bool last = i + 1 == a.n;
         float *dst = xt + (i64)i * a.ld;
+        // SHADOW: rows v and v+1 of two neighbouring lanes (columns c, c+1) are exchanged so that the even lane holds
+        // both columns of row v and the odd lane both of row v+1: 4-byte stores of two bf16 values
+        // (a wave-uniform base plus a 32-bit byte offset per lane; the copy is stored in 32 x 32 tiles, so the wave's
+        // tile is 2 KB of consecutive memory and a store instruction covers two whole cache lines)
+        char *sbase = SHADOW ? reinterpret_cast<char *>(a.shadow + (i64)i * a.O * a.K + shadow_tile(o0, k0, a.K)) : nullptr;
+        float keep = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const float nxt = last ? xh[v] : xn[v];   // the ring closes on worker 0's original tile
@@ -870,6 +967,18 @@ __global__ void __launch_bounds__(256) mlp_fused_ring_kernel(FusedArgs a)
                 const float e = o - xh[v];
                 s1[v] += e;
                 s2[v & 3] += e * e;
+            }
+            if (SHADOW) {
+                if (!(v & 1)) {
+                    keep = o;
+                } else {
+                    const bool odd = l32 & 1;
+                    const float send = odd ? keep : o;   // the odd lane gives away row v-1, the even lane row v
+                    const float recv = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(send), 0xB1, 0xf, 0xf, true));
+                    const unsigned pk = odd ? pack2(recv, o) : pack2(keep, recv);
+                    const unsigned rowb = (unsigned)(((v >> 2) * 8 + (v & 3) - 1) * 32) * 2u;   // row of v - 1 inside the tile, bytes
+                    __builtin_nontemporal_store(pk, reinterpret_cast<unsigned *>(sbase + (shadow_lane + rowb)));
+                }
             }
             xm[v] = xc[v];
             xc[v] = nxt;
@@ -1230,6 +1339,46 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         boff[l] = off; off += m.widths[l + 1];
     }
 
+    // "bf16_shadow": which layers read the bf16 weights the previous call left, which leave them for the next one.
+    // Only hidden layers qualify (their weights are read twice, by the forward and by the data gradient; for the
+    // first layer the extra write would cost what the forward saves), only on the ring kernel, never under capture
+    // (a recorded call could not know what the buffer holds when it is replayed).
+    std::vector<const bf16_t *> wb_use(L, nullptr);
+    std::vector<bf16_t *> wb_emit(L, nullptr);
+    if (fuse) {
+        const bool was_valid = ctx->shadow_valid && ctx->shadow_X == X && ctx->shadow_model.kind == m.kind &&
+                               ctx->shadow_model.widths == m.widths && (int)ctx->shadow_off.size() == L;
+        ctx->shadow_valid = false;
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cap) != hipSuccess) cap = hipStreamCaptureStatusNone;
+        if (ctx->opt_bf16_shadow && ctx->ring_uniform && cap == hipStreamCaptureStatusNone) {
+            std::vector<int64_t> soff(L, -1);
+            size_t elems = 0;
+            for (int l = 1; l < L; ++l) {
+                if (!layer_fusable(ctx, m.widths[l], m.widths[l + 1], woff[l])) continue;
+                soff[l] = (int64_t)elems;
+                elems += (size_t)n * m.widths[l] * m.widths[l + 1];
+            }
+            if (elems * sizeof(bf16_t) > ctx->shadow_bytes) {
+                if (hipStreamSynchronize(s) != hipSuccess) return DPSGD_EDEVICE;
+                if (ctx->shadow) (void)hipFree(ctx->shadow);
+                ctx->shadow = nullptr;
+                ctx->shadow_bytes = 0;
+                if (hipMalloc(&ctx->shadow, elems * sizeof(bf16_t)) != hipSuccess) {
+                    (void)hipGetLastError();
+                    return DPSGD_ENOMEM;
+                }
+                ctx->shadow_bytes = elems * sizeof(bf16_t);
+            } else if (was_valid && soff == ctx->shadow_off) {
+                for (int l = 1; l < L; ++l)
+                    if (soff[l] >= 0) wb_use[l] = (const bf16_t *)ctx->shadow + soff[l];
+            }
+            for (int l = 1; l < L; ++l)
+                if (soff[l] >= 0) wb_emit[l] = (bf16_t *)ctx->shadow + soff[l];
+            ctx->shadow_off = soff;
+        }
+    }
+
     {   // bf16 copy (if needed) and transposed copy of the inputs
         const int F = m.widths[0];
         dim3 grid((unsigned)((F + 31) / 32), (unsigned)(Bp / 32), (unsigned)n);
@@ -1250,6 +1399,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         a.B = B; a.Bp = Bp; a.K = m.widths[l]; a.O = m.widths[l + 1];
         const bool last = (l == L - 1);
         if (last) a.z = ws.logits; else { a.h = ws.h[l + 1]; a.ht = ws.ht[l + 1]; }
+        a.wb = wb_use[l];
         const bool vec = base_ok && (a.K % 8) == 0 && (woff[l] % 4) == 0 && aligned16(act[l]);
         if (last && vec && a.O <= 32 && (a.K % 16) == 0 && a.K >= 256) {
             hipLaunchKernelGGL(mlp_fwd_last_kernel, dim3((unsigned)((B + 31) / 32), (unsigned)n), dim3(512), 0, s, a);
@@ -1288,6 +1438,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             da.dz = ws.dz[cur]; da.X = X; da.ld = ctx->ld; da.woff = woff[l]; da.hprev = ws.h[l];
             da.dzp = ws.dz[cur ^ 1]; da.dzpt = ws.dzt[l];
             da.B = B; da.Bp = Bp; da.K = K; da.O = O;
+            da.wb = wb_use[l];
             const bool vec = base_ok && (K % 4) == 0 && (O % 8) == 0 && (woff[l] % 4) == 0;
             if (t.mt == 1) st = dgrad_launch<1, 4, 1>(s, n, da, vec);
             else if (t.wm == 1) st = dgrad_launch<1, 4, 2>(s, n, da, vec);
@@ -1323,8 +1474,14 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             dim3 grid((unsigned)(K / 128), (unsigned)(O / 32));
             np = (i64)grid.x * grid.y * 4;
             if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
-            if (cons) hipLaunchKernelGGL(mlp_fused_ring_kernel<true>, grid, dim3(256), 0, s, fa);
-            else hipLaunchKernelGGL(mlp_fused_ring_kernel<false>, grid, dim3(256), 0, s, fa);
+            fa.shadow = wb_emit[l];
+            if (fa.shadow) {
+                if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, true>), grid, dim3(256), 0, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, true>), grid, dim3(256), 0, s, fa);
+            } else {
+                if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, false>), grid, dim3(256), 0, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, false>), grid, dim3(256), 0, s, fa);
+            }
         } else if (!ctx->opt_torus_window || !torus8(ctx)) {
             FusedTorusColArgs fa{};
             fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
@@ -1371,6 +1528,18 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         if (l < L) run0 = boff[l];
     }
     if (st == DPSGD_OK && cons) st = launch_consensus_finalize(ctx, nparts, consensus);
+    if (st == DPSGD_OK) {   // the bf16 copies describe X as this call leaves it
+        bool any = false, all = true;
+        for (int l = 0; l < L; ++l) {
+            any = any || wb_emit[l] != nullptr;
+            all = all && (wb_emit[l] == nullptr || fused[l]);
+        }
+        if (any && all) {
+            ctx->shadow_valid = true;
+            ctx->shadow_X = X;
+            ctx->shadow_model = m;
+        }
+    }
     return st;
 }
 }  // namespace

@@ -17,7 +17,7 @@ ITERS = 3      # iterations recorded in one graph
 REPLAYS = 3
 
 
-def graph_case(cfg, bf16):
+def graph_case(cfg, bf16, options=()):
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = synth.padded_stride(d)
     model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=bf16)
@@ -35,6 +35,8 @@ def graph_case(cfg, bf16):
         loss_e, loss_g = torch.zeros(ITERS, cfg.n, device="cuda"), torch.zeros(ITERS, cfg.n, device="cuda")
         cons_e, cons_g = torch.zeros(ITERS, device="cuda"), torch.zeros(ITERS, device="cuda")
         ctx = B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld, stream=side)
+        for key, value in options:
+            ctx.set_option(key, value)
 
         def iterations(X, loss, cons):
             for k, (inp_d, tgt_d) in enumerate(batches):
@@ -71,6 +73,13 @@ def graph_case(cfg, bf16):
 
 def test_graph_of_fused_ring_steps():
     graph_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=6), bf16=True)
+
+
+def test_graph_with_the_bf16_shadow_option():
+    """Recorded calls neither read nor write the bf16 weight copy (its contents at replay time are unknown); the
+    eager calls between the replays do.  Both must agree bit for bit."""
+    graph_case(shrink(CONFIGS[3], widths=(1024, 1024, 1024, 10), batch=32, n=5), bf16=True,
+               options=(("bf16_shadow", 1),))
 
 
 def test_graph_of_fused_torus_steps():

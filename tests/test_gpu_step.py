@@ -228,3 +228,58 @@ def test_two_contexts_on_two_streams_do_not_share_state():
     for (xa, ca), (xb, cb) in zip(results[False], results[True]):
         assert np.array_equal(xa, xb)
         assert ca == cb
+
+
+def test_bf16_shadow_option_gives_the_same_trajectory_and_is_dropped_when_x_changes():
+    """With "bf16_shadow" the fused kernel leaves the bf16 rounding of the new hidden-layer weights for the next
+    call's forward and data gradient: the same values, so every iterate must be bit-identical to the run without
+    the option.  A dpsgd_mix_step in between (X changes behind the copy's back), a second matrix X and a smaller
+    minibatch must all be handled."""
+    cfg = shrink(CONFIGS[3], widths=(1024, 1024, 1024, 10), batch=32, n=5, iters=6)
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    ld = synth.padded_stride(d)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    X0 = to_dev(synth.make_replicas(cfg), ld)
+    batches = []
+    for k in range(cfg.iters):
+        inp, tgt = synth.make_batch(cfg, k)
+        batches.append((bf16_dev(inp), torch.from_numpy(tgt).cuda()))
+
+    def run(shadow):
+        Xa, Xb = X0.clone(), (X0 * 1.01).contiguous()
+        G = torch.zeros_like(Xa)
+        loss = torch.zeros(cfg.iters + 2, cfg.n, device="cuda")
+        cons = torch.zeros(cfg.iters + 2, device="cuda")
+        snaps = []
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("bf16_shadow", 1 if shadow else 0)
+            for k, (inp_d, tgt_d) in enumerate(batches):
+                ctx.step(model, Xa, inp_d, tgt_d, cfg.batch, G, loss[k], cons[k:k + 1], input_is_bf16=True)
+                snaps.append(Xa.clone())
+                if k == 2:      # X changes through another entry point: the copy must not be used afterwards
+                    G.copy_(Xa).mul_(1e-2)
+                    ctx.mix_step(Xa, G, Xa, None)
+                if k == 3:      # another matrix in between, then back
+                    ctx.step(model, Xb, inp_d, tgt_d, cfg.batch, G, loss[cfg.iters], cons[cfg.iters:cfg.iters + 1],
+                             input_is_bf16=True)
+                    snaps.append(Xb.clone())
+                if k == 4:      # the caller edits X itself and says so by switching the option off and on
+                    Xa[:, :100] += 1e-3
+                    ctx.set_option("bf16_shadow", 1 if shadow else 0)
+            # a smaller minibatch (other workspace layout) on the same X
+            inp_d, tgt_d = batches[0]
+            half = cfg.batch // 2
+            inp_h = inp_d.view(cfg.n, cfg.batch, -1)[:, :half].contiguous()
+            tgt_h = tgt_d.view(cfg.n, cfg.batch)[:, :half].contiguous()
+            ctx.step(model, Xa, inp_h, tgt_h, half, G, loss[cfg.iters + 1], cons[cfg.iters + 1:], input_is_bf16=True)
+            snaps.append(Xa.clone())
+            torch.cuda.synchronize()
+        return snaps, loss.clone(), cons.clone()
+
+    plain, loss_p, cons_p = run(False)
+    shadow, loss_s, cons_s = run(True)
+    assert len(plain) == len(shadow)
+    for k, (a, b) in enumerate(zip(plain, shadow)):
+        assert torch.equal(a, b), f"snapshot {k} differs"
+    assert torch.equal(loss_p, loss_s)
+    assert torch.equal(cons_p, cons_s)
