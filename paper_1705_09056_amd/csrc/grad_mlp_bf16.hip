@@ -5,14 +5,19 @@
 // skinny GEMMs (M = minibatch rows) with distinct weight operands: a weight is used only B times
 // per pass and the kernels are bound by streaming the fp32 master weights from HBM (forward,
 // data gradient) and by writing the fp32 gradient (weight gradient).  Design:
-//   forward   Z[b][o]  = sum_k A[b][k] W[o][k] + bias[o]      W streamed once, fp32 -> bf16 in
-//                                                             registers, staged in LDS (double
-//                                                             buffered), A tile shared by 4 waves
+//   forward   Z[b][o]  = sum_k A[b][k] W[o][k] + bias[o]      W streamed once (non-temporal loads),
+//                                                             fp32 -> bf16 in registers, staged in LDS
+//                                                             (double buffered), A tile shared by the
+//                                                             waves; minibatches <= 32: 512-byte rows
+//                                                             of W per tile, waves split the chunk
 //   dgrad     dA[b][k] = sum_o dZ[b][o] W[o][k]               W streamed once, transposed on the
 //                                                             way into LDS
 //   wgrad     dW[o][k] = sum_b dZ^T[o][b] A^T[k][b]           operands are tiny (L2-resident
 //                                                             transposed bf16 copies), output
 //                                                             streamed to G once
+//   step      the weight gradient of a large layer is formed inside the kernel that applies
+//             X <- W X - gamma G (ring, torus), so it never reaches memory; optionally the kernel also
+//             leaves the bf16 rounding of the new weights for the next forward / dgrad
 // MFMA: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  Lane l of an A (B) operand holds row
 // (column) l%32 and the 8 consecutive k values 8*(l/32)..+7; accumulator register v of lane l is
 // element (row (v/4)*8 + (l/32)*4 + v%4, column l%32).
