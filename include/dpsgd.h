@@ -138,7 +138,8 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
 /* Launch-shape knobs for measurements; unknown keys give DPSGD_EINVAL.  Defaults are chosen from
  * (n, d).  Keys: "mix_bands" (row bands per workgroup of the ring kernel, 0 = auto),
  * "mix_vec" (floats per lane: 0 = auto, 1, 2 or 4), "mix_force_csr" (1: run the generic CSR
- * kernel even for ring / torus tags), "torus_window" (1: dpsgd_step on a torus with 8 columns uses the kernel
+ * kernel even for ring / torus tags), "mix_narrow" (1: the ring kernel with one float4 per lane also for wide
+ * matrices, where the default gives a lane eight), "torus_window" (1: dpsgd_step on a torus with 8 columns uses the kernel
  * that keeps three grid rows of tiles in one wave's registers instead of one wave per grid column),
  * "bf16_shadow" (1: dpsgd_step on the ring also leaves the bf16 rounding of the new hidden-layer weights of a bf16 MLP
  * in a buffer of the context, and the next dpsgd_step on the same X and model reads them instead of the fp32

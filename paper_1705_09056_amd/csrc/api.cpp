@@ -305,6 +305,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
     } else if (k == "mix_vec") {
         if (!(value == 0 || value == 1 || value == 2 || value == 4)) return DPSGD_EINVAL;
         ctx->opt_mix_vec = (int32_t)value;
+    } else if (k == "mix_narrow") {
+        ctx->opt_mix_narrow = value ? 1 : 0;
     } else if (k == "mix_force_csr") {
         ctx->opt_mix_force_csr = value ? 1 : 0;
     } else if (k == "torus_window") {

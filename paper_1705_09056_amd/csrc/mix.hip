@@ -32,6 +32,18 @@ template <int V> __device__ __forceinline__ void vstore(float *p, typename VecT<
 {
     *reinterpret_cast<typename VecT<V>::type *>(p) = v;
 }
+// a * x + y with one rounding, spelled out so that every ring kernel rounds the same way (left to the compiler,
+// two kernels may fuse different products of  w x_{i-1} + w x_i + w x_{i+1} - gamma g)
+__device__ __forceinline__ float fma_s(float a, float x, float y) { return __builtin_fmaf(a, x, y); }
+template <typename T> __device__ __forceinline__ T fma_s(float a, T x, T y) { return __builtin_elementwise_fma((T)(a), x, y); }
+// the update of one element or vector: fixed order and roundings
+template <typename T> __device__ __forceinline__ T ring_update(float w, T xm, T xc, T xn, float gamma, T g)
+{
+    T acc = w * xm;
+    acc = fma_s(w, xc, acc);
+    acc = fma_s(w, xn, acc);
+    return fma_s(-gamma, g, acc);
+}
 template <int V> __device__ __forceinline__ float hsum(typename VecT<V>::type v);
 template <> __device__ __forceinline__ float hsum<1>(float v) { return v; }
 template <> __device__ __forceinline__ float hsum<2>(VecT<2>::type v) { return v.x + v.y; }
@@ -147,10 +159,7 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
         // Rows r0 .. r1-2 read their successor from memory in branch-free chunks of U rows (2U
         // loads in flight per lane); the band's last row takes the halo fetched above.
         auto form = [&](vec xn, vec g, float *dst) {
-            vec acc = w * xm;
-            acc = w * xc + acc;
-            acc = w * xn + acc;
-            vec o = acc - gamma * g;
+            const vec o = ring_update(w, xm, xc, xn, gamma, g);
             vstore<V>(dst, o);
             if (CONS) st.add(o);
             xm = xc;
@@ -208,6 +217,80 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
             double v = wave_sum((double)st.m2());
             if (lane == 0) partials[blockIdx.x] = v;
         }
+    }
+}
+
+// The same walk for wide matrices with fat lanes: one wave per workgroup, every lane owns P float4 column groups
+// 1 KB apart (the wave covers P KB of a row), U rows in flight.  Fewer, fatter waves keep more bytes in flight per
+// memory instruction stream: a bare copy-like probe of this walk moves 5.2 TB/s with one float4 per lane and 5.5-5.6
+// with eight.  No row bands, no momentum (those stay with mix_ring_kernel); the shift of the consensus sums is
+// worker 0's ORIGINAL value, which the lane keeps anyway for the ring's wrap-around.  Same arithmetic, same order
+// as mix_ring_kernel.  grid.x = ncols / (256 P) (whole groups only: no lane is ever idle), block 64; 16-byte aligned rows.
+template <int P, int U, bool CONS>
+__global__ void __launch_bounds__(64)
+mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ld, float w, float gamma,
+                    double *__restrict__ partials)
+{
+    typedef VecT<4>::type vec;
+    const int lane = threadIdx.x;
+    const i64 c0 = ((i64)blockIdx.x * P * 64 + lane) * 4;   // group q starts 256 columns further
+    vec xm[P], xc[P], x0[P], s1[P];
+    float s2 = 0.f;
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        const i64 c = c0 + (i64)q * 256;
+        xm[q] = vload<4>(Xin + (i64)(n - 1) * ld + c);
+        xc[q] = vload<4>(Xin + c);
+        x0[q] = xc[q];
+        s1[q] = (vec)(0.f);
+    }
+    auto form = [&](int row, int q, vec xs, vec g) {
+        const vec xn = row + 1 < n ? xs : x0[q];   // the ring closes on worker 0's original row
+        const vec o = ring_update(w, xm[q], xc[q], xn, gamma, g);
+        __builtin_nontemporal_store(o, reinterpret_cast<vec *>(Xout + (i64)row * ld + c0 + (i64)q * 256));
+        if (CONS) {
+            const vec e = o - x0[q];
+            s1[q] += e;
+            s2 += hsum<4>(e * e);
+        }
+        xm[q] = xc[q];
+        xc[q] = xn;
+    };
+    int row = 0;
+    for (; row + U <= n; row += U) {
+        vec xs[U][P], gs[U][P];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int rn = row + u + 1 < n ? row + u + 1 : n - 1;   // (the last row's successor is x0: clamped, unused)
+#pragma unroll
+            for (int q = 0; q < P; ++q) {
+                const i64 c = c0 + (i64)q * 256;
+                gs[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(G + (i64)(row + u) * ld + c));
+                xs[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Xin + (i64)rn * ld + c));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < P; ++q) form(row + u, q, xs[u][q], gs[u][q]);
+    }
+    for (; row < n; ++row) {
+        const int rn = row + 1 < n ? row + 1 : n - 1;
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            const i64 c = c0 + (i64)q * 256;
+            const vec g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(G + (i64)row * ld + c));
+            const vec x = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Xin + (i64)rn * ld + c));
+            form(row, q, x, g);
+        }
+    }
+    if (CONS) {
+        float m2 = s2;
+        const float inv_n = 1.0f / (float)n;
+#pragma unroll
+        for (int q = 0; q < P; ++q) m2 -= hsum<4>(s1[q] * s1[q]) * inv_n;
+        const double v = wave_sum((double)m2);
+        if (lane == 0) partials[blockIdx.x] = v;
     }
 }
 
@@ -465,10 +548,32 @@ size_t stats_lds_bytes(int bands, int vec) { return bands > 1 ? (size_t)bands * 
 
 template <int V>
 dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols,
-                         bool cons, double *partials, i64 *nparts, float *Vel = nullptr, float mu = 0.f)
+                         bool cons, double *partials, i64 *nparts, float *Vel = nullptr, float mu = 0.f,
+                         bool narrow = false)
 {
     const i64 groups = groups_for(ncols, V);
     const int bands = pick_bands(ctx, groups);
+    constexpr int kFatP = 8;               // float4 groups per lane of the fat-lane kernel
+    constexpr i64 kFatMinGroups = 8192;   // it needs that many single-wave workgroups to fill the chip
+    if (V == 4 && !Vel && bands == 1 && !narrow && !ctx->opt_mix_narrow && ctx->opt_mix_bands == 0 && ctx->n >= 3 &&
+        ncols / (256 * kFatP) >= kFatMinGroups) {
+        // wide matrix: whole groups of 2048 columns go to the fat-lane kernel, the rest to the kernel below
+        const i64 fat_groups = ncols / (256 * kFatP), fat_cols = fat_groups * 256 * kFatP;
+        if (fat_groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
+        if (cons)
+            hipLaunchKernelGGL((mix_ring_fat_kernel<kFatP, 1, true>), dim3((unsigned)fat_groups), dim3(64), 0, ctx->stream,
+                               Xin + col0, G + col0, Xout + col0, ctx->n, ctx->ld, ctx->ring_w, ctx->gamma, partials);
+        else
+            hipLaunchKernelGGL((mix_ring_fat_kernel<kFatP, 2, false>), dim3((unsigned)fat_groups), dim3(64), 0, ctx->stream,
+                               Xin + col0, G + col0, Xout + col0, ctx->n, ctx->ld, ctx->ring_w, ctx->gamma, partials);
+        dpsgd_status st = hip_status(hipGetLastError());
+        i64 rest = 0;
+        if (st == DPSGD_OK && fat_cols < ncols)
+            st = ring_launch<V>(ctx, Xin, G, Xout, col0 + fat_cols, ncols - fat_cols, cons, partials + fat_groups, &rest,
+                                Vel, mu, true);
+        *nparts = fat_groups + rest;
+        return st;
+    }
     const int rpb = (ctx->n + bands - 1) / bands;
     const int used = (ctx->n + rpb - 1) / rpb;   // every launched band owns at least one row
     dim3 grid((unsigned)groups), block(64u * (unsigned)used);

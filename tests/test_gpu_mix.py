@@ -231,6 +231,41 @@ def test_full_size_config4_ring():
     _full_size_mix(112, 268365, B.Topology.ring(), oracle.ring(112).with_fp32_values())
 
 
+@pytest.mark.parametrize("n", [5, 8])
+@pytest.mark.parametrize("with_consensus", [True, False])
+def test_fat_lane_ring_kernel_matches_the_narrow_one_bitwise(n, with_consensus):
+    """Wide matrices (at least 8192 groups of 2048 columns) take the kernel with eight float4 per lane; same
+    arithmetic in the same order as the one-float4 kernel, so the outputs must be identical.  d leaves a remainder of
+    1341 columns for the narrow kernel and the scalar tail; n = 5 leaves a row for the remainder loop of the variant
+    with two rows in flight."""
+    d = 8192 * 2048 + 1341
+    ld = (d + 63) // 64 * 64
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(170509056 + n)
+    Xd = torch.randn(ld, device="cuda", generator=gen) + 0.05 * torch.randn(n, ld, device="cuda", generator=gen)
+    Gd = torch.randn(n, ld, device="cuda", generator=gen)
+    outs, conss = [], []
+    for narrow in (0, 1):
+        out = torch.full_like(Xd, 777.0)
+        cons = torch.zeros(1, device="cuda") if with_consensus else None
+        with B.Dpsgd(n, d, B.Topology.ring(), 0.1, ld=ld) as ctx:
+            ctx.set_option("mix_narrow", narrow)
+            ctx.mix_step(Xd, Gd, out, cons)
+            torch.cuda.synchronize()
+        outs.append(out)
+        conss.append(None if cons is None else float(cons.item()))
+    assert torch.equal(outs[0], outs[1])
+    assert bool(torch.all(outs[0][:, d:] == 777.0))
+    if with_consensus:
+        assert conss[0] == pytest.approx(conss[1], rel=1e-5)
+    # in place gives the same as out of place
+    Xi = Xd.clone()
+    with B.Dpsgd(n, d, B.Topology.ring(), 0.1, ld=ld) as ctx:
+        ctx.mix_step(Xi, Gd, Xi, None)
+        torch.cuda.synchronize()
+    assert torch.equal(Xi[:, :d], outs[0][:, :d])
+
+
 # ------------------------------------------------------------------ momentum variant (dpsgd_mix_step_momentum)
 def run_momentum(n, d, ld, topo_b, topo_o, seed, inplace, mu=0.9, gamma=0.05, steps=3, options=()):
     rng = np.random.default_rng(seed)
