@@ -230,6 +230,35 @@ def test_two_contexts_on_two_streams_do_not_share_state():
         assert ca == cb
 
 
+@pytest.mark.parametrize("widths,batch", [
+    ((1024, 1024, 1024, 10), 32),     # one hidden layer with a copy, read by the forward and the data gradient
+    ((1024, 1024, 1152, 1024, 10), 32),   # two of them, 36 and 32 output tiles
+    ((1024, 1024, 1120, 10), 32),     # 35 output tiles: written, but the readers want multiples of 64 and use fp32
+    ((1024, 1024, 1024, 10), 64),     # minibatch 64: the forward of that tiling reads fp32, the data gradient the copy
+])
+def test_bf16_shadow_option_on_other_shapes(widths, batch):
+    cfg = shrink(CONFIGS[3], widths=widths, batch=batch, n=4, iters=3)
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    ld = synth.padded_stride(d)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    X0 = to_dev(synth.make_replicas(cfg), ld)
+    runs = []
+    for shadow in (0, 1):
+        X = X0.clone()
+        G = torch.zeros_like(X)
+        loss = torch.zeros(cfg.iters, cfg.n, device="cuda")
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("bf16_shadow", shadow)
+            for k in range(cfg.iters):
+                inp, tgt = synth.make_batch(cfg, k)
+                ctx.step(model, X, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, G, loss[k], None,
+                         input_is_bf16=True)
+            torch.cuda.synchronize()
+        runs.append((X, loss))
+    assert torch.equal(runs[0][0], runs[1][0])
+    assert torch.equal(runs[0][1], runs[1][1])
+
+
 def test_bf16_shadow_option_gives_the_same_trajectory_and_is_dropped_when_x_changes():
     """With "bf16_shadow" the fused kernel leaves the bf16 rounding of the new hidden-layer weights for the next
     call's forward and data gradient: the same values, so every iterate must be bit-identical to the run without
