@@ -53,6 +53,10 @@ def parse():
     ap.add_argument("--momentum", type=float, default=0.0,
                     help="run the heavy-ball variant dpsgd_mix_step_momentum with this mu (two-call path; a variant "
                          "of the benchmark, flagged in the output)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="variant for comparison: the averaging W X runs on a second stream beside dpsgd_grad, then "
+                         "X = (W X) - gamma G is formed by a third pass (three existing entry points, 8 + 12 bytes per "
+                         "(worker, parameter) instead of the mix kernel's 12); not the benchmark's path")
     ap.add_argument("--shadow", action="store_true",
                     help="dpsgd_step with the bf16_shadow option: the fused kernel leaves the bf16 rounding of the new "
                          "hidden-layer weights for the next iteration's forward and data gradient (same results; the "
@@ -239,15 +243,41 @@ def main():
                 fused_weights += w_in * w_out
                 if args.shadow and ring_ok and l >= 1:
                     shadow_weights += w_in * w_out
-    fused = fused_weights > 0 and not args.two_call and not args.momentum
+    fused = fused_weights > 0 and not args.two_call and not args.momentum and not args.overlap
     Vel = torch.zeros_like(X) if args.momentum else None
     if args.momentum:
         variant = (variant + "; " if variant else "") + f"heavy-ball momentum {args.momentum} (not the benchmark's update)"
+
+    if args.overlap:
+        # Algorithm 1 steps 3 and 4 do not depend on each other: W X on a side stream while the gradient runs, then
+        # the update X = (W X) - gamma G as a mix with the identity for W.  The averaging context has gamma = 0 and
+        # is handed X itself as its "gradient", so that pass reads nothing beyond X (the second read of a row hits
+        # in cache).
+        variant = (variant + "; " if variant else "") + \
+            "gradient and averaging on two streams, update as a third pass (comparison only)"
+        main_stream, side_stream = torch.cuda.current_stream(), torch.cuda.Stream()
+        Xavg = torch.zeros_like(X)
+        ctx_avg = B.Dpsgd(cfg.n, d, topo, 0.0, ld=ld, stream=side_stream)
+        ident = B.Topology.csr(np.arange(cfg.n + 1, dtype=np.int32), np.arange(cfg.n, dtype=np.int32),
+                               np.ones(cfg.n, dtype=np.float32))
+        ctx_upd = B.Dpsgd(cfg.n, d, ident, cfg.gamma, ld=ld)
 
     def step(k, ev=None):
         inp_d, tgt_d = pool[k % len(pool)]
         if fused:
             ctx.step(model, X, inp_d, tgt_d, cfg.batch, G, loss, cons, input_is_bf16=cfg.bf16)
+            return
+        if args.overlap:
+            side_stream.wait_stream(main_stream)
+            with torch.cuda.stream(side_stream):
+                ctx_avg.mix_step(X, X, Xavg, None)
+            ctx.grad(model, X, inp_d, tgt_d, cfg.batch, G, loss, input_is_bf16=cfg.bf16)
+            main_stream.wait_stream(side_stream)
+            if ev is not None:
+                ev[0].record()
+            ctx_upd.mix_step(Xavg, G, X, cons)
+            if ev is not None:
+                ev[1].record()
             return
         ctx.grad(model, X, inp_d, tgt_d, cfg.batch, G, loss, input_is_bf16=cfg.bf16)
         if ev is not None:
@@ -284,7 +314,8 @@ def main():
         launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / launches
         mix_ms = fused_ms / K
     else:
-        kernel_name = "mix_step (Algorithm 1 steps 4-5 fused)"
+        kernel_name = "update pass X = (W X) - gamma G (identity as W)" if args.overlap else \
+            "mix_step (Algorithm 1 steps 4-5 fused)"
         mix_ms = sum(a.elapsed_time(b) for a, b in evs) / K
         launch_ms = mix_ms
         launch_bytes = (20.0 if Vel is not None else 12.0) * cfg.n * d
@@ -317,6 +348,9 @@ def main():
     final_loss = float(loss.mean().item())
     final_cons = None if cons is None else float(cons.item())
     ctx.close()
+    if args.overlap:
+        ctx_avg.close()
+        ctx_upd.close()
 
     achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
     eager_ms = total_ms
@@ -334,7 +368,8 @@ def main():
         "config": {"workload": cfg.name, "model_kind": int(cfg.model_kind), "widths": list(cfg.widths), "n": cfg.n,
                    "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "gamma": cfg.gamma,
                    "minibatch_pool": len(pool), "consensus": cons is not None,
-                   "path": "dpsgd_step" if fused else ("dpsgd_grad + dpsgd_mix_step_momentum" if Vel is not None
+                   "path": "dpsgd_step" if fused else "dpsgd_grad beside dpsgd_mix_step, then dpsgd_mix_step" if args.overlap
+                   else ("dpsgd_grad + dpsgd_mix_step_momentum" if Vel is not None
                                                            else "dpsgd_grad + dpsgd_mix_step"),
                    **({"launch": f"one HIP graph of {K} iterations, one replay timed",
                        "eager_ms_per_step": eager_ms / K} if graph_ms is not None else {}),
