@@ -233,6 +233,7 @@ def main():
         ctx.set_option("bf16_shadow", 1)
     # layers whose weight gradient dpsgd_step forms inside the mix kernel (same rule as the library)
     fused_weights = 0
+    rows_kernel = []     # per fused ring layer: does the [16 rows][1 KB] kernel take it (same rule as the library)
     shadow_weights = 0   # of those, the hidden-layer weights whose bf16 copy the fused kernel also writes (--shadow)
     ring_ok = cfg.topology == "ring" and cfg.n >= 3
     torus_ok = cfg.topology == "torus" and 3 <= cfg.torus_dims[1] <= 8 and cfg.torus_dims[0] >= 3
@@ -241,6 +242,7 @@ def main():
             w_in, w_out = cfg.widths[l], cfg.widths[l + 1]
             if w_in % (128 if ring_ok else 32) == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
                 fused_weights += w_in * w_out
+                rows_kernel.append(ring_ok and cfg.batch <= 32 and w_in % 256 == 0 and not args.shadow)
                 if args.shadow and ring_ok and l >= 1:
                     shadow_weights += w_in * w_out
     fused = fused_weights > 0 and not args.two_call and not args.momentum and not args.overlap
@@ -308,7 +310,9 @@ def main():
     total_ms = t_begin.elapsed_time(t_end)
     if fused:
         fused_ms, launches = ctx.read_timing()
-        kernel_name = ("mlp_fused_ring_kernel" if ring_ok else "mlp_fused_torus_cols_kernel") + \
+        ring_name = "mlp_fused_ring_rows_kernel" if all(rows_kernel) else "mlp_fused_ring_kernel" if not any(rows_kernel) \
+            else "mlp_fused_ring_rows_kernel / mlp_fused_ring_kernel"
+        kernel_name = (ring_name if ring_ok else "mlp_fused_torus_cols_kernel") + \
             " (weight gradient + Algorithm 1 steps 4-5, in place)"
         launch_ms = fused_ms / launches
         launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / launches

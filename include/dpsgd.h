@@ -141,12 +141,17 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * kernel even for ring / torus tags), "mix_narrow" (1: the ring kernel with one float4 per lane also for wide
  * matrices, where the default gives a lane eight), "torus_window" (1: dpsgd_step on a torus with 8 columns uses the kernel
  * that keeps three grid rows of tiles in one wave's registers instead of one wave per grid column),
+ * "ring_rows" (default 1: dpsgd_step on the ring, bf16 MLP, minibatch of at most 32 rows: layers whose input width is
+ * a multiple of 256 use the kernel whose workgroups own [16 rows][1 KB] of the weight matrix, each wave whole 1 KB
+ * row pieces; 0: the kernel with 32 x 32 tiles per wave for every layer.  The two add up the minibatch in a different
+ * order inside the matrix instructions, so their results agree to fp32 rounding, not bit for bit),
  * "bf16_shadow" (1: dpsgd_step on the ring also leaves the bf16 rounding of the new hidden-layer weights of a bf16 MLP
  * in a buffer of the context, and the next dpsgd_step on the same X and model reads them instead of the fp32
  * weights in its forward and data-gradient kernels: the same values, half the bytes.  The caller promises that
  * between two dpsgd_step calls nobody else writes X; every dpsgd_mix_step* call, a change of this option, another
  * X or model, and calls recorded under stream capture drop the copy.  Costs 2 bytes per hidden-layer weight and
- * worker of device memory),
+ * worker of device memory.  Uses the 32 x 32 kernel for every layer, as "ring_rows" 0 does, and gives bit for bit the
+ * iterates of that setting),
  * "time_fused" (see dpsgd_read_timing). */
 dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value);
 

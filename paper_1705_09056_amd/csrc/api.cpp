@@ -309,6 +309,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
         ctx->opt_mix_narrow = value ? 1 : 0;
     } else if (k == "mix_force_csr") {
         ctx->opt_mix_force_csr = value ? 1 : 0;
+    } else if (k == "ring_rows") {
+        ctx->opt_ring_rows = value ? 1 : 0;
     } else if (k == "torus_window") {
         ctx->opt_torus_window = value ? 1 : 0;
     } else if (k == "bf16_shadow") {

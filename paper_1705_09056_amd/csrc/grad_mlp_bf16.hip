@@ -33,6 +33,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KC = 64;        // contraction elements staged per step
 constexpr int PITCH = KC + 8; // LDS row pitch in bf16 elements (144 B: 16 B aligned, spreads banks)
@@ -1001,6 +1002,132 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_kernel(FusedArgs a)
     }
 }
 
+// The same pass for minibatches of at most 32 rows with a workgroup tile of [16 rows][1 KB]: every load and store
+// instruction of a wave covers 1 KB of one row of the weight matrix (the 32 x 32 layout above touches 128-byte
+// pieces of two rows), which streams ~10 % faster from HBM.  Wave wv owns rows o0 + 4 wv .. + 3 and all 256 columns,
+// lane l the four columns k0 + 4 l .. + 3.  The gradient of that [4][256] strip comes from v_mfma_f32_4x4x4_16B_bf16:
+// 16 independent 4 x 4 blocks, block l / 4 taking row l % 4 of A from lane l and column l % 4 of B, so with the same
+// four rows of dZ^T in every block and tile t handing column 4 l + t of the activations to lane l, register r of
+// tile t is the gradient at (row r, column 4 l + t): the four tiles are the four components of the lane's float4.
+// A strip that thin reuses nothing, so the operands go through LDS: per worker the 256 activation columns x 32
+// samples (16 KB, one consecutive block of the T copy) and the 16 dZ rows, fetched one worker ahead into registers
+// and written to the other of two buffers; one barrier per worker.  grid (K / 256, O / 16), block 256.
+constexpr int ROWS_PLANE = 65;   // 16-byte units per (tile, sample octet) plane of the activation buffer: 64 lanes + 1 of padding
+
+template <bool CONS>
+__global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a)
+{
+    __shared__ u32x4 bt[2][16 * ROWS_PLANE];   // [tile t][octet][lane]: samples 8 octet .. + 7 of column 4 lane + t
+    __shared__ u32x4 at[2][64];                // [octet][row 0..15] of dZ^T
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int k0 = blockIdx.x * 256, o0 = blockIdx.y * 16;
+    // element (r, t) of this lane: row o0 + 4 wave + r, column k0 + 4 lane + t
+    float *xt = a.X + a.woff + (i64)(o0 + 4 * wave) * a.K + k0 + 4 * lane;
+    auto load_tile = [&](const float *p, i64 rs, float (&x)[16]) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p + r * rs));
+            x[4 * r] = v.x; x[4 * r + 1] = v.y; x[4 * r + 2] = v.z; x[4 * r + 3] = v.w;
+        }
+    };
+    // operands in fragment order (tfrag_off) with Bp = 32: per 32 rows [sample group of 16][half][row][8 samples].
+    // Activations: the block of columns k0 .. k0 + 255 is 1024 consecutive 16-byte units; unit u = tid + 256 q is
+    // column (u / 128) * 32 + u % 32, octet (u / 32) % 4, and goes to plane (column % 4, octet), slot column / 4.
+    const u32x4 *bsrc = reinterpret_cast<const u32x4 *>(a.at + (i64)(k0 >> 5) * 1024) + tid;
+    const int bslot = ((tid & 3) * 4 + ((tid >> 5) & 3)) * ROWS_PLANE + (tid >> 7) * 8 + ((tid & 31) >> 2);
+    // dZ^T: lane (octet = lane / 16, row = lane % 16) of every wave fetches one unit; wave 0 writes them
+    const int aoc = lane >> 4;
+    const u32x4 *asrc = reinterpret_cast<const u32x4 *>(
+        a.dzt + ((i64)(o0 >> 5) * 2 + (aoc >> 1)) * 512 + (aoc & 1) * 256 + ((o0 & 31) + (lane & 15)) * 8);
+    const i64 b_worker = (i64)a.K * 4, a_worker = (i64)a.O * 4;   // 16-byte units per worker (32 samples x 2 bytes)
+    u32x4 breg[4], areg;
+    auto fetch_ops = [&](int worker) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) breg[q] = bsrc[worker * b_worker + 256 * q];
+        areg = asrc[worker * a_worker];
+    };
+    auto stage_ops = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bt[buf][bslot + 16 * q] = breg[q];
+        if (wave == 0) at[buf][lane] = areg;
+    };
+
+    float xm[16], xc[16], xh[16], xn[16], xf[16], s1[16], s2[4] = {0.f, 0.f, 0.f, 0.f};
+    fetch_ops(0);
+    load_tile(xt + (i64)(a.n - 1) * a.ld, a.K, xm);
+    load_tile(xt, a.K, xc);
+    load_tile(xt + (i64)(1 % a.n) * a.ld, a.K, xn);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        xh[v] = xc[v];
+        s1[v] = 0.f;
+    }
+    stage_ops(0);
+    __syncthreads();
+    for (int i = 0; i < a.n; ++i) {
+        const int buf = i & 1;
+        // both fetches are unconditional (exact wait counts): past the last worker the operand fetch repeats the last
+        // worker's and the tile fetch reads one cached line of the operand array (values never used); the operands
+        // are issued first so that they can be waited for without waiting for the tile
+        fetch_ops(i + 1 < a.n ? i + 1 : i);
+        {
+            const bool far = i + 2 < a.n;
+            const float *src = far ? xt + (i64)(i + 2) * a.ld : reinterpret_cast<const float *>(a.dzt) + 4 * lane;
+            load_tile(src, far ? (i64)a.K : 0, xf);
+        }
+        f32x4 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+        for (int oc = 0; oc < 4; ++oc) {
+            const u32x4 av = at[buf][oc * 16 + 4 * wave + (lane & 3)];
+            const s16x4 alo = __builtin_bit_cast(s16x4, u32x2{av.x, av.y}), ahi = __builtin_bit_cast(s16x4, u32x2{av.z, av.w});
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const u32x4 bv = bt[buf][(t * 4 + oc) * ROWS_PLANE + lane];
+                acc[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, __builtin_bit_cast(s16x4, u32x2{bv.x, bv.y}), acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi, __builtin_bit_cast(s16x4, u32x2{bv.z, bv.w}), acc[t], 0, 0, 0);
+            }
+        }
+        const bool last = i + 1 == a.n;
+        float *dst = xt + (i64)i * a.ld;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            f32x4 out;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int v = 4 * r + t;
+                const float nxt = last ? xh[v] : xn[v];   // the ring closes on worker 0's original tile
+                float mix = a.w * xm[v];
+                mix = a.w * xc[v] + mix;
+                mix = a.w * nxt + mix;
+                const float o = mix - a.gamma * acc[t][r];
+                out[t] = o;
+                if (CONS) {
+                    const float e = o - xh[v];
+                    s1[v] += e;
+                    s2[t] += e * e;
+                }
+                xm[v] = xc[v];
+                xc[v] = nxt;
+                xn[v] = xf[v];
+            }
+            __builtin_nontemporal_store(out, reinterpret_cast<f32x4 *>(dst + (i64)r * a.K));
+        }
+        stage_ops(buf ^ 1);   // every wave has read this buffer's previous contents before the barrier that ended step i - 1
+        __syncthreads();
+    }
+    if (CONS) {
+        float m2 = (s2[0] + s2[1]) + (s2[2] + s2[3]);
+        const float inv_n = 1.0f / (float)a.n;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m2 -= s1[v] * s1[v] * inv_n;
+        double t = (double)m2;
+        for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
+        if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = t;
+    }
+}
+
 // ------------------------------------------- the same fusion on a 2-D torus with 8 columns
 // Worker (r, c) = r * 8 + c averages itself, (r +- 1, c) and (r, c +- 1) with weight w (indices modulo the grid).
 // A wave owns a 16 x 16 tile of the weight matrix for ALL workers and walks the grid row by row with the
@@ -1480,7 +1607,13 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             np = (i64)grid.x * grid.y * 4;
             if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
             fa.shadow = wb_emit[l];
-            if (fa.shadow) {
+            const bool rows = ctx->opt_ring_rows && !ctx->opt_bf16_shadow && Bp == 32 && (K % 256) == 0 && (O % 32) == 0 &&
+                              (woff[l] % 4) == 0 && base_ok;
+            if (rows) {   // same number of workgroups and of partial sums as the 32 x 32 kernel
+                dim3 grid_rows((unsigned)(K / 256), (unsigned)(O / 16));
+                if (cons) hipLaunchKernelGGL(mlp_fused_ring_rows_kernel<true>, grid_rows, dim3(256), 0, s, fa);
+                else hipLaunchKernelGGL(mlp_fused_ring_rows_kernel<false>, grid_rows, dim3(256), 0, s, fa);
+            } else if (fa.shadow) {
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, true>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, true>), grid, dim3(256), 0, s, fa);
             } else {

@@ -230,6 +230,46 @@ def test_two_contexts_on_two_streams_do_not_share_state():
         assert ca == cb
 
 
+@pytest.mark.parametrize("widths,batch,n", [
+    ((1024, 1024, 10), 32, 5),        # 4 x 64 workgroups per layer, odd ring
+    ((2048, 512, 4096, 10), 20, 3),   # ragged minibatch (padded to 32), the smallest ring, K = 2048 and 512
+    ((1280, 2080, 10), 32, 4),        # 65 row groups of 32 and 5 column blocks
+])
+def test_row_layout_ring_kernel_agrees_with_the_tile_layout_one(widths, batch, n):
+    """Minibatches of at most 32 rows take the [16 rows][1 KB] kernel where K % 256 == 0; "ring_rows" 0 forces the
+    32 x 32 one.  The two sum the minibatch in a different order inside the MFMA (4 samples at a time against 16),
+    so they agree to fp32 rounding of the gradient, not bit for bit."""
+    cfg = shrink(CONFIGS[3], widths=widths, batch=batch, n=n, iters=2)
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    ld = synth.padded_stride(d)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    X0 = to_dev(synth.make_replicas(cfg), ld)
+    runs = []
+    for rows in (0, 1):
+        X = X0.clone()
+        G = torch.zeros_like(X)
+        loss = torch.zeros(cfg.iters, cfg.n, device="cuda")
+        cons = torch.zeros(cfg.iters, device="cuda")
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("ring_rows", rows)
+            for k in range(cfg.iters):
+                inp, tgt = synth.make_batch(cfg, k)
+                ctx.step(model, X, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, G, loss[k], cons[k:k + 1],
+                         input_is_bf16=True)
+            torch.cuda.synchronize()
+        runs.append((X, loss, cons))
+    (Xa, la, ca), (Xb, lb, cb) = runs
+    print(f"rows vs tiles {widths} B={batch} n={n}: max |dX| {float((Xa - Xb).abs().max()):.3e}, "
+          f"bit-identical {bool(torch.equal(Xa, Xb))}, consensus {ca.tolist()} {cb.tolist()}", flush=True)
+    assert not torch.equal(Xa, X0)
+    # one step moves an element by gamma * g; the two gradients differ by a few ulp of their own size
+    step = float((Xa - X0).abs().max())
+    assert float((Xa - Xb).abs().max()) <= 1e-5 * step + 1e-7
+    assert torch.allclose(la, lb, rtol=1e-5, atol=1e-6)
+    assert torch.allclose(ca, cb, rtol=1e-5, atol=0.0)
+    assert bool(torch.all(Xb[:, d:] == X0[:, d:]))     # padding columns untouched
+
+
 @pytest.mark.parametrize("widths,batch", [
     ((1024, 1024, 1024, 10), 32),     # one hidden layer with a copy, read by the forward and the data gradient
     ((1024, 1024, 1152, 1024, 10), 32),   # two of them, 36 and 32 output tiles
@@ -249,6 +289,7 @@ def test_bf16_shadow_option_on_other_shapes(widths, batch):
         loss = torch.zeros(cfg.iters, cfg.n, device="cuda")
         with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
             ctx.set_option("bf16_shadow", shadow)
+            ctx.set_option("ring_rows", 0)     # the option keeps to the 32 x 32 kernel; compare like with like
             for k in range(cfg.iters):
                 inp, tgt = synth.make_batch(cfg, k)
                 ctx.step(model, X, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, G, loss[k], None,
@@ -282,6 +323,7 @@ def test_bf16_shadow_option_gives_the_same_trajectory_and_is_dropped_when_x_chan
         snaps = []
         with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
             ctx.set_option("bf16_shadow", 1 if shadow else 0)
+            ctx.set_option("ring_rows", 0)     # the option keeps to the 32 x 32 kernel; compare like with like
             for k, (inp_d, tgt_d) in enumerate(batches):
                 ctx.step(model, Xa, inp_d, tgt_d, cfg.batch, G, loss[k], cons[k:k + 1], input_is_bf16=True)
                 snaps.append(Xa.clone())
