@@ -63,6 +63,7 @@ struct dpsgd_ctx {
     const float *shadow_X = nullptr;
     dpsgd_model_desc shadow_model;
     std::vector<int64_t> shadow_off;   // per layer: element offset of its [n][O][K] block, or -1
+    std::vector<char> shadow_strips;   // per layer: the block is in [16][256] tiles (written by the ring kernel with 1 KB rows), not 32 x 32
 
     // gradient workspace (activations, bf16 operand copies), owned by the context
     void *ws = nullptr;

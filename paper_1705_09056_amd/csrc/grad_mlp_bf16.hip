@@ -72,6 +72,12 @@ __device__ __forceinline__ i64 tfrag_worker(int w, int rows, int Bp) { return (i
 // fused kernel writes a wave's tile as 2 KB of consecutive memory (whole cache lines per store instruction), and
 // the forward / data-gradient kernels read the tiles of their [64][128] blocks as runs of 8 KB.
 __device__ __forceinline__ i64 shadow_tile(int o, int k, int K) { return ((i64)(o >> 5) * (K >> 5) + (k >> 5)) * 1024; }
+// Copies written by the [16 rows][1 KB] fused kernel (K % 256 == 0) are stored in its own tiles instead, [O/16][K/256][16][256]:
+// a wave's store of one row is 512 consecutive bytes, and a reader's 128-wide piece of a row 256.
+__device__ __forceinline__ i64 shadow_strip(int o, int k, int K)
+{
+    return ((i64)(o >> 4) * (K >> 8) + (k >> 8)) * 4096 + (o & 15) * 256 + (k & 255);
+}
 
 // Workgroups are dealt to the 8 XCDs round-robin by linear id and every XCD has its own L2.  For a grid
 // (tiles, 1, n) with n a multiple of 8 the ids are renumbered so that all tiles of a worker run on one XCD and
@@ -161,7 +167,8 @@ struct FwdArgs {
     bf16_t *h;             // [n][B][O]   (hidden layers)
     bf16_t *ht;            // T copy of h (hidden layers)
     float *z;              // [n][B][O]   (last layer, fp32 logits)
-    const bf16_t *wb;      // bf16 copy of the weights (32 x 32 tiles, see shadow_tile) left by the previous fused step, or null
+    const bf16_t *wb;      // bf16 copy of the weights left by the previous fused step, or null
+    int wb_strips;         // its layout: 0 = 32 x 32 tiles (shadow_tile), 1 = [16][256] tiles (shadow_strip)
 };
 
 // Epilogue of one 32 x 32 accumulator tile of the forward product: lane owns output column o and the 16 rows
@@ -342,21 +349,34 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
     f32x4 wreg[WB16 ? 1 : WQ];
     u32x4 breg0[WB16 ? BQ : 1];
     u32x4 areg[AQ];
-    // already rounded weights: 8 tiles of 2 KB (O % 64 == 0 and K % 128 == 0 hold), 128 threads per tile
+    // already rounded weights (O % 64 == 0 and K % 128 == 0 hold): 16-byte unit u of the [64][128] block is, in the
+    // 32 x 32-tile layout, unit u % 128 of tile u / 128 (8 tiles of 2 KB); in the [16][256] layout, 8 columns of row u / 16
+    auto unit_w16 = [&](int u, int &row, int &kq) {
+        if (g.wb_strips) {
+            row = u >> 4;
+            kq = (u & 15) * 8;
+        } else {
+            const int t = u >> 7, within = u & 127;
+            row = (t >> 2) * 32 + (within >> 2);
+            kq = (t & 3) * 32 + (within & 3) * 8;
+        }
+    };
     auto fetch_w16 = [&](int k0, u32x4 (&br)[WB16 ? BQ : 1]) {
 #pragma unroll
         for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
-            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
-            br[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
-                Wb16 + shadow_tile(o0 + (t >> 2) * 32, k0 + (t & 3) * 32, g.K) + within * 8));
+            int row, kq;
+            unit_w16(tid + 256 * q, row, kq);
+            const i64 off = g.wb_strips ? shadow_strip(o0 + row, k0 + kq, g.K)
+                                        : shadow_tile(o0 + row, k0 + kq, g.K) + (row & 31) * 32 + (kq & 31);
+            br[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Wb16 + off));
         }
     };
     auto stage_w16 = [&](int buf, const u32x4 (&br)[WB16 ? BQ : 1]) {
         bf16_t *Wb = Wt + buf * TO * PITCH2;
 #pragma unroll
         for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
-            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
-            const int row = (t >> 2) * 32 + (within >> 2), kq = (t & 3) * 32 + (within & 3) * 8;
+            int row, kq;
+            unit_w16(tid + 256 * q, row, kq);
             *reinterpret_cast<u32x4 *>(Wb + row * PITCH2 + kq) = br[q];
         }
     };
@@ -631,7 +651,8 @@ struct DgradArgs {
     bf16_t *dzp;          // [n][B][K]
     bf16_t *dzpt;         // T copy of dzp
     int B, Bp, K, O;
-    const bf16_t *wb;     // bf16 copy of the weights (32 x 32 tiles, see shadow_tile) left by the previous fused step, or null
+    const bf16_t *wb;     // bf16 copy of the weights left by the previous fused step, or null
+    int wb_strips;        // its layout: 0 = 32 x 32 tiles (shadow_tile), 1 = [16][256] tiles (shadow_strip)
 };
 
 // grid (ceil(K / (32 WN)), ceil(B / (32 WM MT)), n), block 256.
@@ -659,21 +680,35 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
     f32x4 wreg[WB16 ? 1 : WQ];
     u32x4 breg0[WB16 ? BQ : 1];
     u32x4 dreg[DQ];
-    // already rounded weights: 2 x TK / 32 tiles of 2 KB (O % 64 == 0 and K % TK == 0 hold), 128 threads per tile
+    // already rounded weights (O % 64 == 0 and K % TK == 0 hold): 16-byte unit u of the [64][TK] block is, in the
+    // 32 x 32-tile layout, unit u % 128 of tile u / 128 (2 x TK / 32 tiles of 2 KB); in the [16][256] layout, 8 columns
+    // of row u / (TK / 8)
+    auto unit_w16 = [&](int u, int &orow, int &kq) {
+        if (g.wb_strips) {
+            orow = u / (TK / 8);
+            kq = (u % (TK / 8)) * 8;
+        } else {
+            const int t = u >> 7, within = u & 127;
+            orow = (t / (TK / 32)) * 32 + (within >> 2);
+            kq = (t % (TK / 32)) * 32 + (within & 3) * 8;
+        }
+    };
     auto fetch_w16 = [&](int oc, u32x4 (&br)[WB16 ? BQ : 1]) {
 #pragma unroll
         for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
-            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
-            br[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
-                Wb16 + shadow_tile(oc + (t / (TK / 32)) * 32, kt0 + (t % (TK / 32)) * 32, g.K) + within * 8));
+            int orow, kq;
+            unit_w16(tid + 256 * q, orow, kq);
+            const i64 off = g.wb_strips ? shadow_strip(oc + orow, kt0 + kq, g.K)
+                                        : shadow_tile(oc + orow, kt0 + kq, g.K) + (orow & 31) * 32 + (kq & 31);
+            br[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(Wb16 + off));
         }
     };
     auto stage_w16 = [&](int buf, const u32x4 (&br)[WB16 ? BQ : 1]) {
         bf16_t *Wb = Wt + buf * KC * WP;
 #pragma unroll
         for (int q = 0; q < (WB16 ? BQ : 0); ++q) {
-            const int u = tid + 256 * q, t = u >> 7, within = u & 127;
-            const int orow = (t / (TK / 32)) * 32 + (within >> 2), kq = (t % (TK / 32)) * 32 + (within & 3) * 8;
+            int orow, kq;
+            unit_w16(tid + 256 * q, orow, kq);
             *reinterpret_cast<u32x4 *>(Wb + orow * WP + kq) = br[q];
         }
     };
@@ -1014,7 +1049,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_kernel(FusedArgs a)
 // and written to the other of two buffers; one barrier per worker.  grid (K / 256, O / 16), block 256.
 constexpr int ROWS_PLANE = 65;   // 16-byte units per (tile, sample octet) plane of the activation buffer: 64 lanes + 1 of padding
 
-template <bool CONS>
+template <bool CONS, bool SHADOW>
 __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a)
 {
     __shared__ u32x4 bt[2][16 * ROWS_PLANE];   // [tile t][octet][lane]: samples 8 octet .. + 7 of column 4 lane + t
@@ -1091,6 +1126,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
         }
         const bool last = i + 1 == a.n;
         float *dst = xt + (i64)i * a.ld;
+        bf16_t *sdst = SHADOW ? a.shadow + (i64)i * a.O * a.K + shadow_strip(o0 + 4 * wave, k0 + 4 * lane, a.K) : nullptr;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             f32x4 out;
@@ -1113,6 +1149,10 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
                 xn[v] = xf[v];
             }
             __builtin_nontemporal_store(out, reinterpret_cast<f32x4 *>(dst + (i64)r * a.K));
+            if (SHADOW) {   // the lane's four columns of the row, 8 bytes; the wave's row piece is 512 consecutive bytes
+                const u32x2 pk = {pack2(out.x, out.y), pack2(out.z, out.w)};
+                __builtin_nontemporal_store(pk, reinterpret_cast<u32x2 *>(sdst + r * 256));
+            }
         }
         stage_ops(buf ^ 1);   // every wave has read this buffer's previous contents before the barrier that ended step i - 1
         __syncthreads();
@@ -1477,9 +1517,17 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
     // (a recorded call could not know what the buffer holds when it is replayed).
     std::vector<const bf16_t *> wb_use(L, nullptr);
     std::vector<bf16_t *> wb_emit(L, nullptr);
+    const bool base_ok = aligned16(X) && (ctx->ld % 4) == 0;
+    // layers the [16 rows][1 KB] ring kernel takes; a copy it writes is in its own tile layout, and a reader is told
+    // the layout the copy was written in (the minibatch, hence the kernel, may differ between the two calls)
+    std::vector<char> rows_kernel(L, 0), strips_use(L, 0);
+    for (int l = 0; l < L; ++l)
+        rows_kernel[l] = ctx->ring_uniform && ctx->opt_ring_rows && Bp == 32 && (m.widths[l] % 256) == 0 &&
+                         (m.widths[l + 1] % 32) == 0 && (woff[l] % 4) == 0 && base_ok;
     if (fuse) {
         const bool was_valid = ctx->shadow_valid && ctx->shadow_X == X && ctx->shadow_model.kind == m.kind &&
-                               ctx->shadow_model.widths == m.widths && (int)ctx->shadow_off.size() == L;
+                               ctx->shadow_model.widths == m.widths && (int)ctx->shadow_off.size() == L &&
+                               (int)ctx->shadow_strips.size() == L;
         ctx->shadow_valid = false;
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(s, &cap) != hipSuccess) cap = hipStreamCaptureStatusNone;
@@ -1503,11 +1551,15 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
                 ctx->shadow_bytes = elems * sizeof(bf16_t);
             } else if (was_valid && soff == ctx->shadow_off) {
                 for (int l = 1; l < L; ++l)
-                    if (soff[l] >= 0) wb_use[l] = (const bf16_t *)ctx->shadow + soff[l];
+                    if (soff[l] >= 0) {
+                        wb_use[l] = (const bf16_t *)ctx->shadow + soff[l];
+                        strips_use[l] = ctx->shadow_strips[l];
+                    }
             }
             for (int l = 1; l < L; ++l)
                 if (soff[l] >= 0) wb_emit[l] = (bf16_t *)ctx->shadow + soff[l];
             ctx->shadow_off = soff;
+            ctx->shadow_strips = rows_kernel;
         }
     }
 
@@ -1523,7 +1575,6 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             hipLaunchKernelGGL(prep_input_kernel<false>, grid, dim3(256), 0, s, inputs, ws.a0, ws.at0, B, Bp, F);
     }
     const Tiling t = pick_tiling(B);
-    const bool base_ok = aligned16(X) && (ctx->ld % 4) == 0;
     dpsgd_status st = DPSGD_OK;
     for (int l = 0; l < L && st == DPSGD_OK; ++l) {
         FwdArgs a{};
@@ -1532,6 +1583,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         const bool last = (l == L - 1);
         if (last) a.z = ws.logits; else { a.h = ws.h[l + 1]; a.ht = ws.ht[l + 1]; }
         a.wb = wb_use[l];
+        a.wb_strips = strips_use[l];
         const bool vec = base_ok && (a.K % 8) == 0 && (woff[l] % 4) == 0 && aligned16(act[l]);
         if (last && vec && a.O <= 32 && (a.K % 16) == 0 && a.K >= 256) {
             hipLaunchKernelGGL(mlp_fwd_last_kernel, dim3((unsigned)((B + 31) / 32), (unsigned)n), dim3(512), 0, s, a);
@@ -1571,6 +1623,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             da.dzp = ws.dz[cur ^ 1]; da.dzpt = ws.dzt[l];
             da.B = B; da.Bp = Bp; da.K = K; da.O = O;
             da.wb = wb_use[l];
+            da.wb_strips = strips_use[l];
             const bool vec = base_ok && (K % 4) == 0 && (O % 8) == 0 && (woff[l] % 4) == 0;
             if (t.mt == 1) st = dgrad_launch<1, 4, 1>(s, n, da, vec);
             else if (t.wm == 1) st = dgrad_launch<1, 4, 2>(s, n, da, vec);
@@ -1607,12 +1660,15 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             np = (i64)grid.x * grid.y * 4;
             if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
             fa.shadow = wb_emit[l];
-            const bool rows = ctx->opt_ring_rows && !ctx->opt_bf16_shadow && Bp == 32 && (K % 256) == 0 && (O % 32) == 0 &&
-                              (woff[l] % 4) == 0 && base_ok;
-            if (rows) {   // same number of workgroups and of partial sums as the 32 x 32 kernel
+            if (rows_kernel[l]) {   // same number of workgroups and of partial sums as the 32 x 32 kernel
                 dim3 grid_rows((unsigned)(K / 256), (unsigned)(O / 16));
-                if (cons) hipLaunchKernelGGL(mlp_fused_ring_rows_kernel<true>, grid_rows, dim3(256), 0, s, fa);
-                else hipLaunchKernelGGL(mlp_fused_ring_rows_kernel<false>, grid_rows, dim3(256), 0, s, fa);
+                if (fa.shadow) {
+                    if (cons) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<true, true>), grid_rows, dim3(256), 0, s, fa);
+                    else hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<false, true>), grid_rows, dim3(256), 0, s, fa);
+                } else {
+                    if (cons) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<true, false>), grid_rows, dim3(256), 0, s, fa);
+                    else hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<false, false>), grid_rows, dim3(256), 0, s, fa);
+                }
             } else if (fa.shadow) {
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, true>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, true>), grid, dim3(256), 0, s, fa);

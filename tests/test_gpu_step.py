@@ -276,7 +276,8 @@ def test_row_layout_ring_kernel_agrees_with_the_tile_layout_one(widths, batch, n
     ((1024, 1024, 1120, 10), 32),     # 35 output tiles: written, but the readers want multiples of 64 and use fp32
     ((1024, 1024, 1024, 10), 64),     # minibatch 64: the forward of that tiling reads fp32, the data gradient the copy
 ])
-def test_bf16_shadow_option_on_other_shapes(widths, batch):
+@pytest.mark.parametrize("ring_rows", [1, 0])
+def test_bf16_shadow_option_on_other_shapes(widths, batch, ring_rows):
     cfg = shrink(CONFIGS[3], widths=widths, batch=batch, n=4, iters=3)
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = synth.padded_stride(d)
@@ -289,7 +290,7 @@ def test_bf16_shadow_option_on_other_shapes(widths, batch):
         loss = torch.zeros(cfg.iters, cfg.n, device="cuda")
         with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
             ctx.set_option("bf16_shadow", shadow)
-            ctx.set_option("ring_rows", 0)     # the option keeps to the 32 x 32 kernel; compare like with like
+            ctx.set_option("ring_rows", ring_rows)     # which fused kernel writes the copy, hence its layout
             for k in range(cfg.iters):
                 inp, tgt = synth.make_batch(cfg, k)
                 ctx.step(model, X, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, G, loss[k], None,
@@ -300,7 +301,8 @@ def test_bf16_shadow_option_on_other_shapes(widths, batch):
     assert torch.equal(runs[0][1], runs[1][1])
 
 
-def test_bf16_shadow_option_gives_the_same_trajectory_and_is_dropped_when_x_changes():
+@pytest.mark.parametrize("ring_rows", [1, 0])
+def test_bf16_shadow_option_gives_the_same_trajectory_and_is_dropped_when_x_changes(ring_rows):
     """With "bf16_shadow" the fused kernel leaves the bf16 rounding of the new hidden-layer weights for the next
     call's forward and data gradient: the same values, so every iterate must be bit-identical to the run without
     the option.  A dpsgd_mix_step in between (X changes behind the copy's back), a second matrix X and a smaller
@@ -318,12 +320,12 @@ def test_bf16_shadow_option_gives_the_same_trajectory_and_is_dropped_when_x_chan
     def run(shadow):
         Xa, Xb = X0.clone(), (X0 * 1.01).contiguous()
         G = torch.zeros_like(Xa)
-        loss = torch.zeros(cfg.iters + 2, cfg.n, device="cuda")
-        cons = torch.zeros(cfg.iters + 2, device="cuda")
+        loss = torch.zeros(cfg.iters + 4, cfg.n, device="cuda")
+        cons = torch.zeros(cfg.iters + 4, device="cuda")
         snaps = []
         with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
             ctx.set_option("bf16_shadow", 1 if shadow else 0)
-            ctx.set_option("ring_rows", 0)     # the option keeps to the 32 x 32 kernel; compare like with like
+            ctx.set_option("ring_rows", ring_rows)     # which fused kernel writes the copy, hence its layout
             for k, (inp_d, tgt_d) in enumerate(batches):
                 ctx.step(model, Xa, inp_d, tgt_d, cfg.batch, G, loss[k], cons[k:k + 1], input_is_bf16=True)
                 snaps.append(Xa.clone())
@@ -342,7 +344,15 @@ def test_bf16_shadow_option_gives_the_same_trajectory_and_is_dropped_when_x_chan
             half = cfg.batch // 2
             inp_h = inp_d.view(cfg.n, cfg.batch, -1)[:, :half].contiguous()
             tgt_h = tgt_d.view(cfg.n, cfg.batch)[:, :half].contiguous()
-            ctx.step(model, Xa, inp_h, tgt_h, half, G, loss[cfg.iters + 1], cons[cfg.iters + 1:], input_is_bf16=True)
+            ctx.step(model, Xa, inp_h, tgt_h, half, G, loss[cfg.iters + 1], cons[cfg.iters + 1:cfg.iters + 2], input_is_bf16=True)
+            snaps.append(Xa.clone())
+            # a larger one: other kernels read the copy the call above left (its layout goes by the writer), and the
+            # copy they leave is read by the minibatch of 32 again
+            inp_2 = inp_d.view(cfg.n, cfg.batch, -1).repeat(1, 2, 1).contiguous()
+            tgt_2 = tgt_d.view(cfg.n, cfg.batch).repeat(1, 2).contiguous()
+            ctx.step(model, Xa, inp_2, tgt_2, 2 * cfg.batch, G, loss[cfg.iters + 2], cons[cfg.iters + 2:cfg.iters + 3], input_is_bf16=True)
+            snaps.append(Xa.clone())
+            ctx.step(model, Xa, inp_d, tgt_d, cfg.batch, G, loss[cfg.iters + 3], cons[cfg.iters + 3:cfg.iters + 4], input_is_bf16=True)
             snaps.append(Xa.clone())
             torch.cuda.synchronize()
         return snaps, loss.clone(), cons.clone()
