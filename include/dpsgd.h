@@ -150,8 +150,7 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * weights in its forward and data-gradient kernels: the same values, half the bytes.  The caller promises that
  * between two dpsgd_step calls nobody else writes X; every dpsgd_mix_step* call, a change of this option, another
  * X or model, and calls recorded under stream capture drop the copy.  Costs 2 bytes per hidden-layer weight and
- * worker of device memory.  Uses the 32 x 32 kernel for every layer, as "ring_rows" 0 does, and gives bit for bit the
- * iterates of that setting),
+ * worker of device memory.  The iterates are bit for bit those of the same "ring_rows" setting without the copy),
  * "time_fused" (see dpsgd_read_timing). */
 dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value);
 

@@ -17,10 +17,13 @@
 //                                                             streamed to G once
 //   step      the weight gradient of a large layer is formed inside the kernel that applies
 //             X <- W X - gamma G (ring, torus), so it never reaches memory; optionally the kernel also
-//             leaves the bf16 rounding of the new weights for the next forward / dgrad
+//             leaves the bf16 rounding of the new weights for the next forward / dgrad.  On the
+//             ring with minibatches <= 32 a wave moves whole 1 KB row pieces of X and takes the
+//             gradient of its [4 rows][256 columns] strip from 4 x 4 x 4 MFMA blocks
 // MFMA: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  Lane l of an A (B) operand holds row
 // (column) l%32 and the 8 consecutive k values 8*(l/32)..+7; accumulator register v of lane l is
-// element (row (v/4)*8 + (l/32)*4 + v%4, column l%32).
+// element (row (v/4)*8 + (l/32)*4 + v%4, column l%32).  (v_mfma_f32_16x16x32_bf16 on the torus and
+// v_mfma_f32_4x4x4_16B_bf16 in the 1 KB-row ring kernel: layouts at those kernels.)
 #include "grad_common.h"
 
 namespace dpsgd {
