@@ -42,7 +42,7 @@ def test_default_workload_fused_path_short_run():
     check_common(out, 3, 1)
     assert out["config"]["workload"] == "mlp3_ring64" and out["config"]["path"] == "dpsgd_step"
     assert out["dtype"] == "bf16"
-    assert "mlp_fused_ring_kernel" in out["roofline"]["kernel"]
+    assert "mlp_fused_ring_rows_kernel" in out["roofline"]["kernel"]
     assert out["roofline"]["algorithmic_bytes_per_launch"] == pytest.approx(8.0 * 64 * (3072 * 4096 + 4096 * 4096) / 2)
     assert out["roofline"]["traffic"] is not None and out["roofline"]["traffic"] >= out["roofline"]["algorithmic_bytes_per_launch"]
 
