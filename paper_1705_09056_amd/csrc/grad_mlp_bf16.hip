@@ -1050,12 +1050,12 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_kernel(FusedArgs a)
 // A strip that thin reuses nothing, so the operands go through LDS: per worker the 256 activation columns x 32
 // samples (16 KB, one consecutive block of the T copy) and the 16 dZ rows, fetched one worker ahead into registers
 // and written to the other of two buffers; one barrier per worker.  grid (K / 256, O / 16), block 256.
-constexpr int ROWS_PLANE = 65;   // 16-byte units per (tile, sample octet) plane of the activation buffer: 64 lanes + 1 of padding
+constexpr int ROWS_PLANE = 66;   // 16-byte units per (sample octet, tile) plane of the activation buffer: 64 lanes + 2 of padding
 
 template <bool CONS, bool SHADOW>
 __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a)
 {
-    __shared__ u32x4 bt[2][16 * ROWS_PLANE];   // [tile t][octet][lane]: samples 8 octet .. + 7 of column 4 lane + t
+    __shared__ u32x4 bt[2][16 * ROWS_PLANE];   // [octet][tile t][lane]: samples 8 octet .. + 7 of column 4 lane + t
     __shared__ u32x4 at[2][64];                // [octet][row 0..15] of dZ^T
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int k0 = blockIdx.x * 256, o0 = blockIdx.y * 16;
@@ -1072,7 +1072,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
     // Activations: the block of columns k0 .. k0 + 255 is 1024 consecutive 16-byte units; unit u = tid + 256 q is
     // column (u / 128) * 32 + u % 32, octet (u / 32) % 4, and goes to plane (column % 4, octet), slot column / 4.
     const u32x4 *bsrc = reinterpret_cast<const u32x4 *>(a.at + (i64)(k0 >> 5) * 1024) + tid;
-    const int bslot = ((tid & 3) * 4 + ((tid >> 5) & 3)) * ROWS_PLANE + (tid >> 7) * 8 + ((tid & 31) >> 2);
+    const int bslot = (((tid >> 5) & 3) * 4 + (tid & 3)) * ROWS_PLANE + (tid >> 7) * 8 + ((tid & 31) >> 2);
     // dZ^T: lane (octet = lane / 16, row = lane % 16) of every wave fetches one unit; wave 0 writes them
     const int aoc = lane >> 4;
     const u32x4 *asrc = reinterpret_cast<const u32x4 *>(
@@ -1122,7 +1122,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
             const s16x4 alo = __builtin_bit_cast(s16x4, u32x2{av.x, av.y}), ahi = __builtin_bit_cast(s16x4, u32x2{av.z, av.w});
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const u32x4 bv = bt[buf][(t * 4 + oc) * ROWS_PLANE + lane];
+                const u32x4 bv = bt[buf][(oc * 4 + t) * ROWS_PLANE + lane];
                 acc[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, __builtin_bit_cast(s16x4, u32x2{bv.x, bv.y}), acc[t], 0, 0, 0);
                 acc[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi, __builtin_bit_cast(s16x4, u32x2{bv.z, bv.w}), acc[t], 0, 0, 0);
             }
