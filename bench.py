@@ -57,6 +57,8 @@ def parse():
                     help="variant for comparison: the averaging W X runs on a second stream beside dpsgd_grad, then "
                          "X = (W X) - gamma G is formed by a third pass (three existing entry points, 8 + 12 bytes per "
                          "(worker, parameter) instead of the mix kernel's 12); not the benchmark's path")
+    ap.add_argument("--ring-rows", type=int, default=-1,
+                    help="set the library's ring_rows option (see include/dpsgd.h); -1 leaves the default")
     ap.add_argument("--shadow", action="store_true",
                     help="dpsgd_step with the bf16_shadow option: the fused kernel leaves the bf16 rounding of the new "
                          "hidden-layer weights for the next iteration's forward and data gradient (same results; the "
@@ -231,6 +233,9 @@ def main():
     ctx = B.Dpsgd(cfg.n, d, topo, cfg.gamma, ld=ld)
     if args.shadow:
         ctx.set_option("bf16_shadow", 1)
+    if args.ring_rows >= 0:
+        ctx.set_option("ring_rows", args.ring_rows)
+        variant = (variant + "; " if variant else "") + f"ring_rows={args.ring_rows}"
     # layers whose weight gradient dpsgd_step forms inside the mix kernel (same rule as the library)
     fused_weights = 0
     rows_kernel = []     # per fused ring layer: does the [16 rows][1 KB] kernel take it (same rule as the library)
