@@ -1070,7 +1070,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
     };
     // operands in fragment order (tfrag_off) with Bp = 32: per 32 rows [sample group of 16][half][row][8 samples].
     // Activations: the block of columns k0 .. k0 + 255 is 1024 consecutive 16-byte units; unit u = tid + 256 q is
-    // column (u / 128) * 32 + u % 32, octet (u / 32) % 4, and goes to plane (column % 4, octet), slot column / 4.
+    // column (u / 128) * 32 + u % 32, octet (u / 32) % 4, and goes to plane (octet, column % 4), slot column / 4.
     const u32x4 *bsrc = reinterpret_cast<const u32x4 *>(a.at + (i64)(k0 >> 5) * 1024) + tid;
     const int bslot = (((tid >> 5) & 3) * 4 + (tid & 3)) * ROWS_PLANE + (tid >> 7) * 8 + ((tid & 31) >> 2);
     // dZ^T: lane (octet = lane / 16, row = lane % 16) of every wave fetches one unit; wave 0 writes them
