@@ -57,6 +57,9 @@ def parse():
                     help="variant for comparison: the averaging W X runs on a second stream beside dpsgd_grad, then "
                          "X = (W X) - gamma G is formed by a third pass (three existing entry points, 8 + 12 bytes per "
                          "(worker, parameter) instead of the mix kernel's 12); not the benchmark's path")
+    ap.add_argument("--ld-multiple", type=int, default=0,
+                    help="row stride of X: d rounded up to a multiple of this many floats (0 = the stride the library "
+                         "recommends for the topology, dpsgd_recommended_ld)")
     ap.add_argument("--ring-rows", type=int, default=-1,
                     help="set the library's ring_rows option (see include/dpsgd.h); -1 leaves the default")
     ap.add_argument("--shadow", action="store_true",
@@ -210,8 +213,8 @@ def main():
     if args.graph:   # capture needs a stream other than the default one; the library launches on torch's current stream
         torch.cuda.set_stream(torch.cuda.Stream())
     d = synth.model_dim(cfg.model_kind, cfg.widths)
-    ld = synth.padded_stride(d)
     topo = B.Topology.ring() if cfg.topology == "ring" else B.Topology.torus(*cfg.torus_dims)
+    ld = synth.padded_stride(d, args.ld_multiple) if args.ld_multiple else B.recommended_ld(d, topo)
     model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=cfg.bf16)
 
     # replicas: n copies of x_0 (Algorithm 1, Require)
@@ -375,7 +378,7 @@ def main():
         "dtype": "bf16" if cfg.bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "model_kind": int(cfg.model_kind), "widths": list(cfg.widths), "n": cfg.n,
-                   "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "gamma": cfg.gamma,
+                   "topology": cfg.topology, "batch_per_worker": cfg.batch, "d": d, "ld": ld, "gamma": cfg.gamma,
                    "minibatch_pool": len(pool), "consensus": cons is not None,
                    "path": "dpsgd_step" if fused else "dpsgd_grad beside dpsgd_mix_step, then dpsgd_mix_step" if args.overlap
                    else ("dpsgd_grad + dpsgd_mix_step_momentum" if Vel is not None

@@ -112,6 +112,15 @@ typedef struct {
 /* Length d the model implies, or -1 if the description is invalid.  Host only. */
 int64_t dpsgd_model_dim(const dpsgd_model *model);
 
+/* A row stride ld >= d (in floats) for the n x d replica matrix that the kernels stream well; dpsgd_create accepts
+ * any ld >= d, this is a recommendation for the caller's allocation.  -1 if d < 1 or W is NULL.  Host only.
+ * Ring and every other topology: d rounded up to a multiple of 256 floats, so that the 1 KB row pieces the ring
+ * kernels move are 1 KB-aligned for every worker.  2-D torus: a multiple of 64 floats that is not a multiple of
+ * 256, so that the tiles of a grid row's workers, which the fused torus kernel touches together, start 256 bytes
+ * apart inside their 1 KB granules instead of on top of each other.  (A layout decision for HBM, like the
+ * parameter server's sharding in Section 5.1 is for its network; the paper has no counterpart.) */
+int64_t dpsgd_recommended_ld(int64_t d, const dpsgd_topology *W);
+
 /* One minibatch per worker (Algorithm 1 step 2 has already happened in the caller). */
 typedef struct {
     const void *inputs;      /* device, [n][batch][features]; fp32, or bf16 if input_is_bf16 */

@@ -20,7 +20,7 @@ TOPO_CSR, TOPO_RING, TOPO_TORUS2D, TOPO_COMPLETE, TOPO_RING_CHORD = range(5)
 MODEL_LSQ, MODEL_SOFTMAX, MODEL_MLP, MODEL_RESNET20 = range(4)
 
 EXPORTS = (
-    "dpsgd_topology_build", "dpsgd_model_dim", "dpsgd_create", "dpsgd_destroy", "dpsgd_set_gamma",
+    "dpsgd_topology_build", "dpsgd_model_dim", "dpsgd_recommended_ld", "dpsgd_create", "dpsgd_destroy", "dpsgd_set_gamma",
     "dpsgd_set_option", "dpsgd_topology_export", "dpsgd_grad", "dpsgd_step", "dpsgd_mix_step", "dpsgd_mix_step_swapped",
     "dpsgd_mix_step_momentum", "dpsgd_mean", "dpsgd_read_timing", "dpsgd_strerror",
 )
@@ -62,6 +62,8 @@ def load():
     L.dpsgd_topology_build.argtypes = [C.c_int32, C.POINTER(_Topology), i32p, i32p, f32p, i64p]
     L.dpsgd_model_dim.restype = C.c_int64
     L.dpsgd_model_dim.argtypes = [C.POINTER(_Model)]
+    L.dpsgd_recommended_ld.restype = C.c_int64
+    L.dpsgd_recommended_ld.argtypes = [C.c_int64, C.POINTER(_Topology)]
     L.dpsgd_create.restype = C.c_int
     L.dpsgd_create.argtypes = [C.POINTER(vp), C.c_int32, C.c_int64, C.c_int64, C.POINTER(_Topology), C.c_float, vp]
     L.dpsgd_destroy.restype = C.c_int
@@ -153,6 +155,15 @@ def topology_build(n: int, topo: Topology):
                                   col.ctypes.data_as(C.POINTER(C.c_int32)),
                                   val.ctypes.data_as(C.POINTER(C.c_float)), C.byref(nnz)), "dpsgd_topology_build")
     return rowptr, col, val
+
+
+def recommended_ld(d: int, topo: Topology) -> int:
+    """Host only: the row stride (floats) dpsgd_recommended_ld suggests for an n x d replica matrix."""
+    t = topo._c()
+    ld = int(load().dpsgd_recommended_ld(d, C.byref(t)))
+    if ld < 0:
+        raise DpsgdError(EINVAL, "dpsgd_recommended_ld")
+    return ld
 
 
 class Model:

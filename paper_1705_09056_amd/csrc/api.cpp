@@ -208,6 +208,17 @@ int64_t dpsgd_model_dim(const dpsgd_model *m)
     return -1;
 }
 
+int64_t dpsgd_recommended_ld(int64_t d, const dpsgd_topology *W)
+{
+    if (d < 1 || !W || d > ((int64_t)1 << 60)) return -1;
+    if (W->kind == DPSGD_TOPO_TORUS2D) {
+        int64_t ld = (d + 63) / 64 * 64;
+        if (ld % 256 == 0) ld += 64;
+        return ld;
+    }
+    return (d + 255) / 256 * 256;
+}
+
 dpsgd_status dpsgd_create(dpsgd_ctx **out, int32_t n, int64_t d, int64_t ld, const dpsgd_topology *W, float gamma,
                           void *hip_stream)
 {

@@ -123,6 +123,21 @@ def test_model_dim():
     assert B.Model(9, [4]).dim == -1
 
 
+def test_recommended_row_stride():
+    ring, torus = B.Topology.ring(), B.Topology.torus(8, 8)
+    assert B.recommended_ld(29409290, ring) == 29409536          # 256 x 114881: rows 1 KB-aligned
+    assert B.recommended_ld(29409290, torus) == 29409344         # 64 x 459521, 64 beyond a multiple of 256
+    assert B.recommended_ld(256, ring) == 256 and B.recommended_ld(257, ring) == 512
+    assert B.recommended_ld(256, torus) == 320 and B.recommended_ld(193, torus) == 320 and B.recommended_ld(192, torus) == 192
+    for d in (1, 63, 64, 65, 1000, 30730, 268365):
+        for topo in (ring, torus, B.Topology.complete(), B.Topology.ring_chord()):
+            ld = B.recommended_ld(d, topo)
+            assert d <= ld < d + 320 and ld % 64 == 0
+            assert (ld % 256 != 0) if topo is torus else (ld % 256 == 0)
+    with pytest.raises(B.DpsgdError):
+        B.recommended_ld(0, ring)
+
+
 def test_create_rejects_bad_arguments_before_any_device_call():
     L = B.load()
     h = C.c_void_p(None)

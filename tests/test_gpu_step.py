@@ -118,7 +118,7 @@ def test_step_config3_full_size_one_worker(topology):
     cfg = CONFIGS[3] if topology == "ring" else CONFIG3_TORUS
     me, nbrs = (7, (6, 8)) if topology == "ring" else (27, (19, 26, 28, 35))
     d = synth.model_dim(cfg.model_kind, cfg.widths)
-    ld = synth.padded_stride(d)
+    ld = B.recommended_ld(d, topo_for(cfg))     # as bench.py lays X out
     x0 = synth.make_x0(cfg)
     rng = synth.rng(cfg.index, 95)
     Xa = torch.zeros(cfg.n, ld, device="cuda")
