@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
 # scaled by what the same counters read for a plain copy of known size (2.0 and 1.0); see profiles/.
 MEASURED_TRAFFIC = {("mlp3_ring64", "two-call"): 22.80e9,     # mix_ring_fat_kernel
-                    ("mlp3_ring64", "fused"): 7.88e9,         # mlp_fused_ring_rows_kernel, average of its two launches
+                    ("mlp3_ring64", "fused"): 7.89e9,         # mlp_fused_ring_rows_kernel, average of its two launches
                     ("mlp3_torus8x8", "fused"): 8.13e9}       # mlp_fused_torus_cols_kernel, likewise
 
 
