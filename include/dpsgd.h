@@ -141,16 +141,16 @@ dpsgd_status dpsgd_create(dpsgd_ctx **out, int32_t n, int64_t d, int64_t ld, con
 /* Waits for the context's stream, then frees the context and everything it owns.  NULL is accepted. */
 dpsgd_status dpsgd_destroy(dpsgd_ctx *ctx);
 
-/* Changes the step length for later dpsgd_mix_step calls (learning-rate schedules, Section 5.3). */
+/* Changes the step length gamma of Algorithm 1 step 5 for every later call that applies the update: dpsgd_mix_step,
+ * dpsgd_mix_step_swapped, dpsgd_mix_step_momentum and dpsgd_step (learning-rate schedules, Section 5.3).  Calls already
+ * enqueued, or recorded into a HIP graph, keep the value they were issued with. */
 dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
 
 /* Launch-shape knobs for measurements; unknown keys give DPSGD_EINVAL.  Defaults are chosen from
  * (n, d).  Keys: "mix_bands" (row bands per workgroup of the ring kernel, 0 = auto),
  * "mix_vec" (floats per lane: 0 = auto, 1, 2 or 4), "mix_force_csr" (1: run the generic CSR
  * kernel even for ring / torus tags), "mix_narrow" (1: the ring kernel with one float4 per lane also for wide
- * matrices, where the default gives a lane eight), "torus_window" (1: dpsgd_step on a torus with 8 columns uses the kernel
- * that keeps three grid rows of tiles in one wave's registers instead of one wave per grid column),
- * "ring_rows" (default 1: dpsgd_step on the ring, bf16 MLP, minibatch of at most 32 rows: layers whose input width is
+ * matrices, where the default gives a lane eight), "ring_rows" (default 1: dpsgd_step on the ring, bf16 MLP, minibatch of at most 32 rows: layers whose input width is
  * a multiple of 256 use the kernel whose workgroups own [16 rows][1 KB] of the weight matrix, each wave whole 1 KB
  * row pieces; 0: the kernel with 32 x 32 tiles per wave for every layer.  The two add up the minibatch in a different
  * order inside the matrix instructions, so their results agree to fp32 rounding, not bit for bit),
@@ -185,7 +185,12 @@ dpsgd_status dpsgd_grad(dpsgd_ctx *ctx, const dpsgd_model *model, const float *X
  *            owns whole columns and reads all of them before it writes
  *   consensus device, 1 float, may be NULL: M = (1/n) sum_i || xbar - X_out[i] ||^2 of the OUTPUT
  *            iterates (the consensus distance of Theorem 4 / eq. 13), reduced in a fixed order.
- * Each X and G element is read once from HBM and each X_out element written once. */
+ * Each X and G element is read once from HBM and each X_out element written once.
+ * Limits.  Theorem 3's ring (DPSGD_TOPO_RING, n >= 3) walks the rows with three of them in registers: any n, in place or
+ * not.  Every other W stages the n rows of a column slab in 64 KB of LDS, which holds n <= 256 workers (n <= 64 with 16-byte
+ * accesses, n <= 128 with 8-byte ones; beyond that narrower accesses are used).  For n > 256 such a W is mixed by a gather
+ * kernel that cannot work in place: X_out == X_in then returns DPSGD_EUNSUPPORTED and nothing is launched; out of place
+ * it takes up to 65535 workers (more: DPSGD_EUNSUPPORTED). */
 dpsgd_status dpsgd_mix_step(dpsgd_ctx *ctx, const float *X_in, const float *G, float *X_out, float *consensus);
 
 /* Footnote [c]'s admissible reordering: update first, then average,
@@ -214,7 +219,9 @@ dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const fl
  *   X          device, n x d (stride ld), overwritten by the next iterate
  *   G_scratch  device, n x d (stride ld), must not overlap X; on return it holds the gradient only of those
  *              parameters whose update was not fused (contents otherwise unspecified)
- *   loss, consensus  as in dpsgd_grad and dpsgd_mix_step; either may be NULL */
+ *   loss, consensus  as in dpsgd_grad and dpsgd_mix_step; either may be NULL
+ * The update is in place, so the in-place limit of dpsgd_mix_step applies: a W other than Theorem 3's ring with n > 256
+ * workers returns DPSGD_EUNSUPPORTED (after the gradient has been written to G_scratch; X is untouched). */
 dpsgd_status dpsgd_step(dpsgd_ctx *ctx, const dpsgd_model *model, float *X, const dpsgd_batch *batch, float *G_scratch,
                         float *loss, float *consensus);
 

@@ -656,16 +656,6 @@ void orc_grad_all(int32_t kind, int32_t n_layers, const int32_t *widths, int32_t
     }
 }
 
-/* One full iteration of Algorithm 1 for all workers: G = dF(X; xi), Xn = W X - gamma G. */
-void orc_iteration(int32_t kind, int32_t n_layers, const int32_t *widths, int32_t n, int64_t d,
-                   const int32_t *rowptr, const int32_t *col, const double *val, double gamma,
-                   const double *X, const double *inputs, const void *targets, int32_t B,
-                   double *G, double *loss, double *Xn, int32_t bf16_operands)
-{
-    orc_grad_all(kind, n_layers, widths, n, d, X, inputs, targets, B, G, loss, bf16_operands);
-    orc_mix_step(n, d, rowptr, col, val, X, G, gamma, Xn);
-}
-
 int32_t orc_num_threads(void)
 {
 #ifdef _OPENMP

@@ -310,6 +310,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
 {
     if (!ctx || !key) return DPSGD_EINVAL;
     const std::string k(key);
+    // a bf16 weight copy was written by the kernels the old options selected: none survives a change of options
+    ctx->shadow_valid = false;
     if (k == "mix_bands") {
         if (value < 0 || value > 16) return DPSGD_EINVAL;
         ctx->opt_mix_bands = (int32_t)value;
@@ -322,8 +324,6 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
         ctx->opt_mix_force_csr = value ? 1 : 0;
     } else if (k == "ring_rows") {
         ctx->opt_ring_rows = value ? 1 : 0;
-    } else if (k == "torus_window") {
-        ctx->opt_torus_window = value ? 1 : 0;
     } else if (k == "bf16_shadow") {
         ctx->opt_bf16_shadow = value ? 1 : 0;
         ctx->shadow_valid = false;

@@ -46,7 +46,6 @@ struct dpsgd_ctx {
     int32_t opt_mix_bands = 0, opt_mix_vec = 0, opt_mix_force_csr = 0;
     int32_t opt_mix_narrow = 0;     // ring mix of a wide matrix: one float4 per lane instead of the fat-lane kernel
     int32_t opt_ring_rows = 1;      // dpsgd_step on the ring, minibatch <= 32: the [16 rows][1 KB] kernel where the layer's shape allows
-    int32_t opt_torus_window = 0;   // dpsgd_step on an 8-column torus: the register-window kernel instead of the wave-per-column one
 
     // measurement aid: HIP events around the fused wgrad+mix launches of dpsgd_step ("time_fused")
     int32_t opt_time_fused = 0;

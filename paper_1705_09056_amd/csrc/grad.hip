@@ -25,7 +25,9 @@ dpsgd_status launch_step(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, co
 {
     if (is_dense(m) && m.compute_bf16 && (ctx->ring_uniform || ctx->torus_uniform) && !ctx->opt_mix_force_csr)
         return launch_step_mlp_bf16(ctx, m, X, inputs, targets, G, loss, consensus);
-    // everything else: the two calls of the boundary, back to back, in place
+    // everything else: the two calls of the boundary, back to back, in place.  X changes without the fused kernels
+    // seeing it, so a bf16 weight copy they left for this X is stale from here on.
+    ctx->shadow_valid = false;
     dpsgd_status st = launch_grad(ctx, m, X, inputs, targets, G, loss);
     if (st != DPSGD_OK) return st;
     return launch_mix(ctx, X, G, X, consensus, false);

@@ -1002,10 +1002,11 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_kernel(FusedArgs a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const float nxt = last ? xh[v] : xn[v];   // the ring closes on worker 0's original tile
+            // the order and roundings of the ring mix kernel: three fused multiply-adds after the first product
             float mix = a.w * xm[v];
-            mix = a.w * xc[v] + mix;
-            mix = a.w * nxt + mix;
-            const float o = mix - a.gamma * acc[v];
+            mix = __builtin_fmaf(a.w, xc[v], mix);
+            mix = __builtin_fmaf(a.w, nxt, mix);
+            const float o = __builtin_fmaf(-a.gamma, acc[v], mix);
             __builtin_nontemporal_store(o, dst + row_off(v));
             if (CONS) {   // per element the sum of (x - shift); the squares need no per-element sum
                 const float e = o - xh[v];
@@ -1137,10 +1138,10 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
             for (int t = 0; t < 4; ++t) {
                 const int v = 4 * r + t;
                 const float nxt = last ? xh[v] : xn[v];   // the ring closes on worker 0's original tile
-                float mix = a.w * xm[v];
-                mix = a.w * xc[v] + mix;
-                mix = a.w * nxt + mix;
-                const float o = mix - a.gamma * acc[t][r];
+                float mix = a.w * xm[v];     // order and roundings of the ring mix kernel
+                mix = __builtin_fmaf(a.w, xc[v], mix);
+                mix = __builtin_fmaf(a.w, nxt, mix);
+                const float o = __builtin_fmaf(-a.gamma, acc[t][r], mix);
                 out[t] = o;
                 if (CONS) {
                     const float e = o - xh[v];
@@ -1165,110 +1166,6 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
         const float inv_n = 1.0f / (float)a.n;
 #pragma unroll
         for (int v = 0; v < 16; ++v) m2 -= s1[v] * s1[v] * inv_n;
-        double t = (double)m2;
-        for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
-        if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = t;
-    }
-}
-
-// ------------------------------------------- the same fusion on a 2-D torus with 8 columns
-// Worker (r, c) = r * 8 + c averages itself, (r +- 1, c) and (r, c +- 1) with weight w (indices modulo the grid).
-// A wave owns a 16 x 16 tile of the weight matrix for ALL workers and walks the grid row by row with the
-// original tiles of grid rows r - 1, r, r + 1 in registers (plus grid row 0, which the last row wraps to, and
-// the row being fetched ahead): 5 x 8 tiles of 4 registers.  The gradient tile of a worker is one
-// v_mfma_f32_16x16x32_bf16 per 32 minibatch rows.  The four waves of a workgroup take adjacent 16-column tiles,
-// so that together they touch 256 consecutive bytes of a row.  grid (K / 64, O / 16), block 256.
-struct FusedTorusArgs {
-    float *X;
-    i64 ld, woff;
-    const bf16_t *dzt;   // T copy of dZ [n][B][O]
-    const bf16_t *at;    // T copy of A  [n][B][K]
-    int R, K, O, Bp;     // R grid rows (n = 8 R)
-    float w, gamma;
-    double *partials;    // one per wave (CONS only)
-};
-
-template <bool CONS>
-__global__ void __launch_bounds__(256) mlp_fused_torus8_kernel(FusedTorusArgs a)
-{
-    constexpr int C = 8;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n16 = lane & 15, q = lane >> 4;
-    const int k0 = blockIdx.x * 64 + wave * 16, o0 = blockIdx.y * 16;
-    // element i of this lane: row o0 + 4 q + i, column k0 + n16
-    float *xt = a.X + a.woff + (i64)(o0 + 4 * q) * a.K + k0 + n16;
-    auto load_tile = [&](int worker) {
-        const float *p = xt + (i64)worker * a.ld;
-        f32x4 v;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = p[(i64)i * a.K];
-        return v;
-    };
-    // operands in fragment order (tfrag_off): rows in groups of 32, samples in groups of 16 split into halves of 8;
-    // this lane needs row (tile row + n16) and the 8 samples 32 s + 8 q .. + 7
-    const int steps = a.Bp / 32;
-    const i64 op_step = 1024;   // two groups of 16 samples
-    auto op_off = [&](int row) {
-        return ((i64)(row >> 5) * (a.Bp >> 4) + (q >> 1)) * 512 + (q & 1) * 256 + (row & 31) * 8;
-    };
-    const bf16_t *ap = a.dzt + op_off(o0 + n16);
-    const bf16_t *bp = a.at + op_off(k0 + n16);
-    const i64 a_worker = (i64)a.O * a.Bp, b_worker = (i64)a.K * a.Bp;
-
-    f32x4 first[C], prev[C], cur[C], next[C], ahead[C];
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-        first[c] = load_tile(c);
-        prev[c] = load_tile((a.R - 1) * C + c);
-        next[c] = load_tile(C + c);
-        cur[c] = first[c];
-    }
-    const f32x4 shift = first[0];
-    f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
-    for (int r = 0; r < a.R; ++r) {
-        if (r + 2 < a.R) {   // all of grid row r + 2 is in flight while row r is worked on
-#pragma unroll
-            for (int c = 0; c < C; ++c) ahead[c] = load_tile((r + 2) * C + c);
-        } else {
-#pragma unroll
-            for (int c = 0; c < C; ++c) ahead[c] = first[c];   // grid row R - 1 wraps to row 0
-        }
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const int worker = r * C + c;
-            const bf16_t *ai = ap + worker * a_worker, *bi = bp + worker * b_worker;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int st = 0; st < steps; ++st)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ai + st * op_step), frag(bi + st * op_step), acc, 0, 0, 0);
-            float *dst = xt + (i64)worker * a.ld;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float m = a.w * prev[c][i];
-                m = a.w * cur[(c + C - 1) % C][i] + m;
-                m = a.w * cur[c][i] + m;
-                m = a.w * cur[(c + 1) % C][i] + m;
-                m = a.w * next[c][i] + m;
-                const float o = m - a.gamma * acc[i];
-                dst[(i64)i * a.K] = o;
-                if (CONS) {
-                    const float e = o - shift[i];
-                    s1[i] += e;
-                    s2[i] += e * e;
-                }
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            prev[c] = cur[c];
-            cur[c] = next[c];
-            next[c] = ahead[c];
-        }
-    }
-    if (CONS) {
-        const float inv_n = 1.0f / (float)(a.R * C);
-        float m2 = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) m2 += s2[i] - s1[i] * s1[i] * inv_n;
         double t = (double)m2;
         for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
         if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = t;
@@ -1384,13 +1281,13 @@ __global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTor
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int v = 4 * h + e;          // register 2 i + j with i = v / 2, j = v % 2
-                float m = a.w * up[v];
-                m = a.w * lv[e] + m;
-                m = a.w * cur[v] + m;
-                m = a.w * rv[e] + m;
-                m = a.w * down[v] + m;
+                float m = a.w * up[v];            // one product, then fused multiply-adds: fixed roundings
+                m = __builtin_fmaf(a.w, lv[e], m);
+                m = __builtin_fmaf(a.w, cur[v], m);
+                m = __builtin_fmaf(a.w, rv[e], m);
+                m = __builtin_fmaf(a.w, down[v], m);
                 const float g = (v & 1) ? acc_o[v >> 1] : acc_e[v >> 1];
-                const float o = m - a.gamma * g;
+                const float o = __builtin_fmaf(-a.gamma, g, m);
                 o4[e] = o;
                 if (CONS) {
                     const float d = o - shift[v];
@@ -1480,14 +1377,12 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
 
 // A layer's weight gradient can be fused into the mix when a kernel exists for the topology (Theorem 3's ring; a
 // torus with 3 to 8 columns and at least 3 grid rows) and its tiles divide the matrix.
-bool torus8(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 == 8 && ctx->dim0 >= 3; }
 bool torus_cols(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 >= 3 && ctx->dim1 <= 8 && ctx->dim0 >= 3; }
 
 bool layer_fusable(const dpsgd_ctx *ctx, int K, int O, i64 woff)
 {
     if (ctx->opt_mix_force_csr || woff < 0 || (i64)K * O < (1 << 20)) return false;
     if (ctx->ring_uniform) return (K % 128) == 0 && (O % 32) == 0;
-    if (ctx->opt_torus_window && torus8(ctx)) return (K % 64) == 0 && (O % 32) == 0;   // 16 x 16 tiles
     if (torus_cols(ctx)) return (K % 32) == 0 && (O % 32) == 0 && (woff % 2) == 0 && (ctx->ld % 2) == 0;   // 8-byte accesses
     return false;
 }
@@ -1529,6 +1424,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
                          (m.widths[l + 1] % 32) == 0 && (woff[l] % 4) == 0 && base_ok;
     if (fuse) {
         const bool was_valid = ctx->shadow_valid && ctx->shadow_X == X && ctx->shadow_model.kind == m.kind &&
+                               ctx->shadow_model.compute_bf16 == m.compute_bf16 &&
                                ctx->shadow_model.widths == m.widths && (int)ctx->shadow_off.size() == L &&
                                (int)ctx->shadow_strips.size() == L;
         ctx->shadow_valid = false;
@@ -1679,7 +1575,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, false>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, false>), grid, dim3(256), 0, s, fa);
             }
-        } else if (!ctx->opt_torus_window || !torus8(ctx)) {
+        } else {
             FusedTorusColArgs fa{};
             fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
             fa.R = ctx->dim0; fa.C = ctx->dim1; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->torus_w; fa.gamma = ctx->gamma;
@@ -1697,16 +1593,6 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
                 if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 1>), grid, dim3(64u * fa.C), shm, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 1>), grid, dim3(64u * fa.C), shm, s, fa);
             }
-        } else {
-            FusedTorusArgs fa{};
-            fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
-            fa.R = ctx->dim0; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->torus_w; fa.gamma = ctx->gamma;
-            fa.partials = ctx->d_partials + nparts;
-            dim3 grid((unsigned)(K / 64), (unsigned)(O / 16));
-            np = (i64)grid.x * grid.y * 4;
-            if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
-            if (cons) hipLaunchKernelGGL(mlp_fused_torus8_kernel<true>, grid, dim3(256), 0, s, fa);
-            else hipLaunchKernelGGL(mlp_fused_torus8_kernel<false>, grid, dim3(256), 0, s, fa);
         }
         if (cons) nparts += np;
         st = hip_status(hipGetLastError());

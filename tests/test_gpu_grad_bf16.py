@@ -1,8 +1,12 @@
-"""GPU parity of dpsgd_grad with bf16 MFMA operands (softmax regression / ReLU MLP) against the
-CPU oracle in its bf16-operand mode (operands of every contraction rounded to bf16, fp64 sums), so
-that ReLU decisions are taken on the same rounded values on both sides.  Bar: 2e-2 relative
-Frobenius; the kernels are expected to sit far below it (fp32 vs fp64 accumulation only), which
-TIGHT checks.  The distance to the un-rounded fp64 gradient is printed as the cost of bf16."""
+"""GPU parity of dpsgd_grad with bf16 MFMA operands (softmax regression / ReLU MLP) against the CPU oracle.
+
+Two oracles judge every case.  The plain fp64 oracle (no rounding inside) binds the loss at the 2e-2 bar of
+the bf16 workloads, and the gradient through the identity  dist(GPU, plain) == dist(oracle with bf16 operands,
+plain)  to two digits: the operand rounding the workload prescribes moves the gradient by 0.2-4e-2 of its norm
+whoever computes it (tests/test_oracle_bf16_gap.py shows that on the CPU with two independent implementations),
+and the kernel must add nothing to that.  The oracle in its bf16-operand mode (the same operand roundings, fp64
+sums; ReLU decisions taken on the same rounded values) is the tight check of the kernel itself: TIGHT on the
+whole gradient and per layer, Frobenius and element-wise."""
 import numpy as np
 import pytest
 import torch
@@ -12,8 +16,9 @@ from paper_1705_09056_amd import binding as B
 from paper_1705_09056_amd import synth
 from paper_1705_09056_amd.configs import CONFIGS, CONFIG3_TORUS, MODEL_MLP, MODEL_SOFTMAX, shrink
 
-from conftest import rel_err
+from conftest import check_close, max_err, rel_err
 from gpu_util import bf16_dev, from_dev, oracle_topo_for, to_dev, topo_for
+from parity_cases import MLP_ALIGNED, mlp_inputs
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -22,12 +27,9 @@ TIGHT = 2e-3
 
 def grad_case(cfg, ld, k=0, spread=0.3, bf16_inputs=True, extra_bias=0.0):
     d = synth.model_dim(cfg.model_kind, cfg.widths)
-    X = synth.make_replicas(cfg, spread=spread, key=k)
-    if extra_bias:
-        X = X + np.float32(extra_bias) * synth.rng(cfg.index, 98, k).standard_normal(X.shape).astype(np.float32)
-    inp, tgt = synth.make_batch(cfg, k)
+    X, inp, tgt = mlp_inputs(cfg, k, spread, extra_bias)
     Gref, lref = oracle.grad_all(cfg.model_kind, cfg.widths, X, inp, tgt, bf16_operands=True)
-    Gplain, _ = oracle.grad_all(cfg.model_kind, cfg.widths, X, inp, tgt)
+    Gplain, lplain = oracle.grad_all(cfg.model_kind, cfg.widths, X, inp, tgt)
     Xd = to_dev(X, ld)
     Gd = torch.full_like(Xd, 777.0)
     loss = torch.zeros(cfg.n, device="cuda")
@@ -40,27 +42,25 @@ def grad_case(cfg, ld, k=0, spread=0.3, bf16_inputs=True, extra_bias=0.0):
         ctx.grad(model, Xd, inp_d, tgt_d, cfg.batch, Gd, loss, input_is_bf16=bf16_inputs)   # workspace reuse
         torch.cuda.synchronize()
     G = from_dev(Gd, d)
-    e_all = rel_err(G, Gref)
     lay = synth.param_layout(cfg.model_kind, cfg.widths)
-    per = {p.name: rel_err(G[:, p.offset:p.offset + p.size], Gref[:, p.offset:p.offset + p.size]) for p in lay}
-    print("  rel err G %.3e  loss %.3e  per-layer %s" % (e_all, rel_err(loss.cpu().numpy(), lref),
-                                                        {k_: "%.2e" % v for k_, v in per.items()}), flush=True)
-    print("  distance to the un-rounded fp64 gradient: %.3e" % rel_err(G, Gplain), flush=True)
-    assert e_all < TIGHT
-    assert all(v < TIGHT for v in per.values())
+    e_all, m_all = check_close(G, Gref, TIGHT, "G vs bf16-operand oracle", flips=True)
+    per = {p.name: check_close(G[:, p.offset:p.offset + p.size], Gref[:, p.offset:p.offset + p.size], TIGHT, p.name,
+                               flips=True)
+           for p in lay}
+    print("  rel err G %.3e (max element %.3e rms)  loss %.3e  per-layer %s" % (
+        e_all, m_all, rel_err(loss.cpu().numpy(), lref), {k_: "%.2e/%.2e" % v for k_, v in per.items()}), flush=True)
     assert rel_err(loss.cpu().numpy(), lref) < TIGHT
+    # against the plain fp64 oracle: the loss meets the bar of the bf16 workloads, and the gradient is as far from
+    # the un-rounded one as the operand rounding alone puts it (the CPU oracle with the same roundings), no further
+    assert rel_err(loss.cpu().numpy(), lplain) < TOL
+    gap_gpu, gap_rounding = rel_err(G, Gplain), rel_err(Gref, Gplain)
+    print("  distance to the un-rounded fp64 gradient: GPU %.3e, bf16-operand oracle %.3e" % (gap_gpu, gap_rounding),
+          flush=True)
+    assert abs(gap_gpu - gap_rounding) <= 0.02 * gap_rounding + 2e-5
+    return gap_gpu
 
 
-@pytest.mark.parametrize("widths,batch,n", [
-    ((3072, 1024, 10), 128, 2),        # configs[2] layer shapes
-    ((3072, 256, 256, 10), 32, 3),     # configs[3] structure, narrower hidden layers
-    ((512, 4096, 10), 32, 2),          # a full-width 4096 hidden layer
-    ((256, 128, 10), 64, 2),           # the 64-row tiling
-    ((256, 128, 64, 10), 130, 2),      # more than one row block
-    ((64, 272, 7), 37, 3),             # class layer on the split-contraction kernel, ragged minibatch
-    ((128, 256, 32), 33, 2),           # 32 outputs: the widest class layer that kernel takes
-    ((128, 256, 33), 33, 2),           # 33 outputs: back on the general tile
-])
+@pytest.mark.parametrize("widths,batch,n", MLP_ALIGNED)
 def test_mlp_bf16_aligned(widths, batch, n):
     cfg = shrink(CONFIGS[2], widths=widths, batch=batch, n=n)
     d = synth.model_dim(MODEL_MLP, widths)
@@ -107,10 +107,16 @@ def sampled_full_size(cfg, sample):
         torch.cuda.synchronize()
     for i in sample:
         l, g = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[i], inp[i], tgt[i], bf16_operands=True)
-        e = rel_err(Gd[i, :d].cpu().numpy(), g)
-        print(f"  worker {i}: rel err G {e:.3e}, loss {float(loss[i]):.5f} vs {l:.5f}", flush=True)
-        assert e < TIGHT
+        lp, gp = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[i], inp[i], tgt[i])
+        got = Gd[i, :d].cpu().numpy()
+        e, m = check_close(got, g, TIGHT, f"worker {i}", flips=True)
+        gap_gpu, gap_rounding = rel_err(got, gp), rel_err(g, gp)
+        print(f"  worker {i}: rel err G {e:.3e} (max element {m:.3e} rms), loss {float(loss[i]):.5f} vs {l:.5f} "
+              f"(plain fp64 {lp:.5f}); distance to the un-rounded gradient: GPU {gap_gpu:.3e}, oracle {gap_rounding:.3e}",
+              flush=True)
         assert abs(float(loss[i]) - l) < TIGHT * abs(l)
+        assert abs(float(loss[i]) - lp) < TOL * abs(lp)
+        assert abs(gap_gpu - gap_rounding) <= 0.02 * gap_rounding + 2e-5
     del Xd, Gd
     torch.cuda.empty_cache()
 
@@ -121,32 +127,3 @@ def test_config2_full_size_sampled_workers():
 
 def test_config3_full_size_sampled_workers():
     sampled_full_size(CONFIGS[3], [5, 63])
-
-
-def test_config2_short_trajectory_single_step_gate():
-    """Reduced configs[2] (hidden width 128): every iteration one GPU step from the oracle's iterate."""
-    cfg = shrink(CONFIGS[2], widths=(3072, 128, 10), n=4, iters=6)
-    d = synth.model_dim(cfg.model_kind, cfg.widths)
-    ld = synth.padded_stride(d)
-    topo_o = oracle_topo_for(cfg)
-    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
-    Xo = synth.make_replicas(cfg).astype(np.float64)
-    Xfree = to_dev(Xo, ld)
-    Gd = torch.full_like(Xfree, 777.0)
-    with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
-        for k in range(cfg.iters):
-            inp, tgt = synth.make_batch(cfg, k)
-            inp_d, tgt_d = bf16_dev(inp), torch.from_numpy(tgt).cuda()
-            Xn, Gref, _ = oracle.iteration(cfg.model_kind, cfg.widths, topo_o, np.float32(cfg.gamma), Xo, inp, tgt,
-                                           bf16_operands=True)
-            Xs = to_dev(Xo, ld)
-            ctx.grad(model, Xs, inp_d, tgt_d, cfg.batch, Gd, input_is_bf16=True)
-            assert rel_err(from_dev(Gd, d), Gref) < TOL
-            ctx.mix_step(Xs, Gd, Xs)
-            step_err = rel_err(from_dev(Xs, d), Xn)
-            ctx.grad(model, Xfree, inp_d, tgt_d, cfg.batch, Gd, input_is_bf16=True)
-            ctx.mix_step(Xfree, Gd, Xfree)
-            traj_err = rel_err(from_dev(Xfree, d), Xn)
-            print(f"  k={k}: single-step {step_err:.3e}  trajectory {traj_err:.3e}", flush=True)
-            assert step_err < TOL and traj_err < TOL
-            Xo = Xn

@@ -7,7 +7,7 @@ import torch
 import oracle
 from paper_1705_09056_amd import binding as B
 
-from conftest import rel_err
+from conftest import check_close, rel_err
 from gpu_util import from_dev, to_dev
 
 pytestmark = pytest.mark.gpu
@@ -49,7 +49,7 @@ def run_mix(n, d, ld, topo_b, topo_o, seed, inplace, cons, swapped=False, option
         ctx.mix_step(Xd, Gd, out, cd, swapped=swapped)
         torch.cuda.synchronize()
     got = from_dev(out, d)
-    assert rel_err(got, ref) < TOL
+    check_close(got, ref, TOL, "X_next")
     if not inplace:
         assert np.array_equal(from_dev(Xd, d), X.astype(np.float64))     # input untouched
     assert np.array_equal(from_dev(Gd, d), G.astype(np.float64))
@@ -164,7 +164,7 @@ def test_mean(n, d, ld):
     with B.Dpsgd(n, d, B.Topology.ring(), 0.1, ld=ld) as ctx:
         ctx.mean(Xd, out)
         torch.cuda.synchronize()
-    assert rel_err(out.cpu().numpy(), oracle.mean(X)) < TOL
+    check_close(out.cpu().numpy(), oracle.mean(X), TOL, "xbar")
 
 
 def test_multi_step_invariants_on_device():
@@ -209,7 +209,7 @@ def _full_size_mix(n, d, topo_b, topo_o, gamma=0.1):
         ctx.mix_step(Xd, Gd, Xd, cons)
         torch.cuda.synchronize()
     got = Xd[:, cols_d].cpu().numpy()
-    assert rel_err(got, ref) < TOL
+    check_close(got, ref, TOL, "sampled columns of X_next")
     # consensus of the whole output, accumulated by the oracle over column chunks
     total = 0.0
     step = 2_000_000
@@ -286,8 +286,8 @@ def run_momentum(n, d, ld, topo_b, topo_o, seed, inplace, mu=0.9, gamma=0.05, st
             ctx.mix_step_momentum(Xd, Gd, Vd, mu, out, cd)
             torch.cuda.synchronize()
             Xd = out
-            assert rel_err(from_dev(Xd, d), Xo) < TOL
-            assert rel_err(from_dev(Vd, d), Vo) < TOL
+            check_close(from_dev(Xd, d), Xo, TOL, "X_next")
+            check_close(from_dev(Vd, d), Vo, TOL, "V_next")
             assert np.array_equal(from_dev(Gd, d), G.astype(np.float64))
             assert float(cd.item()) == pytest.approx(oracle.consensus(Xo), rel=1e-4)
 
@@ -330,3 +330,52 @@ def test_momentum_rejects_bad_arguments():
         with pytest.raises(B.DpsgdError) as e:
             ctx.mix_step_momentum(Xd, Gd, Gd, 0.9, Xd)      # V aliases G
         assert e.value.status == B.EINVAL
+
+
+def test_step_in_place_without_slab_is_refused_and_leaves_x_alone():
+    """dpsgd_step is in place, so a W that is not Theorem 3's ring with n > 256 workers has no kernel: the status says
+    so, and X still holds the iterate it held (the gradient has been written to the scratch matrix)."""
+    n, feat = 300, 20
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((n, feat)).astype(np.float32)
+    Xd, Gd = to_dev(X), to_dev(np.zeros_like(X))
+    inp = torch.from_numpy(rng.standard_normal((n, 4, feat)).astype(np.float32)).cuda()
+    tgt = torch.from_numpy(rng.standard_normal((n, 4)).astype(np.float32)).cuda()
+    with B.Dpsgd(n, feat, B.Topology.complete(), 0.1) as ctx:
+        with pytest.raises(B.DpsgdError) as e:
+            ctx.step(B.Model(B.MODEL_LSQ, [feat]), Xd, inp, tgt, 4, Gd)
+        assert e.value.status == B.EUNSUPPORTED
+        torch.cuda.synchronize()
+    assert np.array_equal(from_dev(Xd, feat), X.astype(np.float64))
+
+
+@pytest.mark.parametrize("topo", ["ring", "torus"])
+def test_averaging_on_a_second_stream_then_update_equals_mix_step(topo):
+    """Footnote [b]: Algorithm 1's steps 3 and 4 do not depend on each other.  The composition bench.py --overlap
+    times - the averaging W X on a second stream (a context with gamma = 0) while the first stream is busy, then
+    X_next = (W X) - gamma G as a mix with the identity for W - gives dpsgd_mix_step's result and the oracle's."""
+    n, dims = (12, None) if topo == "ring" else (12, (3, 4))
+    d, ld, gamma = 20011, 20032, 0.07
+    tb = B.Topology.ring() if topo == "ring" else B.Topology.torus(*dims)
+    to = (oracle.ring(n) if topo == "ring" else oracle.torus(*dims)).with_fp32_values()
+    X, G = random_state(n, d, 77)
+    ref = oracle.mix_step(to, X, G, np.float32(gamma))
+    Xd, Gd = to_dev(X, ld), to_dev(G, ld)
+    direct, avg, out = torch.full_like(Xd, 777.0), torch.full_like(Xd, 777.0), torch.full_like(Xd, 777.0)
+    c_direct, c_out = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    ident = B.Topology.csr(np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32), np.ones(n, dtype=np.float32))
+    with B.Dpsgd(n, d, tb, gamma, ld=ld) as ctx, B.Dpsgd(n, d, tb, 0.0, ld=ld, stream=side) as ctx_avg, \
+            B.Dpsgd(n, d, ident, gamma, ld=ld) as ctx_upd:
+        ctx.mix_step(Xd, Gd, direct, c_direct)
+        side.wait_stream(main)
+        with torch.cuda.stream(side):
+            ctx_avg.mix_step(Xd, Xd, avg, None)        # gamma = 0: the "gradient" operand contributes nothing
+        busy = torch.randn(1 << 20, device="cuda").sum()    # the first stream does something else meanwhile
+        main.wait_stream(side)
+        ctx_upd.mix_step(avg, Gd, out, c_out)
+        torch.cuda.synchronize()
+    del busy
+    check_close(from_dev(out, d), ref, TOL, "overlapped composition vs oracle")
+    check_close(from_dev(out, d), from_dev(direct, d), TOL, "overlapped composition vs dpsgd_mix_step")
+    assert float(c_out) == pytest.approx(float(c_direct), rel=1e-5)

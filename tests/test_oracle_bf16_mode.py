@@ -13,40 +13,49 @@ from paper_1705_09056_amd import synth
 from conftest import rel_err
 
 
-def tq(x):
-    return x.to(torch.bfloat16).to(torch.float64)
+class Casts:
+    """The roundings of the bf16 workloads as torch operations in arithmetic type `dtype`; with casts=False every
+    one of them is the identity (plain autograd)."""
+
+    def __init__(self, dtype=torch.float64, casts=True):
+        self.dtype, self.casts = dtype, casts
+        outer = self
+
+        class RoundGrad(torch.autograd.Function):
+            """Identity whose incoming gradient is rounded to bf16."""
+
+            @staticmethod
+            def forward(ctx, x):
+                return x.clone()
+
+            @staticmethod
+            def backward(ctx, g):
+                return outer.tq(g)
+
+        self.round_grad = RoundGrad.apply
+
+    def tq(self, x):
+        return x.to(torch.bfloat16).to(self.dtype) if self.casts else x
+
+    def rq(self, x):
+        """Value rounded to bf16, gradient passed through unchanged."""
+        return x + (self.tq(x) - x).detach()
 
 
-def rq(x):
-    """Value rounded to bf16, gradient passed through unchanged."""
-    return x + (tq(x) - x).detach()
-
-
-class RoundGrad(torch.autograd.Function):
-    """Identity whose incoming gradient is rounded to bf16."""
-
-    @staticmethod
-    def forward(ctx, x):
-        return x.clone()
-
-    @staticmethod
-    def backward(ctx, g):
-        return tq(g)
-
-
-def torch_mlp_bf16(widths, x, inp, lab):
-    xs = torch.tensor(x, dtype=torch.float64, requires_grad=True)
-    a = tq(torch.tensor(inp, dtype=torch.float64))
+def torch_mlp_bf16(widths, x, inp, lab, dtype=torch.float64, casts=True):
+    c = Casts(dtype, casts)
+    xs = torch.tensor(x, dtype=dtype, requires_grad=True)
+    a = c.tq(torch.tensor(inp, dtype=dtype))
     off, L = 0, len(widths) - 1
     for l in range(L):
         O, I = widths[l + 1], widths[l]
         W = xs[off:off + O * I].reshape(O, I); off += O * I
         b = xs[off:off + O]; off += O
-        z = RoundGrad.apply(F.linear(a, rq(W), b))
-        a = rq(F.relu(z)) if l < L - 1 else z
+        z = c.round_grad(F.linear(a, c.rq(W), b))
+        a = c.rq(F.relu(z)) if l < L - 1 else z
     loss = F.cross_entropy(a, torch.tensor(lab, dtype=torch.long))
     loss.backward()
-    return float(loss.detach()), xs.grad.numpy()
+    return float(loss.detach()), xs.grad.double().numpy()
 
 
 @pytest.mark.parametrize("kind,widths", [(oracle.SOFTMAX, [9, 4]), (oracle.MLP, [12, 10, 5]), (oracle.MLP, [8, 7, 6, 3])])
@@ -66,11 +75,12 @@ def test_mlp_bf16_mode_against_autograd_with_casts(kind, widths):
     assert 1e-5 < rel_err(g, g_plain) < 5e-2
 
 
-def torch_resnet_bf16(widths, x, inp, lab):
+def torch_resnet_bf16(widths, x, inp, lab, dtype=torch.float64, casts=True):
+    q = Casts(dtype, casts)
     cin, H, W, base, blocks, classes = widths
-    xs = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    xs = torch.tensor(x, dtype=dtype, requires_grad=True)
     B = inp.shape[0]
-    a = tq(torch.tensor(inp, dtype=torch.float64)).reshape(B, cin, H, W)
+    a = q.tq(torch.tensor(inp, dtype=dtype)).reshape(B, cin, H, W)
     off = 0
 
     def take(shape):
@@ -81,7 +91,7 @@ def torch_resnet_bf16(widths, x, inp, lab):
         return t
 
     w, b = take((base, cin, 3, 3)), take((1,))
-    a = rq(F.relu(RoundGrad.apply(F.conv2d(a, rq(w), padding=1) + b)))
+    a = q.rq(F.relu(q.round_grad(F.conv2d(a, q.rq(w), padding=1) + b)))
     cprev = base
     for s in range(3):
         c = base << s
@@ -89,14 +99,14 @@ def torch_resnet_bf16(widths, x, inp, lab):
             stride = 2 if (s > 0 and j == 0) else 1
             w1, b1 = take((c, cprev, 3, 3)), take((1,))
             w2, b2 = take((c, c, 3, 3)), take((1,))
-            u = rq(F.relu(RoundGrad.apply(F.conv2d(a, rq(w1), stride=stride, padding=1) + b1)))
+            u = q.rq(F.relu(q.round_grad(F.conv2d(a, q.rq(w1), stride=stride, padding=1) + b1)))
             sc = a if stride == 1 else F.pad(a[:, :, ::2, ::2], (0, 0, 0, 0, 0, c - cprev))
-            a = rq(F.relu(RoundGrad.apply(F.conv2d(u, rq(w2), padding=1) + b2 + sc)))
+            a = q.rq(F.relu(q.round_grad(F.conv2d(u, q.rq(w2), padding=1) + b2 + sc)))
             cprev = c
     wf, bf = take((classes, cprev)), take((classes,))
     loss = F.cross_entropy(F.linear(a.mean(dim=(2, 3)), wf, bf), torch.tensor(lab, dtype=torch.long))
     loss.backward()
-    return float(loss.detach()), xs.grad.numpy()
+    return float(loss.detach()), xs.grad.double().numpy()
 
 
 @pytest.mark.parametrize("widths,B", [([2, 6, 6, 2, 1, 3], 2), ([3, 8, 8, 4, 2, 10], 3)])
