@@ -225,6 +225,26 @@ dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const fl
 dpsgd_status dpsgd_step(dpsgd_ctx *ctx, const dpsgd_model *model, float *X, const dpsgd_batch *batch, float *G_scratch,
                         float *loss, float *consensus);
 
+/* dpsgd_mix_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It needs no context and calls no hipMalloc / hipFree (nor any other allocating
+ * routine): what dpsgd_mix_step keeps in buffers of its context - the per-workgroup partial sums of the consensus
+ * distance, the device CSR of a torus - lives in one fixed array of 4 MiB + 64 KiB of device memory inside the library,
+ * which every GPU the library runs on holds from the first use until the process ends.
+ *   n, d, ld, gamma, X_in, G, X_out, consensus   as in dpsgd_create / dpsgd_mix_step (ld == 0 means ld == d); X_out may
+ *            be X_in; the caller still owns and passes every input and output
+ *   W        a tag only: DPSGD_TOPO_RING with n >= 3, or DPSGD_TOPO_TORUS2D with both dimensions >= 3 and n <= 256
+ *   hip_stream  the hipStream_t the kernels are enqueued on (NULL = the default stream)
+ * Same kernels, same results, bit for bit, as dpsgd_mix_step on a context created with the same arguments.
+ * Limits: d <= 33 554 432 (2^25) parameters per worker; anything larger, any other W (CSR, complete graph, ring with
+ * a far link, rings and tori with coinciding neighbours) and a torus with n > 256 return DPSGD_EUNSUPPORTED before
+ * anything is launched; argument errors return DPSGD_EINVAL as in dpsgd_mix_step.
+ * All calls on one GPU share that GPU's array: the kernels overwrite every part of it they later read (nothing has to
+ * start at zero), so consecutive calls on one stream are independent of each other, but two calls that overlap in
+ * time on the same GPU (different streams or threads) race on it.  The first call on a device looks up the array's
+ * address and must not be made under stream capture; later ones only enqueue kernels. */
+dpsgd_status dpsgd_mix_step_static(int32_t n, int64_t d, int64_t ld, const dpsgd_topology *W, float gamma,
+                                   const float *X_in, const float *G, float *X_out, float *consensus, void *hip_stream);
+
 /* Algorithm 1 step 7: xbar = (1/n) sum_i X[i].  X device n x d (stride ld); xbar device, d floats. */
 dpsgd_status dpsgd_mean(dpsgd_ctx *ctx, const float *X, float *xbar);
 

@@ -22,7 +22,7 @@ MODEL_LSQ, MODEL_SOFTMAX, MODEL_MLP, MODEL_RESNET20 = range(4)
 EXPORTS = (
     "dpsgd_topology_build", "dpsgd_model_dim", "dpsgd_recommended_ld", "dpsgd_create", "dpsgd_destroy", "dpsgd_set_gamma",
     "dpsgd_set_option", "dpsgd_topology_export", "dpsgd_grad", "dpsgd_step", "dpsgd_mix_step", "dpsgd_mix_step_swapped",
-    "dpsgd_mix_step_momentum", "dpsgd_mean", "dpsgd_read_timing", "dpsgd_strerror",
+    "dpsgd_mix_step_momentum", "dpsgd_mix_step_static", "dpsgd_mean", "dpsgd_read_timing", "dpsgd_strerror",
 )
 
 
@@ -83,6 +83,8 @@ def load():
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp]
     L.dpsgd_mix_step_momentum.restype = C.c_int
     L.dpsgd_mix_step_momentum.argtypes = [vp, vp, vp, vp, C.c_float, vp, vp]
+    L.dpsgd_mix_step_static.restype = C.c_int
+    L.dpsgd_mix_step_static.argtypes = [C.c_int32, C.c_int64, C.c_int64, C.POINTER(_Topology), C.c_float, vp, vp, vp, vp, vp]
     L.dpsgd_mean.restype = C.c_int
     L.dpsgd_mean.argtypes = [vp, vp, vp]
     L.dpsgd_read_timing.restype = C.c_int
@@ -164,6 +166,21 @@ def recommended_ld(d: int, topo: Topology) -> int:
     if ld < 0:
         raise DpsgdError(EINVAL, "dpsgd_recommended_ld")
     return ld
+
+
+def mix_step_static(n: int, d: int, topo: Topology, gamma: float, X_in, G, X_out, consensus=None, ld: int = 0,
+                    stream=None):
+    """dpsgd_mix_step_static: the mix + step without a context and without any allocation (ring / small torus tags)."""
+    import torch
+    ld = int(ld) if ld else int(d)
+    for t, name in ((X_in, "X_in"), (G, "G"), (X_out, "X_out")):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (n, ld):
+            raise ValueError(f"{name} must be a contiguous float32 CUDA tensor of shape ({n}, {ld})")
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    t = topo._c()
+    _check(load().dpsgd_mix_step_static(int(n), int(d), ld, C.byref(t), float(gamma), _ptr(X_in), _ptr(G), _ptr(X_out),
+                                        _ptr(consensus), C.c_void_p(stream.cuda_stream)), "dpsgd_mix_step_static")
 
 
 class Model:

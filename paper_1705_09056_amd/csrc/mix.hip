@@ -12,6 +12,8 @@
 // The consensus distance of the OUTPUT is accumulated on the fly per column (sums of deviations
 // from a per-lane shift, so that no large numbers cancel), reduced across bands in LDS, across
 // lanes with wave shuffles, and across workgroups in a fixed order by a second tiny kernel.
+#include <mutex>
+
 #include "dpsgd_internal.h"
 
 namespace dpsgd {
@@ -802,4 +804,128 @@ dpsgd_status launch_mean(dpsgd_ctx *ctx, const float *X, float *xbar)
     return st;
 }
 
+// ------------------------------------------------------------------ allocation-free entry point
+// dpsgd_mix_step for callers that cannot allocate: no context, no hipMalloc.  What the ordinary call keeps in
+// buffers of its context (per-workgroup partial sums of the consensus distance, the device CSR of a torus) lives
+// in one file-scope device array instead.  Every GPU the library runs on holds its own copy of the array, at its own
+// address, until the process ends; the address is looked up once per device and only that pointer is ever used.
+namespace {
+
+constexpr size_t kStaticCsrBytes = 32 * 1024;                       // rowptr, colidx, vals of a torus with n <= 256
+constexpr size_t kStaticPartialBytes = 4 * 1024 * 1024 + 32 * 1024;
+constexpr size_t kStaticScratchBytes = kStaticPartialBytes + kStaticCsrBytes;
+constexpr int64_t kStaticMaxD = (int64_t)1 << 25;                   // 33 554 432 parameters per worker
+constexpr int32_t kStaticMaxTorusN = 256;
+constexpr int kStaticMaxDevices = 64;
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+void *g_scratch_ptr[kStaticMaxDevices];   // per device: device address of `scratch`, NULL until looked up
+std::mutex g_scratch_mutex;
+
+// Device address of this device's copy of the array (looked up on the first call per device).
+dpsgd_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevices) return DPSGD_EDEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return DPSGD_EDEVICE;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return DPSGD_OK;
+}
+
+// CSR of the 2-D torus (both dimensions >= 3, so the five neighbours are distinct): worker i = r * C + c, itself and
+// (r +- 1, c), (r, c +- 1) at weight w, columns ascending.  One thread per worker.
+__global__ void __launch_bounds__(256) torus_csr_kernel(int R, int C, float w, int *__restrict__ rowptr,
+                                                        int *__restrict__ colidx, float *__restrict__ vals)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int n = R * C;
+    if (i > n) return;
+    rowptr[i] = 5 * i;
+    if (i == n) return;
+    const int r = i / C, c = i % C;
+    int nb[5] = {i, ((r + 1) % R) * C + c, ((r + R - 1) % R) * C + c, r * C + (c + 1) % C, r * C + (c + C - 1) % C};
+    for (int a = 1; a < 5; ++a) {   // insertion sort of five
+        const int v = nb[a];
+        int b = a - 1;
+        while (b >= 0 && nb[b] > v) {
+            nb[b + 1] = nb[b];
+            --b;
+        }
+        nb[b + 1] = v;
+    }
+    for (int a = 0; a < 5; ++a) {
+        colidx[5 * i + a] = nb[a];
+        vals[5 * i + a] = w;
+    }
+}
+
+bool ranges_overlap(const void *a, const void *b, size_t bytes)
+{
+    const char *pa = (const char *)a, *pb = (const char *)b;
+    return pa < pb + bytes && pb < pa + bytes;
+}
+
+}  // namespace
 }  // namespace dpsgd
+
+extern "C" dpsgd_status dpsgd_mix_step_static(int32_t n, int64_t d, int64_t ld, const dpsgd_topology *W, float gamma,
+                                              const float *X_in, const float *G, float *X_out, float *consensus,
+                                              void *hip_stream)
+{
+    using namespace dpsgd;
+    if (n < 1 || d < 1 || !W || !X_in || !G || !X_out || !(gamma == gamma) || gamma - gamma != 0.f) return DPSGD_EINVAL;
+    if (ld == 0) ld = d;
+    if (ld < d || (double)n * (double)ld > 9.0e18 / 4.0) return DPSGD_EINVAL;
+    const size_t bytes = (size_t)n * (size_t)ld * sizeof(float);
+    if (ranges_overlap(G, X_out, bytes)) return DPSGD_EINVAL;
+    if (X_out != X_in && ranges_overlap(X_in, X_out, bytes)) return DPSGD_EINVAL;
+    const bool ring = W->kind == DPSGD_TOPO_RING && n >= 3;
+    const bool torus = W->kind == DPSGD_TOPO_TORUS2D && W->dim0 >= 3 && W->dim1 >= 3 && (int64_t)W->dim0 * W->dim1 == n;
+    if (W->kind == DPSGD_TOPO_TORUS2D && (W->dim0 < 1 || W->dim1 < 1 || (int64_t)W->dim0 * W->dim1 != n)) return DPSGD_EINVAL;
+    // sizes beyond what the fixed array holds, and weight matrices that would need a CSR built on the host
+    if (!ring && !torus) return DPSGD_EUNSUPPORTED;
+    if (d > kStaticMaxD) return DPSGD_EUNSUPPORTED;
+    if (torus && n > kStaticMaxTorusN) return DPSGD_EUNSUPPORTED;
+
+    void *base = nullptr;
+    dpsgd_status st = static_scratch(&base);
+    if (st != DPSGD_OK) return st;
+
+    dpsgd_ctx ctx;   // a description on the stack: owns nothing, frees nothing
+    ctx.n = n;
+    ctx.d = d;
+    ctx.ld = ld;
+    ctx.gamma = gamma;
+    ctx.stream = (hipStream_t)hip_stream;
+    ctx.topo_kind = W->kind;
+    ctx.dim0 = W->dim0;
+    ctx.dim1 = W->dim1;
+    ctx.d_partials = (double *)base;
+    ctx.partials_cap = (int64_t)(kStaticPartialBytes / sizeof(double));
+    if (mix_partials_needed(&ctx) > ctx.partials_cap) return DPSGD_EUNSUPPORTED;
+    if (ring) {
+        ctx.ring_uniform = true;
+        ctx.ring_w = (float)(1.0 / 3.0);
+    } else {
+        ctx.torus_uniform = true;
+        ctx.torus_w = (float)(1.0 / 5.0);
+        unsigned char *csr = (unsigned char *)base + kStaticPartialBytes;
+        ctx.d_rowptr = (int32_t *)csr;
+        ctx.d_colidx = (int32_t *)(csr + 2048);              // (256 + 1) * 4 bytes of row pointers fit in front
+        ctx.d_vals = (float *)(csr + 2048 + 5 * kStaticMaxTorusN * sizeof(int32_t));
+        hipLaunchKernelGGL(torus_csr_kernel, dim3((unsigned)(n / 256 + 1)), dim3(256), 0, ctx.stream, W->dim0, W->dim1,
+                           ctx.torus_w, ctx.d_rowptr, ctx.d_colidx, ctx.d_vals);
+        if (hipGetLastError() != hipSuccess) return DPSGD_EDEVICE;
+    }
+    return launch_mix(&ctx, X_in, G, X_out, consensus, false);
+}
+

@@ -162,3 +162,34 @@ def test_create_rejects_bad_arguments_before_any_device_call():
     assert L.dpsgd_mix_step(None, None, None, None, None) == B.EINVAL
     assert L.dpsgd_mean(None, None, None) == B.EINVAL
     assert L.dpsgd_grad(None, None, None, None, None, None) == B.EINVAL
+
+
+def test_static_mix_step_rejects_what_its_fixed_array_cannot_hold_before_any_device_call():
+    """dpsgd_mix_step_static: argument errors and sizes beyond its fixed device array are decided on the host, so
+    the statuses come back on a machine without a GPU."""
+    L = B.load()
+    fake = C.c_void_p(0x1000)                      # never dereferenced: every case below is refused first
+
+    def call(n, d, ld, topo, x_in=fake, g=C.c_void_p(0x40000000), x_out=fake, gamma=0.1):
+        t = topo._c()
+        return L.dpsgd_mix_step_static(n, d, ld, C.byref(t), C.c_float(gamma), x_in, g, x_out, None, None)
+
+    ring, torus = B.Topology.ring(), B.Topology.torus
+    assert call(8, 64, 64, ring, x_in=None) == B.EINVAL
+    assert call(8, 64, 64, ring, g=None) == B.EINVAL
+    assert call(0, 64, 64, ring) == B.EINVAL
+    assert call(8, 0, 0, ring) == B.EINVAL
+    assert call(8, 64, 63, ring) == B.EINVAL                      # ld < d
+    assert call(8, 64, 64, ring, gamma=float("nan")) == B.EINVAL
+    assert call(8, 64, 64, ring, g=fake) == B.EINVAL              # G aliases X_out
+    assert call(8, 64, 64, ring, x_out=C.c_void_p(0x1100)) == B.EINVAL   # X_out overlaps X_in without being it
+    assert call(12, 64, 64, torus(3, 5)) == B.EINVAL              # 3 x 5 is not 12 workers
+    # valid requests the fixed array has no room or no kernel for
+    assert call(8, (1 << 25) + 1, 0, ring, g=C.c_void_p(1 << 40)) == B.EUNSUPPORTED
+    assert call(2, 64, 64, ring) == B.EUNSUPPORTED                # coinciding neighbours need a CSR
+    assert call(16, 64, 64, torus(2, 8)) == B.EUNSUPPORTED
+    assert call(17 * 16, 64, 64, torus(17, 16)) == B.EUNSUPPORTED # 272 workers: slab beyond the fixed CSR room
+    assert call(8, 64, 64, B.Topology.complete()) == B.EUNSUPPORTED
+    assert call(8, 64, 64, B.Topology.ring_chord()) == B.EUNSUPPORTED
+    rowptr, col, val = B.topology_build(8, ring)
+    assert call(8, 64, 64, B.Topology.csr(rowptr, col, val)) == B.EUNSUPPORTED
