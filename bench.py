@@ -28,11 +28,38 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
-# scaled by what the same counters read for a plain copy of known size (2.0 and 1.0); see profiles/.
-MEASURED_TRAFFIC = {("mlp3_ring64", "two-call"): 22.80e9,     # mix_ring_fat_kernel
-                    ("mlp3_ring64", "fused"): 7.89e9,         # mlp_fused_ring_rows_kernel, average of its two launches
-                    ("mlp3_torus8x8", "fused"): 8.13e9}       # mlp_fused_torus_cols_kernel, likewise
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def traffic_from_profile(workload, path, kernel, ld):
+    """HBM bytes per launch of the dominant kernel as a rocprofv3 --pmc run of this very command counted them
+    (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a plain copy of known size).  A counter
+    run cannot happen inside a timed run, so the figure comes from the committed summary under profiles/ that
+    carries a machine-readable line
+
+        bench-traffic: {"workload": ..., "path": ..., "kernel": ..., "ld": ..., "bytes_per_launch": ...}
+
+    and is used only if workload, path, kernel name and row stride all match what this run launched; otherwise
+    None.  Returns (bytes or None, file name or None)."""
+    try:
+        names = sorted(os.listdir(PROFILES))
+    except OSError:
+        return None, None
+    for name in names:
+        if not name.endswith((".md", ".txt")):
+            continue
+        try:
+            with open(os.path.join(PROFILES, name)) as f:
+                for line in f:
+                    if "bench-traffic:" not in line:
+                        continue
+                    rec = json.loads(line.split("bench-traffic:", 1)[1].strip().rstrip("->").strip())
+                    if (rec.get("workload") == workload and rec.get("path") == path and rec.get("ld") == ld
+                            and rec.get("kernel") and rec["kernel"] in kernel):
+                        return float(rec["bytes_per_launch"]), name
+        except (OSError, ValueError):
+            continue
+    return None, None
 
 
 def parse():
@@ -69,6 +96,11 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="after the eager pass, record the K iterations into one HIP graph and report the timed "
                          "replay of it as the value (pays where the iteration is launch-bound: the small workloads)")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="the timed region (exactly --steps iterations) is run this many times; the median repeat is reported")
+    ap.add_argument("--no-others", action="store_true",
+                    help="the default run also times every other workload of the benchmark definition in short runs after "
+                         "the headline (the `others` array of the JSON line); this leaves them out")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (reference for the FETCH_SIZE / WRITE_SIZE "
                          "counters under rocprofv3 --pmc) and exit")
@@ -121,14 +153,20 @@ def cpu_baseline(cfg, seconds_budget=20.0):
     t_mix = (time.perf_counter() - t0) * (d / dcols)
     # m workers ran on min(m, threads) cores at once; all n workers need n/m such rounds
     t_iter = t_grad * (cfg.n / m) + t_mix
-    # each thread took ceil(m / threads) workers in turn, so one worker's gradient costs one core about this long
-    per_worker = t_grad / (-(-m // max(1, min(threads, m))))
-    t_iter_1 = per_worker * cfg.n + t_mix
+    # one core, measured: one worker's gradient through the single-worker entry of the oracle (no OpenMP inside a
+    # worker), scaled by n; the mix sample above already ran on one thread
+    t0 = time.perf_counter()
+    oracle.loss_grad(cfg.model_kind, cfg.widths, X[0], inp[0], tgt[0])
+    t_one = time.perf_counter() - t0
+    t_iter_1 = t_one * cfg.n + t_mix
     return {
         "value": cfg.n / t_iter, "unit": "worker-iters/s", "cores": int(min(threads, m)), "kind": "oracle",
-        "single_thread_estimate": cfg.n / t_iter_1, "cpu_model": _cpu_model(),
+        "cpu_model": _cpu_model(),
         "sample": f"gradient of {m} of {cfg.n} workers (one minibatch each, OpenMP over workers, {t_grad:.2f} s) "
                   f"scaled by n/{m}; mix+step on {dcols} of {d} columns (single thread, scaled to d)",
+        "single_thread": {"value": cfg.n / t_iter_1, "unit": "worker-iters/s", "cores": 1,
+                          "sample": f"gradient of 1 of {cfg.n} workers on one core ({t_one:.2f} s, measured) scaled by n; "
+                                    f"the same mix+step sample"},
     }
 
 
@@ -178,24 +216,10 @@ def gradient_roofline(cfg, d, step_ms):
             "frac_of_ceiling": achieved / peak / ceiling, "timed_over": "whole iteration (gradient + mix)"}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no sharding across GPUs); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def run_one(args, with_cpu_baseline):
+    """Times one workload as the flags in `args` say and returns its record (the fields of the JSON line)."""
     import numpy as np
     import torch
-
-    if args.calibrate_copy:
-        torch.cuda.set_device(0)
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")    # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
-        return
 
     from paper_1705_09056_amd import binding as B
     from paper_1705_09056_amd import synth
@@ -209,9 +233,7 @@ def main():
         variant = f"batch={cfg.batch}, n={cfg.n}: kernel check, not a benchmark configuration"
     K = args.steps or cfg.iters
     W = args.warmup
-    torch.cuda.set_device(0)
-    if args.graph:   # capture needs a stream other than the default one; the library launches on torch's current stream
-        torch.cuda.set_stream(torch.cuda.Stream())
+    R = max(1, args.repeats)
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     topo = B.Topology.ring() if cfg.topology == "ring" else B.Topology.torus(*cfg.torus_dims)
     ld = synth.padded_stride(d, args.ld_multiple) if args.ld_multiple else B.recommended_ld(d, topo)
@@ -250,7 +272,7 @@ def main():
             w_in, w_out = cfg.widths[l], cfg.widths[l + 1]
             if w_in % (128 if ring_ok else 32) == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
                 fused_weights += w_in * w_out
-                rows_kernel.append(ring_ok and cfg.batch <= 32 and w_in % 256 == 0 and not args.shadow)
+                rows_kernel.append(ring_ok and cfg.batch <= 32 and w_in % 256 == 0 and ld % 4 == 0 and args.ring_rows != 0)
                 if args.shadow and ring_ok and l >= 1:
                     shadow_weights += w_in * w_out
     fused = fused_weights > 0 and not args.two_call and not args.momentum and not args.overlap
@@ -302,34 +324,42 @@ def main():
     for k in range(W):
         step(k)
     torch.cuda.synchronize()
-    # HIP events on the stream the library launches on (torch's current stream was handed to dpsgd_create)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
-    t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
     if fused:
         ctx.set_option("time_fused", 1)
+    # R repeats of the timed region; each is EXACTLY K iterations between two HIP events on the stream the library
+    # launches on (torch's current stream was handed to dpsgd_create).  The repeat with the median time is reported.
+    repeats = []
     wall0 = time.perf_counter()
-    t_begin.record()
-    for k in range(K):
-        step(W + k, evs[k])
-    t_end.record()
-    torch.cuda.synchronize()
+    for r in range(R):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+        t_begin, t_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t_begin.record()
+        for k in range(K):
+            step(W + r * K + k, evs[k])
+        t_end.record()
+        torch.cuda.synchronize()
+        rec = {"total_ms": t_begin.elapsed_time(t_end)}
+        if fused:
+            rec["kernel_ms"], rec["launches"] = ctx.read_timing()
+        else:
+            rec["kernel_ms"], rec["launches"] = sum(a.elapsed_time(b) for a, b in evs), K
+        repeats.append(rec)
     wall = time.perf_counter() - wall0
-    total_ms = t_begin.elapsed_time(t_end)
+    med = sorted(repeats, key=lambda q: q["total_ms"])[len(repeats) // 2]
+    total_ms = med["total_ms"]
+    launch_ms = med["kernel_ms"] / med["launches"]
+    mix_ms = med["kernel_ms"] / K
     if fused:
-        fused_ms, launches = ctx.read_timing()
         ring_name = "mlp_fused_ring_rows_kernel" if all(rows_kernel) else "mlp_fused_ring_kernel" if not any(rows_kernel) \
             else "mlp_fused_ring_rows_kernel / mlp_fused_ring_kernel"
         kernel_name = (ring_name if ring_ok else "mlp_fused_torus_cols_kernel") + \
             " (weight gradient + Algorithm 1 steps 4-5, in place)"
-        launch_ms = fused_ms / launches
-        launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / launches
-        mix_ms = fused_ms / K
+        launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / med["launches"]
     else:
+        mix_kernel = ("mix_ring_fat_kernel" if d >= 8192 * 2048 else "mix_ring_kernel") if ring_ok else "mix_csr_slab_kernel"
         kernel_name = "update pass X = (W X) - gamma G (identity as W)" if args.overlap else \
-            "mix_step (Algorithm 1 steps 4-5 fused)"
-        mix_ms = sum(a.elapsed_time(b) for a, b in evs) / K
-        launch_ms = mix_ms
+            f"dpsgd_mix_step: {mix_kernel} (Algorithm 1 steps 4-5 fused) + consensus reduction"
         launch_bytes = (20.0 if Vel is not None else 12.0) * cfg.n * d
     graph_ms = None
     if args.graph:
@@ -368,6 +398,9 @@ def main():
     eager_ms = total_ms
     if graph_ms is not None:
         total_ms = graph_ms
+    path = "fused" if fused else "two-call"
+    traffic, traffic_file = (None, None) if (variant or args.shadow or args.no_consensus) else \
+        traffic_from_profile(cfg.name, path, kernel_name, ld)
     out = {
         "metric": "worker-iters/sec (grad+mix) at n workers",
         "value": cfg.n * K / (total_ms * 1e-3),
@@ -387,10 +420,11 @@ def main():
                        "eager_ms_per_step": eager_ms / K} if graph_ms is not None else {}),
                    **({"bf16_shadow": True} if args.shadow else {}),
                    **({"variant": variant} if variant else {})},
+        "timing": {"repeats": R, "reported": "the repeat with the median time; each repeat is exactly `steps` iterations",
+                   "ms_per_step_of_each_repeat": [q["total_ms"] / K for q in repeats]},
         "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if (variant or args.shadow) else
-                     MEASURED_TRAFFIC.get((cfg.name, "fused" if fused else "two-call")),
+                     "traffic": traffic, "traffic_source": traffic_file and f"profiles/{traffic_file}",
                      "algorithmic_bytes_per_launch": launch_bytes, "avg_launch_ms": launch_ms},
         "gradient": gradient_roofline(cfg, d, total_ms / K),
         "mean": {"kernel": "dpsgd_mean (Algorithm 1 step 7)", "ms": mean_ms, "algorithmic_bytes": 4.0 * cfg.n * d,
@@ -400,8 +434,63 @@ def main():
         "wall_s": wall,
         "final_mean_loss": final_loss, "final_consensus": final_cons,
     }
-    if not args.no_cpu_baseline and not variant:
+    if with_cpu_baseline and not variant:
         out["cpu_baseline"] = cpu_baseline(cfg)
+    del X, G, pool, Vel, xbar
+    torch.cuda.empty_cache()
+    return out
+
+
+# The other workloads of the benchmark definition, each as a short run after the headline's timed region, so that one
+# invocation witnesses every configuration: (workload, extra flags).  The two-call run of the default workload is the
+# one whose dominant kernel is dpsgd_mix_step itself (12 bytes per worker and parameter).
+OTHERS = (("mlp3_ring64", {"two_call": True}), ("mlp3_torus8x8", {}), ("mlp3_torus8x8", {"two_call": True}),
+          ("mlp2_ring32", {}), ("resnet20_ring112", {}), ("softmax_ring16", {}), ("lsq_ring8", {}))
+
+
+def short_record(rec):
+    """What the `others` array keeps of a run."""
+    g = rec["gradient"]
+    return {"workload": rec["config"]["workload"], "path": rec["config"]["path"], "steps": rec["steps"],
+            "warmup": rec["warmup"], "repeats": rec["timing"]["repeats"], "ms_per_step": rec["ms_per_step"],
+            "value": rec["value"], "unit": rec["unit"], "dtype": rec["dtype"],
+            "dominant_kernel": rec["roofline"]["kernel"], "bound": "hbm", "achieved": rec["roofline"]["achieved"],
+            "frac": rec["roofline"]["frac"], "avg_launch_ms": rec["roofline"]["avg_launch_ms"],
+            "algorithmic_bytes_per_launch": rec["roofline"]["algorithmic_bytes_per_launch"],
+            "gradient_tflops": g["achieved_tflops"], "gradient_frac_of_peak": g["frac_of_peak"],
+            "gradient_frac_of_intensity_ceiling": g["frac_of_ceiling"], "gradient_peak_kind": g["peak_kind"]}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding across GPUs); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")    # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
+
+    torch.cuda.set_device(0)
+    if args.graph:   # capture needs a stream other than the default one; the library launches on torch's current stream
+        torch.cuda.set_stream(torch.cuda.Stream())
+    out = run_one(args, not args.no_cpu_baseline)
+    plain = not (args.batch or args.workers or args.two_call or args.momentum or args.overlap or args.shadow or
+                 args.graph or args.ld_multiple or args.ring_rows >= 0 or args.no_consensus)
+    if plain and args.workload == "mlp3_ring64" and not args.no_others:
+        others = []
+        for name, extra in OTHERS:
+            a = argparse.Namespace(**{**vars(args), "workload": name, "steps": 10, "warmup": 3, "repeats": 3, **extra})
+            others.append(short_record(run_one(a, False)))
+        out["others"] = others
     print(json.dumps(out))
 
 

@@ -222,12 +222,21 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
     }
 }
 
-// The same walk for wide matrices with fat lanes: one wave per workgroup, every lane owns P float4 column groups
-// 1 KB apart (the wave covers P KB of a row), U rows in flight.  Fewer, fatter waves keep more bytes in flight per
-// memory instruction stream: a bare copy-like probe of this walk moves 5.2 TB/s with one float4 per lane and 5.5-5.6
-// with eight.  No row bands, no momentum (those stay with mix_ring_kernel); the shift of the consensus sums is
-// worker 0's ORIGINAL value, which the lane keeps anyway for the ring's wrap-around.  Same arithmetic, same order
-// as mix_ring_kernel.  grid.x = ncols / (256 P) (whole groups only: no lane is ever idle), block 64; 16-byte aligned rows.
+// The same walk for wide matrices with fat lanes: one wave per workgroup, every lane owns P float4 column groups, U
+// rows in flight.  Fewer, fatter waves keep more bytes in flight per memory instruction stream, and WHICH columns a
+// wave owns decides how its accesses fall on the HBM channels: with the wave's row footprint cut into chunks of 512
+// bytes (half a wave per chunk) that sit 32 KB apart, the walk moves 6.2 TB/s at 64 workers x 29.4 M columns where
+// the same walk over 8 KB of consecutive columns moves 5.4 (1 KB chunks 32 or 64 KB apart: 5.9; 512-byte chunks at
+// other distances, and 256-byte chunks at any distance: 5.2-5.9).  So the columns are dealt out in super-blocks of
+// kFatSuper = 2 P x 8192 floats: workgroup k of a super-block (k < 64) owns the 2 P chunks that start
+// k x 128 floats into each 32 KB stripe.
+// No row bands, no momentum (those stay with mix_ring_kernel); the shift of the consensus sums is worker 0's ORIGINAL
+// value, which the lane keeps anyway for the ring's wrap-around.  Same arithmetic, same order as mix_ring_kernel.
+// grid.x = 64 x (ncols / kFatSuper) (whole super-blocks only: no lane is ever idle), block 64; 16-byte aligned rows.
+constexpr int kFatChunkLanes = 32;        // lanes per chunk: 512 bytes
+constexpr i64 kFatStride = 8192;          // floats between two chunks of a wave: 32 KB
+template <int P> constexpr i64 fat_super() { return (i64)P * (64 / kFatChunkLanes) * kFatStride; }
+
 template <int P, int U, bool CONS>
 __global__ void __launch_bounds__(64)
 mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ld, float w, float gamma,
@@ -235,12 +244,16 @@ mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
 {
     typedef VecT<4>::type vec;
     const int lane = threadIdx.x;
-    const i64 c0 = ((i64)blockIdx.x * P * 64 + lane) * 4;   // group q starts 256 columns further
+    constexpr i64 kPerSuper = kFatStride / (kFatChunkLanes * 4);   // workgroups per super-block: 64
+    constexpr i64 kStep = (64 / kFatChunkLanes) * kFatStride;      // floats between a lane's column groups q and q + 1
+    const i64 sb = blockIdx.x / kPerSuper, k = blockIdx.x % kPerSuper;
+    const i64 c0 = sb * fat_super<P>() + k * (kFatChunkLanes * 4) + (lane % kFatChunkLanes) * 4 +
+                   (i64)(lane / kFatChunkLanes) * kFatStride;
     vec xm[P], xc[P], x0[P], s1[P];
     float s2 = 0.f;
 #pragma unroll
     for (int q = 0; q < P; ++q) {
-        const i64 c = c0 + (i64)q * 256;
+        const i64 c = c0 + (i64)q * kStep;
         xm[q] = vload<4>(Xin + (i64)(n - 1) * ld + c);
         xc[q] = vload<4>(Xin + c);
         x0[q] = xc[q];
@@ -249,7 +262,7 @@ mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
     auto form = [&](int row, int q, vec xs, vec g) {
         const vec xn = row + 1 < n ? xs : x0[q];   // the ring closes on worker 0's original row
         const vec o = ring_update(w, xm[q], xc[q], xn, gamma, g);
-        __builtin_nontemporal_store(o, reinterpret_cast<vec *>(Xout + (i64)row * ld + c0 + (i64)q * 256));
+        __builtin_nontemporal_store(o, reinterpret_cast<vec *>(Xout + (i64)row * ld + c0 + (i64)q * kStep));
         if (CONS) {
             const vec e = o - x0[q];
             s1[q] += e;
@@ -266,7 +279,7 @@ mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
             const int rn = row + u + 1 < n ? row + u + 1 : n - 1;   // (the last row's successor is x0: clamped, unused)
 #pragma unroll
             for (int q = 0; q < P; ++q) {
-                const i64 c = c0 + (i64)q * 256;
+                const i64 c = c0 + (i64)q * kStep;
                 gs[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(G + (i64)(row + u) * ld + c));
                 xs[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Xin + (i64)rn * ld + c));
             }
@@ -280,7 +293,7 @@ mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
         const int rn = row + 1 < n ? row + 1 : n - 1;
 #pragma unroll
         for (int q = 0; q < P; ++q) {
-            const i64 c = c0 + (i64)q * 256;
+            const i64 c = c0 + (i64)q * kStep;
             const vec g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(G + (i64)row * ld + c));
             const vec x = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Xin + (i64)rn * ld + c));
             form(row, q, x, g);
@@ -555,12 +568,13 @@ dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float
 {
     const i64 groups = groups_for(ncols, V);
     const int bands = pick_bands(ctx, groups);
-    constexpr int kFatP = 8;               // float4 groups per lane of the fat-lane kernel
-    constexpr i64 kFatMinGroups = 8192;   // it needs that many single-wave workgroups to fill the chip
+    constexpr int kFatP = 8;              // float4 groups per lane of the fat-lane kernel
+    constexpr i64 kFatMinSupers = 64;     // 64 x 64 single-wave workgroups: enough to fill the chip
     if (V == 4 && !Vel && bands == 1 && !narrow && !ctx->opt_mix_narrow && ctx->opt_mix_bands == 0 && ctx->n >= 3 &&
-        ncols / (256 * kFatP) >= kFatMinGroups) {
-        // wide matrix: whole groups of 2048 columns go to the fat-lane kernel, the rest to the kernel below
-        const i64 fat_groups = ncols / (256 * kFatP), fat_cols = fat_groups * 256 * kFatP;
+        ncols / fat_super<kFatP>() >= kFatMinSupers) {
+        // wide matrix: whole super-blocks of columns go to the fat-lane kernel, the rest to the kernel below
+        const i64 supers = ncols / fat_super<kFatP>(), fat_cols = supers * fat_super<kFatP>();
+        const i64 fat_groups = supers * (kFatStride / (kFatChunkLanes * 4));
         if (fat_groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
         if (cons)
             hipLaunchKernelGGL((mix_ring_fat_kernel<kFatP, 1, true>), dim3((unsigned)fat_groups), dim3(64), 0, ctx->stream,
