@@ -230,17 +230,17 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
 // other distances, and 256-byte chunks at any distance: 5.2-5.9).  So the columns are dealt out in super-blocks of
 // kFatSuper = 2 P x 8192 floats: workgroup k of a super-block (k < 64) owns the 2 P chunks that start
 // k x 128 floats into each 32 KB stripe.
-// No row bands, no momentum (those stay with mix_ring_kernel); the shift of the consensus sums is worker 0's ORIGINAL
+// No row bands (those stay with mix_ring_kernel); MOM is the heavy-ball variant as there.  The shift of the consensus sums is worker 0's ORIGINAL
 // value, which the lane keeps anyway for the ring's wrap-around.  Same arithmetic, same order as mix_ring_kernel.
 // grid.x = 64 x (ncols / kFatSuper) (whole super-blocks only: no lane is ever idle), block 64; 16-byte aligned rows.
 constexpr int kFatChunkLanes = 32;        // lanes per chunk: 512 bytes
 constexpr i64 kFatStride = 8192;          // floats between two chunks of a wave: 32 KB
 template <int P> constexpr i64 fat_super() { return (i64)P * (64 / kFatChunkLanes) * kFatStride; }
 
-template <int P, int U, bool CONS>
+template <int P, int U, bool CONS, bool MOM>
 __global__ void __launch_bounds__(64)
 mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ld, float w, float gamma,
-                    double *__restrict__ partials)
+                    double *__restrict__ partials, float *__restrict__ Vel, float mu)
 {
     typedef VecT<4>::type vec;
     const int lane = threadIdx.x;
@@ -272,8 +272,16 @@ mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
         xc[q] = xn;
     };
     int row = 0;
+    // the direction of the step: the gradient itself, or (MOM) the velocity mu v + g, which is written back
+    auto step_dir = [&](int row, int q, vec g, vec v) {
+        if (MOM) {
+            g = mu * v + g;
+            __builtin_nontemporal_store(g, reinterpret_cast<vec *>(Vel + (i64)row * ld + c0 + (i64)q * kStep));
+        }
+        return g;
+    };
     for (; row + U <= n; row += U) {
-        vec xs[U][P], gs[U][P];
+        vec xs[U][P], gs[U][P], vs[MOM ? U : 1][MOM ? P : 1];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int rn = row + u + 1 < n ? row + u + 1 : n - 1;   // (the last row's successor is x0: clamped, unused)
@@ -281,13 +289,14 @@ mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
             for (int q = 0; q < P; ++q) {
                 const i64 c = c0 + (i64)q * kStep;
                 gs[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(G + (i64)(row + u) * ld + c));
+                if (MOM) vs[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Vel + (i64)(row + u) * ld + c));
                 xs[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Xin + (i64)rn * ld + c));
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int q = 0; q < P; ++q) form(row + u, q, xs[u][q], gs[u][q]);
+            for (int q = 0; q < P; ++q) form(row + u, q, xs[u][q], step_dir(row + u, q, gs[u][q], MOM ? vs[u][q] : gs[u][q]));
     }
     for (; row < n; ++row) {
         const int rn = row + 1 < n ? row + 1 : n - 1;
@@ -295,8 +304,9 @@ mix_ring_fat_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
         for (int q = 0; q < P; ++q) {
             const i64 c = c0 + (i64)q * kStep;
             const vec g = __builtin_nontemporal_load(reinterpret_cast<const vec *>(G + (i64)row * ld + c));
+            const vec v = MOM ? __builtin_nontemporal_load(reinterpret_cast<const vec *>(Vel + (i64)row * ld + c)) : g;
             const vec x = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Xin + (i64)rn * ld + c));
-            form(row, q, x, g);
+            form(row, q, x, step_dir(row, q, g, v));
         }
     }
     if (CONS) {
@@ -386,6 +396,114 @@ mix_csr_slab_kernel(const float *Xin, const float *__restrict__ G, float *Xout, 
             double v = wave_sum((double)st.m2());
             if (lane == 0) partials[blockIdx.x] = v;
         }
+    }
+}
+
+// The same for wide matrices, 16-byte accesses, whole super-blocks of columns: every lane owns SP float4 column
+// vectors and the workgroup's 64 x SP vectors are 2 SP chunks of 512 bytes that sit 32 KB apart instead of consecutive
+// columns - workgroup k of a super-block of 2 SP x 8192 columns owns the chunks that start k x 128 floats into each
+// of its 32 KB stripes - which the HBM channels serve faster (see mix_ring_fat_kernel).  Slab: [n][SP][64] float4.
+// grid.x = 64 x (ncols / slab_super<SP>()), every lane active.
+template <int SP> constexpr i64 slab_super() { return (i64)2 * SP * 8192; }
+
+template <int SP, bool CONS, bool SWAPPED>
+__global__ void __launch_bounds__(512)
+mix_csr_slab_wide_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ld,
+                         const int *__restrict__ rowptr, const int *__restrict__ colidx, const float *__restrict__ vals,
+                         float gamma, int rgroups, double *__restrict__ partials, float *__restrict__ Vel, float mu)
+{
+    typedef VecT<4>::type vec;
+    extern __shared__ float lds[];
+    vec *slab = reinterpret_cast<vec *>(lds);
+    const int lane = threadIdx.x & 63;
+    const int rg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const i64 c0 = (i64)(blockIdx.x / 64) * slab_super<SP>() + (i64)(blockIdx.x % 64) * 128 + (lane % 32) * 4 +
+                   (i64)(lane / 32) * 8192;      // column vector q of this lane: c0 + q * 16384
+    auto stage = [&](int row, vec (&x)[SP]) {
+#pragma unroll
+        for (int q = 0; q < SP; ++q) {
+            x[q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(Xin + (i64)row * ld + c0 + q * 16384));
+            if (SWAPPED) x[q] = x[q] - gamma * vload<4>(G + (i64)row * ld + c0 + q * 16384);
+        }
+    };
+    auto put = [&](int row, const vec (&x)[SP]) {
+#pragma unroll
+        for (int q = 0; q < SP; ++q) slab[((size_t)row * SP + q) * 64 + lane] = x[q];
+    };
+    {
+        int row = rg;
+        for (; row + rgroups < n; row += 2 * rgroups) {   // two rows of SP vectors in flight
+            vec a[SP], b[SP];
+            stage(row, a);
+            stage(row + rgroups, b);
+            put(row, a);
+            put(row + rgroups, b);
+        }
+        for (; row < n; row += rgroups) {
+            vec a[SP];
+            stage(row, a);
+            put(row, a);
+        }
+    }
+    __syncthreads();   // the whole slab is in LDS; from here on rows may be overwritten
+
+    ColStats<4> st[SP];
+#pragma unroll
+    for (int q = 0; q < SP; ++q) st[q].init();
+    auto gload = [&](int row, vec (&g)[SP]) {
+#pragma unroll
+        for (int q = 0; q < SP; ++q) {
+            if (SWAPPED) { g[q] = (vec)(0.f); continue; }
+            g[q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(G + (i64)row * ld + c0 + q * 16384));
+            if (Vel) {
+                float *vdst = Vel + (i64)row * ld + c0 + q * 16384;
+                g[q] = mu * vload<4>(vdst) + g[q];
+                vstore<4>(vdst, g[q]);
+            }
+        }
+    };
+    auto form = [&](int row, const vec (&g)[SP]) {
+        const int p0 = rowptr[row], p1 = rowptr[row + 1];
+        vec acc[SP];
+#pragma unroll
+        for (int q = 0; q < SP; ++q) acc[q] = (vec)(0.f);
+        for (int p = p0; p < p1; ++p) {
+            const float wv = vals[p];
+            const size_t src = (size_t)colidx[p] * SP;
+#pragma unroll
+            for (int q = 0; q < SP; ++q) acc[q] = wv * slab[(src + q) * 64 + lane] + acc[q];
+        }
+#pragma unroll
+        for (int q = 0; q < SP; ++q) {
+            const vec o = SWAPPED ? acc[q] : acc[q] - gamma * g[q];
+            __builtin_nontemporal_store(o, reinterpret_cast<vec *>(Xout + (i64)row * ld + c0 + q * 16384));
+            if (CONS) st[q].add(o);
+        }
+    };
+    {
+        int row = rg;
+        for (; row + rgroups < n; row += 2 * rgroups) {
+            vec g0[SP], g1[SP];
+            gload(row, g0);
+            gload(row + rgroups, g1);
+            form(row, g0);
+            form(row + rgroups, g1);
+        }
+        for (; row < n; row += rgroups) {
+            vec g0[SP];
+            gload(row, g0);
+            form(row, g0);
+        }
+    }
+    if (CONS) {
+        double v = 0.0;
+#pragma unroll
+        for (int q = 0; q < SP; ++q) {
+            __syncthreads();   // the slab (q = 0) or the previous vector's statistics are no longer needed
+            combine_bands<4>(st[q], lds, rg, lane, rgroups);
+            if (rg == 0) v += wave_sum((double)st[q].m2());
+        }
+        if (rg == 0 && lane == 0) partials[blockIdx.x] = v;
     }
 }
 
@@ -570,18 +688,21 @@ dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float
     const int bands = pick_bands(ctx, groups);
     constexpr int kFatP = 8;              // float4 groups per lane of the fat-lane kernel
     constexpr i64 kFatMinSupers = 64;     // 64 x 64 single-wave workgroups: enough to fill the chip
-    if (V == 4 && !Vel && bands == 1 && !narrow && !ctx->opt_mix_narrow && ctx->opt_mix_bands == 0 && ctx->n >= 3 &&
+    if (V == 4 && bands == 1 && !narrow && !ctx->opt_mix_narrow && ctx->opt_mix_bands == 0 && ctx->n >= 3 &&
         ncols / fat_super<kFatP>() >= kFatMinSupers) {
         // wide matrix: whole super-blocks of columns go to the fat-lane kernel, the rest to the kernel below
         const i64 supers = ncols / fat_super<kFatP>(), fat_cols = supers * fat_super<kFatP>();
         const i64 fat_groups = supers * (kFatStride / (kFatChunkLanes * 4));
         if (fat_groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
-        if (cons)
-            hipLaunchKernelGGL((mix_ring_fat_kernel<kFatP, 1, true>), dim3((unsigned)fat_groups), dim3(64), 0, ctx->stream,
-                               Xin + col0, G + col0, Xout + col0, ctx->n, ctx->ld, ctx->ring_w, ctx->gamma, partials);
-        else
-            hipLaunchKernelGGL((mix_ring_fat_kernel<kFatP, 2, false>), dim3((unsigned)fat_groups), dim3(64), 0, ctx->stream,
-                               Xin + col0, G + col0, Xout + col0, ctx->n, ctx->ld, ctx->ring_w, ctx->gamma, partials);
+        float *velc = Vel ? Vel + col0 : nullptr;
+#define DPSGD_FAT(U, CONS, MOM)                                                                                          \
+    hipLaunchKernelGGL((mix_ring_fat_kernel<kFatP, U, CONS, MOM>), dim3((unsigned)fat_groups), dim3(64), 0, ctx->stream, \
+                       Xin + col0, G + col0, Xout + col0, ctx->n, ctx->ld, ctx->ring_w, ctx->gamma, partials, velc, mu)
+        if (cons && velc) DPSGD_FAT(1, true, true);
+        else if (cons) DPSGD_FAT(1, true, false);
+        else if (velc) DPSGD_FAT(1, false, true);
+        else DPSGD_FAT(1, false, false);
+#undef DPSGD_FAT
         dpsgd_status st = hip_status(hipGetLastError());
         i64 rest = 0;
         if (st == DPSGD_OK && fat_cols < ncols)
@@ -610,27 +731,76 @@ dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float
 
 constexpr size_t kSlabLdsBudget = 64 * 1024;
 
+// Wide part of a slab launch: whole super-blocks with SP float4 per lane.  Returns the columns it took (0: none).
+template <int SP, bool SWAPPED>
+dpsgd_status slab_wide_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols, bool cons,
+                              double *partials, float *vel, float mu, i64 *cols_done, i64 *parts)
+{
+    const i64 supers = ncols / slab_super<SP>();
+    const i64 groups = supers * 64;
+    if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
+    const int rgroups = ctx->n < 8 ? ctx->n : (SP > 1 ? 8 : 4);
+    size_t shm = (size_t)ctx->n * 64 * SP * 16;
+    if (cons && stats_lds_bytes(rgroups, 4) > shm) shm = stats_lds_bytes(rgroups, 4);
+    if (cons) {
+        auto k = mix_csr_slab_wide_kernel<SP, true, SWAPPED>;
+        if (shm > 64 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)
+            return DPSGD_EDEVICE;
+        hipLaunchKernelGGL(k, dim3((unsigned)groups), dim3(64u * (unsigned)rgroups), shm, ctx->stream, Xin + col0, G + col0,
+                           Xout + col0, ctx->n, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma, rgroups,
+                           partials, vel, mu);
+    } else {
+        auto k = mix_csr_slab_wide_kernel<SP, false, SWAPPED>;
+        if (shm > 64 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)
+            return DPSGD_EDEVICE;
+        hipLaunchKernelGGL(k, dim3((unsigned)groups), dim3(64u * (unsigned)rgroups), shm, ctx->stream, Xin + col0, G + col0,
+                           Xout + col0, ctx->n, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma, rgroups,
+                           partials, vel, mu);
+    }
+    *cols_done = supers * slab_super<SP>();
+    *parts = groups;
+    return hip_status(hipGetLastError());
+}
+
+constexpr size_t kSlabWideLdsBudget = 128 * 1024;   // one workgroup per CU with two float4 per lane
+
 template <int V, bool SWAPPED>
 dpsgd_status slab_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols,
                          bool cons, double *partials, i64 *nparts, float *Vel = nullptr, float mu = 0.f)
 {
     float *vel = Vel ? Vel + col0 : nullptr;
-    const i64 groups = groups_for(ncols, V);
+    // wide matrices: whole super-blocks of columns with the chunked column ownership, the rest consecutively
+    i64 done = 0, parts = 0;
+    if (V == 4 && !ctx->opt_mix_narrow) {
+        dpsgd_status st = DPSGD_OK;
+        if (ncols / slab_super<2>() >= 16 && (size_t)ctx->n * 64 * 2 * 16 <= kSlabWideLdsBudget && ctx->opt_mix_vec != 1)
+            st = slab_wide_launch<2, SWAPPED>(ctx, Xin, G, Xout, col0, ncols, cons, partials, vel, mu, &done, &parts);
+        else if (ncols / slab_super<1>() >= 32)
+            st = slab_wide_launch<1, SWAPPED>(ctx, Xin, G, Xout, col0, ncols, cons, partials, vel, mu, &done, &parts);
+        if (st != DPSGD_OK) return st;
+    }
+    const i64 groups = groups_for(ncols - done, V);
     if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
-    int rgroups = ctx->n < 4 ? ctx->n : 4;
-    size_t shm = (size_t)ctx->n * 64 * V * sizeof(float);
-    const size_t stats = stats_lds_bytes(rgroups, V);
-    if (cons && stats > shm) shm = stats;
-    dim3 grid((unsigned)groups), block(64u * (unsigned)rgroups);
-    if (cons)
-        hipLaunchKernelGGL((mix_csr_slab_kernel<V, true, SWAPPED>), grid, block, shm, ctx->stream, Xin + col0,
-                           G + col0, Xout + col0, ctx->n, ncols, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals,
-                           ctx->gamma, rgroups, partials, vel, mu);
-    else
-        hipLaunchKernelGGL((mix_csr_slab_kernel<V, false, SWAPPED>), grid, block, shm, ctx->stream, Xin + col0,
-                           G + col0, Xout + col0, ctx->n, ncols, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals,
-                           ctx->gamma, rgroups, partials, vel, mu);
-    *nparts = groups;
+    if (groups > 0) {
+        int rgroups = ctx->n < 4 ? ctx->n : 4;
+        size_t shm = (size_t)ctx->n * 64 * V * sizeof(float);
+        const size_t stats = stats_lds_bytes(rgroups, V);
+        if (cons && stats > shm) shm = stats;
+        dim3 grid((unsigned)groups), block(64u * (unsigned)rgroups);
+        const float *xi = Xin + col0 + done, *gi = G + col0 + done;
+        float *xo = Xout + col0 + done, *ve = vel ? vel + done : nullptr;
+        if (cons)
+            hipLaunchKernelGGL((mix_csr_slab_kernel<V, true, SWAPPED>), grid, block, shm, ctx->stream, xi, gi, xo, ctx->n,
+                               ncols - done, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma, rgroups,
+                               partials + parts, ve, mu);
+        else
+            hipLaunchKernelGGL((mix_csr_slab_kernel<V, false, SWAPPED>), grid, block, shm, ctx->stream, xi, gi, xo, ctx->n,
+                               ncols - done, ctx->ld, ctx->d_rowptr, ctx->d_colidx, ctx->d_vals, ctx->gamma, rgroups,
+                               partials + parts, ve, mu);
+    }
+    *nparts = parts + groups;
     return hip_status(hipGetLastError());
 }
 

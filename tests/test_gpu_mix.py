@@ -86,6 +86,30 @@ def test_torus(dims, inplace):
         run_mix(n, d, ld, B.Topology.torus(*dims), oracle.torus(*dims).with_fp32_values(), n + d, inplace, True)
 
 
+@pytest.mark.parametrize("inplace", [False, True])
+def test_wide_matrices_through_the_slab_kernel(inplace):
+    """Wide matrices: the LDS-slab kernel deals whole super-blocks of columns to its workgroups as 512-byte chunks
+    32 KB apart (two float4 per lane while 64 workers' rows fit 128 KB of LDS, one beyond that), the remaining columns
+    consecutively, the last d % 4 one by one."""
+    d, ld = 33 * 16384 + 1000 + 3, 33 * 16384 + 1024
+    run_mix(12, d, ld, B.Topology.torus(3, 4), oracle.torus(3, 4).with_fp32_values(), 21, inplace, True)
+    run_mix(8, d, ld, B.Topology.ring_chord(), oracle.ring_chord(8).with_fp32_values(), 22, inplace, True)
+    run_mix(6, d, ld, B.Topology.ring(), oracle.ring(6).with_fp32_values(), 23, inplace, True, swapped=True)
+    run_mix(72, d, ld, B.Topology.torus(8, 9), oracle.torus(8, 9).with_fp32_values(), 24, inplace, True)   # one float4 per lane
+
+
+@pytest.mark.parametrize("dims", [(3, 3), (8, 8), (5, 4), (3, 8), (9, 7)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_wide_torus(dims, inplace):
+    """Tori of several shapes with more than a million columns (chunked column ownership of the slab kernel, its
+    consecutive remainder and the tail columns), with and without the consensus distance."""
+    n = dims[0] * dims[1]
+    d = 16 * 65536 + 16384 + 1000 + 2
+    run_mix(n, d, d + 2, B.Topology.torus(*dims), oracle.torus(*dims).with_fp32_values(), 30 + n, inplace, True)
+    if dims == (5, 4):
+        run_mix(n, d, d + 2, B.Topology.torus(*dims), oracle.torus(*dims).with_fp32_values(), 31 + n, inplace, False)
+
+
 def test_ring_tag_through_the_csr_kernel_matches():
     run_mix(16, 9000, 9024, B.Topology.ring(), oracle.ring(16).with_fp32_values(), 3, True, True,
             options=(("mix_force_csr", 1),))
@@ -302,10 +326,20 @@ def test_momentum_torus_ring_chord_and_gather():
     run_momentum(12, 3001, 3008, B.Topology.torus(3, 4), oracle.torus(3, 4).with_fp32_values(), 81, True)
     run_momentum(16, 3001, 3001, B.Topology.ring_chord(), oracle.ring_chord(16).with_fp32_values(), 82, True, mu=0.5)
     run_momentum(300, 700, 704, B.Topology.complete(), oracle.complete(300).with_fp32_values(), 83, False)
+    # wide: the slab kernel's chunked column ownership, with the velocity riding along
+    run_momentum(12, 33 * 16384 + 77, 33 * 16384 + 128, B.Topology.torus(3, 4), oracle.torus(3, 4).with_fp32_values(), 84, True,
+                 steps=2)
 
 
-def test_momentum_zero_equals_plain_step_bitwise():
-    n, d, ld = 16, 9000, 9024
+def test_momentum_on_a_wide_ring_takes_the_fat_lane_kernel():
+    """64 super-blocks of 131072 columns and a remainder: the fat-lane ring kernel carries the velocity too."""
+    d = 64 * 131072 + 2048 + 5
+    run_momentum(3, d, d + 3, B.Topology.ring(), oracle.ring(3).with_fp32_values(), 85, True, steps=2)
+    run_momentum(3, d, d + 59, B.Topology.ring(), oracle.ring(3).with_fp32_values(), 86, False, steps=1)
+
+
+@pytest.mark.parametrize("n,d,ld", [(16, 9000, 9024), (3, 64 * 131072 + 300, 64 * 131072 + 512)])
+def test_momentum_zero_equals_plain_step_bitwise(n, d, ld):
     X, G = random_state(n, d, 91)
     Xd, Gd = to_dev(X, ld), to_dev(G, ld)
     Vd = to_dev(np.ones((n, d), np.float32), ld)
