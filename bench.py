@@ -357,7 +357,8 @@ def run_one(args, with_cpu_baseline):
             " (weight gradient + Algorithm 1 steps 4-5, in place)"
         launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / med["launches"]
     else:
-        mix_kernel = ("mix_ring_fat_kernel" if d >= 8192 * 2048 else "mix_ring_kernel") if ring_ok else "mix_csr_slab_kernel"
+        mix_kernel = ("mix_ring_fat_kernel" if d >= 64 * 131072 else "mix_ring_kernel") if ring_ok else \
+            ("mix_csr_slab_wide_kernel" if d >= 16 * 32768 else "mix_csr_slab_kernel")
         kernel_name = "update pass X = (W X) - gamma G (identity as W)" if args.overlap else \
             f"dpsgd_mix_step: {mix_kernel} (Algorithm 1 steps 4-5 fused) + consensus reduction"
         launch_bytes = (20.0 if Vel is not None else 12.0) * cfg.n * d
