@@ -96,6 +96,9 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="after the eager pass, record the K iterations into one HIP graph and report the timed "
                          "replay of it as the value (pays where the iteration is launch-bound: the small workloads)")
+    ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
+                    help="set a launch-shape option of the library (dpsgd_set_option, see include/dpsgd.h); may be repeated; "
+                         "the run is flagged as a variant")
     ap.add_argument("--repeats", type=int, default=5,
                     help="the timed region (exactly --steps iterations) is run this many times; the median repeat is reported")
     ap.add_argument("--no-others", action="store_true",
@@ -261,6 +264,10 @@ def run_one(args, with_cpu_baseline):
     if args.ring_rows >= 0:
         ctx.set_option("ring_rows", args.ring_rows)
         variant = (variant + "; " if variant else "") + f"ring_rows={args.ring_rows}"
+    for kv in args.option:
+        key, _, val = kv.partition("=")
+        ctx.set_option(key, int(val))
+        variant = (variant + "; " if variant else "") + kv
     # layers whose weight gradient dpsgd_step forms inside the mix kernel (same rule as the library)
     fused_weights = 0
     rows_kernel = []     # per fused ring layer: does the [16 rows][1 KB] kernel take it (same rule as the library)
@@ -485,7 +492,7 @@ def main():
         torch.cuda.set_stream(torch.cuda.Stream())
     out = run_one(args, not args.no_cpu_baseline)
     plain = not (args.batch or args.workers or args.two_call or args.momentum or args.overlap or args.shadow or
-                 args.graph or args.ld_multiple or args.ring_rows >= 0 or args.no_consensus)
+                 args.graph or args.ld_multiple or args.ring_rows >= 0 or args.no_consensus or args.option)
     if plain and args.workload == "mlp3_ring64" and not args.no_others:
         others = []
         for name, extra in OTHERS:

@@ -117,8 +117,8 @@ int64_t dpsgd_model_dim(const dpsgd_model *model);
  * Ring and every other topology: d rounded up to a multiple of 256 floats, so that the 1 KB row pieces the ring
  * kernels move are 1 KB-aligned for every worker.  2-D torus: a multiple of 64 floats that is not a multiple of
  * 256, so that the tiles of a grid row's workers, which the fused torus kernel touches together, start 256 bytes
- * apart inside their 1 KB granules instead of on top of each other.  (A layout decision for HBM, like the
- * parameter server's sharding in Section 5.1 is for its network; the paper has no counterpart.) */
+ * apart inside their 1 KB granules instead of on top of each other.  (A layout decision for this GPU's memory; the
+ * paper, whose replicas live on different machines, has no counterpart.) */
 int64_t dpsgd_recommended_ld(int64_t d, const dpsgd_topology *W);
 
 /* One minibatch per worker (Algorithm 1 step 2 has already happened in the caller). */
@@ -146,8 +146,9 @@ dpsgd_status dpsgd_destroy(dpsgd_ctx *ctx);
  * enqueued, or recorded into a HIP graph, keep the value they were issued with. */
 dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
 
-/* Launch-shape knobs for measurements; unknown keys give DPSGD_EINVAL.  Defaults are chosen from
- * (n, d).  Keys: "mix_bands" (row bands per workgroup of the ring kernel, 0 = auto),
+/* Launch-shape knobs for measurements and comparisons (no passage of the paper: they select between kernels that
+ * compute the same iteration); unknown keys give DPSGD_EINVAL.  Defaults are chosen from (n, d) and are what the
+ * benchmark runs.  Changing any option drops a bf16 weight copy ("bf16_shadow").  Keys: "mix_bands" (row bands per workgroup of the ring kernel, 0 = auto),
  * "mix_vec" (floats per lane: 0 = auto, 1, 2 or 4), "mix_force_csr" (1: run the generic CSR
  * kernel even for ring / torus tags), "mix_narrow" (1: the ring kernel with one float4 per lane also for wide
  * matrices, where the default gives a lane eight), "ring_rows" (default 1: dpsgd_step on the ring, bf16 MLP, minibatch of at most 32 rows: layers whose input width is
@@ -212,10 +213,15 @@ dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const fl
 
 /* One whole iteration of Algorithm 1 in place: X <- W X - gamma * grad(X), i.e. the result of dpsgd_grad(X -> G)
  * followed by dpsgd_mix_step(X, G -> X), up to the order of floating-point sums.  Footnote [b] observes that steps 3
- * and 4 are independent; here they share one pass over X wherever a kernel exists for it: for bf16 MLPs on the ring
- * (DPSGD_TOPO_RING) and on a torus with 3 to 8 columns (DPSGD_TOPO_TORUS2D, 3 <= dim1 <= 8, dim0 >= 3) the weight gradient of every large
- * layer is formed inside the mix kernel and never written to memory.  All other
- * cases run the two calls back to back.
+ * and 4 are independent; here they share one pass over X wherever a kernel exists for it.
+ * Fused (the weight gradient of a layer is formed inside the mix kernel and never written to memory): model MLP or
+ * SOFTMAX with compute_bf16 = 1, on DPSGD_TOPO_RING with n >= 3 or on DPSGD_TOPO_TORUS2D with dim0 >= 3 and
+ * 3 <= dim1 <= 8, for every layer with at least 2^20 weights whose outputs are a multiple of 32 and whose inputs are a
+ * multiple of 128 (ring) or of 32 (torus; also 8-byte aligned rows); the remaining parameters of such a model (small
+ * layers, biases) take the ordinary gradient kernels and the mix kernels on their column ranges inside the same call.
+ * Not fused - the call runs dpsgd_grad and an in-place dpsgd_mix_step back to back, same results: every other
+ * topology (DPSGD_TOPO_RING_CHORD, DPSGD_TOPO_COMPLETE, DPSGD_TOPO_CSR, rings with n < 3, tori with a dimension < 3 or
+ * more than 8 columns), fp32 arithmetic (compute_bf16 = 0), LSQ and RESNET20 models, and the "mix_force_csr" option.
  *   X          device, n x d (stride ld), overwritten by the next iterate
  *   G_scratch  device, n x d (stride ld), must not overlap X; on return it holds the gradient only of those
  *              parameters whose update was not fused (contents otherwise unspecified)

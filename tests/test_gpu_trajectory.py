@@ -14,7 +14,8 @@ Two gates per iteration k, as for the convex workloads:
        after ~15 iterations and the iterate itself after ~24 (different ReLU decisions, then growing drift).
 
 Both oracles run the recursion: the one with the workload's bf16 operand roundings and the plain fp64 one.  K' is what
-about two minutes of oracle time allow: the oracle is plain scalar C."""
+one to two minutes of oracle time allow: the oracle is plain scalar C.  Each iteration's line goes to the terminal as
+it is computed (past pytest's capture), so a run of these minutes-long tests shows its progress."""
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -35,7 +36,11 @@ TIGHT = 3e-3    # one step against the oracle with the same operand roundings
 HORIZON = 10    # iterations over which a free-running trajectory must stay under the bar
 
 
-def run_trajectory(cfg, iters):
+def run_trajectory(cfg, iters, capsys):
+    def say(text):
+        with capsys.disabled():
+            print(text, flush=True)
+
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = synth.padded_stride(d, 256)
     topo_o = oracle_topo_for(cfg)
@@ -51,10 +56,10 @@ def run_trajectory(cfg, iters):
     first_over = {name: {} for name in free}
     worst = {name: {} for name in free}
     pool = ThreadPoolExecutor(max_workers=2)
-    print(f"trajectory {cfg.name}: widths={cfg.widths} n={cfg.n} B={cfg.batch} gamma={cfg.gamma} iterations={iters} "
-          f"of K={CONFIGS[cfg.index].iters}", flush=True)
-    print("   k | single step, update vs rounding oracle: Frobenius/largest element (two-call, dpsgd_step) | own trajectory of "
-          "each path", flush=True)
+    say(f"\ntrajectory {cfg.name}: widths={cfg.widths} n={cfg.n} B={cfg.batch} gamma={cfg.gamma} iterations={iters} "
+        f"of K={CONFIGS[cfg.index].iters}")
+    say("   k | single step, update vs rounding oracle: Frobenius/largest element (two-call, dpsgd_step) | own trajectory of "
+        "each path")
 
     def advance(ctx, name, X, inp_d, tgt_d):
         if name == "two-call":
@@ -116,29 +121,27 @@ def run_trajectory(cfg, iters):
                     assert q["X vs rounding oracle"] < TOL, f"k={k} {name} X vs rounding oracle: {q['X vs rounding oracle']:.3e}"
                     assert q["X vs plain oracle"] < TOL, f"k={k} {name} X vs plain oracle: {q['X vs plain oracle']:.3e}"
                     assert q["xbar vs plain oracle"] < TOL
-            print("  " + "  ".join(line), flush=True)
+            say("  " + "  ".join(line))
             Xr, Xp = Xr_next, Xp_next
     pool.shutdown()
     for name in free:
-        print(f"  {name}, worst over {iters} iterations: " + "; ".join(f"{k_} {v:.2e}" for k_, v in worst[name].items()), flush=True)
-        print(f"  {name}, first iteration over {TOL:g}: " + ("; ".join(f"{k_}: k={v}" for k_, v in first_over[name].items()) or "none"),
-              flush=True)
+        say(f"  {name}, worst over {iters} iterations: " + "; ".join(f"{k_} {v:.2e}" for k_, v in worst[name].items()))
+        say(f"  {name}, first iteration over {TOL:g}: " + ("; ".join(f"{k_}: k={v}" for k_, v in first_over[name].items()) or "none"))
     # the two device paths against each other
     a, b = from_dev(free["two-call"], d), from_dev(free["dpsgd_step"], d)
-    print(f"  two-call vs dpsgd_step after {iters} iterations: {rel_err(a, b):.3e} (max element {max_err(a, b):.3e} rms)",
-          flush=True)
+    say(f"  two-call vs dpsgd_step after {iters} iterations: {rel_err(a, b):.3e} (max element {max_err(a, b):.3e} rms)")
 
 
 @pytest.mark.timeout(400)
-def test_config2_trajectory_full_widths():
-    run_trajectory(shrink(CONFIGS[2], n=3), iters=40)
+def test_config2_trajectory_full_widths(capsys):
+    run_trajectory(shrink(CONFIGS[2], n=3), 32, capsys)
 
 
 @pytest.mark.timeout(400)
-def test_config3_trajectory_full_widths():
-    run_trajectory(shrink(CONFIGS[3], n=3), iters=8)
+def test_config3_trajectory_full_widths(capsys):
+    run_trajectory(shrink(CONFIGS[3], n=3), 6, capsys)
 
 
 @pytest.mark.timeout(400)
-def test_config4_trajectory_full_size_images():
-    run_trajectory(shrink(CONFIGS[4], n=3), iters=CONFIGS[4].iters)
+def test_config4_trajectory_full_size_images(capsys):
+    run_trajectory(shrink(CONFIGS[4], n=3), 12, capsys)
