@@ -49,6 +49,7 @@ struct dpsgd_ctx {
 
     // measurement aid: HIP events around the fused wgrad+mix launches of dpsgd_step ("time_fused")
     int32_t opt_time_fused = 0;
+    int32_t opt_conv_band_rows = 0; // output rows per workgroup of the MFMA convolutions: 8, 16, or 0 = chosen per convolution
     std::vector<hipEvent_t> ev;   // pairs (start, stop)
     int64_t ev_pairs = 0, ev_launches = 0;
 

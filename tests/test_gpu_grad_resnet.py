@@ -120,3 +120,30 @@ def test_config4_full_size_sampled_workers():
         assert abs(float(loss[i]) - l) < TIGHT * abs(l)
         assert abs(float(loss[i]) - lp) < TOL * abs(lp)
         assert abs(gap_gpu - gap_rounding) <= 0.1 * gap_rounding
+
+
+@pytest.mark.parametrize("widths,batch,n", [((3, 32, 32, 16, 1, 10), 3, 2), ((3, 32, 32, 16, 3, 10), 4, 8),
+                                            ((3, 16, 16, 16, 2, 10), 6, 3), ((3, 8, 8, 16, 1, 10), 5, 2)])
+def test_workgroup_tile_height_changes_no_bit(widths, batch, n):
+    """The convolutions with 8 or 16 output rows of an image per workgroup ("conv_band_rows"; the default picks per
+    convolution): which rows share a workgroup changes no sum, so gradient and loss are identical bit for bit (the
+    default's result is the one the oracle checks above)."""
+    cfg = shrink(CONFIGS[4], widths=widths, batch=batch, n=n)
+    d = synth.model_dim(MODEL_RESNET20, widths)
+    ld = synth.padded_stride(d)
+    X, inp, tgt = resnet_inputs(cfg, 0.3)
+    Xd, inp_d, tgt_d = to_dev(X, ld), bf16_dev(inp), torch.from_numpy(tgt).cuda()
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    got = {}
+    for rows in (0, 8, 16):
+        Gd = torch.full_like(Xd, 777.0)
+        loss = torch.zeros(cfg.n, device="cuda")
+        print(f"conv_band_rows={rows} widths={widths} n={n} B={batch}", flush=True)
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("conv_band_rows", rows)
+            ctx.grad(model, Xd, inp_d, tgt_d, cfg.batch, Gd, loss, input_is_bf16=True)
+            torch.cuda.synchronize()
+        got[rows] = (from_dev(Gd, d), loss.cpu().numpy())
+    for rows in (8, 16):
+        assert np.array_equal(got[rows][0], got[0][0]), f"gradient differs with {rows} rows per workgroup"
+        assert np.array_equal(got[rows][1], got[0][1])
