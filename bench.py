@@ -358,8 +358,11 @@ def run_one(args, with_cpu_baseline):
     launch_ms = med["kernel_ms"] / med["launches"]
     mix_ms = med["kernel_ms"] / K
     if fused:
-        ring_name = "mlp_fused_ring_rows_kernel" if all(rows_kernel) else "mlp_fused_ring_kernel" if not any(rows_kernel) \
-            else "mlp_fused_ring_rows_kernel / mlp_fused_ring_kernel"
+        # minibatches of more than 32 rows (padded to a multiple of 32): operands through LDS unless switched off
+        tiles_name = "mlp_fused_ring_lds_kernel" if (cfg.batch > 32 and not args.shadow and "fused_lds=0" not in args.option) \
+            else "mlp_fused_ring_kernel"
+        ring_name = "mlp_fused_ring_rows_kernel" if all(rows_kernel) else tiles_name if not any(rows_kernel) \
+            else "mlp_fused_ring_rows_kernel / " + tiles_name
         kernel_name = (ring_name if ring_ok else "mlp_fused_torus_cols_kernel") + \
             " (weight gradient + Algorithm 1 steps 4-5, in place)"
         launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / med["launches"]

@@ -161,6 +161,9 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * between two dpsgd_step calls nobody else writes X; every dpsgd_mix_step* call, a change of this option, another
  * X or model, and calls recorded under stream capture drop the copy.  Costs 2 bytes per hidden-layer weight and
  * worker of device memory.  The iterates are bit for bit those of the same "ring_rows" setting without the copy),
+ * "fused_lds" (default 1: dpsgd_step on the ring, bf16 MLP, minibatch of more than 32 rows: the operands of the fused
+ * weight-gradient + mix kernel travel from L2 into LDS asynchronously, one worker ahead; 0: they are fetched into
+ * registers two steps at a time.  Same bits),
  * "conv_band_rows" (output rows of an image per workgroup of the CNN's 3 x 3 convolution kernels: 8, 16, or 0 = chosen
  * per convolution, the default; every setting gives the same bits),
  * "time_fused" (see dpsgd_read_timing). */

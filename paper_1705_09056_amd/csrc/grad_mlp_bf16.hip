@@ -1041,6 +1041,109 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_kernel(FusedArgs a)
     }
 }
 
+// The 32 x 32-tile pass for minibatches of more than 32 rows (4 to 8 operand steps per worker).  Fetched into
+// registers two steps at a time, the operands cost a wave one L2 round trip per pair of steps, one after the
+// other.  Here a worker's operands - the 32 rows of dZ^T all four waves share and each wave's 32 columns of the
+// activations, steps KB each, consecutive in the fragment-ordered copies - travel from L2 straight into LDS
+// (16 bytes per lane, no registers), asynchronously: they are requested as soon as every wave has read the
+// previous worker's from LDS, and land while the wave forms and stores that worker's update.  One round trip per
+// worker, hidden; two workgroup barriers per worker.  grid (K / 128, O / 32), block 256, dynamic LDS 5 * steps KB.
+template <bool CONS>
+__global__ void __launch_bounds__(256, 3) mlp_fused_ring_lds_kernel(FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char fused_lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int k0 = blockIdx.x * 128 + wave * 32, o0 = blockIdx.y * 32;
+    const int steps = a.Bp / 16;
+    u32x4 *lds_a = reinterpret_cast<u32x4 *>(fused_lds);               // [steps][64]: dZ^T rows o0 .. o0 + 31
+    u32x4 *lds_b = lds_a + (1 + wave) * steps * 64;                    // [steps][64]: this wave's activation columns
+    // element v of this lane: row o0 + (v/4)*8 + half*4 + v%4, column k0 + l32
+    float *xt = a.X + a.woff + (i64)(o0 + half * 4) * a.K + k0 + l32;
+    auto row_off = [&](int v) { return (i64)((v >> 2) * 8 + (v & 3)) * a.K; };
+    const bf16_t *ap = a.dzt + (i64)(o0 >> 5) * steps * 512 + lane * 8;
+    const bf16_t *bp = a.at + (i64)(k0 >> 5) * steps * 512 + lane * 8;
+    // worker w's operands on their way to LDS: this wave's own activation steps and every fourth step of dZ^T
+    auto request_ops = [&](int w) {
+        const bf16_t *aw = ap + (i64)w * a.O * a.Bp, *bw = bp + (i64)w * a.K * a.Bp;
+        for (int st = 0; st < steps; ++st) __builtin_amdgcn_global_load_lds(bw + st * 512, lds_b + st * 64, 16, 0, 0);
+        for (int st = wave; st < steps; st += 4) __builtin_amdgcn_global_load_lds(aw + st * 512, lds_a + st * 64, 16, 0, 0);
+    };
+
+    float xm[16], xc[16], xh[16], xn[16], xf[16], s1[16], s2[4] = {0.f, 0.f, 0.f, 0.f};
+    request_ops(0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        xm[v] = xt[(i64)(a.n - 1) * a.ld + row_off(v)];
+        xc[v] = xt[row_off(v)];
+        xh[v] = xc[v];
+        xn[v] = xt[(i64)(1 % a.n) * a.ld + row_off(v)];
+        s1[v] = 0.f;
+    }
+    __builtin_amdgcn_s_waitcnt(0);   // everything requested so far has arrived (vmcnt = 0)
+    __syncthreads();
+    for (int i = 0; i < a.n; ++i) {
+        {   // the tile of worker i + 2 (past the last worker: one cached line of the operand array, values never used)
+            const bool far = i + 2 < a.n;
+            const float *src = far ? xt + (i64)(i + 2) * a.ld : reinterpret_cast<const float *>(a.dzt) + lane;
+            const i64 rs = far ? (i64)a.K : 0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) xf[v] = __builtin_nontemporal_load(src + ((v >> 2) * 8 + (v & 3)) * rs);
+        }
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        {   // two steps at a time (the minibatch is padded to a multiple of 32), the next pair read ahead of the MFMAs
+            u32x4 pa0 = lds_a[lane], pb0 = lds_b[lane], pa1 = lds_a[64 + lane], pb1 = lds_b[64 + lane];
+            for (int st = 2; st < steps; st += 2) {
+                const u32x4 na0 = lds_a[st * 64 + lane], nb0 = lds_b[st * 64 + lane];
+                const u32x4 na1 = lds_a[st * 64 + 64 + lane], nb1 = lds_b[st * 64 + 64 + lane];
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pa0), __builtin_bit_cast(bf16x8, pb0), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pa1), __builtin_bit_cast(bf16x8, pb1), acc, 0, 0, 0);
+                pa0 = na0; pb0 = nb0; pa1 = na1; pb1 = nb1;
+            }
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pa0), __builtin_bit_cast(bf16x8, pb0), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, pa1), __builtin_bit_cast(bf16x8, pb1), acc, 0, 0, 0);
+        }
+        __syncthreads();   // every wave has read worker i's operands
+        if (i + 1 < a.n) request_ops(i + 1);
+        const bool last = i + 1 == a.n;
+        float *dst = xt + (i64)i * a.ld;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float nxt = last ? xh[v] : xn[v];   // the ring closes on worker 0's original tile
+            // the order and roundings of the ring mix kernel: three fused multiply-adds after the first product
+            float mix = a.w * xm[v];
+            mix = __builtin_fmaf(a.w, xc[v], mix);
+            mix = __builtin_fmaf(a.w, nxt, mix);
+            const float o = __builtin_fmaf(-a.gamma, acc[v], mix);
+            __builtin_nontemporal_store(o, dst + row_off(v));
+            if (CONS) {
+                const float e = o - xh[v];
+                s1[v] += e;
+                s2[v & 3] += e * e;
+            }
+            xm[v] = xc[v];
+            xc[v] = nxt;
+            xn[v] = xf[v];
+        }
+        // The next worker's operands must be in LDS, for every wave, before anyone reads them.  (This also waits for
+        // the 16 stores above, which were issued after the operand requests; the compiler puts the same full wait in
+        // front of the barrier by itself.)
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    }
+    if (CONS) {
+        float m2 = (s2[0] + s2[1]) + (s2[2] + s2[3]);
+        const float inv_n = 1.0f / (float)a.n;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) m2 -= s1[v] * s1[v] * inv_n;
+        double t = (double)m2;
+        for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
+        if (lane == 0) a.partials[((i64)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave] = t;
+    }
+}
+
 // The same pass for minibatches of at most 32 rows with a workgroup tile of [16 rows][1 KB]: every load and store
 // instruction of a wave covers 1 KB of one row of the weight matrix (the 32 x 32 layout above touches 128-byte
 // pieces of two rows), which streams ~10 % faster from HBM.  Wave wv owns rows o0 + 4 wv .. + 3 and all 256 columns,
@@ -1571,6 +1674,10 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             } else if (fa.shadow) {
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, true>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, true>), grid, dim3(256), 0, s, fa);
+            } else if (Bp >= 64 && ctx->opt_fused_lds) {   // operands through LDS: 5 KB per 16 minibatch rows
+                const size_t shm = (size_t)5 * (Bp / 16) * 1024;
+                if (cons) hipLaunchKernelGGL((mlp_fused_ring_lds_kernel<true>), grid, dim3(256), shm, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_ring_lds_kernel<false>), grid, dim3(256), shm, s, fa);
             } else {
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, false>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, false>), grid, dim3(256), 0, s, fa);

@@ -283,6 +283,43 @@ def test_row_layout_ring_kernel_agrees_with_the_tile_layout_one(widths, batch, n
     assert bool(torch.all(Xb[:, d:] == X0[:, d:]))     # padding columns untouched
 
 
+@pytest.mark.parametrize("widths,batch,n", [
+    ((3072, 1024, 10), 128, 4),       # configs[2]'s layer: 8 operand steps per worker, 40 KB of LDS per workgroup
+    ((1024, 1024, 10), 64, 5),        # 4 steps, odd ring
+    ((1280, 2080, 10), 90, 3),        # ragged minibatch padded to 96 (6 steps: two waves fetch two steps of dZ^T, two one)
+    ((512, 1024, 10), 150, 3),        # padded to 160: 10 steps
+])
+def test_operands_through_lds_change_no_bit(widths, batch, n):
+    """Minibatches of more than 32 rows on the ring: the fused kernel whose operands travel from L2 into LDS
+    asynchronously ("fused_lds" 1, the default) and the one that fetches them into registers ("fused_lds" 0) issue the
+    same matrix instructions on the same operands in the same order: iterates, losses and consensus distances are
+    identical bit for bit over three iterations."""
+    cfg = shrink(CONFIGS[2], widths=widths, batch=batch, n=n, iters=3)
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    ld = synth.padded_stride(d)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    X0 = to_dev(synth.make_replicas(cfg), ld)
+    runs = []
+    for lds in (1, 0):
+        X = X0.clone()
+        G = torch.zeros_like(X)
+        loss = torch.zeros(cfg.iters, cfg.n, device="cuda")
+        cons = torch.zeros(cfg.iters, device="cuda")
+        print(f"fused_lds={lds} widths={widths} B={batch} n={n}", flush=True)
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("fused_lds", lds)
+            for k in range(cfg.iters):
+                inp, tgt = synth.make_batch(cfg, k)
+                ctx.step(model, X, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, G, loss[k], cons[k:k + 1],
+                         input_is_bf16=True)
+            torch.cuda.synchronize()
+        runs.append((X, loss, cons))
+    (Xa, la, ca), (Xb, lb, cb) = runs
+    assert not torch.equal(Xa, X0)
+    assert torch.equal(Xa, Xb), f"max |dX| {float((Xa - Xb).abs().max()):.3e}"
+    assert torch.equal(la, lb) and torch.equal(ca, cb)
+
+
 @pytest.mark.parametrize("widths,batch", [
     ((1024, 1024, 1024, 10), 32),     # one hidden layer with a copy, read by the forward and the data gradient
     ((1024, 1024, 1152, 1024, 10), 32),   # two of them, 36 and 32 output tiles
