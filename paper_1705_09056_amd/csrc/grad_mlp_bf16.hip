@@ -226,59 +226,65 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
     const float *Wg = g.X + (i64)w * g.ld + g.woff;
     const bf16_t *Ag = g.act + (i64)w * g.B * g.K;
 
-    f32x4 wreg[WQ];
+    // The weights (fp32, from HBM) are fetched TWO chunks ahead into two register sets, the activations (bf16, L2
+    // resident) one chunk ahead: with a large minibatch there are few workgroups per CU and the bytes each keeps in
+    // flight bound the rate.  VEC loads are branch-free (an element outside the matrix reads a clamped address and
+    // is replaced by zero), so that the loads of one fetch are issued back to back and waited for by count.
     u32x4 areg[AQ];
-    auto fetch = [&](int k0) {
+    auto fetch_w = [&](int k0, f32x4 (&wreg)[WQ]) {
 #pragma unroll
         for (int q = 0; q < WQ; ++q) {
             const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 4;
             const int o = o0 + row, k = k0 + kq;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (o < g.O) {
+            if (VEC) {   // K % 8 == 0: a group of four is inside the row or outside it
+                v = __builtin_nontemporal_load(   // stage() replaces what lies outside the matrix by zero
+                    reinterpret_cast<const f32x4 *>(Wg + (i64)(o < g.O ? o : g.O - 1) * g.K + (k < g.K ? k : 0)));
+            } else if (o < g.O) {
                 const float *p = Wg + (i64)o * g.K + k;
-                if (VEC) {
-                    if (k < g.K) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
-                } else {
-                    if (k < g.K) v.x = p[0];
-                    if (k + 1 < g.K) v.y = p[1];
-                    if (k + 2 < g.K) v.z = p[2];
-                    if (k + 3 < g.K) v.w = p[3];
-                }
+                if (k < g.K) v.x = p[0];
+                if (k + 1 < g.K) v.y = p[1];
+                if (k + 2 < g.K) v.z = p[2];
+                if (k + 3 < g.K) v.w = p[3];
             }
             wreg[q] = v;
         }
+    };
+    auto fetch_a = [&](int k0) {
 #pragma unroll
         for (int q = 0; q < AQ; ++q) {
             const int u = tid + 256 * q, row = u >> 3, kq = (u & 7) * 8;
             const int b = b0 + row, k = k0 + kq;
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (b < g.B) {
+            if (VEC) {
+                v = *reinterpret_cast<const u32x4 *>(Ag + (i64)(b < g.B ? b : g.B - 1) * g.K + (k < g.K ? k : 0));
+            } else if (b < g.B) {
                 const bf16_t *p = Ag + (i64)b * g.K + k;
-                if (VEC) {
-                    if (k < g.K) v = *reinterpret_cast<const u32x4 *>(p);
-                } else {
-                    unsigned short e[8];
+                unsigned short e[8];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) e[i] = (k + i < g.K) ? p[i] : (unsigned short)0;
-                    v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
-                    v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
-                }
+                for (int i = 0; i < 8; ++i) e[i] = (k + i < g.K) ? p[i] : (unsigned short)0;
+                v.x = e[0] | ((unsigned)e[1] << 16); v.y = e[2] | ((unsigned)e[3] << 16);
+                v.z = e[4] | ((unsigned)e[5] << 16); v.w = e[6] | ((unsigned)e[7] << 16);
             }
             areg[q] = v;
         }
     };
-    auto stage = [&](int buf) {
+    // k0: the chunk the registers hold (VEC: decides which of the clamped loads lie outside the matrix)
+    auto stage = [&](int buf, const f32x4 (&wreg)[WQ], int k0) {
         bf16_t *Wb = Wt + buf * TO * PITCH, *Ab = At + buf * MBLK * PITCH;
 #pragma unroll
         for (int q = 0; q < WQ; ++q) {
             const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 4;
             u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
+            if (VEC && !(o0 + row < g.O && k0 + kq < g.K)) p = (u32x2){0u, 0u};
             *reinterpret_cast<u32x2 *>(Wb + row * PITCH + kq) = p;
         }
 #pragma unroll
         for (int q = 0; q < AQ; ++q) {
             const int u = tid + 256 * q, row = u >> 3, kq = (u & 7) * 8;
-            *reinterpret_cast<u32x4 *>(Ab + row * PITCH + kq) = areg[q];
+            u32x4 v = areg[q];
+            if (VEC && !(b0 + row < g.B && k0 + kq < g.K)) v = (u32x4){0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4 *>(Ab + row * PITCH + kq) = v;
         }
     };
 
@@ -287,18 +293,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
     for (int m = 0; m < MT; ++m)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
-
-    // Workgroups start their walk over the contraction at different chunks: started together at chunk 0 they
-    // would all read the same column range of W at the same time, rows a multiple of 4 KB apart.
-    const int nchunks = (g.K + KC - 1) / KC;
-    const int start = (int)((unsigned)(tile * 5 + w * 3) % (unsigned)nchunks);
-    auto chunk_k = [&](int c) { const int cc = c + start; return (cc >= nchunks ? cc - nchunks : cc) * KC; };
-    fetch(chunk_k(0));
-    stage(0);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < nchunks) fetch(chunk_k(c + 1));
+    auto multiply = [&](int buf) {
         const bf16_t *Wb = Wt + buf * TO * PITCH + (wn * 32 + l32) * PITCH + 8 * half;
         const bf16_t *Ab = At + buf * MBLK * PITCH + (wm * MT * 32 + l32) * PITCH + 8 * half;
 #pragma unroll
@@ -310,11 +305,140 @@ __global__ void __launch_bounds__(256) mlp_fwd_kernel(FwdArgs g)
                 acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aa, bw, acc[m], 0, 0, 0);
             }
         }
-        if (c + 1 < nchunks) stage(buf ^ 1);
+    };
+
+    // Workgroups start their walk over the contraction at different chunks: started together at chunk 0 they
+    // would all read the same column range of W at the same time, rows a multiple of 4 KB apart.
+    const int nchunks = (g.K + KC - 1) / KC;
+    const int start = (int)((unsigned)(tile * 5 + w * 3) % (unsigned)nchunks);
+    auto chunk_k = [&](int c) { const int cc = c + start; return (cc >= nchunks ? cc - nchunks : cc) * KC; };
+    f32x4 w_even[WQ], w_odd[WQ];   // weights of the even and of the odd chunks on their way
+    fetch_w(chunk_k(0), w_even);
+    fetch_a(chunk_k(0));
+    fetch_w(chunk_k(nchunks > 1 ? 1 : 0), w_odd);
+    stage(0, w_even, chunk_k(0));
+    __syncthreads();
+    // one step: chunk c is multiplied from LDS buffer c % 2 while the activations of chunk c + 1 and the weights of
+    // chunk c + 2 are on their way (the activations are requested first: staging waits for them, not for the younger
+    // weight loads).  Past the end the fetches repeat the last chunk (values never used): no branch around a load.
+    auto step = [&](int c, f32x4 (&w_this)[WQ], const f32x4 (&w_next)[WQ]) {
+        const int last = nchunks - 1;
+        fetch_a(chunk_k(c + 1 < nchunks ? c + 1 : last));
+        __builtin_amdgcn_sched_barrier(0);   // keep this order of issue: the wait for the activations counts on it
+        fetch_w(chunk_k(c + 2 < nchunks ? c + 2 : last), w_this);   // chunk c's weights are in LDS: its registers are free
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(c & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        stage((c & 1) ^ 1, w_next, chunk_k(c + 1 < nchunks ? c + 1 : last));   // (past the end: written, never read)
         __syncthreads();
+    };
+    for (int c = 0; c < nchunks; c += 2) {
+        step(c, w_even, w_odd);
+        if (c + 1 < nchunks) step(c + 1, w_odd, w_even);
     }
 
     // epilogue: lane owns output column o, 16 rows per m-tile
+    const int o = o0 + wn * 32 + l32;
+    if (o >= g.O) return;
+    const float bias = g.X[(i64)w * g.ld + g.boff + o];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) fwd_store_tile<LAST>(g, w, o, b0 + (wm * MT + m) * 32, half, bias, acc[m]);
+}
+
+// Minibatches of more than 64 rows (one 128-row block of the minibatch per workgroup, so the weights are read once):
+// the product above with chunks of 128 contraction elements, so that a row of the weight tile is 512 consecutive
+// bytes (with 64 the kernel above streams 4.2 TB/s of weights at 3072 x 1024 x 32 workers, bound by the 256-byte
+// pieces, whatever the prefetch distance).  One LDS buffer of (64 + 128) rows x 272 bytes (three workgroups per CU)
+// instead of two: the next chunk waits in registers while the current one is multiplied, and goes to LDS between
+// two barriers.  Rows 16-byte aligned and K % 8 == 0 (the VEC case of the kernel above); loads are branch-free
+// (clamped addresses; what lies outside the matrix is replaced by zero on its way to LDS).
+// grid (ceil(O / 64), ceil(B / 128), n), block 256 = 2 x 2 waves, each two 32 x 32 tiles.
+constexpr int KCW = 128;
+constexpr int PITCHW = KCW + 8;
+
+template <bool LAST>
+__global__ void __launch_bounds__(256, 3) mlp_fwd_wide_kernel(FwdArgs g)
+{
+    constexpr int TO = 64, MBLK = 128, MT = 2, WQ = 8, AQ = 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *Wt = reinterpret_cast<bf16_t *>(smem);   // [TO][PITCHW]
+    bf16_t *At = Wt + TO * PITCHW;                    // [MBLK][PITCHW]
+    int w, tile;
+    worker_tile_on_one_xcd(tile, w);
+    const int o0 = tile * TO, b0 = blockIdx.y * MBLK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+    const float *Wg = g.X + (i64)w * g.ld + g.woff;
+    const bf16_t *Ag = g.act + (i64)w * g.B * g.K;
+
+    f32x4 wreg[WQ];
+    u32x4 areg[AQ];
+    // unit u = tid + 256 q.  W: row u / 32, floats (u % 32) * 4 .. + 3 (a wave instruction: two rows x 512 bytes);
+    // A: row u / 16, elements (u % 16) * 8 .. + 7
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < AQ; ++q) {
+            const int u = tid + 256 * q, b = b0 + (u >> 4), k = k0 + (u & 15) * 8;
+            areg[q] = *reinterpret_cast<const u32x4 *>(Ag + (i64)(b < g.B ? b : g.B - 1) * g.K + (k < g.K ? k : 0));
+        }
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, o = o0 + (u >> 5), k = k0 + (u & 31) * 4;
+            wreg[q] = __builtin_nontemporal_load(
+                reinterpret_cast<const f32x4 *>(Wg + (i64)(o < g.O ? o : g.O - 1) * g.K + (k < g.K ? k : 0)));
+        }
+    };
+    auto stage = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
+            u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
+            if (!(o0 + row < g.O && k0 + kq < g.K)) p = (u32x2){0u, 0u};
+            *reinterpret_cast<u32x2 *>(Wt + row * PITCHW + kq) = p;
+        }
+#pragma unroll
+        for (int q = 0; q < AQ; ++q) {
+            const int u = tid + 256 * q, row = u >> 4, kq = (u & 15) * 8;
+            u32x4 v = areg[q];
+            if (!(b0 + row < g.B && k0 + kq < g.K)) v = (u32x4){0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4 *>(At + row * PITCHW + kq) = v;
+        }
+    };
+
+    f32x16 acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[m][v] = 0.f;
+
+    // workgroups start their walk over the contraction at different chunks (see the kernel above)
+    const int nchunks = (g.K + KCW - 1) / KCW;
+    const int start = (int)((unsigned)(tile * 5 + w * 3) % (unsigned)nchunks);
+    auto chunk_k = [&](int c) { const int cc = c + start; return (cc >= nchunks ? cc - nchunks : cc) * KCW; };
+    fetch(chunk_k(0));
+    stage(chunk_k(0));
+    __syncthreads();
+    const bf16_t *Wb = Wt + (wn * 32 + l32) * PITCHW + 8 * half;
+    const bf16_t *Ab = At + (wm * MT * 32 + l32) * PITCHW + 8 * half;
+    for (int c = 0; c < nchunks; ++c) {
+        const int nxt = chunk_k(c + 1 < nchunks ? c + 1 : c);   // past the end: the last chunk again, never used
+        fetch(nxt);
+        __builtin_amdgcn_sched_barrier(0);   // the loads are on their way before the first LDS read
+#pragma unroll
+        for (int ks = 0; ks < KCW / 16; ++ks) {
+            const bf16x8 bw = frag(Wb + ks * 16);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const bf16x8 aa = frag(Ab + m * 32 * PITCHW + ks * 16);
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aa, bw, acc[m], 0, 0, 0);
+            }
+        }
+        __syncthreads();   // every wave has read chunk c
+        stage(nxt);
+        __syncthreads();
+    }
+
     const int o = o0 + wn * 32 + l32;
     if (o >= g.O) return;
     const float bias = g.X[(i64)w * g.ld + g.boff + o];
@@ -858,6 +982,13 @@ template <int WM, int WN, int MT>
 dpsgd_status fwd_launch(hipStream_t s, int n, const FwdArgs &a, bool vec, bool last)
 {
     constexpr int TO = 32 * WN, MBLK = 32 * WM * MT;
+    if (WM == 2 && WN == 2 && MT == 2 && vec && !a.wb) {   // 128-row minibatch blocks: 512-byte row pieces
+        dim3 grid((unsigned)((a.O + 63) / 64), (unsigned)((a.B + 127) / 128), (unsigned)n);
+        const size_t shm = (size_t)(64 + 128) * PITCHW * sizeof(bf16_t);
+        if (last) hipLaunchKernelGGL(mlp_fwd_wide_kernel<true>, grid, dim3(256), shm, s, a);
+        else hipLaunchKernelGGL(mlp_fwd_wide_kernel<false>, grid, dim3(256), shm, s, a);
+        return hip_status(hipGetLastError());
+    }
     dim3 grid((unsigned)((a.O + TO - 1) / TO), (unsigned)((a.B + MBLK - 1) / MBLK), (unsigned)n);
     const size_t shm = (size_t)2 * (TO + MBLK) * PITCH * sizeof(bf16_t);
     if (vec && last) hipLaunchKernelGGL((mlp_fwd_kernel<WM, WN, MT, true, true>), grid, dim3(256), shm, s, a);
