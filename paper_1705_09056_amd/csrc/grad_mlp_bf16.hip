@@ -582,7 +582,8 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(Ab + ks * 16), frag(Wb + ks * 16), acc, 0, 0, 0);
     };
     // (fetching the half-size bf16 chunks two ahead, to keep as many bytes in flight as with fp32 weights, was measured
-    // and is slower: 400 against 387 us)
+    // and is slower: 400 against 387 us; so is fetching the fp32 chunks two ahead with branch-free loads: 635 against
+    // 615 us - with three workgroups per CU the memory system is already saturated, unlike in mlp_fwd_kernel's case)
     fetch_w16(chunk_k(0), breg0);
     fetch_w32(chunk_k(0));
     fetch_a(chunk_k(0));
