@@ -394,6 +394,19 @@ int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 // neighbouring dword.  Waves split the output-channel tiles first, then the pixels; a workgroup
 // owns a strided subset of the worker's images and writes its partial sums, which
 // wgrad_reduce_kernel adds in a fixed order.
+struct WgradReduceJob {
+    const float *part;     // the conv's partial sums, [n][splits][psz]
+    i64 w_off, b_off;      // where the conv's weights and its scalar bias sit in a worker's parameter vector
+    int splits, psz, tiles, ci_tiles, CIr;
+    int block0;            // first blockIdx.x of this job
+};
+constexpr int kMaxReduceJobs = 48;
+struct WgradReduceTable {
+    WgradReduceJob job[kMaxReduceJobs];
+    int njobs;
+};
+static_assert(sizeof(WgradReduceTable) <= sizeof(WgradReduceList::table), "the caller's storage holds the job table");
+
 struct WgradMfmaArgs {
     const bf16_t *inT;     // [n*B][CIr][H][W]
     const bf16_t *doutT;   // [n*B][CO][Ho][Wo]
@@ -586,22 +599,28 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
     if (tid == 0) out[psz - 1] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// G[w_off + ...] = sum over splits of the partials (ascending split), G[b_off] = sum of the bias partials.
-// grid (tiles + 1, n), block 256: block T sums the (co tile, ci tile) pair T, reading along the accumulator
-// order (consecutive threads, consecutive floats), turns the tile into G's [c_out][c_in][tap] order in LDS and
-// writes 16 runs of up to 144 consecutive floats; the last block adds the bias partials.
-__global__ void __launch_bounds__(256)
-wgrad_reduce_kernel(const float *__restrict__ part, int splits, int psz, int ci_tiles, int CIr, float *__restrict__ G, i64 ld,
-                    i64 w_off, i64 b_off)
+// G[w_off + ...] = sum over splits of the partials (ascending split), G[b_off] = sum of the bias partials, for every
+// convolution of the network in one launch (the jobs travel in the kernel arguments).
+// grid (sum over jobs of tiles + 1, n), block 256: block T of a job sums its (co tile, ci tile) pair T, reading along
+// the accumulator order (consecutive threads, consecutive floats), turns the tile into G's [c_out][c_in][tap] order
+// in LDS and writes 16 runs of up to 144 consecutive floats; the job's last block adds the bias partials.
+__global__ void __launch_bounds__(256) wgrad_reduce_kernel(WgradReduceTable tbl, float *__restrict__ G, i64 ld)
 {
     __shared__ float tile[16 * 16 * 9];
-    const int T = blockIdx.x, w = blockIdx.y, tid = threadIdx.x;
-    const float *p = part + (i64)w * splits * psz;
-    if (T == (int)gridDim.x - 1) {
+    int lo = 0, hi = tbl.njobs - 1;   // the job of this workgroup: last one whose first block is <= blockIdx.x
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int)blockIdx.x >= tbl.job[mid].block0) lo = mid; else hi = mid - 1;
+    }
+    const WgradReduceJob &jb = tbl.job[lo];
+    const int T = (int)blockIdx.x - jb.block0, w = blockIdx.y, tid = threadIdx.x;
+    const int splits = jb.splits, psz = jb.psz;
+    const float *p = jb.part + (i64)w * splits * psz;
+    if (T == jb.tiles) {
         if (tid == 0) {
             float s = 0.f;
             for (int k = 0; k < splits; ++k) s += p[(i64)k * psz + psz - 1];
-            G[(i64)w * ld + b_off] = s;
+            G[(i64)w * ld + jb.b_off] = s;
         }
         return;
     }
@@ -620,11 +639,11 @@ wgrad_reduce_kernel(const float *__restrict__ part, int splits, int psz, int ci_
         for (int k = 0; k < 9; ++k) tile[(ol * 16 + cl) * 9 + k] = s[k];
     }
     __syncthreads();
-    const int o0 = (T / ci_tiles) * 16, c0 = (T % ci_tiles) * 16;
-    const int run = (CIr - c0 < 16 ? CIr - c0 : 16) * 9;   // floats of one c_out row that exist
+    const int o0 = (T / jb.ci_tiles) * 16, c0 = (T % jb.ci_tiles) * 16;
+    const int run = (jb.CIr - c0 < 16 ? jb.CIr - c0 : 16) * 9;   // floats of one c_out row that exist
     for (int e = tid; e < 16 * 144; e += 256) {
         const int ol = e / 144, r = e % 144;
-        if (r < run) G[(i64)w * ld + w_off + ((i64)(o0 + ol) * CIr + c0) * 9 + r] = tile[e];
+        if (r < run) G[(i64)w * ld + jb.w_off + ((i64)(o0 + ol) * jb.CIr + c0) * 9 + r] = tile[e];
     }
 }
 
@@ -648,7 +667,7 @@ bool wgrad_mfma_ok(const ConvDesc &c)
 }
 
 template <int CI, int CO, int STRIDE>
-dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs &a, float *G)
+dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs &a, WgradReduceJob *job)
 {
     constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, WT = wgrad_wave_groups(CI, CO), NTI = CI / 16 / WT;
     size_t shm = (size_t)CI * wgrad_channel_pitch((7 * STRIDE + 3) * STRIDE * (a.Wo + 16)) * sizeof(bf16_t);
@@ -658,8 +677,8 @@ dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs
     hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256 * WT), shm,
                        ctx->stream, a);
     constexpr int tiles = (CO / 16) * (CI / 16), psz = tiles * 9 * 256 + 1;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)(tiles + 1), (unsigned)ctx->n), dim3(256), 0, ctx->stream, a.part,
-                       a.splits, psz, CI / 16, a.CIr, G, ctx->ld, c.w_off, c.b_off);
+    job->part = a.part; job->w_off = c.w_off; job->b_off = c.b_off; job->splits = a.splits; job->psz = psz;
+    job->tiles = tiles; job->ci_tiles = CI / 16; job->CIr = a.CIr; job->block0 = 0;
     return hip_status(hipGetLastError());
 }
 
@@ -852,20 +871,48 @@ dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dou
     return launch_conv<64, 32, 1, 2, true>(ctx, a);
 }
 
-dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials)
+dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials,
+                              WgradReduceList *pending)
 {
-    if (!wgrad_mfma_ok(c) || !partials) return conv_weight_grad_generic(ctx, c, B, in, dout, G);
+    if (!wgrad_mfma_ok(c) || !partials || !pending) return conv_weight_grad_generic(ctx, c, B, in, dout, G);
+    if (pending->njobs >= kMaxReduceJobs) {   // (a network of more than 48 convolutions: sum what is pending first)
+        const dpsgd_status st = conv_weight_grad_finish(ctx, pending, G);
+        if (st != DPSGD_OK) return st;
+    }
     WgradMfmaArgs a{};
     a.inT = in.t; a.doutT = dout.t; a.H = c.H; a.W = c.W; a.Ho = c.Ho; a.Wo = c.Wo; a.B = B; a.CIr = c.Ci;
     a.splits = wgrad_splits(B, c.Co, c.stride); a.part = partials;
     const int cip = (c.Ci + 15) / 16 * 16;
+    WgradReduceJob job{};
+    dpsgd_status st;
     if (c.stride == 1) {
-        if (cip == 16) return launch_wgrad<16, 16, 1>(ctx, c, a, G);
-        if (cip == 32) return launch_wgrad<32, 32, 1>(ctx, c, a, G);
-        return launch_wgrad<64, 64, 1>(ctx, c, a, G);
+        if (cip == 16) st = launch_wgrad<16, 16, 1>(ctx, c, a, &job);
+        else if (cip == 32) st = launch_wgrad<32, 32, 1>(ctx, c, a, &job);
+        else st = launch_wgrad<64, 64, 1>(ctx, c, a, &job);
+    } else if (cip == 16) {
+        st = launch_wgrad<16, 32, 2>(ctx, c, a, &job);
+    } else {
+        st = launch_wgrad<32, 64, 2>(ctx, c, a, &job);
     }
-    if (cip == 16) return launch_wgrad<16, 32, 2>(ctx, c, a, G);
-    return launch_wgrad<32, 64, 2>(ctx, c, a, G);
+    if (st != DPSGD_OK) return st;
+    WgradReduceTable *tbl = reinterpret_cast<WgradReduceTable *>(pending->table);
+    job.block0 = pending->blocks;
+    tbl->job[pending->njobs] = job;
+    pending->njobs += 1;
+    tbl->njobs = pending->njobs;
+    pending->blocks += job.tiles + 1;
+    return DPSGD_OK;
+}
+
+dpsgd_status conv_weight_grad_finish(dpsgd_ctx *ctx, WgradReduceList *pending, float *G)
+{
+    if (!pending || pending->njobs == 0) return DPSGD_OK;
+    const WgradReduceTable *tbl = reinterpret_cast<const WgradReduceTable *>(pending->table);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)pending->blocks, (unsigned)ctx->n), dim3(256), 0, ctx->stream, *tbl, G,
+                       ctx->ld);
+    pending->njobs = 0;
+    pending->blocks = 0;
+    return hip_status(hipGetLastError());
 }
 
 }  // namespace dpsgd

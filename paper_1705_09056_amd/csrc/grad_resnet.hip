@@ -296,7 +296,8 @@ struct Workspace {
     std::vector<bf16_t *> wpack_f, wpack_d;
     bf16_t *image_bf16 = nullptr;         // bf16 copy of an fp32 image (channel-major, as given)
     bf16_t *image_nhwc8 = nullptr;        // image padded to 8 channels, pixel-major (MFMA stem only)
-    float *pool = nullptr, *dpool = nullptr, *logits = nullptr, *partials = nullptr;
+    float *pool = nullptr, *dpool = nullptr, *logits = nullptr;
+    std::vector<float *> partials;        // per conv: the partial sums of its weight gradient
     size_t bytes = 0;
 };
 
@@ -310,7 +311,8 @@ Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPla
         return q;
     };
     const size_t nB = (size_t)ctx->n * m.batch;
-    size_t biggest = 0, part = 0;
+    size_t biggest = 0;
+    std::vector<size_t> part;
     for (const ConvDesc &c : p.convs) {
         const size_t e = nB * c.Ho * c.Wo * c.Co;
         Tensor t;
@@ -320,8 +322,7 @@ Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPla
         biggest = e > biggest ? e : biggest;
         w.wpack_f.push_back((bf16_t *)take(conv_pack_bytes(c, false) * ctx->n));
         w.wpack_d.push_back((bf16_t *)take(conv_pack_bytes(c, true) * ctx->n));
-        const size_t pb = conv_wgrad_partial_bytes(c, m.batch) * ctx->n;
-        part = pb > part ? pb : part;
+        part.push_back(conv_wgrad_partial_bytes(c, m.batch) * ctx->n);
     }
     for (int i = 0; i < 3; ++i) w.delta[i].t = (bf16_t *)take(biggest * 2);
     if (!m.input_is_bf16) w.image_bf16 = (bf16_t *)take(nB * p.convs[0].Ci * p.convs[0].H * p.convs[0].W * 2);
@@ -329,7 +330,7 @@ Workspace carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, const ResnetPla
     w.pool = (float *)take(nB * p.C_last * 4);
     w.dpool = (float *)take(nB * p.C_last * 4);
     w.logits = (float *)take(nB * p.classes * 4);
-    w.partials = (float *)take(part);
+    for (size_t pb : part) w.partials.push_back((float *)take(pb));
     w.bytes = off + 256;
     return w;
 }
@@ -394,6 +395,7 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
 
     // ---- backward
     Tensor dv = ws.delta[0], du = ws.delta[1], dnext = ws.delta[2];
+    WgradReduceList pending;   // the sums over the weight-gradient partials, one launch after the last convolution
     {
         const i64 total = nB * HWl * p.C_last;
         hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks).t, ws.dpool, HWl,
@@ -402,10 +404,10 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     for (int j = p.nblocks - 1; j >= 0; --j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
         // conv2: weight and bias gradient from dv and u; du = [u > 0] * dgrad(dv)
-        if ((st = conv_weight_grad(ctx, c2, B, u_of(j), dv, G, ws.partials)) != DPSGD_OK) return st;
+        if ((st = conv_weight_grad(ctx, c2, B, u_of(j), dv, G, ws.partials[2 + 2 * j], &pending)) != DPSGD_OK) return st;
         if ((st = conv_data_grad(ctx, c2, B, dv, X, ws.wpack_d[2 + 2 * j], none, u_of(j), du)) != DPSGD_OK) return st;
         // conv1: from du and a_j; next dv = [a_j > 0] * (dgrad(du) + shortcut delta)
-        if ((st = conv_weight_grad(ctx, c1, B, a_of(j), du, G, ws.partials)) != DPSGD_OK) return st;
+        if ((st = conv_weight_grad(ctx, c1, B, a_of(j), du, G, ws.partials[1 + 2 * j], &pending)) != DPSGD_OK) return st;
         const ShortcutRef scd{dv.t, c2.Co, c2.Ho, c2.Wo, c1.stride};
         if ((st = conv_data_grad(ctx, c1, B, du, X, ws.wpack_d[1 + 2 * j], scd, a_of(j), dnext)) != DPSGD_OK) return st;
         Tensor t = dv; dv = dnext; dnext = t;
@@ -413,7 +415,7 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     if (stem_mfma) {   // stem: weight and bias gradient only
         Tensor img;
         img.t = const_cast<bf16_t *>(image_chw);
-        if ((st = conv_weight_grad(ctx, p.convs[0], B, img, dv, G, ws.partials)) != DPSGD_OK) return st;
+        if ((st = conv_weight_grad(ctx, p.convs[0], B, img, dv, G, ws.partials[0], &pending)) != DPSGD_OK) return st;
     } else {
         const ConvDesc &c = p.convs[0];
         dim3 grid((unsigned)c.Ci, (unsigned)c.Co, (unsigned)n);
@@ -424,7 +426,8 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
         hipLaunchKernelGGL(sum_delta_kernel, dim3((unsigned)n), dim3(1024), 0, s, dv.t, (i64)B * c.Ho * c.Wo * c.Co, G,
                            ctx->ld, c.b_off);
     }
-    return hip_status(hipGetLastError());
+    if ((st = hip_status(hipGetLastError())) != DPSGD_OK) return st;
+    return conv_weight_grad_finish(ctx, &pending, G);
 }
 
 // ---- shape-generic building blocks (used directly, and as the fallback of the MFMA dispatch)

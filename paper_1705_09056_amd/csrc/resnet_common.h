@@ -64,8 +64,19 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
 // din = round([act > 0] * (conv^T(dout) + shortcut delta)).
 dpsgd_status conv_data_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor dout, const float *X, const bf16_t *wpack_d,
                             ShortcutRef scd, Tensor act, Tensor din);
-// G[w_off..] = dout (*) in, G[b_off] = sum(dout).  partials: scratch of conv_wgrad_partial_bytes(c, B) * n bytes.
-dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials);
+// The weight-gradient kernels of the MFMA path leave partial sums (several workgroups per worker); what turns them
+// into G is collected here and done for all convolutions of the network by ONE launch, conv_weight_grad_finish.
+struct WgradReduceList {
+    alignas(8) unsigned char table[2560];   // the job table the reduction kernel takes as its argument
+    int njobs = 0, blocks = 0;
+};
+// G[w_off..] = dout (*) in, G[b_off] = sum(dout).  partials: this conv's own scratch of conv_wgrad_partial_bytes(c, B) * n
+// bytes, which must stay untouched until conv_weight_grad_finish(pending) has run on the same stream; G holds the
+// result only after that call.  Without partials or pending (or for shapes the MFMA kernel does not take) G is
+// written directly.
+dpsgd_status conv_weight_grad(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, Tensor dout, float *G, float *partials,
+                              WgradReduceList *pending);
+dpsgd_status conv_weight_grad_finish(dpsgd_ctx *ctx, WgradReduceList *pending, float *G);
 
 // Bytes per worker of the packed weights of one conv (forward operand, or data-gradient operand).
 size_t conv_pack_bytes(const ConvDesc &c, bool dgrad);
