@@ -626,6 +626,24 @@ __global__ void __launch_bounds__(256) consensus_stage2_kernel(const double *__r
     if (threadIdx.x == 0) out[0] = (float)(t * inv_n);
 }
 
+// Few partials (up to kSmallCount): both stages in one workgroup, one launch instead of two.
+__global__ void __launch_bounds__(256) consensus_small_kernel(const double *__restrict__ partials, int count, double inv_n,
+                                                               float *__restrict__ out)
+{
+    __shared__ double sh[256];
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int i = threadIdx.x;
+    for (; i + 768 < count; i += 1024) {
+        s0 += partials[i];
+        s1 += partials[i + 256];
+        s2 += partials[i + 512];
+        s3 += partials[i + 768];
+    }
+    for (; i < count; i += 256) s0 += partials[i];
+    const double t = block_sum_256((s0 + s1) + (s2 + s3), sh);
+    if (threadIdx.x == 0) out[0] = (float)(t * inv_n);
+}
+
 // --------------------------------------------------------------------------- host helpers
 struct Plan {
     int vec;        // floats per lane for the bulk launch
@@ -824,9 +842,15 @@ dpsgd_status stats_launch(dpsgd_ctx *ctx, const float *X, i64 col0, i64 ncols, f
 }
 
 constexpr int kStage1Blocks = 128;   // the partials buffer keeps this many extra slots at its end
+constexpr i64 kSmallCount = 8192;    // up to this many partials one workgroup sums them in one launch
 
 dpsgd_status finalize_consensus(dpsgd_ctx *ctx, i64 count, float *consensus)
 {
+    if (count <= kSmallCount) {
+        hipLaunchKernelGGL(consensus_small_kernel, dim3(1), dim3(256), 0, ctx->stream, ctx->d_partials, (int)count,
+                           1.0 / (double)ctx->n, consensus);
+        return hip_status(hipGetLastError());
+    }
     double *stage1 = ctx->d_partials + (ctx->partials_cap - kStage1Blocks);
     i64 per = (count + kStage1Blocks - 1) / kStage1Blocks;
     if (per < 256) per = 256;
