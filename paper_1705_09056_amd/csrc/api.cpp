@@ -330,6 +330,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
     } else if (k == "conv_band_rows") {
         if (!(value == 0 || value == 8 || value == 16)) return DPSGD_EINVAL;
         ctx->opt_conv_band_rows = (int32_t)value;
+    } else if (k == "ring_chunks") {
+        ctx->opt_ring_chunks = value ? 1 : 0;
     } else if (k == "fused_lds") {
         ctx->opt_fused_lds = value ? 1 : 0;
     } else if (k == "time_fused") {

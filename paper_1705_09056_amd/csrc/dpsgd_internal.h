@@ -48,6 +48,7 @@ struct dpsgd_ctx {
     int32_t opt_ring_rows = 1;      // dpsgd_step on the ring, minibatch <= 32: the [16 rows][1 KB] kernel where the layer's shape allows
 
     // measurement aid: HIP events around the fused wgrad+mix launches of dpsgd_step ("time_fused")
+    int32_t opt_ring_chunks = 1;    // the [16 rows][1 KB] kernel at K = 4096 or 8192: waves own 512-byte pieces 32 KB apart
     int32_t opt_fused_lds = 1;      // dpsgd_step on the ring, minibatch > 32: operands of the fused kernel through LDS
     int32_t opt_time_fused = 0;
     int32_t opt_conv_band_rows = 0; // output rows per workgroup of the MFMA convolutions: 8, 16, or 0 = chosen per convolution

@@ -1288,15 +1288,29 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_lds_kernel(FusedArgs a)
 // and written to the other of two buffers; one barrier per worker.  grid (K / 256, O / 16), block 256.
 constexpr int ROWS_PLANE = 66;   // 16-byte units per (sample octet, tile) plane of the activation buffer: 64 lanes + 2 of padding
 
-template <bool CONS, bool SHADOW>
+// RS: which elements of the workgroup's [16 rows][256 cols] a wave owns.  0: rows 4 wave .. + 3, all 256 columns (an
+// instruction covers 1 KB of one row).  1 or 2 (K = 8192 or 4096, i.e. RS rows = 32 KB): waves 2 g and 2 g + 1 share
+// eight rows RS apart and take 128 columns each; an instruction covers two 512-byte pieces of rows RS apart (lanes
+// 0-31 / 32-63) and the wave's eight pieces lie 32 KB apart, which the HBM channels serve faster (see
+// mix_ring_fat_kernel): an in-place walk with this kernel's traffic moves 6.1 TB/s that way against 5.75.
+// The same elements get the same sums: the three maps give the same bits.
+template <bool CONS, bool SHADOW, int RS>
 __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a)
 {
     __shared__ u32x4 bt[2][16 * ROWS_PLANE];   // [octet][tile t][lane]: samples 8 octet .. + 7 of column 4 lane + t
     __shared__ u32x4 at[2][64];                // [octet][row 0..15] of dZ^T
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int k0 = blockIdx.x * 256, o0 = blockIdx.y * 16;
-    // element (r, t) of this lane: row o0 + 4 wave + r, column k0 + 4 lane + t
-    float *xt = a.X + a.woff + (i64)(o0 + 4 * wave) * a.K + k0 + 4 * lane;
+    // element (r, t) of this lane: row o0 + row0 + rstep r, column k0 + col0 + t
+    //   RS 0: row0 = 4 wave, rstep = 1, col0 = 4 lane
+    //   RS 2: row0 = wave / 2 + 2 (lane / 32), rstep = 4 (rows wave / 2 + 2 j, j = 2 r + lane / 32), col0 = 128 (wave % 2) + 4 (lane % 32)
+    //   RS 1: row0 = 8 (wave / 2) + lane / 32, rstep = 2 (rows 8 (wave / 2) + j)
+    const int row0 = RS == 0 ? 4 * wave : RS == 2 ? (wave >> 1) + 2 * (lane >> 5) : 8 * (wave >> 1) + (lane >> 5);
+    constexpr int rstep = RS == 0 ? 1 : RS == 2 ? 4 : 2;
+    const int col0 = RS == 0 ? 4 * lane : 128 * (wave & 1) + 4 * (lane & 31);
+    const int bslot_read = col0 >> 2;   // this lane's slot in a plane of the activation buffer
+    const i64 rstride = (i64)rstep * a.K;
+    float *xt = a.X + a.woff + (i64)(o0 + row0) * a.K + k0 + col0;
     auto load_tile = [&](const float *p, i64 rs, float (&x)[16]) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -1328,9 +1342,9 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
 
     float xm[16], xc[16], xh[16], xn[16], xf[16], s1[16], s2[4] = {0.f, 0.f, 0.f, 0.f};
     fetch_ops(0);
-    load_tile(xt + (i64)(a.n - 1) * a.ld, a.K, xm);
-    load_tile(xt, a.K, xc);
-    load_tile(xt + (i64)(1 % a.n) * a.ld, a.K, xn);
+    load_tile(xt + (i64)(a.n - 1) * a.ld, rstride, xm);
+    load_tile(xt, rstride, xc);
+    load_tile(xt + (i64)(1 % a.n) * a.ld, rstride, xn);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         xh[v] = xc[v];
@@ -1347,25 +1361,25 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
         {
             const bool far = i + 2 < a.n;
             const float *src = far ? xt + (i64)(i + 2) * a.ld : reinterpret_cast<const float *>(a.dzt) + 4 * lane;
-            load_tile(src, far ? (i64)a.K : 0, xf);
+            load_tile(src, far ? rstride : 0, xf);
         }
         f32x4 acc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
         for (int oc = 0; oc < 4; ++oc) {
-            const u32x4 av = at[buf][oc * 16 + 4 * wave + (lane & 3)];
+            const u32x4 av = at[buf][oc * 16 + row0 + rstep * (lane & 3)];
             const s16x4 alo = __builtin_bit_cast(s16x4, u32x2{av.x, av.y}), ahi = __builtin_bit_cast(s16x4, u32x2{av.z, av.w});
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const u32x4 bv = bt[buf][(oc * 4 + t) * ROWS_PLANE + lane];
+                const u32x4 bv = bt[buf][(oc * 4 + t) * ROWS_PLANE + bslot_read];
                 acc[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(alo, __builtin_bit_cast(s16x4, u32x2{bv.x, bv.y}), acc[t], 0, 0, 0);
                 acc[t] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ahi, __builtin_bit_cast(s16x4, u32x2{bv.z, bv.w}), acc[t], 0, 0, 0);
             }
         }
         const bool last = i + 1 == a.n;
         float *dst = xt + (i64)i * a.ld;
-        bf16_t *sdst = SHADOW ? a.shadow + (i64)i * a.O * a.K + shadow_strip(o0 + 4 * wave, k0 + 4 * lane, a.K) : nullptr;
+        bf16_t *sdst = SHADOW ? a.shadow + (i64)i * a.O * a.K + shadow_strip(o0 + row0, k0 + col0, a.K) : nullptr;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             f32x4 out;
@@ -1387,10 +1401,10 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
                 xc[v] = nxt;
                 xn[v] = xf[v];
             }
-            __builtin_nontemporal_store(out, reinterpret_cast<f32x4 *>(dst + (i64)r * a.K));
+            __builtin_nontemporal_store(out, reinterpret_cast<f32x4 *>(dst + (i64)r * rstride));
             if (SHADOW) {   // the lane's four columns of the row, 8 bytes; the wave's row piece is 512 consecutive bytes
                 const u32x2 pk = {pack2(out.x, out.y), pack2(out.z, out.w)};
-                __builtin_nontemporal_store(pk, reinterpret_cast<u32x2 *>(sdst + r * 256));
+                __builtin_nontemporal_store(pk, reinterpret_cast<u32x2 *>(sdst + r * rstep * 256));
             }
         }
         stage_ops(buf ^ 1);   // every wave has read this buffer's previous contents before the barrier that ended step i - 1
@@ -1796,13 +1810,22 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             fa.shadow = wb_emit[l];
             if (rows_kernel[l]) {   // same number of workgroups and of partial sums as the 32 x 32 kernel
                 dim3 grid_rows((unsigned)(K / 256), (unsigned)(O / 16));
+                // rows of 32 KB (16 KB): a wave's pieces one row (two rows) apart
+                const int rs = !ctx->opt_ring_chunks ? 0 : K == 8192 ? 1 : K == 4096 ? 2 : 0;
+#define DPSGD_ROWS(CONS, SHADOW)                                                                                              \
+    do {                                                                                                                      \
+        if (rs == 2) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<CONS, SHADOW, 2>), grid_rows, dim3(256), 0, s, fa);      \
+        else if (rs == 1) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<CONS, SHADOW, 1>), grid_rows, dim3(256), 0, s, fa); \
+        else hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<CONS, SHADOW, 0>), grid_rows, dim3(256), 0, s, fa);              \
+    } while (0)
                 if (fa.shadow) {
-                    if (cons) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<true, true>), grid_rows, dim3(256), 0, s, fa);
-                    else hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<false, true>), grid_rows, dim3(256), 0, s, fa);
+                    if (cons) DPSGD_ROWS(true, true);
+                    else DPSGD_ROWS(false, true);
                 } else {
-                    if (cons) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<true, false>), grid_rows, dim3(256), 0, s, fa);
-                    else hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<false, false>), grid_rows, dim3(256), 0, s, fa);
+                    if (cons) DPSGD_ROWS(true, false);
+                    else DPSGD_ROWS(false, false);
                 }
+#undef DPSGD_ROWS
             } else if (fa.shadow) {
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, true>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, true>), grid, dim3(256), 0, s, fa);

@@ -283,6 +283,43 @@ def test_row_layout_ring_kernel_agrees_with_the_tile_layout_one(widths, batch, n
     assert bool(torch.all(Xb[:, d:] == X0[:, d:]))     # padding columns untouched
 
 
+@pytest.mark.parametrize("widths,batch,n,shadow", [
+    ((4096, 256, 10), 32, 3, 0),           # K = 4096: a wave's 512-byte pieces two rows apart (16 row groups)
+    ((4096, 288, 10), 20, 4, 0),           # 18 row groups, ragged minibatch
+    ((8192, 128, 10), 32, 3, 0),           # K = 8192: one row apart
+    ((1024, 4096, 1024, 10), 32, 3, 1),    # hidden layer with K = 4096 and its bf16 copy, written by one step and read by the next
+])
+def test_chunked_wave_map_of_the_row_kernel_changes_no_bit(widths, batch, n, shadow):
+    """The [16 rows][1 KB] kernel at K = 4096 or 8192: which wave owns which elements of the workgroup's tile
+    ("ring_chunks" 1, the default: 512-byte pieces 32 KB apart; 0: whole 1 KB rows) changes no sum: iterates, losses
+    and consensus distances are identical bit for bit over three iterations, with and without the bf16 weight copy."""
+    cfg = shrink(CONFIGS[3], widths=widths, batch=batch, n=n, iters=3)
+    d = synth.model_dim(cfg.model_kind, cfg.widths)
+    ld = synth.padded_stride(d)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    X0 = to_dev(synth.make_replicas(cfg), ld)
+    runs = []
+    for chunks in (1, 0):
+        X = X0.clone()
+        G = torch.zeros_like(X)
+        loss = torch.zeros(cfg.iters, cfg.n, device="cuda")
+        cons = torch.zeros(cfg.iters, device="cuda")
+        print(f"ring_chunks={chunks} widths={widths} B={batch} n={n} shadow={shadow}", flush=True)
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("bf16_shadow", shadow)
+            ctx.set_option("ring_chunks", chunks)
+            for k in range(cfg.iters):
+                inp, tgt = synth.make_batch(cfg, k)
+                ctx.step(model, X, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, G, loss[k], cons[k:k + 1],
+                         input_is_bf16=True)
+            torch.cuda.synchronize()
+        runs.append((X, loss, cons))
+    (Xa, la, ca), (Xb, lb, cb) = runs
+    assert not torch.equal(Xa, X0)
+    assert torch.equal(Xa, Xb), f"max |dX| {float((Xa - Xb).abs().max()):.3e}"
+    assert torch.equal(la, lb) and torch.equal(ca, cb)
+
+
 @pytest.mark.parametrize("widths,batch,n", [
     ((3072, 1024, 10), 128, 4),       # configs[2]'s layer: 8 operand steps per worker, 40 KB of LDS per workgroup
     ((1024, 1024, 10), 64, 5),        # 4 steps, odd ring
