@@ -467,6 +467,7 @@ def short_record(rec):
             "value": rec["value"], "unit": rec["unit"], "dtype": rec["dtype"],
             "dominant_kernel": rec["roofline"]["kernel"], "bound": "hbm", "achieved": rec["roofline"]["achieved"],
             "frac": rec["roofline"]["frac"], "avg_launch_ms": rec["roofline"]["avg_launch_ms"],
+            "traffic": rec["roofline"]["traffic"], "traffic_source": rec["roofline"]["traffic_source"],
             "algorithmic_bytes_per_launch": rec["roofline"]["algorithmic_bytes_per_launch"],
             "gradient_tflops": g["achieved_tflops"], "gradient_frac_of_peak": g["frac_of_peak"],
             "gradient_frac_of_intensity_ceiling": g["frac_of_ceiling"], "gradient_peak_kind": g["peak_kind"]}
@@ -499,7 +500,11 @@ def main():
     if plain and args.workload == "mlp3_ring64" and not args.no_others:
         others = []
         for name, extra in OTHERS:
-            a = argparse.Namespace(**{**vars(args), "workload": name, "steps": 10, "warmup": 3, "repeats": 3, **extra})
+            # short runs: 10 iterations of the multi-millisecond workloads, 100 of those whose iteration is a fraction
+            # of a millisecond (ten of them are over before the clocks and caches have settled)
+            quick = name in ("mlp2_ring32", "softmax_ring16", "lsq_ring8")
+            a = argparse.Namespace(**{**vars(args), "workload": name, "steps": 100 if quick else 10,
+                                      "warmup": 10 if quick else 3, "repeats": 3, **extra})
             others.append(short_record(run_one(a, False)))
         out["others"] = others
     print(json.dumps(out))
