@@ -414,8 +414,9 @@ struct WgradMfmaArgs {
     float *part;           // [n][splits][(CO/16)*(CI/16)*9*256 + 1], accumulator order
 };
 
-// 16-byte units of a band's source rows a thread holds while they are in flight (10 rows at stride 1, 17 at stride 2)
-__host__ __device__ constexpr int wgrad_stage(int stride) { return stride == 1 ? 3 : 5; }
+// 16-byte units of a band's source rows a thread holds while they are in flight (8-row bands: 10 rows at stride 1,
+// 17 at stride 2; 16-row bands, stride 1 only: 18 rows)
+__host__ __device__ constexpr int wgrad_stage(int stride, int rb) { return rb == 16 ? 5 : stride == 1 ? 3 : 5; }
 
 __host__ __device__ constexpr int wgrad_channel_pitch(int plane) { return (plane + 119) / 128 * 128 + 8; }
 
@@ -423,12 +424,15 @@ __host__ __device__ constexpr int wgrad_channel_pitch(int plane) { return (plane
 // registers (one wave per SIMD); two groups of four waves split them instead.
 constexpr int wgrad_wave_groups(int ci, int co) { return (ci >= 64 && co >= 64) ? 2 : 1; }
 
-template <int CI, int CO, int STRIDE>
+// RB: output rows per band, 8 or 16.  Every band costs a workgroup two exposed memory latencies (the band's first
+// delta operand, and the next band's source rows, which the short multiply does not cover); 16-row bands halve their
+// number where the image has them.
+template <int CI, int CO, int STRIDE, int RB>
 __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4 : 2)) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
 {
-    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, RB = 8;
+    constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM;
     constexpr int WT = wgrad_wave_groups(CI, CO), NTI = CI / 16 / WT, NT = 256 * WT;
-    constexpr int kWgradStage = wgrad_stage(STRIDE);
+    constexpr int kWgradStage = wgrad_stage(STRIDE, RB);
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *band = reinterpret_cast<bf16_t *>(smem);   // [CI] planes of CP elements, each [ROWS][PLANES][WPAD]
     const int sp = blockIdx.x, w = blockIdx.y;
@@ -656,12 +660,29 @@ int wgrad_splits(int B, int co, int stride)
     return B < m ? B : m;
 }
 
+size_t wgrad_lds_bytes(int ci, int stride, int rb, int Wo)
+{
+    return (size_t)ci * wgrad_channel_pitch(((rb - 1) * stride + 3) * stride * (Wo + 16)) * sizeof(bf16_t);
+}
+
+// Output rows per band of the weight-gradient kernel: 16 at stride 1 and 32 or more channels where the image has them
+// and the band's source rows fit the staging registers and 64 KB of LDS (32 channels on 16 x 16 images: 45.3 -> 39.8
+// us), else 8 (with 16 channels the two more staging registers do not fit beside four workgroups per CU: 54.4 -> 55.9).
+int wgrad_band_rows(const ConvDesc &c)
+{
+    const int cip = (c.Ci + 15) / 16 * 16;
+    if (c.stride == 1 && cip >= 32 && c.Ho % 16 == 0 && cip * 18 * (c.W / 8) <= wgrad_stage(1, 16) * 256 &&
+        wgrad_lds_bytes(cip, 1, 16, c.Wo) <= 64 * 1024)
+        return 16;
+    return 8;
+}
+
 bool wgrad_mfma_ok(const ConvDesc &c)
 {
     const int cip = (c.Ci + 15) / 16 * 16;
     if (!pow2_channels(c.Co) || !pow2_channels(cip)) return false;
     if (c.Ho % 8 || c.Wo % 8 || c.W % 8 || c.W > 64) return false;
-    if (cip * (7 * c.stride + 3) * (c.W / 8) > wgrad_stage(c.stride) * 256) return false;   // a band's source rows fit the staging registers
+    if (cip * (7 * c.stride + 3) * (c.W / 8) > wgrad_stage(c.stride, 8) * 256) return false;   // a band's source rows fit the staging registers
     if (c.stride == 1) return cip == c.Co;
     return c.stride == 2 && c.Co == 2 * c.Ci && c.Ci <= 32 && c.W == 2 * c.Wo && c.H == 2 * c.Ho;
 }
@@ -670,12 +691,18 @@ template <int CI, int CO, int STRIDE>
 dpsgd_status launch_wgrad(dpsgd_ctx *ctx, const ConvDesc &c, const WgradMfmaArgs &a, WgradReduceJob *job)
 {
     constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM, WT = wgrad_wave_groups(CI, CO), NTI = CI / 16 / WT;
-    size_t shm = (size_t)CI * wgrad_channel_pitch((7 * STRIDE + 3) * STRIDE * (a.Wo + 16)) * sizeof(bf16_t);
+    const int rb = STRIDE == 1 ? wgrad_band_rows(c) : 8;
+    size_t shm = wgrad_lds_bytes(CI, STRIDE, rb, a.Wo);
     const size_t red = (size_t)(WK - 1) * WM * NTI * 9 * 256 * sizeof(float);
     if (red > shm) shm = red;
     if (shm < 64) shm = 64;
-    hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE>), dim3((unsigned)a.splits, (unsigned)ctx->n), dim3(256 * WT), shm,
-                       ctx->stream, a);
+    const dim3 grid((unsigned)a.splits, (unsigned)ctx->n), block(256 * WT);
+    if constexpr (STRIDE == 1 && CI >= 32) {
+        if (rb == 16) hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE, 16>), grid, block, shm, ctx->stream, a);
+        else hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE, 8>), grid, block, shm, ctx->stream, a);
+    } else {
+        hipLaunchKernelGGL((conv_wgrad_mfma_kernel<CI, CO, STRIDE, 8>), grid, block, shm, ctx->stream, a);
+    }
     constexpr int tiles = (CO / 16) * (CI / 16), psz = tiles * 9 * 256 + 1;
     job->part = a.part; job->w_off = c.w_off; job->b_off = c.b_off; job->splits = a.splits; job->psz = psz;
     job->tiles = tiles; job->ci_tiles = CI / 16; job->CIr = a.CIr; job->block0 = 0;
