@@ -584,6 +584,45 @@ column_stats_kernel(const float *__restrict__ X, int n, i64 ncols, i64 ld, int b
     }
 }
 
+// The node average of a wide matrix with fat lanes and the chunked column ownership of mix_ring_fat_kernel (one wave
+// per workgroup, P float4 column groups per lane, 512-byte chunks 32 KB apart): the same sums in the same order
+// (rows ascending), read faster.  grid.x = 64 x (ncols / fat_super<P>()), block 64; 16-byte aligned rows.
+template <int P>
+__global__ void __launch_bounds__(64)
+column_mean_fat_kernel(const float *__restrict__ X, int n, i64 ld, float inv_n, float *__restrict__ xbar)
+{
+    typedef VecT<4>::type vec;
+    const int lane = threadIdx.x;
+    constexpr i64 kPerSuper = kFatStride / (kFatChunkLanes * 4);
+    constexpr i64 kStep = (64 / kFatChunkLanes) * kFatStride;
+    const i64 sb = blockIdx.x / kPerSuper, k = blockIdx.x % kPerSuper;
+    const i64 c0 = sb * fat_super<P>() + k * (kFatChunkLanes * 4) + (lane % kFatChunkLanes) * 4 +
+                   (i64)(lane / kFatChunkLanes) * kFatStride;
+    vec sum[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) sum[q] = (vec)(0.f);
+    int row = 0;
+    for (; row + 2 <= n; row += 2) {   // two rows (2 P loads per lane) in flight
+        vec a[P], b[P];
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            a[q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(X + (i64)row * ld + c0 + (i64)q * kStep));
+            b[q] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(X + (i64)(row + 1) * ld + c0 + (i64)q * kStep));
+        }
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            sum[q] += a[q];
+            sum[q] += b[q];
+        }
+    }
+    for (; row < n; ++row)
+#pragma unroll
+        for (int q = 0; q < P; ++q)
+            sum[q] += __builtin_nontemporal_load(reinterpret_cast<const vec *>(X + (i64)row * ld + c0 + (i64)q * kStep));
+#pragma unroll
+    for (int q = 0; q < P; ++q) vstore<4>(xbar + c0 + (i64)q * kStep, sum[q] * inv_n);
+}
+
 // Fixed-order sum of the per-workgroup partials in two stages: block b of the first stage sums the
 // contiguous slice [b*per, (b+1)*per) into stage1[b]; the second stage (one block) adds those and
 // writes consensus = (sum partials) / n.  The order depends only on the launch shape.
@@ -1003,7 +1042,18 @@ dpsgd_status launch_mean(dpsgd_ctx *ctx, const float *X, float *xbar)
     const Plan p = make_plan(ctx, vec);
     i64 np = 0;
     dpsgd_status st = DPSGD_OK;
-    if (p.bulk_cols) {
+    constexpr int kMeanP = 4;
+    if (vec == 4 && !ctx->opt_mix_narrow && p.bulk_cols / fat_super<kMeanP>() >= 64) {
+        // wide matrix: whole super-blocks of columns go to the fat-lane kernel, the rest to the kernel below
+        const i64 supers = p.bulk_cols / fat_super<kMeanP>(), fat_cols = supers * fat_super<kMeanP>();
+        const i64 groups = supers * (kFatStride / (kFatChunkLanes * 4));
+        if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
+        hipLaunchKernelGGL(column_mean_fat_kernel<kMeanP>, dim3((unsigned)groups), dim3(64), 0, ctx->stream, X, ctx->n, ctx->ld,
+                           1.0f / (float)ctx->n, xbar);
+        st = hip_status(hipGetLastError());
+        if (st == DPSGD_OK && fat_cols < p.bulk_cols)
+            st = stats_launch<4, true, false>(ctx, X, fat_cols, p.bulk_cols - fat_cols, xbar, nullptr, &np);
+    } else if (p.bulk_cols) {
         if (vec == 4) st = stats_launch<4, true, false>(ctx, X, 0, p.bulk_cols, xbar, nullptr, &np);
         else if (vec == 2) st = stats_launch<2, true, false>(ctx, X, 0, p.bulk_cols, xbar, nullptr, &np);
         else st = stats_launch<1, true, false>(ctx, X, 0, p.bulk_cols, xbar, nullptr, &np);

@@ -191,6 +191,24 @@ def test_mean(n, d, ld):
     check_close(out.cpu().numpy(), oracle.mean(X), TOL, "xbar")
 
 
+@pytest.mark.parametrize("n", [1, 2, 5])
+def test_mean_of_a_wide_matrix_takes_the_fat_lane_kernel(n):
+    """64 whole super-blocks of 65 536 columns and a ragged rest: the fat-lane mean kernel, the ordinary one on the
+    rest, against the oracle; and bit for bit against the ordinary kernel alone ("mix_narrow")."""
+    d = 64 * 65536 + 3 * 256 + 3
+    ld = d + 5 - (d + 5) % 4 + 4
+    X, _ = random_state(n, d, 7 + n, spread=1.0)
+    Xd = to_dev(X, ld)
+    out, ref = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda")
+    with B.Dpsgd(n, d, B.Topology.ring(), 0.1, ld=ld) as ctx:
+        ctx.mean(Xd, out)
+        ctx.set_option("mix_narrow", 1)
+        ctx.mean(Xd, ref)
+        torch.cuda.synchronize()
+    check_close(out.cpu().numpy(), oracle.mean(X), TOL, "xbar")
+    assert torch.equal(out, ref)
+
+
 def test_multi_step_invariants_on_device():
     """Node-average recursion (proof of Theorem 1) and consensus decay hold for the GPU iterates."""
     n, d, ld, gamma = 16, 4099, 4160, 0.1
