@@ -126,19 +126,18 @@ __device__ __forceinline__ void combine_bands(ColStats<V> &st, float *lds, int b
 }
 
 // ------------------------------------------------------------------------------- ring
-// grid.x = column groups of 64*V columns; block = 64 * bands threads; wave b owns rows
-// [b*rpb, min(n,(b+1)*rpb)).
+// One column group of 64*V columns (group `grp`), walked by a workgroup of 64 * bands threads; wave b owns rows
+// [b*rpb, min(n,(b+1)*rpb)).  The group's consensus partial goes to partials[part].
 // MOM: heavy-ball variant, the step uses v = mu * Vel + g and Vel is overwritten with it.
 template <int V, int U, bool CONS, bool MOM>
-__global__ void __launch_bounds__(512)
-mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld, float w,
-                float gamma, int bands, int rpb, double *__restrict__ partials, float *__restrict__ Vel, float mu)
+__device__ __forceinline__ void ring_walk(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld,
+                                          float w, float gamma, int bands, int rpb, double *__restrict__ partials,
+                                          float *__restrict__ Vel, float mu, float *lds, i64 grp, i64 part)
 {
     typedef typename VecT<V>::type vec;
-    extern __shared__ float lds[];
     const int lane = threadIdx.x & 63;
     const int band = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const i64 c0 = ((i64)blockIdx.x * 64 + lane) * V;
+    const i64 c0 = (grp * 64 + lane) * V;
     const bool active = c0 + V <= ncols;
     const int r0 = band * rpb;
     const int r1 = min(n, r0 + rpb);
@@ -217,9 +216,26 @@ mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int 
         combine_bands<V>(st, lds, band, lane, bands);
         if (band == 0) {
             double v = wave_sum((double)st.m2());
-            if (lane == 0) partials[blockIdx.x] = v;
+            if (lane == 0) partials[part] = v;
         }
     }
+}
+
+// grid.x = column groups of 64*V columns (+ 1 when tail > 0); block = 64 * bands threads.  ncols is a multiple of V.
+// tail (V > 1 only, at most V - 1): the columns ncols .. ncols + tail - 1, which the last workgroup walks one per lane
+// - the same arithmetic, in the same launch, instead of a launch of their own.
+template <int V, int U, bool CONS, bool MOM>
+__global__ void __launch_bounds__(512)
+mix_ring_kernel(const float *Xin, const float *__restrict__ G, float *Xout, int n, i64 ncols, i64 ld, float w,
+                float gamma, int bands, int rpb, double *__restrict__ partials, float *__restrict__ Vel, float mu, int tail)
+{
+    extern __shared__ float lds[];
+    if (V > 1 && tail > 0 && blockIdx.x == gridDim.x - 1) {
+        ring_walk<1, U, CONS, MOM>(Xin + ncols, G + ncols, Xout + ncols, n, tail, ld, w, gamma, bands, rpb, partials,
+                                   MOM ? Vel + ncols : nullptr, mu, lds, 0, blockIdx.x);
+        return;
+    }
+    ring_walk<V, U, CONS, MOM>(Xin, G, Xout, n, ncols, ld, w, gamma, bands, rpb, partials, Vel, mu, lds, blockIdx.x, blockIdx.x);
 }
 
 // The same walk for wide matrices with fat lanes: one wave per workgroup, every lane owns P float4 column groups, U
@@ -736,10 +752,11 @@ int pick_bands(const dpsgd_ctx *ctx, i64 groups)
 
 size_t stats_lds_bytes(int bands, int vec) { return bands > 1 ? (size_t)bands * 64 * (3 * vec + 1) * sizeof(float) : 0; }
 
+// tail: columns right after [col0, col0 + ncols) that the same launch walks one per lane (V > 1, tail < V)
 template <int V>
 dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float *Xout, i64 col0, i64 ncols,
                          bool cons, double *partials, i64 *nparts, float *Vel = nullptr, float mu = 0.f,
-                         bool narrow = false)
+                         bool narrow = false, int tail = 0)
 {
     const i64 groups = groups_for(ncols, V);
     const int bands = pick_bands(ctx, groups);
@@ -764,25 +781,28 @@ dpsgd_status ring_launch(dpsgd_ctx *ctx, const float *Xin, const float *G, float
         i64 rest = 0;
         if (st == DPSGD_OK && fat_cols < ncols)
             st = ring_launch<V>(ctx, Xin, G, Xout, col0 + fat_cols, ncols - fat_cols, cons, partials + fat_groups, &rest,
-                                Vel, mu, true);
+                                Vel, mu, true, tail);
+        else if (st == DPSGD_OK && tail)
+            st = ring_launch<1>(ctx, Xin, G, Xout, col0 + ncols, tail, cons, partials + fat_groups, &rest, Vel, mu);
         *nparts = fat_groups + rest;
         return st;
     }
     const int rpb = (ctx->n + bands - 1) / bands;
     const int used = (ctx->n + rpb - 1) / rpb;   // every launched band owns at least one row
-    dim3 grid((unsigned)groups), block(64u * (unsigned)used);
-    if (groups > 0x7fffffffLL) return DPSGD_EUNSUPPORTED;
+    const i64 wgs = groups + ((V > 1 && tail > 0) ? 1 : 0);
+    dim3 grid((unsigned)wgs), block(64u * (unsigned)used);
+    if (wgs > 0x7fffffffLL || tail >= V) return DPSGD_EUNSUPPORTED;
     const size_t shm = cons ? stats_lds_bytes(used, V) : 0;
     float *vel = Vel ? Vel + col0 : nullptr;
 #define DPSGD_RING(CONS, MOM)                                                                                        \
     hipLaunchKernelGGL((mix_ring_kernel<V, 4, CONS, MOM>), grid, block, shm, ctx->stream, Xin + col0, G + col0,      \
-                       Xout + col0, ctx->n, ncols, ctx->ld, ctx->ring_w, ctx->gamma, used, rpb, partials, vel, mu)
+                       Xout + col0, ctx->n, ncols, ctx->ld, ctx->ring_w, ctx->gamma, used, rpb, partials, vel, mu, tail)
     if (cons && vel) DPSGD_RING(true, true);
     else if (cons) DPSGD_RING(true, false);
     else if (vel) DPSGD_RING(false, true);
     else DPSGD_RING(false, false);
 #undef DPSGD_RING
-    *nparts = groups;
+    *nparts = wgs;
     return hip_status(hipGetLastError());
 }
 
@@ -940,12 +960,14 @@ dpsgd_status launch_mix(dpsgd_ctx *ctx, const float *Xin, const float *G, float 
     if (ring) {
         const int vec = pick_vec(ctx, {Xin, G, Xout, Vel ? Vel : Xin}, 4);
         const Plan p = make_plan(ctx, vec);
+        // the columns beyond the last whole vector ride along in the bulk launch (its last workgroup)
+        const int tail = (int)p.tail_cols;
         if (p.bulk_cols) {
-            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu);
-            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu);
+            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu, false, tail);
+            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu, false, tail);
             else st = ring_launch<1>(ctx, Xin, G, Xout, 0, p.bulk_cols, cons, ctx->d_partials, &n1, Vel, mu);
         }
-        if (st == DPSGD_OK && p.tail_cols)
+        if (st == DPSGD_OK && p.tail_cols && (!p.bulk_cols || vec == 1))
             st = ring_launch<1>(ctx, Xin, G, Xout, p.bulk_cols, p.tail_cols, cons, ctx->d_partials + n1, &n2, Vel, mu);
         if (st != DPSGD_OK) return st;
         return cons ? finalize_consensus(ctx, n1 + n2, consensus) : DPSGD_OK;
@@ -1014,11 +1036,12 @@ dpsgd_status launch_mix_range(dpsgd_ctx *ctx, const float *Xin, const float *G, 
     double *part = ctx->d_partials + *nparts;
     if (ring) {
         if (bulk) {
-            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
-            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
+            if (vec == 4) st = ring_launch<4>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1, nullptr, 0.f, false, (int)tail);
+            else if (vec == 2) st = ring_launch<2>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1, nullptr, 0.f, false, (int)tail);
             else st = ring_launch<1>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
         }
-        if (st == DPSGD_OK && tail) st = ring_launch<1>(ctx, Xin, G, Xout, col0 + bulk, tail, cons, part + n1, &n2);
+        if (st == DPSGD_OK && tail && (!bulk || vec == 1))
+            st = ring_launch<1>(ctx, Xin, G, Xout, col0 + bulk, tail, cons, part + n1, &n2);
     } else {
         if (bulk) {
             if (vec == 4) st = slab_launch<4, false>(ctx, Xin, G, Xout, col0, bulk, cons, part, &n1);
