@@ -1829,7 +1829,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             } else if (fa.shadow) {
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, true>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, true>), grid, dim3(256), 0, s, fa);
-            } else if (Bp >= 64 && ctx->opt_fused_lds) {   // operands through LDS: 5 KB per 16 minibatch rows
+            } else if (Bp >= 64 && Bp <= 192 && ctx->opt_fused_lds) {   // operands through LDS: 5 KB per 16 minibatch rows (at most 60 KB)
                 const size_t shm = (size_t)5 * (Bp / 16) * 1024;
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_lds_kernel<true>), grid, dim3(256), shm, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_lds_kernel<false>), grid, dim3(256), shm, s, fa);
