@@ -78,6 +78,7 @@ def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0):
     ((1024, 1024, 1024, 10), 32, 4),    # two fused layers
     ((1024, 1024, 96, 10), 48, 3),      # a layer too small to fuse between fused ones; 64-row tiling
     ((2048, 512, 10), 128, 3),          # minibatch 128
+    ((1024, 1024, 10), 200, 3),         # minibatch padded to 224: beyond what the LDS operand buffer of the fused kernel holds
     ((100, 70, 33, 5), 37, 4),          # nothing fusable: plain ranges only
 ])
 def test_step_mlp_bf16_ring(widths, batch, n):
