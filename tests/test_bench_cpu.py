@@ -43,3 +43,34 @@ def test_cnn_flop_count_is_about_three_forward_passes():
     g = bench.gradient_roofline(cfg, d, 1.0)
     fwd_mac_per_image = 40.6e6            # stem 0.44 M + 6 x 2.36 M + (1.18 M + 5 x 2.36 M) x 2
     assert g["flop_per_step"] == pytest.approx(2 * 3 * fwd_mac_per_image * 32 * 112, rel=0.02)
+
+
+def test_every_traffic_line_under_profiles_names_a_kernel_and_a_stride_that_exist():
+    """The `bench-traffic:` lines bench.py reads its counter traffic from: each parses, names a kernel that is still in
+    the sources, a benchmark workload, and the row stride bench.py gives that workload by default - a profile that has
+    gone stale (a renamed kernel, a changed stride) fails here instead of silently yielding `traffic: null`."""
+    import glob
+    import json
+    import re
+    src = ""
+    for f in glob.glob(os.path.join(ROOT, "paper_1705_09056_amd", "csrc", "*.hip")):
+        with open(f) as fh:
+            src += fh.read()
+    lines = []
+    for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        with open(f) as fh:
+            lines += [(os.path.basename(f), ln) for ln in fh if "bench-traffic:" in ln]
+    assert len(lines) >= 4
+    for name, ln in lines:
+        rec = json.loads(ln.split("bench-traffic:", 1)[1].strip())
+        assert re.search(r"\b" + re.escape(rec["kernel"]) + r"\b", src), (name, rec["kernel"])
+        cfg = by_name(rec["workload"])
+        d = synth.model_dim(cfg.model_kind, cfg.widths)
+        assert rec["ld"] >= d and rec["ld"] % 64 == 0
+        assert rec["path"] in ("fused", "two-call")
+        # the counted bytes are at least the algorithmic ones of that path and within 20 % of them
+        n = cfg.n
+        if rec["path"] == "two-call":
+            assert 12.0 * n * d <= rec["bytes_per_launch"] <= 1.2 * 12.0 * n * d
+        got, where = bench.traffic_from_profile(rec["workload"], rec["path"], rec["kernel"] + " (anything)", rec["ld"])
+        assert got == rec["bytes_per_launch"] and where == name
