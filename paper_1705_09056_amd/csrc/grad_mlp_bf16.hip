@@ -1300,14 +1300,20 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
     __shared__ u32x4 bt[2][16 * ROWS_PLANE];   // [octet][tile t][lane]: samples 8 octet .. + 7 of column 4 lane + t
     __shared__ u32x4 at[2][64];                // [octet][row 0..15] of dZ^T
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int k0 = blockIdx.x * 256, o0 = blockIdx.y * 16;
+    // RS 3 (rows of 4, 8 or 12 KB: K a multiple of 1024): the workgroup owns 16 rows of a block of 32, wave rows 8 apart
+    // (a multiple of 32 KB), whole 1 KB pieces: rows 4 half + wave + 8 r of block blockIdx.y / 2, half = blockIdx.y % 2
+    const int k0 = blockIdx.x * 256, o0 = RS == 3 ? (blockIdx.y >> 1) * 32 : blockIdx.y * 16;
     // element (r, t) of this lane: row o0 + row0 + rstep r, column k0 + col0 + t
     //   RS 0: row0 = 4 wave, rstep = 1, col0 = 4 lane
     //   RS 2: row0 = wave / 2 + 2 (lane / 32), rstep = 4 (rows wave / 2 + 2 j, j = 2 r + lane / 32), col0 = 128 (wave % 2) + 4 (lane % 32)
     //   RS 1: row0 = 8 (wave / 2) + lane / 32, rstep = 2 (rows 8 (wave / 2) + j)
-    const int row0 = RS == 0 ? 4 * wave : RS == 2 ? (wave >> 1) + 2 * (lane >> 5) : 8 * (wave >> 1) + (lane >> 5);
-    constexpr int rstep = RS == 0 ? 1 : RS == 2 ? 4 : 2;
-    const int col0 = RS == 0 ? 4 * lane : 128 * (wave & 1) + 4 * (lane & 31);
+    const int row0 = RS == 0 ? 4 * wave : RS == 2 ? (wave >> 1) + 2 * (lane >> 5) : RS == 1 ? 8 * (wave >> 1) + (lane >> 5)
+                                                                                   : 4 * (int)(blockIdx.y & 1) + wave;
+    constexpr int rstep = RS == 0 ? 1 : RS == 2 ? 4 : RS == 1 ? 2 : 8;
+    // the workgroup's 16 rows of dZ^T sit in LDS slots 0 .. 15; slot of this lane's row r: slot0 + sstep r
+    const int slot0 = RS == 3 ? wave : row0;
+    constexpr int sstep = RS == 3 ? 4 : rstep;
+    const int col0 = (RS == 0 || RS == 3) ? 4 * lane : 128 * (wave & 1) + 4 * (lane & 31);
     const int bslot_read = col0 >> 2;   // this lane's slot in a plane of the activation buffer
     const i64 rstride = (i64)rstep * a.K;
     float *xt = a.X + a.woff + (i64)(o0 + row0) * a.K + k0 + col0;
@@ -1325,8 +1331,10 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
     const int bslot = (((tid >> 5) & 3) * 4 + (tid & 3)) * ROWS_PLANE + (tid >> 7) * 8 + ((tid & 31) >> 2);
     // dZ^T: lane (octet = lane / 16, row = lane % 16) of every wave fetches one unit; wave 0 writes them
     const int aoc = lane >> 4;
+    // slot lane % 16 holds row (o0 % 32) + slot, or (RS 3) row 4 half + slot % 4 + 8 (slot / 4) of the block
+    const int arow = RS == 3 ? 4 * (int)(blockIdx.y & 1) + (lane & 3) + 8 * ((lane & 15) >> 2) : (o0 & 31) + (lane & 15);
     const u32x4 *asrc = reinterpret_cast<const u32x4 *>(
-        a.dzt + ((i64)(o0 >> 5) * 2 + (aoc >> 1)) * 512 + (aoc & 1) * 256 + ((o0 & 31) + (lane & 15)) * 8);
+        a.dzt + ((i64)(o0 >> 5) * 2 + (aoc >> 1)) * 512 + (aoc & 1) * 256 + arow * 8);
     const i64 b_worker = (i64)a.K * 4, a_worker = (i64)a.O * 4;   // 16-byte units per worker (32 samples x 2 bytes)
     u32x4 breg[4], areg;
     auto fetch_ops = [&](int worker) {
@@ -1368,7 +1376,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
         for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
         for (int oc = 0; oc < 4; ++oc) {
-            const u32x4 av = at[buf][oc * 16 + row0 + rstep * (lane & 3)];
+            const u32x4 av = at[buf][oc * 16 + slot0 + sstep * (lane & 3)];
             const s16x4 alo = __builtin_bit_cast(s16x4, u32x2{av.x, av.y}), ahi = __builtin_bit_cast(s16x4, u32x2{av.z, av.w});
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
@@ -1811,11 +1819,12 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             if (rows_kernel[l]) {   // same number of workgroups and of partial sums as the 32 x 32 kernel
                 dim3 grid_rows((unsigned)(K / 256), (unsigned)(O / 16));
                 // rows of 32 KB (16 KB): a wave's pieces one row (two rows) apart
-                const int rs = !ctx->opt_ring_chunks ? 0 : K == 8192 ? 1 : K == 4096 ? 2 : 0;
+                const int rs = !ctx->opt_ring_chunks ? 0 : K == 8192 ? 1 : K == 4096 ? 2 : ((K % 1024) == 0 && !fa.shadow) ? 3 : 0;
 #define DPSGD_ROWS(CONS, SHADOW)                                                                                              \
     do {                                                                                                                      \
         if (rs == 2) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<CONS, SHADOW, 2>), grid_rows, dim3(256), 0, s, fa);      \
         else if (rs == 1) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<CONS, SHADOW, 1>), grid_rows, dim3(256), 0, s, fa); \
+        else if (rs == 3) hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<CONS, false, 3>), grid_rows, dim3(256), 0, s, fa);  \
         else hipLaunchKernelGGL((mlp_fused_ring_rows_kernel<CONS, SHADOW, 0>), grid_rows, dim3(256), 0, s, fa);              \
     } while (0)
                 if (fa.shadow) {

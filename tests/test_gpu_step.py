@@ -289,11 +289,15 @@ def test_row_layout_ring_kernel_agrees_with_the_tile_layout_one(widths, batch, n
     ((4096, 288, 10), 20, 4, 0),           # 18 row groups, ragged minibatch
     ((8192, 128, 10), 32, 3, 0),           # K = 8192: one row apart
     ((1024, 4096, 1024, 10), 32, 3, 1),    # hidden layer with K = 4096 and its bf16 copy, written by one step and read by the next
+    ((3072, 512, 10), 32, 3, 0),           # K = 3072 (12 KB rows): a wave's 1 KB pieces eight rows apart, 16 rows of a block of 32 per workgroup
+    ((1024, 1056, 2048, 10), 20, 4, 0),    # K = 1024 and K = 1056 (no map: not a multiple of 1024); 33 blocks of 32 rows
+    ((2048, 512, 10), 32, 5, 0),           # K = 2048
 ])
 def test_chunked_wave_map_of_the_row_kernel_changes_no_bit(widths, batch, n, shadow):
-    """The [16 rows][1 KB] kernel at K = 4096 or 8192: which wave owns which elements of the workgroup's tile
-    ("ring_chunks" 1, the default: 512-byte pieces 32 KB apart; 0: whole 1 KB rows) changes no sum: iterates, losses
-    and consensus distances are identical bit for bit over three iterations, with and without the bf16 weight copy."""
+    """The [16 rows][1 KB] kernel: which wave owns which rows ("ring_chunks" 1, the default: pieces a multiple of 32 KB
+    apart where the row length allows it - K = 4096 or 8192: 512-byte pieces; other multiples of 1024: 1 KB pieces
+    eight rows apart; 0: four consecutive rows per wave) changes no sum: iterates, losses and consensus distances are
+    identical bit for bit over three iterations, with and without the bf16 weight copy."""
     cfg = shrink(CONFIGS[3], widths=widths, batch=batch, n=n, iters=3)
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = synth.padded_stride(d)
