@@ -841,10 +841,17 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
         }
     };
     // fp32 weights (unless the bf16 copy is used) and the delta tile
+    // which row of the [64 o][TK k] tile unit u = tid + 256 q takes.  TK = 128 (a row piece is 512 bytes, half a
+    // wave): the two halves of a wave take rows two apart, so that with 16 KB rows every piece a wave fetches lies a
+    // multiple of 32 KB from the others, which the HBM channels serve faster (see mix_ring_fat_kernel).
+    auto tile_row = [&](int u) {
+        const int r = u / (TK / 4);
+        return TK == 128 ? (r & ~7) + ((r >> 1) & 1) + 2 * (r & 1) + 4 * ((r >> 2) & 1) : r;
+    };
     auto fetch = [&](int oc) {
 #pragma unroll
         for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
-            const int u = tid + 256 * q, orow = u / (TK / 4), kq = (u % (TK / 4)) * 4;
+            const int u = tid + 256 * q, orow = tile_row(u), kq = (u % (TK / 4)) * 4;
             const int o = oc + orow, k = kt0 + kq;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (o < g.O) {
@@ -884,7 +891,7 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
         bf16_t *Wb = Wt + buf * KC * WP, *Db = Dt + buf * MBLK * PITCH;
 #pragma unroll
         for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
-            const int u = tid + 256 * q, orow = u / (TK / 4), kq = (u % (TK / 4)) * 4;
+            const int u = tid + 256 * q, orow = tile_row(u), kq = (u % (TK / 4)) * 4;
             u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
             *reinterpret_cast<u32x2 *>(Wb + orow * WP + kq) = p;
         }
