@@ -161,8 +161,8 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * between two dpsgd_step calls nobody else writes X; every dpsgd_mix_step* call, a change of this option, another
  * X or model, and calls recorded under stream capture drop the copy.  Costs 2 bytes per hidden-layer weight and
  * worker of device memory.  The iterates are bit for bit those of the same "ring_rows" setting without the copy),
- * "ring_chunks" (default 1: in that [16 rows][1 KB] kernel, for layers with 4096 or 8192 inputs, a wave owns 512-byte
- * pieces of rows 32 KB apart instead of whole 1 KB rows; 0: whole rows.  Same bits),
+ * "ring_chunks" (default 1: in that [16 rows][1 KB] kernel, for layers whose number of inputs is a multiple of 1024, a
+ * wave owns pieces of rows a multiple of 32 KB apart instead of four consecutive rows; 0: consecutive rows.  Same bits),
  * "fused_lds" (default 1: dpsgd_step on the ring, bf16 MLP, minibatch of more than 32 rows: the operands of the fused
  * weight-gradient + mix kernel travel from L2 into LDS asynchronously, one worker ahead; 0: they are fetched into
  * registers two steps at a time.  Same bits),
