@@ -507,10 +507,13 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
             *reinterpret_cast<u32x4 *>(Wb + row * PITCH2 + kq) = br[q];
         }
     };
+    // which of the tile's 64 rows the 512-byte piece r = (tid + 256 q) / 32 is: the two halves of a wave take rows two
+    // apart, so that with 16 KB rows every piece a wave fetches lies a multiple of 32 KB from the others
+    auto tile_row = [](int r) { return (r & ~7) + ((r >> 1) & 1) + 2 * (r & 1) + 4 * ((r >> 2) & 1); };
     auto fetch_w32 = [&](int k0) {
 #pragma unroll
         for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
-            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
+            const int u = tid + 256 * q, row = tile_row(u >> 5), kq = (u & 31) * 4;
             const int o = o0 + row, k = k0 + kq;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (o < g.O) {
@@ -531,7 +534,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
         bf16_t *Wb = Wt + buf * TO * PITCH2;
 #pragma unroll
         for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
-            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
+            const int u = tid + 256 * q, row = tile_row(u >> 5), kq = (u & 31) * 4;
             u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
             *reinterpret_cast<u32x2 *>(Wb + row * PITCH2 + kq) = p;
         }
