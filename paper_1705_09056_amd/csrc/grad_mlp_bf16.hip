@@ -82,6 +82,17 @@ __device__ __forceinline__ i64 shadow_strip(int o, int k, int K)
     return ((i64)(o >> 4) * (K >> 8) + (k >> 8)) * 4096 + (o & 15) * 256 + (k & 255);
 }
 
+// Which of the 64 rows of a [64 rows][512 bytes] fp32 weight tile the piece r = 2 wave + half + 8 q is (wave 0..3, half
+// of the wave, instruction q 0..7), i.e. which rows one wave's load instructions touch.  The HBM channels serve a wave
+// faster when all its pieces lie a multiple of 32 KB apart (see mix_ring_fat_kernel): with rows of 16 KB or a multiple
+// (K % 4096 == 0) the halves of a wave take rows two apart and the wave keeps to rows of one parity (-5 and -7 us per
+// iteration in the data gradient and the forward of the 4096 x 4096 layer of configs[3]); else consecutive rows (for
+// 12 KB rows, halves eight rows apart were measured and are slightly slower).  A permutation of 0..63 either way.
+__device__ __forceinline__ int weight_tile_row(int r, int K)
+{
+    return (K & 4095) == 0 ? (r & ~7) + ((r >> 1) & 1) + 2 * (r & 1) + 4 * ((r >> 2) & 1) : r;
+}
+
 // Workgroups are dealt to the 8 XCDs round-robin by linear id and every XCD has its own L2.  For a grid
 // (tiles, 1, n) with n a multiple of 8 the ids are renumbered so that all tiles of a worker run on one XCD and
 // the worker's activation (or delta) matrix is fetched into one L2 instead of eight.
@@ -384,7 +395,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fwd_wide_kernel(FwdArgs g)
         }
 #pragma unroll
         for (int q = 0; q < WQ; ++q) {
-            const int u = tid + 256 * q, o = o0 + (u >> 5), k = k0 + (u & 31) * 4;
+            const int u = tid + 256 * q, o = o0 + weight_tile_row(u >> 5, g.K), k = k0 + (u & 31) * 4;
             wreg[q] = __builtin_nontemporal_load(
                 reinterpret_cast<const f32x4 *>(Wg + (i64)(o < g.O ? o : g.O - 1) * g.K + (k < g.K ? k : 0)));
         }
@@ -392,7 +403,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fwd_wide_kernel(FwdArgs g)
     auto stage = [&](int k0) {
 #pragma unroll
         for (int q = 0; q < WQ; ++q) {
-            const int u = tid + 256 * q, row = u >> 5, kq = (u & 31) * 4;
+            const int u = tid + 256 * q, row = weight_tile_row(u >> 5, g.K), kq = (u & 31) * 4;
             u32x2 p = {pack2(wreg[q].x, wreg[q].y), pack2(wreg[q].z, wreg[q].w)};
             if (!(o0 + row < g.O && k0 + kq < g.K)) p = (u32x2){0u, 0u};
             *reinterpret_cast<u32x2 *>(Wt + row * PITCHW + kq) = p;
@@ -507,9 +518,7 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
             *reinterpret_cast<u32x4 *>(Wb + row * PITCH2 + kq) = br[q];
         }
     };
-    // which of the tile's 64 rows the 512-byte piece r = (tid + 256 q) / 32 is: the two halves of a wave take rows two
-    // apart, so that with 16 KB rows every piece a wave fetches lies a multiple of 32 KB from the others
-    auto tile_row = [](int r) { return (r & ~7) + ((r >> 1) & 1) + 2 * (r & 1) + 4 * ((r >> 2) & 1); };
+    auto tile_row = [&](int r) { return weight_tile_row(r, g.K); };   // the 512-byte piece r = (tid + 256 q) / 32
     auto fetch_w32 = [&](int k0) {
 #pragma unroll
         for (int q = 0; q < (WB16 ? 0 : WQ); ++q) {
@@ -844,12 +853,10 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
         }
     };
     // fp32 weights (unless the bf16 copy is used) and the delta tile
-    // which row of the [64 o][TK k] tile unit u = tid + 256 q takes.  TK = 128 (a row piece is 512 bytes, half a
-    // wave): the two halves of a wave take rows two apart, so that with 16 KB rows every piece a wave fetches lies a
-    // multiple of 32 KB from the others, which the HBM channels serve faster (see mix_ring_fat_kernel).
+    // which row of the [64 o][TK k] tile unit u = tid + 256 q takes (TK = 128: a row piece is 512 bytes, half a wave)
     auto tile_row = [&](int u) {
         const int r = u / (TK / 4);
-        return TK == 128 ? (r & ~7) + ((r >> 1) & 1) + 2 * (r & 1) + 4 * ((r >> 2) & 1) : r;
+        return TK == 128 ? weight_tile_row(r, g.K) : r;
     };
     auto fetch = [&](int oc) {
 #pragma unroll
