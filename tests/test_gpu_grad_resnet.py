@@ -87,6 +87,16 @@ def test_resnet_fp32_inputs_on_the_mfma_path():
     grad_case(cfg, synth.padded_stride(d), bf16_inputs=False)
 
 
+@pytest.mark.parametrize("widths,batch", [((3, 32, 16, 16, 1, 10), 3), ((3, 16, 32, 16, 1, 10), 2), ((3, 48, 32, 16, 1, 10), 2)])
+def test_resnet_rectangular_images(widths, batch):
+    """Heights and widths that differ, and a height (48) that 16 divides but 32 does not: the 16-row workgroup tiles of
+    the convolutions and the 16-row bands of the weight gradient at stage 2 see 32 x 16, 16 x 32 and 48 x 32 pixels
+    (stage 2: half of that, stage 3: a quarter, where 8-row tiles take over)."""
+    cfg = shrink(CONFIGS[4], widths=widths, batch=batch, n=2)
+    d = synth.model_dim(MODEL_RESNET20, widths)
+    grad_case(cfg, synth.padded_stride(d), plain=False)
+
+
 def test_resnet_config4_shape_two_workers():
     cfg = shrink(CONFIGS[4], n=3)
     d = synth.model_dim(MODEL_RESNET20, cfg.widths)
