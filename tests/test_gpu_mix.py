@@ -98,6 +98,15 @@ def test_wide_matrices_through_the_slab_kernel(inplace):
     run_mix(72, d, ld, B.Topology.torus(8, 9), oracle.torus(8, 9).with_fp32_values(), 24, inplace, True)   # one float4 per lane
 
 
+@pytest.mark.parametrize("extra", [0, 3, 4 * 64 + 1])
+def test_wide_ring_whose_columns_end_at_or_just_past_whole_super_blocks(extra):
+    """64 super-blocks of 131 072 columns exactly, plus nothing, plus three columns (no whole float4 left: the fat-lane
+    kernel, then the tail alone), plus one column group and one column (the tail rides in the remainder's launch)."""
+    d = 64 * 131072 + extra
+    ld = (d + 3) // 4 * 4
+    run_mix(3, d, ld, B.Topology.ring(), oracle.ring(3).with_fp32_values(), 40 + extra, True, True)
+
+
 @pytest.mark.parametrize("dims", [(3, 3), (8, 8), (5, 4), (3, 8), (9, 7)])
 @pytest.mark.parametrize("inplace", [False, True])
 def test_wide_torus(dims, inplace):
