@@ -1490,7 +1490,7 @@ __global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTor
     const bf16_t *bo = a.at + op_off(k0 + 2 * n16 + 1);     // B of the odd columns
     const int cl = (c + C - 1) % C, cr = (c + 1) % C;
 
-    float up[8], cur[8], down[8], first[8], ahead[8], shift[8], s1[8], s2[8];
+    float up[8], cur[8], down[8], first[8], last[8], ahead[8], shift[8], s1[8], s2[8];
     auto load_tile = [&](float *dst, int r) {
         const float *p = xt + (i64)(r * C + c) * a.ld;
 #pragma unroll
@@ -1506,6 +1506,7 @@ __global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTor
 #pragma unroll
     for (int v = 0; v < 8; ++v) {
         first[v] = cur[v];
+        last[v] = up[v];
         s1[v] = 0.f;
         s2[v] = 0.f;
         shift[v] = 0.f;
@@ -1517,10 +1518,10 @@ __global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTor
         mine[lane] = (f32x4){cur[0], cur[1], cur[2], cur[3]};
         mine[64 + lane] = (f32x4){cur[4], cur[5], cur[6], cur[7]};
         __syncthreads();
-        if (r + 2 < R) load_tile(ahead, r + 2);
-        else {
+        if (r + 3 < R) load_tile(ahead, r + 2);
+        else {   // grid row R - 1 was fetched before the walk and kept: every tile is read once; the last grid row wraps to row 0
 #pragma unroll
-            for (int v = 0; v < 8; ++v) ahead[v] = first[v];   // the last grid row wraps to row 0
+            for (int v = 0; v < 8; ++v) ahead[v] = r + 3 == R ? last[v] : first[v];
         }
         const int worker = r * C + c;
         f32x4 acc_e = {0.f, 0.f, 0.f, 0.f}, acc_o = {0.f, 0.f, 0.f, 0.f};
