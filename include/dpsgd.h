@@ -166,6 +166,10 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * "fused_lds" (default 1: dpsgd_step on the ring, bf16 MLP, minibatch of more than 32 rows: the operands of the fused
  * weight-gradient + mix kernel travel from L2 into LDS asynchronously, one worker ahead; 0: they are fetched into
  * registers two steps at a time.  Same bits),
+ * "class_bwd" (default 1: bf16 MLP whose last layer has at most 16 outputs, minibatch of at most 256 rows: the weight,
+ * bias and data gradient of that layer and the bias gradient of the layer below come from one launch in which a thread
+ * walks the samples of one column of the activations; 0: the tiled kernels of the other layers, three launches.  The
+ * two add up the same products in a different order: results agree to fp32 rounding of the sums),
  * "conv_band_rows" (output rows of an image per workgroup of the CNN's 3 x 3 convolution kernels: 8, 16, or 0 = chosen
  * per convolution, the default; every setting gives the same bits),
  * "time_fused" (see dpsgd_read_timing). */

@@ -334,6 +334,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
         ctx->opt_ring_chunks = value ? 1 : 0;
     } else if (k == "fused_lds") {
         ctx->opt_fused_lds = value ? 1 : 0;
+    } else if (k == "class_bwd") {
+        ctx->opt_class_bwd = value ? 1 : 0;
     } else if (k == "time_fused") {
         ctx->opt_time_fused = value ? 1 : 0;
     } else {

@@ -986,6 +986,117 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
     }
 }
 
+// ------------------------------------------------ backward of the class layer in one launch
+// A layer with at most 16 outputs (the 10 classes) has next to no arithmetic: its weight gradient, its data gradient
+// and the bias gradient of the layer below are each a few FMAs per element of the activation matrix h below it, and
+// as three launches of the tiled kernels above they are 3/4 padding.  Here a thread owns one column k of h and the
+// SG groups of 256 / SG threads of a workgroup deal the samples among themselves in octets (group s takes octets s,
+// s + SG, ...; SG = 4 for minibatches of 64 rows and more, else 1: a thread walks all samples):
+// dW[c][k] += dZ[b][c] h[b][k], dZ'[b][k] = [h[b][k] > 0] sum_c dZ[b][c] bf16(W[c][k]), db'[k] += bf16(dZ'[b][k]) -
+// the operands and roundings of the kernels it replaces (bf16 deltas, activations and weights, fp32 sums).  A thread
+// requests up to 32 samples of its column at once (the launch is bound by that round trip, not by arithmetic); the
+// SG partial sums of dW and db' meet in LDS and are added in group order.  The worker's deltas sit in LDS as fp32.
+// grid (ceil(K SG / 256), n), block 256; C <= CP <= 16 (the arithmetic is unrolled for CP outputs), Bp <= 256.
+struct ClassBwdArgs {
+    const bf16_t *dz;     // [n][B][C] deltas of the class layer
+    const bf16_t *h;      // [n][B][K] post-ReLU activations of the layer below
+    const float *X;
+    float *G;
+    i64 ld, woff, boff, boff_below;
+    bf16_t *dzp;          // [n][B][K] deltas of the layer below, or null when nothing reads them
+    bf16_t *dzpt;         // their T copy
+    int B, Bp, K, C;
+};
+
+template <int CP, int SG>
+__global__ void __launch_bounds__(256) mlp_class_bwd_kernel(ClassBwdArgs g)
+{
+    constexpr int NCOL = 256 / SG;
+    __shared__ float dzs[256][16];
+    __shared__ float red[SG > 1 ? SG : 1][CP + 1][SG > 1 ? NCOL : 1];
+    const int lane = threadIdx.x % NCOL, sg = threadIdx.x / NCOL;
+    const int w = blockIdx.y, k = blockIdx.x * NCOL + lane;
+    const bool k_ok = k < g.K;
+    for (int e = threadIdx.x; e < g.Bp * 16; e += 256) {
+        const int b = e >> 4, c = e & 15;
+        dzs[b][c] = (b < g.B && c < g.C) ? bf2f(g.dz[((i64)w * g.B + b) * g.C + c]) : 0.f;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && (int)threadIdx.x < g.C) {   // bias gradient of the class layer
+        float s = 0.f;
+        for (int b = 0; b < g.B; ++b) s += dzs[b][threadIdx.x];
+        g.G[(i64)w * g.ld + g.boff + threadIdx.x] = s;
+    }
+    float wb[CP], gw[CP];
+#pragma unroll
+    for (int c = 0; c < CP; ++c) {
+        wb[c] = (k_ok && c < g.C) ? bf2f(f2bf(g.X[(i64)w * g.ld + g.woff + (i64)c * g.K + k])) : 0.f;
+        gw[c] = 0.f;
+    }
+    const bf16_t *hp = g.h + (i64)w * g.B * g.K + (k_ok ? k : 0);
+    bf16_t *dst_t = g.dzpt + tfrag_worker(w, g.K, g.Bp);
+    float db = 0.f;
+    const int noct = g.Bp >> 3;
+    for (int base = 0; base < noct; base += 4 * SG) {
+        bf16_t hv[4][8];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int b0 = (base + SG * jj + sg) * 8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) hv[jj][j] = b0 + j < g.B ? hp[(i64)(b0 + j) * g.K] : (bf16_t)0;
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int oc = base + SG * jj + sg;
+            if (oc >= noct) break;
+            const int b0 = oc * 8;
+            unsigned short out[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int b = b0 + j;
+                const bf16_t hraw = hv[jj][j];
+                const float hf = bf2f(hraw);
+                float da = 0.f;
+#pragma unroll
+                for (int c = 0; c < CP; ++c) {
+                    const float d = dzs[b][c];
+                    da = __builtin_fmaf(d, wb[c], da);
+                    gw[c] = __builtin_fmaf(d, hf, gw[c]);
+                }
+                const bool pos = (hraw & 0x7fffu) != 0 && (hraw & 0x8000u) == 0;   // ReLU'(z) = [z > 0]
+                const bf16_t v = f2bf(pos ? da : 0.f);
+                out[j] = v;
+                db += bf2f(v);
+                if (g.dzp && b < g.B && k_ok) g.dzp[((i64)w * g.B + b) * g.K + k] = v;
+            }
+            const u32x4 pk = {(unsigned)out[0] | ((unsigned)out[1] << 16), (unsigned)out[2] | ((unsigned)out[3] << 16),
+                              (unsigned)out[4] | ((unsigned)out[5] << 16), (unsigned)out[6] | ((unsigned)out[7] << 16)};
+            if (k_ok) *reinterpret_cast<u32x4 *>(dst_t + tfrag_off(k, b0, g.Bp)) = pk;
+        }
+    }
+    if (SG == 1) {
+        if (!k_ok) return;
+#pragma unroll
+        for (int c = 0; c < CP; ++c)
+            if (c < g.C) g.G[(i64)w * g.ld + g.woff + (i64)c * g.K + k] = gw[c];
+        g.G[(i64)w * g.ld + g.boff_below + k] = db;
+        return;
+    }
+#pragma unroll
+    for (int c = 0; c < CP; ++c) red[sg][c][lane] = gw[c];
+    red[sg][CP][lane] = db;
+    __syncthreads();
+    if (!k_ok) return;
+    // the groups' partial sums in group order; group s writes the outputs c = s, s + SG, ... (c = CP: the bias below)
+    for (int c = sg; c <= CP; c += SG) {
+        float t = red[0][c][lane];
+#pragma unroll
+        for (int q = 1; q < SG; ++q) t += red[q][c][lane];
+        if (c == CP) g.G[(i64)w * g.ld + g.boff_below + k] = t;
+        else if (c < g.C) g.G[(i64)w * g.ld + g.woff + (i64)c * g.K + k] = t;
+    }
+}
+
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 struct Tiling { int wm, wn, mt; };
@@ -1772,12 +1883,36 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
     hipLaunchKernelGGL(softmax_xent_bf16_kernel, dim3((unsigned)n), dim3(256), 0, s, ws.logits, (const int *)targets, B, Bp,
                        C, ws.dz[cur], ws.dzt[L], loss);
     std::vector<char> fused(L, 0);
+    bool bias_below_done = false;
     for (int l = L - 1; l >= 0 && st == DPSGD_OK; --l) {
         const int K = m.widths[l], O = m.widths[l + 1];
         fused[l] = fuse && layer_fusable(ctx, K, O, woff[l]) && (ctx->ring_uniform || (reinterpret_cast<uintptr_t>(X) & 7) == 0);
+        if (l == L - 1 && l > 0 && O <= 16 && Bp <= 256 && !fused[l] && ctx->opt_class_bwd) {
+            // the class layer: weight, bias and data gradient and the bias gradient of the layer below in one launch
+            ClassBwdArgs ca{};
+            ca.dz = ws.dz[cur]; ca.h = ws.h[l]; ca.X = X; ca.G = G; ca.ld = ctx->ld; ca.woff = woff[l]; ca.boff = boff[l];
+            ca.boff_below = boff[l - 1];
+            ca.dzp = l - 1 > 0 ? ws.dz[cur ^ 1] : nullptr;   // read by the data gradient of the layer below, if there is one
+            ca.dzpt = ws.dzt[l];
+            ca.B = B; ca.Bp = Bp; ca.K = K; ca.C = O;
+            const int sgroups = Bp >= 64 ? 4 : 1;   // sample groups per workgroup, 256 / sgroups columns each
+            const dim3 cgrid((unsigned)(((i64)K * sgroups + 255) / 256), (unsigned)n);
+            if (sgroups == 4) {
+                if (O <= 10) hipLaunchKernelGGL((mlp_class_bwd_kernel<10, 4>), cgrid, dim3(256), 0, s, ca);
+                else hipLaunchKernelGGL((mlp_class_bwd_kernel<16, 4>), cgrid, dim3(256), 0, s, ca);
+            } else {
+                if (O <= 10) hipLaunchKernelGGL((mlp_class_bwd_kernel<10, 1>), cgrid, dim3(256), 0, s, ca);
+                else hipLaunchKernelGGL((mlp_class_bwd_kernel<16, 1>), cgrid, dim3(256), 0, s, ca);
+            }
+            st = hip_status(hipGetLastError());
+            bias_below_done = true;
+            cur ^= 1;
+            continue;
+        }
         if (fused[l]) {   // only the bias gradient goes to G; the weight gradient is formed inside the mix
-            hipLaunchKernelGGL(bias_grad_bf16_kernel, dim3((unsigned)((O + 255) / 256), (unsigned)n), dim3(256), 0, s,
-                               ws.dzt[l + 1], O, Bp, G, ctx->ld, boff[l]);
+            if (!(bias_below_done && l == L - 2))
+                hipLaunchKernelGGL(bias_grad_bf16_kernel, dim3((unsigned)((O + 255) / 256), (unsigned)n), dim3(256), 0, s,
+                                   ws.dzt[l + 1], O, Bp, G, ctx->ld, boff[l]);
         } else {
             WgradArgs wa{};
             wa.dzt = ws.dzt[l + 1]; wa.at = actt[l]; wa.G = G; wa.ld = ctx->ld; wa.woff = woff[l]; wa.boff = boff[l];

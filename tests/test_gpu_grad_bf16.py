@@ -127,3 +127,31 @@ def test_config2_full_size_sampled_workers():
 
 def test_config3_full_size_sampled_workers():
     sampled_full_size(CONFIGS[3], [5, 63])
+
+
+@pytest.mark.parametrize("widths,batch,n", [((3072, 1024, 10), 128, 3), ((200, 150, 70, 10), 20, 4), ((96, 50, 16), 33, 2)])
+def test_class_layer_backward_in_one_launch_agrees_with_the_tiled_kernels(widths, batch, n):
+    """The class layer's backward (weight, bias and data gradient, bias gradient of the layer below) as one launch
+    against the three launches of the tiled kernels it replaces ("class_bwd" 0): the same products, summed in another
+    order, so the gradients agree far inside the bar to the oracle."""
+    cfg = shrink(CONFIGS[2], widths=widths, batch=batch, n=n)
+    d = synth.model_dim(MODEL_MLP, widths)
+    ld = synth.padded_stride(d)
+    X, inp, tgt = mlp_inputs(cfg, 0, 0.3, 0.0)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    out = []
+    for setting in (1, 0):
+        Xd = to_dev(X, ld)
+        Gd = torch.full_like(Xd, 777.0)
+        loss = torch.zeros(cfg.n, device="cuda")
+        print(f"class_bwd={setting} widths={widths} n={n} B={batch}", flush=True)
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("class_bwd", setting)
+            ctx.grad(model, Xd, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, Gd, loss, input_is_bf16=True)
+            torch.cuda.synchronize()
+        out.append(from_dev(Gd, d))
+    for p in synth.param_layout(cfg.model_kind, cfg.widths):
+        sl = slice(p.offset, p.offset + p.size)
+        e = rel_err(out[0][:, sl], out[1][:, sl])
+        print(f"  {p.name}: one launch vs tiled kernels {e:.3e}", flush=True)
+        assert e < 5e-4
