@@ -183,6 +183,11 @@ struct FwdArgs {
     float *z;              // [n][B][O]   (last layer, fp32 logits)
     const bf16_t *wb;      // bf16 copy of the weights left by the previous fused step, or null
     int wb_strips;         // its layout: 0 = 32 x 32 tiles (shadow_tile), 1 = [16][256] tiles (shadow_strip)
+    // class layer only (mlp_fwd_last_kernel), or null: softmax cross-entropy in the same launch
+    const int *labels;     // [n][B]
+    bf16_t *sm_dz;         // [n][B][O] deltas of the class layer
+    bf16_t *sm_dzt;        // their T copy
+    float *loss_part;      // [n][ceil(B / 32)]: each workgroup's sum of the sample losses
 };
 
 // Epilogue of one 32 x 32 accumulator tile of the forward product: lane owns output column o and the 16 rows
@@ -640,10 +645,13 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
 // would walk the whole contraction alone.  Here a workgroup owns 32 samples of one worker and its 8
 // waves split K; operands come straight from global memory (activations bf16, weights fp32 rounded
 // in registers), the partial tiles meet in LDS.  grid (ceil(B / 32), n), block 512.  K % 16 == 0.
+// With g.sm_dz set the launch goes on to the softmax cross-entropy of its 32 samples (the arithmetic of
+// softmax_xent_bf16_kernel, a thread per sample) and leaves the sum of their losses in g.loss_part.
 __global__ void __launch_bounds__(512) mlp_fwd_last_kernel(FwdArgs g)
 {
     constexpr int NW = 8;
     __shared__ float red[NW][16][64];
+    __shared__ float zs[32][33];
     const int w = blockIdx.y, b0 = blockIdx.x * 32;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -678,8 +686,40 @@ __global__ void __launch_bounds__(512) mlp_fwd_last_kernel(FwdArgs g)
         float sum = 0.f;
 #pragma unroll
         for (int q = 0; q < NW; ++q) sum += red[q][v][l];
-        g.z[((i64)w * g.B + bb) * g.O + oo] = sum + g.X[(i64)w * g.ld + g.boff + oo];
+        sum += g.X[(i64)w * g.ld + g.boff + oo];
+        g.z[((i64)w * g.B + bb) * g.O + oo] = sum;
+        if (g.sm_dz) zs[bb - b0][oo] = sum;
     }
+    if (!g.sm_dz) return;
+    __syncthreads();
+    if (threadIdx.x >= 64) return;
+    float local = 0.f;
+    if (threadIdx.x < 32) {
+        const int bb = b0 + (int)threadIdx.x, C = g.O;
+        bf16_t *dzt = g.sm_dzt + tfrag_worker(w, C, g.Bp);
+        if (bb >= g.B) {   // a padded sample: zeros in the T copy
+            if (bb < g.Bp)
+                for (int c = 0; c < C; ++c) dzt[tfrag_off(c, bb, g.Bp)] = 0;
+        } else {
+            const float *zb = zs[threadIdx.x];
+            const float invB = 1.0f / (float)g.B;
+            int lab = g.labels[(i64)w * g.B + bb];
+            lab = lab < 0 ? 0 : (lab >= C ? C - 1 : lab);
+            float mx = zb[0];
+            for (int c = 1; c < C; ++c) mx = fmaxf(mx, zb[c]);
+            float se = 0.f;
+            for (int c = 0; c < C; ++c) se += expf(zb[c] - mx);
+            const float lse = mx + logf(se);
+            local = lse - zb[lab];
+            for (int c = 0; c < C; ++c) {
+                const bf16_t v = f2bf((expf(zb[c] - lse) - (c == lab ? 1.f : 0.f)) * invB);
+                g.sm_dz[((i64)w * g.B + bb) * C + c] = v;
+                dzt[tfrag_off(c, bb, g.Bp)] = v;
+            }
+        }
+    }
+    for (int off = 16; off > 0; off >>= 1) local += __shfl_down(local, off, 64);
+    if (threadIdx.x == 0) g.loss_part[(i64)w * gridDim.x + blockIdx.x] = local;
 }
 
 // ------------------------------------------------------------- softmax cross-entropy
@@ -1006,6 +1046,10 @@ struct ClassBwdArgs {
     bf16_t *dzp;          // [n][B][K] deltas of the layer below, or null when nothing reads them
     bf16_t *dzpt;         // their T copy
     int B, Bp, K, C;
+    // with the softmax in the class layer's forward launch: its per-workgroup loss sums, to be added up here
+    const float *loss_part;   // [n][chunks] or null
+    int chunks;
+    float *loss;              // [n]
 };
 
 template <int CP, int SG>
@@ -1026,6 +1070,11 @@ __global__ void __launch_bounds__(256) mlp_class_bwd_kernel(ClassBwdArgs g)
         float s = 0.f;
         for (int b = 0; b < g.B; ++b) s += dzs[b][threadIdx.x];
         g.G[(i64)w * g.ld + g.boff + threadIdx.x] = s;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 64 && g.loss_part && g.loss) {   // the worker's loss: partial sums in order
+        float s = 0.f;
+        for (int c = 0; c < g.chunks; ++c) s += g.loss_part[(i64)w * g.chunks + c];
+        g.loss[w] = s * (1.0f / (float)g.B);
     }
     float wb[CP], gw[CP];
 #pragma unroll
@@ -1724,7 +1773,7 @@ namespace {
 struct MlpWs {
     bf16_t *a0 = nullptr, *at0 = nullptr;
     std::vector<bf16_t *> h, ht, dzt;   // per layer output l = 1..L: h/ht for hidden layers, dzt for all
-    float *logits = nullptr;
+    float *logits = nullptr, *loss_part = nullptr;
     bf16_t *dz[2] = {nullptr, nullptr};
     size_t bytes = 0;
 };
@@ -1756,6 +1805,7 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
         widest = widest > (size_t)m.widths[l] ? widest : (size_t)m.widths[l];
     }
     w.logits = (float *)take(n * B * (size_t)m.widths[L] * 4);
+    w.loss_part = (float *)take(n * ((B + 31) / 32) * 4);
     for (int i = 0; i < 2; ++i) w.dz[i] = (bf16_t *)take(n * B * widest * 2);
     w.bytes = off + 256;
     return w;
@@ -1861,6 +1911,11 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
     }
     const Tiling t = pick_tiling(B);
     dpsgd_status st = DPSGD_OK;
+    // a class layer of at most 16 outputs on top of a hidden layer: its backward is one launch (mlp_class_bwd_kernel)
+    // and the softmax rides in its forward launch
+    const bool class_path = L > 1 && m.widths[L] <= 16 && Bp <= 256 && ctx->opt_class_bwd &&
+                            !(fuse && layer_fusable(ctx, m.widths[L - 1], m.widths[L], woff[L - 1]));
+    bool softmax_in_fwd = false;
     for (int l = 0; l < L && st == DPSGD_OK; ++l) {
         FwdArgs a{};
         a.act = act[l]; a.X = X; a.ld = ctx->ld; a.woff = woff[l]; a.boff = boff[l];
@@ -1871,6 +1926,10 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
         a.wb_strips = strips_use[l];
         const bool vec = base_ok && (a.K % 8) == 0 && (woff[l] % 4) == 0 && aligned16(act[l]);
         if (last && vec && a.O <= 32 && (a.K % 16) == 0 && a.K >= 256) {
+            if (class_path) {
+                a.labels = (const int *)targets; a.sm_dz = ws.dz[0]; a.sm_dzt = ws.dzt[L]; a.loss_part = ws.loss_part;
+                softmax_in_fwd = true;
+            }
             hipLaunchKernelGGL(mlp_fwd_last_kernel, dim3((unsigned)((B + 31) / 32), (unsigned)n), dim3(512), 0, s, a);
             st = hip_status(hipGetLastError());
         } else if (t.mt == 1) st = fwd_ksplit_launch(s, n, a, vec, last);
@@ -1880,14 +1939,15 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
     if (st != DPSGD_OK) return st;
     const int C = m.widths[L];
     int cur = 0;
-    hipLaunchKernelGGL(softmax_xent_bf16_kernel, dim3((unsigned)n), dim3(256), 0, s, ws.logits, (const int *)targets, B, Bp,
-                       C, ws.dz[cur], ws.dzt[L], loss);
+    if (!softmax_in_fwd)
+        hipLaunchKernelGGL(softmax_xent_bf16_kernel, dim3((unsigned)n), dim3(256), 0, s, ws.logits, (const int *)targets, B, Bp,
+                           C, ws.dz[cur], ws.dzt[L], loss);
     std::vector<char> fused(L, 0);
     bool bias_below_done = false;
     for (int l = L - 1; l >= 0 && st == DPSGD_OK; --l) {
         const int K = m.widths[l], O = m.widths[l + 1];
         fused[l] = fuse && layer_fusable(ctx, K, O, woff[l]) && (ctx->ring_uniform || (reinterpret_cast<uintptr_t>(X) & 7) == 0);
-        if (l == L - 1 && l > 0 && O <= 16 && Bp <= 256 && !fused[l] && ctx->opt_class_bwd) {
+        if (l == L - 1 && class_path && !fused[l]) {
             // the class layer: weight, bias and data gradient and the bias gradient of the layer below in one launch
             ClassBwdArgs ca{};
             ca.dz = ws.dz[cur]; ca.h = ws.h[l]; ca.X = X; ca.G = G; ca.ld = ctx->ld; ca.woff = woff[l]; ca.boff = boff[l];
@@ -1895,6 +1955,7 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             ca.dzp = l - 1 > 0 ? ws.dz[cur ^ 1] : nullptr;   // read by the data gradient of the layer below, if there is one
             ca.dzpt = ws.dzt[l];
             ca.B = B; ca.Bp = Bp; ca.K = K; ca.C = O;
+            ca.loss_part = softmax_in_fwd ? ws.loss_part : nullptr; ca.chunks = (B + 31) / 32; ca.loss = loss;
             const int sgroups = Bp >= 64 ? 4 : 1;   // sample groups per workgroup, 256 / sgroups columns each
             const dim3 cgrid((unsigned)(((i64)K * sgroups + 255) / 256), (unsigned)n);
             if (sgroups == 4) {
