@@ -336,6 +336,9 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
         ctx->opt_fused_lds = value ? 1 : 0;
     } else if (k == "class_bwd") {
         ctx->opt_class_bwd = value ? 1 : 0;
+    } else if (k == "fused_slab") {
+        if (value < 0 || value > 2) return DPSGD_EINVAL;
+        ctx->opt_fused_slab = (int32_t)value;
     } else if (k == "time_fused") {
         ctx->opt_time_fused = value ? 1 : 0;
     } else {

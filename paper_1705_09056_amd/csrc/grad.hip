@@ -23,7 +23,10 @@ dpsgd_status launch_grad(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const float 
 dpsgd_status launch_step(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, const void *inputs, const void *targets,
                          float *G, float *loss, float *consensus)
 {
-    if (is_dense(m) && m.compute_bf16 && (ctx->ring_uniform || ctx->torus_uniform) && !ctx->opt_mix_force_csr)
+    // the bf16 MLP path fuses the weight gradient of its large layers into the mix where a kernel exists for W: the
+    // ring, a torus of at most 8 columns, or any W of at most 64 workers
+    const bool any_w = ctx->opt_fused_slab && ctx->n <= 64 && ctx->d_rowptr;
+    if (is_dense(m) && m.compute_bf16 && (ctx->ring_uniform || ctx->torus_uniform || any_w) && !ctx->opt_mix_force_csr)
         return launch_step_mlp_bf16(ctx, m, X, inputs, targets, G, loss, consensus);
     // everything else: the two calls of the boundary, back to back, in place.  X changes without the fused kernels
     // seeing it, so a bf16 weight copy they left for this X is stale from here on.

@@ -1766,6 +1766,182 @@ __global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTor
     }
 }
 
+// ---------------------------------------- fusion for any W of at most 64 workers: every worker's tile in LDS
+// The ring and torus kernels above keep a walk's few live tiles in registers; a general sparse W has no such walk.
+// Here a workgroup owns a [16 rows][32 M columns] tile of the weight matrix for ALL workers and first brings the n
+// tiles into LDS (2 M KB each, in the register order of the lanes that fetched them; n M <= 64, i.e. 128 KB), which
+// also makes the in-place update safe: nothing is written before everything has been read.  After the barrier wave
+// v takes workers v, v + 8, ...: the gradient tile from v_mfma_f32_16x16x32_bf16 as in the torus kernel (even and
+// odd input columns, a lane owns two adjacent floats of four rows), the combination sum_j W_ij x_j from LDS in CSR
+// order (one product, then fused multiply-adds: the roundings of the CSR mix kernel), and the row goes back to X.
+// The operands of a wave's next worker are fetched while it works on the current one (the first before the barrier).
+// grid (K / (32 M), O / 16), block 512, dynamic LDS max(n M 2 KB, 2 KB (8 M + 1)).
+struct FusedSlabArgs {
+    float *X;
+    i64 ld, woff;
+    const bf16_t *dzt;   // T copy of dZ [n][B][O]
+    const bf16_t *at;    // T copy of A  [n][B][K]
+    const int *rowptr, *colidx;   // W as CSR, device
+    const float *vals;
+    int n, K, O, Bp;
+    float gamma;
+    double *partials;    // one per workgroup (CONS only)
+};
+
+template <bool CONS, int M>
+__global__ void __launch_bounds__(512) mlp_fused_slab_kernel(FusedSlabArgs a)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    constexpr int NW = 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    f32x4 *tiles = reinterpret_cast<f32x4 *>(smem);   // [n][M][2][64]: a tile as 2 groups of 4 registers per lane
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n16 = lane & 15, q = lane >> 4;
+    const int k0 = blockIdx.x * (32 * M), o0 = blockIdx.y * 16;
+    const int steps = a.Bp / 32;
+    // registers 2 i + j of group m of this lane: row o0 + 4 q + i, column k0 + 32 m + 2 n16 + j
+    float *xt = a.X + a.woff + (i64)(o0 + 4 * q) * a.K + k0 + 2 * n16;
+    // operands in fragment order (tfrag_off): this lane's row and its samples 32 s + 8 q .. + 7
+    auto op_off = [&](int row) {
+        return ((i64)(row >> 5) * (a.Bp >> 4) + (q >> 1)) * 512 + (q & 1) * 256 + (row & 31) * 8;
+    };
+    const bf16_t *ap = a.dzt + op_off(o0 + n16);   // A: 16 outputs
+    i64 be_off[M], bo_off[M];                      // B of the even and of the odd columns of group m
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        be_off[m] = op_off(k0 + 32 * m + 2 * n16);
+        bo_off[m] = op_off(k0 + 32 * m + 2 * n16 + 1);
+    }
+    bf16x8 af0, be0[M], bo0[M];
+    auto fetch_ops = [&](int worker) {
+        af0 = frag(ap + (i64)worker * a.O * a.Bp);
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            be0[m] = frag(a.at + (i64)worker * a.K * a.Bp + be_off[m]);
+            bo0[m] = frag(a.at + (i64)worker * a.K * a.Bp + bo_off[m]);
+        }
+    };
+    fetch_ops(wave < a.n ? wave : 0);
+
+    // ---- all tiles into LDS, four per wave at a time (16 loads in flight per lane)
+    const int items = a.n * M;
+    for (int t0 = wave; t0 < items; t0 += 4 * NW) {
+        f32x2 v[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = t0 + u * NW < items ? t0 + u * NW : t0;
+            const float *p = xt + (i64)(t / M) * a.ld + 32 * (t % M);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[u][i] = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p + (i64)i * a.K));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = t0 + u * NW;
+            if (t < items) {
+                tiles[(t * 2 + 0) * 64 + lane] = (f32x4){v[u][0].x, v[u][0].y, v[u][1].x, v[u][1].y};
+                tiles[(t * 2 + 1) * 64 + lane] = (f32x4){v[u][2].x, v[u][2].y, v[u][3].x, v[u][3].y};
+            }
+        }
+    }
+    __syncthreads();
+
+    float shift[M][8], s1[M][8], s2[2] = {0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < M; ++m) {   // the shift of the consensus sums: worker 0's original tile
+        const f32x4 z0 = tiles[(m * 2 + 0) * 64 + lane], z1 = tiles[(m * 2 + 1) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            shift[m][i] = z0[i];
+            shift[m][4 + i] = z1[i];
+            s1[m][i] = 0.f;
+            s1[m][4 + i] = 0.f;
+        }
+    }
+    for (int w = wave; w < a.n; w += NW) {
+        const int e0 = a.rowptr[w], e1 = a.rowptr[w + 1];
+        const i64 aw = (i64)w * a.O * a.Bp, bw = (i64)w * a.K * a.Bp;
+        f32x4 acc_e[M], acc_o[M];
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            acc_e[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af0, be0[m], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+            acc_o[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af0, bo0[m], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        }
+        fetch_ops(w + NW < a.n ? w + NW : w);   // (past the wave's last worker: the same again, values never used)
+        for (int st = 1; st < steps; ++st) {
+            const bf16x8 af = frag(ap + aw + st * 1024);
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                acc_e[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, frag(a.at + bw + be_off[m] + st * 1024), acc_e[m], 0, 0, 0);
+                acc_o[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, frag(a.at + bw + bo_off[m] + st * 1024), acc_o[m], 0, 0, 0);
+            }
+        }
+        float *dst = xt + (i64)w * a.ld;
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            float mix[8];
+            {
+                const int j = a.colidx[e0];
+                const float wv = a.vals[e0];
+                const f32x4 x0 = tiles[((j * M + m) * 2 + 0) * 64 + lane], x1 = tiles[((j * M + m) * 2 + 1) * 64 + lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    mix[i] = wv * x0[i];
+                    mix[4 + i] = wv * x1[i];
+                }
+            }
+            for (int e = e0 + 1; e < e1; ++e) {
+                const int j = a.colidx[e];
+                const float wv = a.vals[e];
+                const f32x4 x0 = tiles[((j * M + m) * 2 + 0) * 64 + lane], x1 = tiles[((j * M + m) * 2 + 1) * 64 + lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    mix[i] = __builtin_fmaf(wv, x0[i], mix[i]);
+                    mix[4 + i] = __builtin_fmaf(wv, x1[i], mix[4 + i]);
+                }
+            }
+            float o8[8];
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {   // register 2 i + j with i = v / 2, j = v % 2
+                const float g = (v & 1) ? acc_o[m][v >> 1] : acc_e[m][v >> 1];
+                const float o = __builtin_fmaf(-a.gamma, g, mix[v]);
+                o8[v] = o;
+                if (CONS) {
+                    const float d = o - shift[m][v];
+                    s1[m][v] += d;
+                    s2[v & 1] += d * d;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                __builtin_nontemporal_store((f32x2){o8[2 * i], o8[2 * i + 1]}, reinterpret_cast<f32x2 *>(dst + 32 * m + (i64)i * a.K));
+        }
+    }
+    if (CONS) {
+        // per element the sums of (x - shift) over the waves (they enter squared); the squares need no per-element sum
+        __syncthreads();
+        float *red = reinterpret_cast<float *>(smem);   // [NW][8 M + 1][64]
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+#pragma unroll
+            for (int v = 0; v < 8; ++v) red[(wave * (8 * M + 1) + m * 8 + v) * 64 + lane] = s1[m][v];
+        red[(wave * (8 * M + 1) + 8 * M) * 64 + lane] = s2[0] + s2[1];
+        __syncthreads();
+        if (wave == 0) {
+            const float inv_n = 1.0f / (float)a.n;
+            float m2 = 0.f;
+            for (int w2 = 0; w2 < NW; ++w2) m2 += red[(w2 * (8 * M + 1) + 8 * M) * 64 + lane];
+            for (int v = 0; v < 8 * M; ++v) {
+                float t1 = 0.f;
+                for (int w2 = 0; w2 < NW; ++w2) t1 += red[(w2 * (8 * M + 1) + v) * 64 + lane];
+                m2 -= t1 * t1 * inv_n;
+            }
+            double t = (double)m2;
+            for (int off = 32; off > 0; off >>= 1) t += __shfl_down(t, off, 64);
+            if (lane == 0) a.partials[(i64)blockIdx.y * gridDim.x + blockIdx.x] = t;
+        }
+    }
+}
+
 }  // namespace
 
 // Workspace layout shared by the size query and the launches.
@@ -1815,11 +1991,20 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
 // torus with 3 to 8 columns and at least 3 grid rows) and its tiles divide the matrix.
 bool torus_cols(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 >= 3 && ctx->dim1 <= 8 && ctx->dim0 >= 3; }
 
+// Any other W of at most 64 workers: the kernel that holds every worker's tile in LDS ("fused_slab": 0 never, 1 where
+// no walk kernel exists, 2 also instead of the torus walk).
+bool slab_fusion(const dpsgd_ctx *ctx)
+{
+    if (ctx->opt_fused_slab == 0 || ctx->ring_uniform || ctx->n > 64 || !ctx->d_rowptr) return false;
+    return ctx->opt_fused_slab == 2 || !torus_cols(ctx);
+}
+
 bool layer_fusable(const dpsgd_ctx *ctx, int K, int O, i64 woff)
 {
     if (ctx->opt_mix_force_csr || woff < 0 || (i64)K * O < (1 << 20)) return false;
     if (ctx->ring_uniform) return (K % 128) == 0 && (O % 32) == 0;
-    if (torus_cols(ctx)) return (K % 32) == 0 && (O % 32) == 0 && (woff % 2) == 0 && (ctx->ld % 2) == 0;   // 8-byte accesses
+    if (torus_cols(ctx) || slab_fusion(ctx))
+        return (K % 32) == 0 && (O % 32) == 0 && (woff % 2) == 0 && (ctx->ld % 2) == 0;   // 8-byte accesses
     return false;
 }
 
@@ -2060,6 +2245,38 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
                 if (cons) hipLaunchKernelGGL((mlp_fused_ring_kernel<true, false>), grid, dim3(256), 0, s, fa);
                 else hipLaunchKernelGGL((mlp_fused_ring_kernel<false, false>), grid, dim3(256), 0, s, fa);
             }
+        } else if (slab_fusion(ctx)) {
+            FusedSlabArgs fa{};
+            fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];
+            fa.rowptr = ctx->d_rowptr; fa.colidx = ctx->d_colidx; fa.vals = ctx->d_vals;
+            fa.n = n; fa.K = K; fa.O = O; fa.Bp = Bp; fa.gamma = ctx->gamma;
+            fa.partials = ctx->d_partials + nparts;
+            // column groups of 32 per workgroup: as many as 128 KB of LDS hold for n workers and as divide the inputs
+            int mg = 4;
+            while (mg > 1 && (n * mg > 64 || (K % (32 * mg)) != 0)) mg >>= 1;
+            dim3 grid((unsigned)(K / (32 * mg)), (unsigned)(O / 16));
+            np = (i64)grid.x * grid.y;
+            if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
+            const size_t slab = (size_t)n * mg * 2048, red = (size_t)2048 * (8 * mg + 1);
+            const size_t shm = slab > red ? slab : red;
+#define DPSGD_SLAB_ONE(CONS, MG)                                                                                                \
+    do {                                                                                                                        \
+        auto kern = mlp_fused_slab_kernel<CONS, MG>;                                                                            \
+        if (shm > 64 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                                        \
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)         \
+            return DPSGD_EDEVICE;                                                                                               \
+        hipLaunchKernelGGL(kern, grid, dim3(512), shm, s, fa);                                                                  \
+    } while (0)
+#define DPSGD_SLAB(MG)                                                                                              \
+    do {                                                                                                            \
+        if (cons) DPSGD_SLAB_ONE(true, MG);                                                                         \
+        else DPSGD_SLAB_ONE(false, MG);                                                                             \
+    } while (0)
+            if (mg == 4) DPSGD_SLAB(4);
+            else if (mg == 2) DPSGD_SLAB(2);
+            else DPSGD_SLAB(1);
+#undef DPSGD_SLAB
+#undef DPSGD_SLAB_ONE
         } else {
             FusedTorusColArgs fa{};
             fa.X = X; fa.ld = ctx->ld; fa.woff = woff[l]; fa.dzt = ws.dzt[l + 1]; fa.at = actt[l];

@@ -18,7 +18,7 @@ TOL = 2e-2
 TIGHT = 2e-3
 
 
-def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0):
+def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0, expect_fused=None):
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = ld or synth.padded_stride(d)
     X = synth.make_replicas(cfg, spread=spread)
@@ -47,6 +47,12 @@ def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0):
         ctx.mean(Xa, xbar)
         torch.cuda.synchronize()
     A, Bm = from_dev(Xa, d), from_dev(Xb, d)
+    if expect_fused is not None:
+        # the scratch gradient of a fused layer's weights is never written: the sentinel is still there
+        for p in synth.param_layout(cfg.model_kind, cfg.widths):
+            if p.size >= (1 << 20):
+                untouched = bool((Ga[:, p.offset:p.offset + p.size] == 777.0).all())
+                assert untouched == expect_fused, f"{p.name}: fused={untouched}, expected {expect_fused}"
     X64 = X.astype(np.float64)
     tight, bar = (TIGHT, TOL) if bf16 else (1e-4, 1e-5)
     # the update itself (X_next - X) is what the gradient kernels produce; compare it, not just X_next: over the
@@ -100,11 +106,31 @@ def test_step_mlp_bf16_torus(dims, widths, batch):
     step_case(shrink(CONFIG3_TORUS, widths=widths, batch=batch, n=dims[0] * dims[1], torus_dims=dims))
 
 
+@pytest.mark.parametrize("topology,n,dims,widths,batch,options", [
+    ("ring_chord", 8, None, (1024, 1024, 10), 32, ()),                 # the supplement's ring with a far link: [16][128] tiles
+    ("ring_chord", 16, None, (1024, 1024, 1024, 10), 32, ()),          # its 16 workers, two fused layers
+    ("ring_chord", 40, None, (1024, 1024, 10), 48, ()),                # 40 workers: [16][32] tiles; two operand steps
+    ("ring_chord", 6, None, (1056, 1024, 10), 32, ()),                 # fewer workers than waves; 33 column groups: no wider tile divides
+    ("torus", 27, (3, 9), (1024, 1024, 10), 32, ()),                   # 9 grid columns: beyond the torus walk, [16][64] tiles
+    ("torus", 16, (2, 8), (1024, 1024, 10), 32, ()),                   # 2 grid rows: neighbours coincide, weights differ per entry
+    ("torus", 16, (4, 4), (1024, 1024, 10), 32, (("fused_slab", 2),)),  # instead of the torus walk
+    ("torus", 64, (8, 8), (1024, 1024, 10), 32, (("fused_slab", 2),)),  # 64 workers fill the 128 KB
+])
+def test_step_mlp_bf16_any_topology_through_lds(topology, n, dims, widths, batch, options):
+    """Weight gradient formed inside the mix for a W without a walk kernel: every worker's tile in LDS, rows combined
+    in CSR order."""
+    base = CONFIG3_TORUS if topology == "torus" else CONFIGS[2]
+    kw = dict(torus_dims=dims) if topology == "torus" else dict(topology=topology)
+    step_case(shrink(base, widths=widths, batch=batch, n=n, **kw), options=options, expect_fused=True)
+
+
 def test_step_falls_back_on_other_topologies_and_fp32():
-    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=27, torus_dims=(3, 9)))   # 9 columns: no fused kernel
-    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=16, torus_dims=(2, 8)))   # 2 grid rows: neighbours coincide
-    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1000, 10), batch=32, n=24, torus_dims=(3, 8)))   # 1000 outputs: tiles do not divide
-    step_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=8, topology="ring_chord"))     # CSR topology
+    step_case(shrink(CONFIG3_TORUS, widths=(1024, 1000, 10), batch=32, n=24, torus_dims=(3, 8)),
+              expect_fused=False)   # 1000 outputs: tiles do not divide
+    step_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=8, topology="ring_chord"),
+              options=(("fused_slab", 0),), expect_fused=False)   # switched off: the two calls
+    step_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=66, topology="ring_chord"),
+              expect_fused=False)   # more workers than 128 KB of LDS hold tiles for
     step_case(shrink(CONFIGS[1], widths=(300, 10), batch=16, n=6), bf16=False)
     step_case(shrink(CONFIGS[0], widths=(64,), batch=32, n=8), bf16=False, spread=1.0)
 
