@@ -80,6 +80,9 @@ def parse():
     ap.add_argument("--momentum", type=float, default=0.0,
                     help="run the heavy-ball variant dpsgd_mix_step_momentum with this mu (two-call path; a variant "
                          "of the benchmark, flagged in the output)")
+    ap.add_argument("--topology", default="", choices=["", "ring_chord"],
+                    help="override the workload's W: ring_chord = the supplement's ring with a link to the farthest "
+                         "node (its 16-machine runs); a variant, flagged as such in the output")
     ap.add_argument("--overlap", action="store_true",
                     help="variant for comparison: the averaging W X runs on a second stream beside dpsgd_grad, then "
                          "X = (W X) - gamma G is formed by a third pass (three existing entry points, 8 + 12 bytes per "
@@ -150,7 +153,8 @@ def cpu_baseline(cfg, seconds_budget=20.0):
     rng = np.random.default_rng(0)
     Xs = rng.standard_normal((cfg.n, dcols))
     Gs = rng.standard_normal((cfg.n, dcols))
-    topo = oracle.ring(cfg.n) if cfg.topology == "ring" else oracle.torus(*cfg.torus_dims)
+    topo = oracle.ring(cfg.n) if cfg.topology == "ring" else oracle.ring_chord(cfg.n) if cfg.topology == "ring_chord" \
+        else oracle.torus(*cfg.torus_dims)
     t0 = time.perf_counter()
     oracle.mix_step(topo, Xs, Gs, cfg.gamma)
     t_mix = (time.perf_counter() - t0) * (d / dcols)
@@ -234,11 +238,16 @@ def run_one(args, with_cpu_baseline):
         import dataclasses
         cfg = dataclasses.replace(cfg, batch=args.batch or cfg.batch, n=args.workers or cfg.n)
         variant = f"batch={cfg.batch}, n={cfg.n}: kernel check, not a benchmark configuration"
+    if args.topology:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, topology=args.topology)
+        variant = (variant + "; " if variant else "") + f"W = {args.topology}: not a benchmark configuration"
     K = args.steps or cfg.iters
     W = args.warmup
     R = max(1, args.repeats)
     d = synth.model_dim(cfg.model_kind, cfg.widths)
-    topo = B.Topology.ring() if cfg.topology == "ring" else B.Topology.torus(*cfg.torus_dims)
+    topo = B.Topology.ring() if cfg.topology == "ring" else B.Topology.ring_chord() if cfg.topology == "ring_chord" \
+        else B.Topology.torus(*cfg.torus_dims)
     ld = synth.padded_stride(d, args.ld_multiple) if args.ld_multiple else B.recommended_ld(d, topo)
     model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=cfg.bf16)
 
@@ -274,7 +283,9 @@ def run_one(args, with_cpu_baseline):
     shadow_weights = 0   # of those, the hidden-layer weights whose bf16 copy the fused kernel also writes (--shadow)
     ring_ok = cfg.topology == "ring" and cfg.n >= 3
     torus_ok = cfg.topology == "torus" and 3 <= cfg.torus_dims[1] <= 8 and cfg.torus_dims[0] >= 3
-    if cfg.bf16 and cfg.model_kind in (MODEL_MLP, MODEL_SOFTMAX) and (ring_ok or torus_ok):
+    # any other W of at most 64 workers: the kernel that holds every worker's tile in LDS
+    slab_ok = not ring_ok and not torus_ok and cfg.n <= 64 and "fused_slab=0" not in args.option
+    if cfg.bf16 and cfg.model_kind in (MODEL_MLP, MODEL_SOFTMAX) and (ring_ok or torus_ok or slab_ok):
         for l in range(len(cfg.widths) - 1):
             w_in, w_out = cfg.widths[l], cfg.widths[l + 1]
             if w_in % (128 if ring_ok else 32) == 0 and w_out % 32 == 0 and w_in * w_out >= (1 << 20):
@@ -363,7 +374,7 @@ def run_one(args, with_cpu_baseline):
             else "mlp_fused_ring_kernel"
         ring_name = "mlp_fused_ring_rows_kernel" if all(rows_kernel) else tiles_name if not any(rows_kernel) \
             else "mlp_fused_ring_rows_kernel / " + tiles_name
-        kernel_name = (ring_name if ring_ok else "mlp_fused_torus_cols_kernel") + \
+        kernel_name = (ring_name if ring_ok else "mlp_fused_torus_cols_kernel" if torus_ok else "mlp_fused_slab_kernel") + \
             " (weight gradient + Algorithm 1 steps 4-5, in place)"
         launch_bytes = (8.0 * fused_weights + 2.0 * shadow_weights) * cfg.n * K / med["launches"]
     else:

@@ -170,6 +170,10 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * bias and data gradient of that layer and the bias gradient of the layer below come from one launch in which a thread
  * walks the samples of one column of the activations; 0: the tiled kernels of the other layers, three launches.  The
  * two add up the same products in a different order: results agree to fp32 rounding of the sums),
+ * "fused_slab" (default 1: dpsgd_step, bf16 MLP, a W of at most 64 workers that is neither Theorem 3's ring nor a torus
+ * of 3 to 8 columns: the weight gradient of the large layers is formed inside a mix kernel that holds every worker's tile
+ * in LDS; 0: such a W runs dpsgd_grad and dpsgd_mix_step back to back; 2: that kernel also takes the tori the torus
+ * kernel would take.  Results agree to fp32 rounding),
  * "conv_band_rows" (output rows of an image per workgroup of the CNN's 3 x 3 convolution kernels: 8, 16, or 0 = chosen
  * per convolution, the default; every setting gives the same bits),
  * "time_fused" (see dpsgd_read_timing). */
@@ -226,13 +230,16 @@ dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const fl
  * followed by dpsgd_mix_step(X, G -> X), up to the order of floating-point sums.  Footnote [b] observes that steps 3
  * and 4 are independent; here they share one pass over X wherever a kernel exists for it.
  * Fused (the weight gradient of a layer is formed inside the mix kernel and never written to memory): model MLP or
- * SOFTMAX with compute_bf16 = 1, on DPSGD_TOPO_RING with n >= 3 or on DPSGD_TOPO_TORUS2D with dim0 >= 3 and
- * 3 <= dim1 <= 8, for every layer with at least 2^20 weights whose outputs are a multiple of 32 and whose inputs are a
- * multiple of 128 (ring) or of 32 (torus; also 8-byte aligned rows); the remaining parameters of such a model (small
- * layers, biases) take the ordinary gradient kernels and the mix kernels on their column ranges inside the same call.
- * Not fused - the call runs dpsgd_grad and an in-place dpsgd_mix_step back to back, same results: every other
- * topology (DPSGD_TOPO_RING_CHORD, DPSGD_TOPO_COMPLETE, DPSGD_TOPO_CSR, rings with n < 3, tori with a dimension < 3 or
- * more than 8 columns), fp32 arithmetic (compute_bf16 = 0), LSQ and RESNET20 models, and the "mix_force_csr" option.
+ * SOFTMAX with compute_bf16 = 1, on DPSGD_TOPO_RING with n >= 3 (a walk around the ring with three rows in
+ * registers), on DPSGD_TOPO_TORUS2D with dim0 >= 3 and 3 <= dim1 <= 8 (a walk down the grid columns), and on every
+ * other W of at most 64 workers - DPSGD_TOPO_RING_CHORD, DPSGD_TOPO_COMPLETE, DPSGD_TOPO_CSR, the remaining rings and
+ * tori - through a kernel that holds every worker's tile in LDS; for every layer with at least 2^20 weights whose
+ * outputs are a multiple of 32 and whose inputs are a multiple of 128 (ring) or of 32 (any other W; also 8-byte
+ * aligned rows); the remaining parameters of such a model (small layers, biases) take the ordinary gradient kernels
+ * and the mix kernels on their column ranges inside the same call.
+ * Not fused - the call runs dpsgd_grad and an in-place dpsgd_mix_step back to back, same results: a W other than
+ * those two walks with more than 64 workers, fp32 arithmetic (compute_bf16 = 0), LSQ and RESNET20 models, and the
+ * "mix_force_csr" option.
  *   X          device, n x d (stride ld), overwritten by the next iterate
  *   G_scratch  device, n x d (stride ld), must not overlap X; on return it holds the gradient only of those
  *              parameters whose update was not fused (contents otherwise unspecified)

@@ -1771,11 +1771,12 @@ __global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTor
 // Here a workgroup owns a [16 rows][32 M columns] tile of the weight matrix for ALL workers and first brings the n
 // tiles into LDS (2 M KB each, in the register order of the lanes that fetched them; n M <= 64, i.e. 128 KB), which
 // also makes the in-place update safe: nothing is written before everything has been read.  After the barrier wave
-// v takes workers v, v + 8, ...: the gradient tile from v_mfma_f32_16x16x32_bf16 as in the torus kernel (even and
+// v takes workers v, v + NW, ...: the gradient tile from v_mfma_f32_16x16x32_bf16 as in the torus kernel (even and
 // odd input columns, a lane owns two adjacent floats of four rows), the combination sum_j W_ij x_j from LDS in CSR
 // order (one product, then fused multiply-adds: the roundings of the CSR mix kernel), and the row goes back to X.
 // The operands of a wave's next worker are fetched while it works on the current one (the first before the barrier).
-// grid (K / (32 M), O / 16), block 512, dynamic LDS max(n M 2 KB, 2 KB (8 M + 1)).
+// grid (K / (32 M), O / 16), block 64 NW (NW = 8 waves, 16 for a slab of more than 64 KB), dynamic LDS
+// max(n M 2 KB, NW (8 M + 1) 256 B).
 struct FusedSlabArgs {
     float *X;
     i64 ld, woff;
@@ -1788,11 +1789,10 @@ struct FusedSlabArgs {
     double *partials;    // one per workgroup (CONS only)
 };
 
-template <bool CONS, int M>
-__global__ void __launch_bounds__(512) mlp_fused_slab_kernel(FusedSlabArgs a)
+template <bool CONS, int M, int NW>
+__global__ void __launch_bounds__(64 * NW) mlp_fused_slab_kernel(FusedSlabArgs a)
 {
     typedef float f32x2 __attribute__((ext_vector_type(2)));
-    constexpr int NW = 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     f32x4 *tiles = reinterpret_cast<f32x4 *>(smem);   // [n][M][2][64]: a tile as 2 groups of 4 registers per lane
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -2252,29 +2252,32 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             fa.n = n; fa.K = K; fa.O = O; fa.Bp = Bp; fa.gamma = ctx->gamma;
             fa.partials = ctx->d_partials + nparts;
             // column groups of 32 per workgroup: as many as 128 KB of LDS hold for n workers and as divide the inputs
-            int mg = 4;
+            // (64 KB, two workgroups per CU, where that leaves a group: one fills the slab while the other works on its own)
+            int mg = n <= 8 ? 4 : n <= 16 ? 2 : 1;
             while (mg > 1 && (n * mg > 64 || (K % (32 * mg)) != 0)) mg >>= 1;
+            const int nw = (mg == 1 && n > 48) ? 16 : 8;   // a full slab has the CU to itself: 16 waves of 4 workers each
             dim3 grid((unsigned)(K / (32 * mg)), (unsigned)(O / 16));
             np = (i64)grid.x * grid.y;
             if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
-            const size_t slab = (size_t)n * mg * 2048, red = (size_t)2048 * (8 * mg + 1);
+            const size_t slab = (size_t)n * mg * 2048, red = (size_t)256 * nw * (8 * mg + 1);
             const size_t shm = slab > red ? slab : red;
-#define DPSGD_SLAB_ONE(CONS, MG)                                                                                                \
+#define DPSGD_SLAB_ONE(CONS, MG, NWV)                                                                                              \
     do {                                                                                                                        \
-        auto kern = mlp_fused_slab_kernel<CONS, MG>;                                                                            \
+        auto kern = mlp_fused_slab_kernel<CONS, MG, NWV>;                                                                       \
         if (shm > 64 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                                        \
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)         \
             return DPSGD_EDEVICE;                                                                                               \
-        hipLaunchKernelGGL(kern, grid, dim3(512), shm, s, fa);                                                                  \
+        hipLaunchKernelGGL(kern, grid, dim3(64 * NWV), shm, s, fa);                                                             \
     } while (0)
-#define DPSGD_SLAB(MG)                                                                                              \
+#define DPSGD_SLAB(MG, NWV)                                                                                         \
     do {                                                                                                            \
-        if (cons) DPSGD_SLAB_ONE(true, MG);                                                                         \
-        else DPSGD_SLAB_ONE(false, MG);                                                                             \
+        if (cons) DPSGD_SLAB_ONE(true, MG, NWV);                                                                    \
+        else DPSGD_SLAB_ONE(false, MG, NWV);                                                                        \
     } while (0)
-            if (mg == 4) DPSGD_SLAB(4);
-            else if (mg == 2) DPSGD_SLAB(2);
-            else DPSGD_SLAB(1);
+            if (mg == 4) DPSGD_SLAB(4, 8);
+            else if (mg == 2) DPSGD_SLAB(2, 8);
+            else if (nw == 16) DPSGD_SLAB(1, 16);
+            else DPSGD_SLAB(1, 8);
 #undef DPSGD_SLAB
 #undef DPSGD_SLAB_ONE
         } else {

@@ -18,12 +18,13 @@ TOL = 2e-2
 TIGHT = 2e-3
 
 
-def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0, expect_fused=None):
+def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0, expect_fused=None, topos=None):
     d = synth.model_dim(cfg.model_kind, cfg.widths)
     ld = ld or synth.padded_stride(d)
     X = synth.make_replicas(cfg, spread=spread)
     inp, tgt = synth.make_batch(cfg, 0)
-    topo_o = oracle_topo_for(cfg)
+    # topos: (W for the library, the same W for the oracle) where the workload's topology name does not say it
+    topo_o = topos[1] if topos else oracle_topo_for(cfg)
     Xn, Gref, lref = oracle.iteration(cfg.model_kind, cfg.widths, topo_o, np.float32(cfg.gamma), X, inp, tgt,
                                       bf16_operands=bf16)
     # the plain fp64 oracle (no rounding inside) binds the iterate-level outputs at the bar of the bf16 workloads
@@ -38,7 +39,7 @@ def step_case(cfg, bf16=True, spread=0.3, options=(), ld=0, expect_fused=None):
     ca, cb = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
     xbar = torch.zeros(d, device="cuda")
     print(f"step {cfg.name} widths={cfg.widths} n={cfg.n} B={cfg.batch} topo={cfg.topology}", flush=True)
-    with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+    with B.Dpsgd(cfg.n, d, topos[0] if topos else topo_for(cfg), cfg.gamma, ld=ld) as ctx:
         for key, value in options:
             ctx.set_option(key, value)
         ctx.step(model, Xa, inp_d, tgt_d, cfg.batch, Ga, la, ca, input_is_bf16=bf16)
@@ -122,6 +123,22 @@ def test_step_mlp_bf16_any_topology_through_lds(topology, n, dims, widths, batch
     base = CONFIG3_TORUS if topology == "torus" else CONFIGS[2]
     kw = dict(torus_dims=dims) if topology == "torus" else dict(topology=topology)
     step_case(shrink(base, widths=widths, batch=batch, n=n, **kw), options=options, expect_fused=True)
+
+
+def test_step_mlp_bf16_csr_topologies_through_lds():
+    """General sparse W handed over as CSR: a hypercube (degree 4), the complete graph (every row combines all
+    tiles) and a random symmetric doubly stochastic matrix with unequal weights."""
+    from test_gpu_mix import hypercube_csr, random_symmetric_ds
+    rowptr, col, val = hypercube_csr(4)
+    cfg = shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=16)
+    step_case(cfg, expect_fused=True,
+              topos=(B.Topology.csr(rowptr, col, val), oracle.Topology(16, rowptr, col, val.astype(np.float64))))
+    cfg = shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=32, n=12)
+    step_case(cfg, expect_fused=True, topos=(B.Topology.complete(), oracle.complete(12).with_fp32_values()))
+    rowptr, col, val = random_symmetric_ds(20, np.random.default_rng(20))
+    cfg = shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=64, n=20)
+    step_case(cfg, expect_fused=True,
+              topos=(B.Topology.csr(rowptr, col, val), oracle.Topology(20, rowptr, col, val.astype(np.float64))))
 
 
 def test_step_falls_back_on_other_topologies_and_fp32():
