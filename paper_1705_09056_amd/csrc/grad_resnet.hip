@@ -183,21 +183,36 @@ pool_fwd_kernel(const bf16_t *__restrict__ a, int HW, i64 total, float *__restri
 }
 
 // One workgroup per worker.  pool / dpool: [n][B][C] fp32, z: [n][B][K] fp32.
+// STAGED: the worker's pooled features, FC weights (rows one float apart from a multiple of the bank count) and logits
+// sit in LDS ((B (C + 1) + K (C + 1) + B K) floats of dynamic LDS) and
+// every loop below reads them from there; the arithmetic and its order are the same either way, so are the bits.
+template <bool STAGED>
 __global__ void __launch_bounds__(256)
 head_kernel(const float *__restrict__ X, i64 ld, i64 fcw_off, i64 fcb_off, int B, int HW, int C, int K,
             const int *__restrict__ labels, const float *__restrict__ pool, float *__restrict__ z,
             float *__restrict__ dpool, float *__restrict__ G, float *__restrict__ loss)
 {
     __shared__ float red[256];
+    extern __shared__ __attribute__((aligned(16))) float head_lds[];
     const int w = blockIdx.x, tid = threadIdx.x;
     const float *fw = X + (i64)w * ld + fcw_off, *fb = X + (i64)w * ld + fcb_off;
     const float *pw = pool + (i64)w * B * C;
     float *zw = z + (i64)w * B * K, *dpw = dpool + (i64)w * B * C;
+    const int CP = STAGED ? C + 1 : C;   // row pitch of the pooled features and of the FC weights
+    if (STAGED) {
+        float *ps = head_lds, *fs = ps + B * CP;
+        for (int e = tid; e < B * C; e += 256) ps[(e / C) * CP + e % C] = pw[e];
+        for (int e = tid; e < K * C; e += 256) fs[(e / C) * CP + e % C] = fw[e];
+        __syncthreads();
+        pw = ps;
+        fw = fs;
+        zw = fs + K * CP;
+    }
     const float inv_hw = 1.0f / (float)HW;
     for (int e = tid; e < B * K; e += 256) {
         const int b = e / K, o = e % K;
         float s = fb[o];
-        for (int ch = 0; ch < C; ++ch) s = fw[o * C + ch] * pw[b * C + ch] + s;
+        for (int ch = 0; ch < C; ++ch) s = fw[o * CP + ch] * pw[b * CP + ch] + s;
         zw[e] = s;
     }
     __syncthreads();
@@ -225,7 +240,7 @@ head_kernel(const float *__restrict__ X, i64 ld, i64 fcw_off, i64 fcb_off, int B
     for (int e = tid; e < K * C; e += 256) {
         const int o = e / C, ch = e % C;
         float s = 0.f;
-        for (int b = 0; b < B; ++b) s = zw[b * K + o] * pw[b * C + ch] + s;
+        for (int b = 0; b < B; ++b) s = zw[b * K + o] * pw[b * CP + ch] + s;
         G[(i64)w * ld + fcw_off + e] = s;
     }
     for (int o = tid; o < K; o += 256) {
@@ -236,7 +251,7 @@ head_kernel(const float *__restrict__ X, i64 ld, i64 fcw_off, i64 fcb_off, int B
     for (int e = tid; e < B * C; e += 256) {
         const int b = e / C, ch = e % C;
         float s = 0.f;
-        for (int o = 0; o < K; ++o) s = zw[b * K + o] * fw[o * C + ch] + s;
+        for (int o = 0; o < K; ++o) s = zw[b * K + o] * fw[o * CP + ch] + s;
         dpw[e] = s * inv_hw;
     }
 }
@@ -390,8 +405,15 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     const int HWl = p.H_last * p.W_last;
     hipLaunchKernelGGL(pool_fwd_kernel, dim3(blocks_for(nB * p.C_last)), dim3(256), 0, s, a_of(p.nblocks).t, HWl,
                        nB * p.C_last, ws.pool);
-    hipLaunchKernelGGL(head_kernel, dim3((unsigned)n), dim3(256), 0, s, X, ctx->ld, p.fcw_off, p.fcb_off, B, HWl, p.C_last,
-                       p.classes, (const int *)targets, ws.pool, ws.logits, ws.dpool, G, loss);
+    {
+        const size_t head_lds = ((size_t)(B + p.classes) * (p.C_last + 1) + (size_t)B * p.classes) * sizeof(float);
+        if (head_lds <= 48 * 1024)
+            hipLaunchKernelGGL(head_kernel<true>, dim3((unsigned)n), dim3(256), head_lds, s, X, ctx->ld, p.fcw_off, p.fcb_off, B,
+                               HWl, p.C_last, p.classes, (const int *)targets, ws.pool, ws.logits, ws.dpool, G, loss);
+        else
+            hipLaunchKernelGGL(head_kernel<false>, dim3((unsigned)n), dim3(256), 0, s, X, ctx->ld, p.fcw_off, p.fcb_off, B, HWl,
+                               p.C_last, p.classes, (const int *)targets, ws.pool, ws.logits, ws.dpool, G, loss);
+    }
 
     // ---- backward
     Tensor dv = ws.delta[0], du = ws.delta[1], dnext = ws.delta[2];
