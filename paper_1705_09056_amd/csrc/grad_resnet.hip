@@ -265,6 +265,22 @@ pool_bwd_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dpool, i
     dv[idx] = bf16_positive(a[idx]) ? f2bf(dpool[idx / HW]) : (bf16_t)0;
 }
 
+// The same for HW % 8 == 0: a thread takes 8 pixels of one (image, channel) plane, 16 bytes in and out.
+__global__ void __launch_bounds__(256)
+pool_bwd_vec_kernel(const bf16_t *__restrict__ a, const float *__restrict__ dpool, int HW, i64 total8, bf16_t *__restrict__ dv)
+{
+    const i64 u = (i64)blockIdx.x * 256 + threadIdx.x;   // over 16-byte units of [w*b][c][t]
+    if (u >= total8) return;
+    const uint4 v = *reinterpret_cast<const uint4 *>(a + u * 8);
+    const unsigned d = f2bf(dpool[(u * 8) / HW]);
+    const unsigned in[4] = {v.x, v.y, v.z, v.w};
+    unsigned out[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+        out[h] = (bf16_positive((bf16_t)(in[h] & 0xffffu)) ? d : 0u) | (bf16_positive((bf16_t)(in[h] >> 16)) ? d << 16 : 0u);
+    *reinterpret_cast<uint4 *>(dv + u * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
 unsigned blocks_for(i64 total) { return (unsigned)((total + 255) / 256); }
 
 }  // namespace
@@ -420,8 +436,12 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     WgradReduceList pending;   // the sums over the weight-gradient partials, one launch after the last convolution
     {
         const i64 total = nB * HWl * p.C_last;
-        hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks).t, ws.dpool, HWl,
-                           total, dv.t);
+        if ((HWl & 7) == 0)
+            hipLaunchKernelGGL(pool_bwd_vec_kernel, dim3(blocks_for(total / 8)), dim3(256), 0, s, a_of(p.nblocks).t, ws.dpool, HWl,
+                               total / 8, dv.t);
+        else
+            hipLaunchKernelGGL(pool_bwd_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a_of(p.nblocks).t, ws.dpool, HWl,
+                               total, dv.t);
     }
     for (int j = p.nblocks - 1; j >= 0; --j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
