@@ -86,6 +86,12 @@ def test_graph_of_fused_torus_steps():
     graph_case(shrink(CONFIG3_TORUS, widths=(1024, 1024, 10), batch=32, n=12, torus_dims=(3, 4)), bf16=True)
 
 
+def test_graph_of_fused_steps_on_the_ring_with_a_far_link():
+    """The kernel that holds every worker's tile in LDS (a W without a walk kernel), with minibatches of 128 rows:
+    the class layer's one-launch backward with its samples split over groups, softmax in the forward launch."""
+    graph_case(shrink(CONFIGS[2], widths=(1024, 1024, 10), batch=128, n=10, topology="ring_chord"), bf16=True)
+
+
 def test_graph_of_fp32_softmax_and_lsq_steps():
     graph_case(shrink(CONFIGS[1], widths=(300, 10), batch=16, n=6), bf16=False)
     graph_case(shrink(CONFIGS[0], widths=(64,), batch=32, n=8), bf16=False)
