@@ -141,6 +141,25 @@ def test_step_mlp_bf16_csr_topologies_through_lds():
               topos=(B.Topology.csr(rowptr, col, val), oracle.Topology(20, rowptr, col, val.astype(np.float64))))
 
 
+def test_launch_options_reject_unknown_keys_and_values():
+    """dpsgd_set_option: every documented key is accepted with its documented values, anything else is DPSGD_EINVAL and
+    leaves the context usable."""
+    with B.Dpsgd(8, 64, B.Topology.ring(), 0.1) as ctx:
+        for key, good, bad in (("fused_slab", (0, 1, 2), (3, -1)), ("class_bwd", (0, 1), ()), ("fused_lds", (0, 1), ()),
+                               ("ring_rows", (0, 1), ()), ("ring_chunks", (0, 1), ()), ("mix_vec", (0, 1, 2, 4), (3, 8)),
+                               ("mix_bands", (0, 16), (17, -1)), ("conv_band_rows", (0, 8, 16), (4, 32))):
+            for v in good:
+                ctx.set_option(key, v)
+            for v in bad:
+                with pytest.raises(B.DpsgdError) as e:
+                    ctx.set_option(key, v)
+                assert e.value.status == B.EINVAL
+        with pytest.raises(B.DpsgdError) as e:
+            ctx.set_option("no_such_option", 1)
+        assert e.value.status == B.EINVAL
+        ctx.set_option("fused_slab", 1)
+
+
 def test_step_falls_back_on_other_topologies_and_fp32():
     step_case(shrink(CONFIG3_TORUS, widths=(1024, 1000, 10), batch=32, n=24, torus_dims=(3, 8)),
               expect_fused=False)   # 1000 outputs: tiles do not divide
