@@ -282,7 +282,7 @@ def run_one(args, with_cpu_baseline):
     rows_kernel = []     # per fused ring layer: does the [16 rows][1 KB] kernel take it (same rule as the library)
     shadow_weights = 0   # of those, the hidden-layer weights whose bf16 copy the fused kernel also writes (--shadow)
     ring_ok = cfg.topology == "ring" and cfg.n >= 3
-    torus_ok = cfg.topology == "torus" and 3 <= cfg.torus_dims[1] <= 8 and cfg.torus_dims[0] >= 3
+    torus_ok = cfg.topology == "torus" and 3 <= cfg.torus_dims[1] <= 16 and cfg.torus_dims[0] >= 3
     # any other W of at most 64 workers: the kernel that holds every worker's tile in LDS
     slab_ok = not ring_ok and not torus_ok and cfg.n <= 64 and "fused_slab=0" not in args.option
     if cfg.bf16 and cfg.model_kind in (MODEL_MLP, MODEL_SOFTMAX) and (ring_ok or torus_ok or slab_ok):

@@ -171,7 +171,7 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * walks the samples of one column of the activations; 0: the tiled kernels of the other layers, three launches.  The
  * two add up the same products in a different order: results agree to fp32 rounding of the sums),
  * "fused_slab" (default 1: dpsgd_step, bf16 MLP, a W of at most 64 workers that is neither Theorem 3's ring nor a torus
- * of 3 to 8 columns: the weight gradient of the large layers is formed inside a mix kernel that holds every worker's tile
+ * of 3 to 16 columns: the weight gradient of the large layers is formed inside a mix kernel that holds every worker's tile
  * in LDS; 0: such a W runs dpsgd_grad and dpsgd_mix_step back to back; 2: that kernel also takes the tori the torus
  * kernel would take.  Results agree to fp32 rounding),
  * "conv_band_rows" (output rows of an image per workgroup of the CNN's 3 x 3 convolution kernels: 8, 16, or 0 = chosen
@@ -231,7 +231,7 @@ dpsgd_status dpsgd_mix_step_momentum(dpsgd_ctx *ctx, const float *X_in, const fl
  * and 4 are independent; here they share one pass over X wherever a kernel exists for it.
  * Fused (the weight gradient of a layer is formed inside the mix kernel and never written to memory): model MLP or
  * SOFTMAX with compute_bf16 = 1, on DPSGD_TOPO_RING with n >= 3 (a walk around the ring with three rows in
- * registers), on DPSGD_TOPO_TORUS2D with dim0 >= 3 and 3 <= dim1 <= 8 (a walk down the grid columns), and on every
+ * registers), on DPSGD_TOPO_TORUS2D with dim0 >= 3 and 3 <= dim1 <= 16 (a walk down the grid columns), and on every
  * other W of at most 64 workers - DPSGD_TOPO_RING_CHORD, DPSGD_TOPO_COMPLETE, DPSGD_TOPO_CSR, the remaining rings and
  * tori - through a kernel that holds every worker's tile in LDS; for every layer with at least 2^20 weights whose
  * outputs are a multiple of 32 and whose inputs are a multiple of 128 (ring) or of 32 (any other W; also 8-byte

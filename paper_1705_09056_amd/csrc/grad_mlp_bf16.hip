@@ -1606,7 +1606,7 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
     }
 }
 
-// ---------------------------------------- torus fusion, one wave per grid column (C <= 8 columns)
+// ---------------------------------------- torus fusion, one wave per grid column (C <= 16 columns)
 // A workgroup owns one 16 x 32 tile (outputs x inputs) of the weight matrix for ALL workers; wave c takes grid
 // column c and walks down it like the ring kernel walks the ring: the tiles of workers (r-1, c), (r, c),
 // (r+1, c) stay in its registers.  The row neighbours (r, c-1) and (r, c+1) belong to the neighbouring waves: at
@@ -1614,8 +1614,9 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
 // The gradient tile is two v_mfma_f32_16x16x32_bf16 per 32 minibatch rows, one for the even and one for the odd
 // input columns, so that a lane owns two adjacent columns of four rows: every access is 8 bytes per lane and 16
 // lanes cover a 128-byte line.  8 registers per tile keep the kernel at 4 waves per SIMD.
-// KT such groups of C waves sit side by side along the inputs (KT x 128-byte row segments per workgroup).
-// grid (K / (32 KT), O / 16), block 64 C KT, dynamic LDS KT * 2 * C * 2 KB.
+// KT such groups of C waves sit side by side along the inputs (KT x 128-byte row segments per workgroup): two for up
+// to 8 grid columns, one beyond (the 16 waves of a workgroup are then all columns of one group).
+// grid (K / (32 KT), O / 16), block 64 C KT <= 1024, dynamic LDS KT * 2 * C * 2 KB.
 struct FusedTorusColArgs {
     float *X;
     i64 ld, woff;
@@ -1626,8 +1627,8 @@ struct FusedTorusColArgs {
     double *partials;    // one per workgroup (CONS only)
 };
 
-template <bool CONS, int KT>
-__global__ void __launch_bounds__(512 * KT) mlp_fused_torus_cols_kernel(FusedTorusColArgs a)
+template <bool CONS, int KT, int MAXC>   // MAXC: the most grid columns (waves per group) a launch may have
+__global__ void __launch_bounds__(64 * MAXC * KT) mlp_fused_torus_cols_kernel(FusedTorusColArgs a)
 {
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -1988,8 +1989,8 @@ MlpWs carve(const dpsgd_ctx *ctx, const dpsgd_model_desc &m, unsigned char *base
 }
 
 // A layer's weight gradient can be fused into the mix when a kernel exists for the topology (Theorem 3's ring; a
-// torus with 3 to 8 columns and at least 3 grid rows) and its tiles divide the matrix.
-bool torus_cols(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 >= 3 && ctx->dim1 <= 8 && ctx->dim0 >= 3; }
+// torus with 3 to 16 columns and at least 3 grid rows; any other W of at most 64 workers) and its tiles divide the matrix.
+bool torus_cols(const dpsgd_ctx *ctx) { return ctx->torus_uniform && ctx->dim1 >= 3 && ctx->dim1 <= 16 && ctx->dim0 >= 3; }
 
 // Any other W of at most 64 workers: the kernel that holds every worker's tile in LDS ("fused_slab": 0 never, 1 where
 // no walk kernel exists, 2 also instead of the torus walk).
@@ -2286,17 +2287,20 @@ dpsgd_status run_mlp_bf16(dpsgd_ctx *ctx, const dpsgd_model_desc &m, float *X, c
             fa.R = ctx->dim0; fa.C = ctx->dim1; fa.K = K; fa.O = O; fa.Bp = Bp; fa.w = ctx->torus_w; fa.gamma = ctx->gamma;
             fa.partials = ctx->d_partials + nparts;
             // two groups of waves side by side (256-byte row segments) when the inputs divide
-            const int kt = (K % 64) == 0 ? 2 : 1;
+            const int kt = ((K % 64) == 0 && fa.C <= 8) ? 2 : 1;
             dim3 grid((unsigned)(K / (32 * kt)), (unsigned)(O / 16));
             np = (i64)grid.x * grid.y * kt;
             if (nparts + np > ctx->partials_cap - 256) return DPSGD_EINVAL;
             const size_t shm = (size_t)2 * fa.C * 2048 * kt;
             if (kt == 2) {
-                if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 2>), grid, dim3(128u * fa.C), shm, s, fa);
-                else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 2>), grid, dim3(128u * fa.C), shm, s, fa);
+                if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 2, 8>), grid, dim3(128u * fa.C), shm, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 2, 8>), grid, dim3(128u * fa.C), shm, s, fa);
+            } else if (fa.C <= 8) {
+                if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 1, 8>), grid, dim3(64u * fa.C), shm, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 1, 8>), grid, dim3(64u * fa.C), shm, s, fa);
             } else {
-                if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 1>), grid, dim3(64u * fa.C), shm, s, fa);
-                else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 1>), grid, dim3(64u * fa.C), shm, s, fa);
+                if (cons) hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<true, 1, 16>), grid, dim3(64u * fa.C), shm, s, fa);
+                else hipLaunchKernelGGL((mlp_fused_torus_cols_kernel<false, 1, 16>), grid, dim3(64u * fa.C), shm, s, fa);
             }
         }
         if (cons) nparts += np;

@@ -100,11 +100,13 @@ def test_step_mlp_bf16_ring(widths, batch, n):
     ((4, 5), (1056, 1024, 10), 40),          # 5 columns; inputs a multiple of 32 but not of 64; ragged minibatch
     ((6, 4), (1024, 1056, 64, 10), 32),      # 4 columns, 33 output tiles
     ((3, 7), (2048, 544, 10), 64),           # 7 columns
+    ((3, 12), (1024, 1024, 10), 32),         # 12 columns: one group of 12 waves per workgroup
+    ((5, 16), (1024, 1024, 10), 32),         # 16 columns, 80 workers: 1024 threads per workgroup
 ])
 def test_step_mlp_bf16_torus(dims, widths, batch):
     """Weight gradient formed inside the torus mix kernel: one wave per grid column, grid rows walked with three
     rows of tiles in registers, row neighbours exchanged through LDS."""
-    step_case(shrink(CONFIG3_TORUS, widths=widths, batch=batch, n=dims[0] * dims[1], torus_dims=dims))
+    step_case(shrink(CONFIG3_TORUS, widths=widths, batch=batch, n=dims[0] * dims[1], torus_dims=dims), expect_fused=True)
 
 
 @pytest.mark.parametrize("topology,n,dims,widths,batch,options", [
@@ -112,7 +114,7 @@ def test_step_mlp_bf16_torus(dims, widths, batch):
     ("ring_chord", 16, None, (1024, 1024, 1024, 10), 32, ()),          # its 16 workers, two fused layers
     ("ring_chord", 40, None, (1024, 1024, 10), 48, ()),                # 40 workers: [16][32] tiles; two operand steps
     ("ring_chord", 6, None, (1056, 1024, 10), 32, ()),                 # fewer workers than waves; 33 column groups: no wider tile divides
-    ("torus", 27, (3, 9), (1024, 1024, 10), 32, ()),                   # 9 grid columns: beyond the torus walk, [16][64] tiles
+    ("torus", 27, (3, 9), (1024, 1024, 10), 32, (("fused_slab", 2),)),  # 9 grid columns, instead of the torus walk: [16][32] tiles
     ("torus", 16, (2, 8), (1024, 1024, 10), 32, ()),                   # 2 grid rows: neighbours coincide, weights differ per entry
     ("torus", 16, (4, 4), (1024, 1024, 10), 32, (("fused_slab", 2),)),  # instead of the torus walk
     ("torus", 64, (8, 8), (1024, 1024, 10), 32, (("fused_slab", 2),)),  # 64 workers fill the 128 KB
