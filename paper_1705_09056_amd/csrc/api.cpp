@@ -339,6 +339,8 @@ dpsgd_status dpsgd_set_option(dpsgd_ctx *ctx, const char *key, int64_t value)
     } else if (k == "fused_slab") {
         if (value < 0 || value > 2) return DPSGD_EINVAL;
         ctx->opt_fused_slab = (int32_t)value;
+    } else if (k == "conv_block") {
+        ctx->opt_conv_block = value ? 1 : 0;
     } else if (k == "time_fused") {
         ctx->opt_time_fused = value ? 1 : 0;
     } else {

@@ -51,6 +51,7 @@ struct dpsgd_ctx {
     int32_t opt_ring_chunks = 1;    // the [16 rows][1 KB] kernel at K = 4096 or 8192: waves own 512-byte pieces 32 KB apart
     int32_t opt_fused_lds = 1;      // dpsgd_step on the ring, minibatch > 32: operands of the fused kernel through LDS
     int32_t opt_time_fused = 0;
+    int32_t opt_conv_block = 1;     // CNN forward: the two convolutions of a resolution-keeping residual block in one launch
     int32_t opt_fused_slab = 1;     // dpsgd_step, bf16 MLP, W without a walk kernel, n <= 64: every worker's tile in LDS (2: also for the torus)
     int32_t opt_class_bwd = 1;      // bf16 MLP: backward of a class layer of at most 16 outputs in one launch
     int32_t opt_conv_band_rows = 0; // output rows per workgroup of the MFMA convolutions: 8, 16, or 0 = chosen per convolution

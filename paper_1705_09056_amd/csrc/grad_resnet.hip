@@ -414,6 +414,12 @@ dpsgd_status launch_grad_resnet(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const
     }
     for (int j = 0; j < p.nblocks; ++j) {
         const ConvDesc &c1 = p.convs[1 + 2 * j], &c2 = p.convs[2 + 2 * j];
+        if (conv_block_forward_ok(ctx, c1, c2) && u_of(j).sign && a_of(j + 1).sign) {
+            if ((st = conv_block_forward(ctx, c1, c2, B, a_of(j), X, ws.wpack_f[1 + 2 * j], ws.wpack_f[2 + 2 * j], u_of(j),
+                                         a_of(j + 1))) != DPSGD_OK)
+                return st;
+            continue;
+        }
         if ((st = conv_forward(ctx, c1, B, a_of(j), X, ws.wpack_f[1 + 2 * j], none, u_of(j))) != DPSGD_OK) return st;
         const ShortcutRef sc{a_of(j).t, c1.Ci, c1.H, c1.W, c1.stride};
         if ((st = conv_forward(ctx, c2, B, u_of(j), X, ws.wpack_f[2 + 2 * j], sc, a_of(j + 1))) != DPSGD_OK) return st;

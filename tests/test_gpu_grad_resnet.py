@@ -157,3 +157,31 @@ def test_workgroup_tile_height_changes_no_bit(widths, batch, n):
     for rows in (8, 16):
         assert np.array_equal(got[rows][0], got[0][0]), f"gradient differs with {rows} rows per workgroup"
         assert np.array_equal(got[rows][1], got[0][1])
+
+
+@pytest.mark.parametrize("widths,batch,n", [((3, 32, 32, 16, 3, 10), 2, 2),    # the benchmark's network: stages 1 and 2 fuse
+                                             ((3, 48, 32, 16, 2, 10), 2, 8),    # six bands per image; 8 workers: one XCD per worker
+                                             ((3, 16, 64, 16, 2, 10), 3, 2),    # 64 pixels wide: stage 1 exceeds the LDS, stage 2 (8 x 32) fuses
+                                             ((3, 32, 16, 16, 1, 10), 1, 3)])   # 16 pixels wide: a pair of MFMA tiles spans two rows
+def test_residual_block_in_one_launch_changes_no_bit(widths, batch, n):
+    """Both forward convolutions of a resolution-keeping residual block in one launch (the intermediate activation
+    stays in LDS for the second one) against the two launches ("conv_block" 0): the same matrix instructions on the
+    same operands, so gradient and loss are bit for bit the same."""
+    cfg = shrink(CONFIGS[4], widths=widths, batch=batch, n=n)
+    d = synth.model_dim(MODEL_RESNET20, widths)
+    ld = synth.padded_stride(d)
+    X, inp, tgt = resnet_inputs(cfg, 0.3)
+    model = B.Model(cfg.model_kind, cfg.widths, compute_bf16=True)
+    out = []
+    for setting in (1, 0):
+        Xd = to_dev(X, ld)
+        Gd = torch.full_like(Xd, 777.0)
+        loss = torch.zeros(cfg.n, device="cuda")
+        print(f"conv_block={setting} widths={widths} n={n} B={batch}", flush=True)
+        with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
+            ctx.set_option("conv_block", setting)
+            ctx.grad(model, Xd, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, Gd, loss, input_is_bf16=True)
+            torch.cuda.synchronize()
+        out.append((Gd.clone(), loss.clone()))
+    assert torch.equal(out[0][1], out[1][1]), "loss differs"
+    assert torch.equal(out[0][0], out[1][0]), "gradient differs"
