@@ -393,7 +393,7 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 // memory once (the backward pass needs it), with its sign bitmap; what is saved is reading it back.  The same matrix
 // instructions on the same operands in the same order as conv3x3_mfma_kernel, so u and out carry the same bits.
 // C = 16 or 32 (every wave keeps all C / 16 output tiles); (TH + 2) W a multiple of 32.
-// grid (H / TH, B, n), block 256, dynamic LDS: the two patches and one band's sign bitmap.
+// grid (H / TH, B, n), block 256, dynamic LDS: the source patch (u takes its place later) and one band's sign bitmap.
 struct ConvBlockArgs {
     const bf16_t *src;               // block input [n*B][C][H][W]
     const bf16_t *wpack1, *wpack2;   // [n][KS][C/16][64][8]
@@ -423,8 +423,10 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
     const int y0 = band * TH, W = a.W, H = a.H, lw = a.lw;
     const int PCX = W + 4, PCU = W + 2;
     bf16_t *xpatch = reinterpret_cast<bf16_t *>(smem);     // [PRX][PCX][PP]: image rows y0 - 2 .., columns -2 ..
-    bf16_t *upatch = xpatch + PRX * PCX * PP;              // [PRU][PCU][PP]: image rows y0 - 1 .., columns -1 ..
-    unsigned char *sign_lds = reinterpret_cast<unsigned char *>(upatch + PRU * PCU * PP);   // TH / 8 * C * W bytes
+    // u takes the source patch's place once conv1 has read it (its values wait in registers across one barrier):
+    // 21 KB instead of 37 KB of LDS at 16 channels x 32 pixels, seven workgroups per CU instead of four
+    bf16_t *upatch = xpatch;                               // [PRU][PCU][PP]: image rows y0 - 1 .., columns -1 ..
+    unsigned char *sign_lds = reinterpret_cast<unsigned char *>(xpatch + PRX * PCX * PP);   // TH / 8 * C * W bytes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
 
@@ -471,7 +473,7 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
             }
         };
         issue(0);
-        const int units = (PRX * PCX + PRU * PCU) * PP / 8;   // both patches start as zeros
+        const int units = PRX * PCX * PP / 8;   // the patch starts as zeros
         for (int u = tid; u < units; u += 256) *reinterpret_cast<u32x4 *>(xpatch + u * 8) = (u32x4){0u, 0u, 0u, 0u};
         __syncthreads();
         commit(0);
@@ -535,11 +537,16 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
     // ---- u = ReLU(conv1(in) + b1) on rows y0 - 1 .. y0 + TH
     load_weights(a.wpack1, PCX);
     __syncthreads();
+    constexpr int MAXP = ((TH + 2) * 32 / 32 + 3) / 4;   // pairs of MFMA tiles per wave at the widest image (32 pixels)
+    u32x4 stash[MAXP][NT];                               // u as conv1 leaves it, until the source patch is free
     {
         const float bias = a.X[(i64)w * a.ld + a.b_off1];
         bf16_t *uT = a.uT + img * C * H * W;
         const int npair = (PRU << lw) >> 5;
-        for (int mp = wave; mp < npair; mp += 4) {
+#pragma unroll
+        for (int it = 0; it < MAXP; ++it) {
+            const int mp = wave + 4 * it;
+            if (mp >= npair) break;
             const bf16_t *pa[2];
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
@@ -562,19 +569,39 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
                 }
                 u32x4 pk = {f2bf_pack(r[0], r[1]), f2bf_pack(r[2], r[3]), f2bf_pack(r[4], r[5]), f2bf_pack(r[6], r[7])};
                 if (!inside) pk = (u32x4){0u, 0u, 0u, 0u};   // a row outside the image is conv2's zero padding
-                const unsigned pw[4] = {pk.x, pk.y, pk.z, pk.w};
-                bf16_t *up = upatch + (uy * PCU + x0 + 1) * PP + o;
-#pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    up[(2 * h) * PP] = (bf16_t)(pw[h] & 0xffffu);
-                    up[(2 * h + 1) * PP] = (bf16_t)(pw[h] >> 16);
-                }
+                stash[it][t] = pk;
                 if (own) {
                     *reinterpret_cast<u32x4 *>(uT + ((o * H + iy) << lw) + x0) = pk;
                     const int q = q0 - W;   // pixel index inside the band's own rows
                     sign_lds[((q >> (lw + 3)) * C + o) * W + ((q & (band_px - 1)) >> 3)] = sign_bits(pk);
                 }
             }
+        }
+    }
+    __syncthreads();   // every wave has read the source patch: u may take its place
+    {
+        const int npair = (PRU << lw) >> 5;
+#pragma unroll
+        for (int it = 0; it < MAXP; ++it) {
+            const int mp = wave + 4 * it;
+            if (mp >= npair) break;
+            const int q0 = mp * 32 + 8 * g;
+            const int uy = q0 >> lw, x0 = q0 & (W - 1);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const unsigned pw[4] = {stash[it][t].x, stash[it][t].y, stash[it][t].z, stash[it][t].w};
+                bf16_t *up = upatch + (uy * PCU + x0 + 1) * PP + t * 16 + n16;
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    up[(2 * h) * PP] = (bf16_t)(pw[h] & 0xffffu);
+                    up[(2 * h + 1) * PP] = (bf16_t)(pw[h] >> 16);
+                }
+            }
+        }
+        // the columns left and right of the image
+        for (int e = tid; e < PRU * 2 * (C / 8); e += 256) {
+            const int c8 = e % (C / 8), side = (e / (C / 8)) & 1, row = e / (2 * (C / 8));
+            *reinterpret_cast<u32x4 *>(upatch + (row * PCU + (side ? W + 1 : 0)) * PP + 8 * c8) = (u32x4){0u, 0u, 0u, 0u};
         }
     }
     flush_signs(a.usign);   // (its barrier also completes the u patch)
@@ -1122,14 +1149,12 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
 }
 
 namespace {
-// Output rows per workgroup of conv_block_fwd_kernel.  8: 38 KB of LDS at 16 channels x 32 pixels, four workgroups per
-// CU; with 16 rows (65 KB, two per CU, an eighth instead of a quarter of u recomputed) the CNN iteration took 2.894
-// instead of 2.877 ms.
+// Output rows per workgroup of conv_block_fwd_kernel.  8: with 16 rows (an eighth instead of a quarter of u recomputed,
+// but three times the LDS and fewer workgroups per CU) the CNN iteration took 2.894 instead of 2.877 ms.
 constexpr int kBlockRows = 8;
 size_t conv_block_lds_bytes(int C, int W)
 {
-    return ((size_t)(kBlockRows + 4) * (W + 4) + (size_t)(kBlockRows + 2) * (W + 2)) * (C + 8) * sizeof(bf16_t) +
-           (size_t)(kBlockRows / 8) * C * W;
+    return (size_t)(kBlockRows + 4) * (W + 4) * (C + 8) * sizeof(bf16_t) + (size_t)(kBlockRows / 8) * C * W;
 }
 }  // namespace
 
@@ -1138,7 +1163,7 @@ bool conv_block_forward_ok(const dpsgd_ctx *ctx, const ConvDesc &c1, const ConvD
     if (!ctx->opt_conv_block) return false;
     if (c1.stride != 1 || c2.stride != 1 || c1.Ci != c1.Co || c2.Ci != c1.Co || c2.Co != c1.Co) return false;
     if (!(c1.Co == 16 || c1.Co == 32) || !fwd_mfma_ok(c1) || !fwd_mfma_ok(c2)) return false;
-    if (c1.H != c2.H || c1.W != c2.W || c1.H % kBlockRows || !(c1.W == 16 || c1.W == 32 || c1.W == 64)) return false;
+    if (c1.H != c2.H || c1.W != c2.W || c1.H % kBlockRows || !(c1.W == 16 || c1.W == 32)) return false;
     return conv_block_lds_bytes(c1.Co, c1.W) <= 64 * 1024;
 }
 
