@@ -392,8 +392,7 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 // pixel-major - rows outside the image as the zeros conv2's padding means - and multiplies again.  u still goes to
 // memory once (the backward pass needs it), with its sign bitmap; what is saved is reading it back.  The same matrix
 // instructions on the same operands in the same order as conv3x3_mfma_kernel, so u and out carry the same bits.
-// C = 16 (every wave keeps all C / 16 output tiles; written for C = 32 as well, which is not launched: see
-// conv_block_forward_ok); (TH + 2) W a multiple of 32.
+// C = 16 or 32 (every wave keeps all C / 16 output tiles); (TH + 2) W a multiple of 32.
 // grid (H / TH, B, n), block 256, dynamic LDS: the source patch (u takes its place later) and one band's sign bitmap.
 struct ConvBlockArgs {
     const bf16_t *src;               // block input [n*B][C][H][W]
@@ -405,7 +404,7 @@ struct ConvBlockArgs {
     i64 ld, b_off1, b_off2;
 };
 
-template <int C, int TH>
+template <int C, int TH, int WMAX>   // WMAX: the widest image a launch may have (sizes the registers u waits in)
 __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
 {
     constexpr int KS = ksteps(C), NT = C / 16, PP = C + 8;
@@ -538,7 +537,7 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
     // ---- u = ReLU(conv1(in) + b1) on rows y0 - 1 .. y0 + TH
     load_weights(a.wpack1, PCX);
     __syncthreads();
-    constexpr int MAXP = ((TH + 2) * 32 / 32 + 3) / 4;   // pairs of MFMA tiles per wave at the widest image (32 pixels)
+    constexpr int MAXP = ((TH + 2) * WMAX / 32 + 3) / 4;   // pairs of MFMA tiles per wave at the widest image
     u32x4 stash[MAXP][NT];                               // u as conv1 leaves it, until the source patch is free
     {
         const float bias = a.X[(i64)w * a.ld + a.b_off1];
@@ -1153,21 +1152,24 @@ namespace {
 // Output rows per workgroup of conv_block_fwd_kernel.  8: with 16 rows (an eighth instead of a quarter of u recomputed,
 // but three times the LDS and fewer workgroups per CU) the CNN iteration took 2.894 instead of 2.877 ms.
 constexpr int kBlockRows = 8;
-size_t conv_block_lds_bytes(int C, int W)
+size_t conv_block_lds_bytes(int C, int W, int th)
 {
-    return (size_t)(kBlockRows + 4) * (W + 4) * (C + 8) * sizeof(bf16_t) + (size_t)(kBlockRows / 8) * C * W;
+    return (size_t)(th + 4) * (W + 4) * (C + 8) * sizeof(bf16_t) + (size_t)(th / 8) * C * W;
 }
+// 16 channels: bands of kBlockRows rows.  32 channels: only images of 16 x 16 pixels, as one band - no row of u is then
+// computed twice (in 8-row bands the launch took 84.7 us against the 81.6 us of the two launches it replaces).
+int conv_block_rows(const ConvDesc &c) { return c.Co == 16 ? kBlockRows : 16; }
 }  // namespace
 
 bool conv_block_forward_ok(const dpsgd_ctx *ctx, const ConvDesc &c1, const ConvDesc &c2)
 {
     if (!ctx->opt_conv_block) return false;
     if (c1.stride != 1 || c2.stride != 1 || c1.Ci != c1.Co || c2.Ci != c1.Co || c2.Co != c1.Co) return false;
-    // (32 channels: 84.7 us against the 81.6 us of the two launches it would replace - 134 registers leave it three
-    // workgroups per CU - so only the 16-channel blocks are taken)
-    if (c1.Co != 16 || !fwd_mfma_ok(c1) || !fwd_mfma_ok(c2)) return false;
-    if (c1.H != c2.H || c1.W != c2.W || c1.H % kBlockRows || !(c1.W == 16 || c1.W == 32)) return false;
-    return conv_block_lds_bytes(c1.Co, c1.W) <= 64 * 1024;
+    if (!(c1.Co == 16 || c1.Co == 32) || !fwd_mfma_ok(c1) || !fwd_mfma_ok(c2)) return false;
+    if (c1.H != c2.H || c1.W != c2.W) return false;
+    if (c1.Co == 16 && (c1.H % kBlockRows || !(c1.W == 16 || c1.W == 32))) return false;
+    if (c1.Co == 32 && !(c1.H == 16 && c1.W == 16)) return false;
+    return conv_block_lds_bytes(c1.Co, c1.W, conv_block_rows(c1)) <= 64 * 1024;
 }
 
 dpsgd_status conv_block_forward(dpsgd_ctx *ctx, const ConvDesc &c1, const ConvDesc &c2, int B, Tensor in, const float *X,
@@ -1177,9 +1179,11 @@ dpsgd_status conv_block_forward(dpsgd_ctx *ctx, const ConvDesc &c1, const ConvDe
     ConvBlockArgs a{};
     a.src = in.t; a.wpack1 = wpack1; a.wpack2 = wpack2; a.uT = u.t; a.yT = out.t; a.usign = u.sign; a.ysign = out.sign;
     a.H = c1.H; a.W = c1.W; a.lw = ilog2(c1.W); a.B = B; a.X = X; a.ld = ctx->ld; a.b_off1 = c1.b_off; a.b_off2 = c2.b_off;
-    const size_t shm = conv_block_lds_bytes(c1.Co, c1.W);
-    const dim3 grid((unsigned)(c1.H / kBlockRows), (unsigned)B, (unsigned)ctx->n);
-    hipLaunchKernelGGL((conv_block_fwd_kernel<16, kBlockRows>), grid, dim3(256), shm, ctx->stream, a);
+    const int th = conv_block_rows(c1);
+    const size_t shm = conv_block_lds_bytes(c1.Co, c1.W, th);
+    const dim3 grid((unsigned)(c1.H / th), (unsigned)B, (unsigned)ctx->n);
+    if (c1.Co == 16) hipLaunchKernelGGL((conv_block_fwd_kernel<16, kBlockRows, 32>), grid, dim3(256), shm, ctx->stream, a);
+    else hipLaunchKernelGGL((conv_block_fwd_kernel<32, 16, 16>), grid, dim3(256), shm, ctx->stream, a);
     return hip_status(hipGetLastError());
 }
 

@@ -159,7 +159,7 @@ def test_workgroup_tile_height_changes_no_bit(widths, batch, n):
         assert np.array_equal(got[rows][1], got[0][1])
 
 
-@pytest.mark.parametrize("widths,batch,n", [((3, 32, 32, 16, 3, 10), 2, 2),    # the benchmark's network: the three blocks of stage 1
+@pytest.mark.parametrize("widths,batch,n", [((3, 32, 32, 16, 3, 10), 2, 2),    # the benchmark's network: the blocks of stages 1 and 2
                                              ((3, 48, 32, 16, 2, 10), 2, 8),    # six bands per image; 8 workers: one XCD per worker
                                              ((3, 8, 32, 16, 2, 10), 3, 2),     # one band per image: both halo rows lie outside it
                                              ((3, 32, 16, 16, 1, 10), 1, 3)])   # 16 pixels wide: a pair of MFMA tiles spans two rows
