@@ -174,7 +174,8 @@ dpsgd_status dpsgd_set_gamma(dpsgd_ctx *ctx, float gamma);
  * of 3 to 16 columns: the weight gradient of the large layers is formed inside a mix kernel that holds every worker's tile
  * in LDS; 0: such a W runs dpsgd_grad and dpsgd_mix_step back to back; 2: that kernel also takes the tori the torus
  * kernel would take.  Results agree to fp32 rounding),
- * "conv_block" (default 1: CNN forward, residual blocks that keep the resolution, 16 channels or 32 on 16 x 16 pixels: both convolutions of
+ * "conv_block" (default 1: CNN forward, residual blocks that keep the resolution (16 channels, 32 on 16 x 16 or 64 on 8 x 8
+ * pixels): both convolutions of
  * the block in one launch, the activation between them kept in LDS for the second one; 0: two launches.  Same bits),
  * "conv_band_rows" (output rows of an image per workgroup of the CNN's 3 x 3 convolution kernels: 8, 16, or 0 = chosen
  * per convolution, the default; every setting gives the same bits),

@@ -392,7 +392,8 @@ __global__ void __launch_bounds__(256) conv3x3_mfma_kernel(ConvMfmaArgs a)
 // pixel-major - rows outside the image as the zeros conv2's padding means - and multiplies again.  u still goes to
 // memory once (the backward pass needs it), with its sign bitmap; what is saved is reading it back.  The same matrix
 // instructions on the same operands in the same order as conv3x3_mfma_kernel, so u and out carry the same bits.
-// C = 16 or 32 (every wave keeps all C / 16 output tiles); (TH + 2) W a multiple of 32.
+// C = 16 or 32 (every wave keeps all C / 16 output tiles) or 64 (a wave keeps one tile of 16 output channels and takes
+// all pixels); (TH + 2) W a multiple of 32, or the band the whole image and TH W a multiple of 32.
 // grid (H / TH, B, n), block 256, dynamic LDS: the source patch (u takes its place later) and one band's sign bitmap.
 struct ConvBlockArgs {
     const bf16_t *src;               // block input [n*B][C][H][W]
@@ -408,6 +409,8 @@ template <int C, int TH, int WMAX>   // WMAX: the widest image a launch may have
 __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
 {
     constexpr int KS = ksteps(C), NT = C / 16, PP = C + 8;
+    // waves that split the output channels (64 channels: one tile of 16 each), and those that split the pixels
+    constexpr int WC = wave_cols(C, C), NTW = NT / WC, WP = 4 / WC;
     constexpr int PRX = TH + 4, PRU = TH + 2;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int band = blockIdx.x, b = blockIdx.y, w = blockIdx.z;
@@ -429,6 +432,10 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
     unsigned char *sign_lds = reinterpret_cast<unsigned char *>(xpatch + PRX * PCX * PP);   // TH / 8 * C * W bytes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
+    const int wc = wave % WC, wp = wave / WC;
+    // a band that is the whole image: the halo rows of u lie outside it, so conv1 multiplies the image's rows only
+    const bool whole = H == TH;
+    const int first = whole ? W : 0, npair1 = ((whole ? TH : PRU) << lw) >> 5;   // conv1's first pixel and pairs of tiles
 
     {   // stage the source rows: a task = (channel pair j, patch row pr, 8 source pixels xc), pixel octets fastest
         constexpr int CP2 = C / 2, FT = 4;
@@ -483,14 +490,14 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
         }
     }
 
-    bf16x8 wf[KS][NT];
+    bf16x8 wf[KS][NTW];
     int koff[KS];
     auto load_weights = [&](const bf16_t *wpack, int PC) {
         const bf16_t *wp_ = wpack + (i64)w * (KS * NT * 512) + lane * 8;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) wf[s][t] = *reinterpret_cast<const bf16x8 *>(wp_ + (s * NT + t) * 512);
+            for (int t = 0; t < NTW; ++t) wf[s][t] = *reinterpret_cast<const bf16x8 *>(wp_ + (s * NT + wc * NTW + t) * 512);
             const int kk = 32 * s + 8 * g;
             int tap = kk / C;
             const int c0 = kk % C;
@@ -499,19 +506,19 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
         }
     };
     // MFMA row r of tile tt is pixel 8 (r / 4) + 4 tt + r % 4 of a group of 32 (see conv3x3_mfma_kernel): accumulator
-    // register i of lane (n16, g) is pixel 8 g + 4 tt + i of channel 16 t + n16
-    auto multiply = [&](const bf16_t *const (&pa)[2], f32x4 (&acc)[2][NT]) {
+    // register i of lane (n16, g) is pixel 8 g + 4 tt + i of channel 16 (wc NTW + t) + n16
+    auto multiply = [&](const bf16_t *const (&pa)[2], f32x4 (&acc)[2][NTW]) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) acc[tt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < NTW; ++t) acc[tt][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
                 const bf16x8 av = *reinterpret_cast<const bf16x8 *>(pa[tt] + koff[s]);
 #pragma unroll
-                for (int t = 0; t < NT; ++t)
+                for (int t = 0; t < NTW; ++t)
                     acc[tt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, wf[s][t], acc[tt][t], 0, 0, 0);
             }
         }
@@ -537,30 +544,29 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
     // ---- u = ReLU(conv1(in) + b1) on rows y0 - 1 .. y0 + TH
     load_weights(a.wpack1, PCX);
     __syncthreads();
-    constexpr int MAXP = ((TH + 2) * WMAX / 32 + 3) / 4;   // pairs of MFMA tiles per wave at the widest image
-    u32x4 stash[MAXP][NT];                               // u as conv1 leaves it, until the source patch is free
+    constexpr int MAXP = ((TH + 2) * WMAX / 32 + WP - 1) / WP;   // pairs of MFMA tiles per wave at the widest image
+    u32x4 stash[MAXP][NTW];                              // u as conv1 leaves it, until the source patch is free
     {
         const float bias = a.X[(i64)w * a.ld + a.b_off1];
         bf16_t *uT = a.uT + img * C * H * W;
-        const int npair = (PRU << lw) >> 5;
 #pragma unroll
         for (int it = 0; it < MAXP; ++it) {
-            const int mp = wave + 4 * it;
-            if (mp >= npair) break;
+            const int mp = wp + WP * it;
+            if (mp >= npair1) break;
             const bf16_t *pa[2];
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
-                const int pi = mp * 32 + 8 * (n16 >> 2) + 4 * tt + (n16 & 3);
+                const int pi = first + mp * 32 + 8 * (n16 >> 2) + 4 * tt + (n16 & 3);
                 pa[tt] = xpatch + ((pi >> lw) * PCX + (pi & (W - 1)) + 1) * PP;
             }
-            const int q0 = mp * 32 + 8 * g;   // first of this lane's 8 pixels (one row: W >= 8)
+            const int q0 = first + mp * 32 + 8 * g;   // first of this lane's 8 pixels (one row: W >= 8)
             const int uy = q0 >> lw, x0 = q0 & (W - 1), iy = y0 - 1 + uy;
             const bool inside = iy >= 0 && iy < H, own = uy >= 1 && uy <= TH;
-            f32x4 acc[2][NT];
+            f32x4 acc[2][NTW];
             multiply(pa, acc);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int o = t * 16 + n16;
+            for (int t = 0; t < NTW; ++t) {
+                const int o = (wc * NTW + t) * 16 + n16;
                 float r[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -580,17 +586,16 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
     }
     __syncthreads();   // every wave has read the source patch: u may take its place
     {
-        const int npair = (PRU << lw) >> 5;
 #pragma unroll
         for (int it = 0; it < MAXP; ++it) {
-            const int mp = wave + 4 * it;
-            if (mp >= npair) break;
-            const int q0 = mp * 32 + 8 * g;
+            const int mp = wp + WP * it;
+            if (mp >= npair1) break;
+            const int q0 = first + mp * 32 + 8 * g;
             const int uy = q0 >> lw, x0 = q0 & (W - 1);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
+            for (int t = 0; t < NTW; ++t) {
                 const unsigned pw[4] = {stash[it][t].x, stash[it][t].y, stash[it][t].z, stash[it][t].w};
-                bf16_t *up = upatch + (uy * PCU + x0 + 1) * PP + t * 16 + n16;
+                bf16_t *up = upatch + (uy * PCU + x0 + 1) * PP + (wc * NTW + t) * 16 + n16;
 #pragma unroll
                 for (int h = 0; h < 4; ++h) {
                     up[(2 * h) * PP] = (bf16_t)(pw[h] & 0xffffu);
@@ -603,6 +608,12 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
             const int c8 = e % (C / 8), side = (e / (C / 8)) & 1, row = e / (2 * (C / 8));
             *reinterpret_cast<u32x4 *>(upatch + (row * PCU + (side ? W + 1 : 0)) * PP + 8 * c8) = (u32x4){0u, 0u, 0u, 0u};
         }
+        if (whole) {   // the rows above and below the image, which conv1 skipped
+            const int row_units = PCU * PP / 8;
+            for (int e = tid; e < 2 * row_units; e += 256)
+                *reinterpret_cast<u32x4 *>(upatch + ((e < row_units ? 0 : PRU - 1) * PCU * PP) + (e % row_units) * 8) =
+                    (u32x4){0u, 0u, 0u, 0u};
+        }
     }
     flush_signs(a.usign);   // (its barrier also completes the u patch)
 
@@ -614,7 +625,7 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
         bf16_t *yT = a.yT + img * C * H * W;
         const bf16_t *scT = a.src + img * C * H * W;
         const int npair = (TH << lw) >> 5;
-        for (int mp = wave; mp < npair; mp += 4) {
+        for (int mp = wp; mp < npair; mp += WP) {
             const bf16_t *pa[2];
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
@@ -623,14 +634,15 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
             }
             const int q0 = mp * 32 + 8 * g;
             const int y = y0 + (q0 >> lw), x0 = q0 & (W - 1);
-            u32x4 sc[NT];   // the block input, fetched before the MFMAs
+            u32x4 sc[NTW];   // the block input, fetched before the MFMAs
 #pragma unroll
-            for (int t = 0; t < NT; ++t) sc[t] = *reinterpret_cast<const u32x4 *>(scT + (((t * 16 + n16) * H + y) << lw) + x0);
-            f32x4 acc[2][NT];
+            for (int t = 0; t < NTW; ++t)
+                sc[t] = *reinterpret_cast<const u32x4 *>(scT + ((((wc * NTW + t) * 16 + n16) * H + y) << lw) + x0);
+            f32x4 acc[2][NTW];
             multiply(pa, acc);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int o = t * 16 + n16;
+            for (int t = 0; t < NTW; ++t) {
+                const int o = (wc * NTW + t) * 16 + n16;
                 const unsigned d[4] = {sc[t].x, sc[t].y, sc[t].z, sc[t].w};
                 float r[8];
 #pragma unroll
@@ -1158,17 +1170,19 @@ size_t conv_block_lds_bytes(int C, int W, int th)
 }
 // 16 channels: bands of kBlockRows rows.  32 channels: only images of 16 x 16 pixels, as one band - no row of u is then
 // computed twice (in 8-row bands the launch took 84.7 us against the 81.6 us of the two launches it replaces).
-int conv_block_rows(const ConvDesc &c) { return c.Co == 16 ? kBlockRows : 16; }
+// 64 channels: images of 8 x 8 pixels, one band.
+int conv_block_rows(const ConvDesc &c) { return c.Co == 16 ? kBlockRows : c.Co == 32 ? 16 : 8; }
 }  // namespace
 
 bool conv_block_forward_ok(const dpsgd_ctx *ctx, const ConvDesc &c1, const ConvDesc &c2)
 {
     if (!ctx->opt_conv_block) return false;
     if (c1.stride != 1 || c2.stride != 1 || c1.Ci != c1.Co || c2.Ci != c1.Co || c2.Co != c1.Co) return false;
-    if (!(c1.Co == 16 || c1.Co == 32) || !fwd_mfma_ok(c1) || !fwd_mfma_ok(c2)) return false;
+    if (!pow2_channels(c1.Co) || !fwd_mfma_ok(c1) || !fwd_mfma_ok(c2)) return false;
     if (c1.H != c2.H || c1.W != c2.W) return false;
     if (c1.Co == 16 && (c1.H % kBlockRows || !(c1.W == 16 || c1.W == 32))) return false;
     if (c1.Co == 32 && !(c1.H == 16 && c1.W == 16)) return false;
+    if (c1.Co == 64 && !(c1.H == 8 && c1.W == 8)) return false;
     return conv_block_lds_bytes(c1.Co, c1.W, conv_block_rows(c1)) <= 64 * 1024;
 }
 
@@ -1183,7 +1197,8 @@ dpsgd_status conv_block_forward(dpsgd_ctx *ctx, const ConvDesc &c1, const ConvDe
     const size_t shm = conv_block_lds_bytes(c1.Co, c1.W, th);
     const dim3 grid((unsigned)(c1.H / th), (unsigned)B, (unsigned)ctx->n);
     if (c1.Co == 16) hipLaunchKernelGGL((conv_block_fwd_kernel<16, kBlockRows, 32>), grid, dim3(256), shm, ctx->stream, a);
-    else hipLaunchKernelGGL((conv_block_fwd_kernel<32, 16, 16>), grid, dim3(256), shm, ctx->stream, a);
+    else if (c1.Co == 32) hipLaunchKernelGGL((conv_block_fwd_kernel<32, 16, 16>), grid, dim3(256), shm, ctx->stream, a);
+    else hipLaunchKernelGGL((conv_block_fwd_kernel<64, 8, 8>), grid, dim3(256), shm, ctx->stream, a);
     return hip_status(hipGetLastError());
 }
 

@@ -64,7 +64,7 @@ dpsgd_status conv_forward(dpsgd_ctx *ctx, const ConvDesc &c, int B, Tensor in, c
 // A residual block that keeps the resolution, both convolutions in one launch: u = conv_forward(c1, in),
 // out = conv_forward(c2, u, shortcut = in), the same bits, without reading u back from memory.  _ok: whether the
 // shapes allow it (stride 1; 16 channels on images of 16 or 32 pixels by a multiple of 8 rows, 32 channels on images of
-// 16 x 16 pixels; "conv_block" option on).
+// 16 x 16 pixels, 64 channels on images of 8 x 8 pixels; "conv_block" option on).
 bool conv_block_forward_ok(const dpsgd_ctx *ctx, const ConvDesc &c1, const ConvDesc &c2);
 dpsgd_status conv_block_forward(dpsgd_ctx *ctx, const ConvDesc &c1, const ConvDesc &c2, int B, Tensor in, const float *X,
                                 const bf16_t *wpack1, const bf16_t *wpack2, Tensor u, Tensor out);

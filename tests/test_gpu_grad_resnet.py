@@ -159,9 +159,9 @@ def test_workgroup_tile_height_changes_no_bit(widths, batch, n):
         assert np.array_equal(got[rows][1], got[0][1])
 
 
-@pytest.mark.parametrize("widths,batch,n", [((3, 32, 32, 16, 3, 10), 2, 2),    # the benchmark's network: the blocks of stages 1 and 2
+@pytest.mark.parametrize("widths,batch,n", [((3, 32, 32, 16, 3, 10), 2, 2),    # the benchmark's network: 16, 32 and 64 channels
                                              ((3, 48, 32, 16, 2, 10), 2, 8),    # six bands per image; 8 workers: one XCD per worker
-                                             ((3, 8, 32, 16, 2, 10), 3, 2),     # one band per image: both halo rows lie outside it
+                                             ((3, 8, 32, 16, 2, 10), 3, 2),     # 16 channels, one band per image: both halo rows lie outside it
                                              ((3, 32, 16, 16, 1, 10), 1, 3)])   # 16 pixels wide: a pair of MFMA tiles spans two rows
 def test_residual_block_in_one_launch_changes_no_bit(widths, batch, n):
     """Both forward convolutions of a resolution-keeping residual block in one launch (the intermediate activation
