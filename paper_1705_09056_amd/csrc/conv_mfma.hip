@@ -65,14 +65,24 @@ constexpr int kPackLds = 64 * 16 * 9;   // bf16 elements: 16 outputs x 64 contra
 __global__ void __launch_bounds__(256) pack_weights_kernel(const float *__restrict__ X, i64 ld, PackTable tbl)
 {
     __shared__ bf16_t tile[kPackLds];
-    // the job of this workgroup: last one whose first block is <= blockIdx.x (bisection over uniform values)
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id and every XCD has its own L2: with n a multiple of 8
+    // the ids are renumbered so that one XCD packs all tiles of a worker, and the weights, which the forward and the
+    // data-gradient tile of a convolution both read, come from memory once instead of once per L2 that wants them.
+    int bx = blockIdx.x, w = blockIdx.y;
+    if ((gridDim.y & 7) == 0) {
+        const unsigned id = blockIdx.x + gridDim.x * blockIdx.y;
+        const unsigned xcd = id & 7, slot = id >> 3;
+        w = (int)((slot / gridDim.x) * 8 + xcd);
+        bx = (int)(slot % gridDim.x);
+    }
+    // the job of this workgroup: last one whose first block is <= bx (bisection over uniform values)
     int lo = 0, hi = tbl.njobs - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if ((int)blockIdx.x >= tbl.job[mid].block0) lo = mid; else hi = mid - 1;
+        if (bx >= tbl.job[mid].block0) lo = mid; else hi = mid - 1;
     }
     const PackJob &jb = tbl.job[lo];
-    const int w = blockIdx.y, t = (int)blockIdx.x - jb.block0, tid = threadIdx.x;
+    const int t = bx - jb.block0, tid = threadIdx.x;
     const int NT = jb.CO / 16;
     const float *Wg = X + (i64)w * ld + jb.w_off;
     const int row9 = jb.Ci * 9;   // floats of one c_out row of W
@@ -700,6 +710,10 @@ __host__ __device__ constexpr int wgrad_stage(int stride, int rb) { return rb ==
 
 __host__ __device__ constexpr int wgrad_channel_pitch(int plane) { return (plane + 119) / 128 * 128 + 8; }
 
+// k-steps whose delta operands a wave requests at once (16 bytes per lane each); two where four workgroups share a CU
+// and leave a wave 128 registers (that is a whole band at 16 channels: 8 k-steps over 4 waves, or 4 over 2)
+__host__ __device__ constexpr int wgrad_delta_ahead(int ci) { return ci <= 16 ? 2 : 4; }
+
 // With 64 x 64 channels a wave that kept all four input-channel tiles would need 144 accumulator
 // registers (one wave per SIMD); two groups of four waves split them instead.
 constexpr int wgrad_wave_groups(int ci, int co) { return (ci >= 64 && co >= 64) ? 2 : 1; }
@@ -712,7 +726,7 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
 {
     constexpr int WM = (CO / 16) < 4 ? (CO / 16) : 4, WK = 4 / WM;
     constexpr int WT = wgrad_wave_groups(CI, CO), NTI = CI / 16 / WT, NT = 256 * WT;
-    constexpr int kWgradStage = wgrad_stage(STRIDE, RB);
+    constexpr int kWgradStage = wgrad_stage(STRIDE, RB), kWgradDeltaAhead = wgrad_delta_ahead(CI);
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *band = reinterpret_cast<bf16_t *>(smem);   // [CI] planes of CP elements, each [ROWS][PLANES][WPAD]
     const int sp = blockIdx.x, w = blockIdx.y;
@@ -792,13 +806,23 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
             if (j + 1 < nb) fetch_band(j + 1);
             // this lane's 8 delta pixels of k-step ks: pixels 32 ks + 8 g .. + 7 of the band (rows are contiguous)
             const bf16_t *dband = a.doutT + ((img * CO + mi * 16 + n16) * a.Ho + y0) * a.Wo + 8 * g;
-            u32x4 av_next = {0u, 0u, 0u, 0u};
-            if (kq < kb) av_next = *reinterpret_cast<const u32x4 *>(dband + 32 * kq);
-            for (int ks = kq; ks < kb; ks += WK) {
+            // The delta operands of kWgradDeltaAhead k-steps are requested together, before the first of them is
+            // multiplied: a k-step is 9 short matrix instructions, far less than a memory latency, so operands fetched
+            // one k-step ahead cost the wave one exposed latency per k-step; fetched together, one per group.
+            for (int ks0 = kq; ks0 < kb; ks0 += WK * kWgradDeltaAhead) {
+            u32x4 dv[kWgradDeltaAhead];
+#pragma unroll
+            for (int e = 0; e < kWgradDeltaAhead; ++e) {
+                dv[e] = (u32x4){0u, 0u, 0u, 0u};
+                if (ks0 + WK * e < kb) dv[e] = *reinterpret_cast<const u32x4 *>(dband + 32 * (ks0 + WK * e));
+            }
+#pragma unroll
+            for (int e = 0; e < kWgradDeltaAhead; ++e) {
+                const int ks = ks0 + WK * e;
+                if (ks >= kb) break;
                 const int q = 32 * ks + 8 * g;          // first of this lane's 8 pixels inside the band
                 const int yy = q / a.Wo, x = q % a.Wo;
-                const u32x4 av = av_next;
-                if (ks + WK < kb) av_next = *reinterpret_cast<const u32x4 *>(dband + 32 * (ks + WK));
+                const u32x4 av = dv[e];
                 if (th == 0)
                     bsum += (bf2f((bf16_t)(av.x & 0xffff)) + bf2f((bf16_t)(av.x >> 16))) +
                             (bf2f((bf16_t)(av.y & 0xffff)) + bf2f((bf16_t)(av.y >> 16))) +
@@ -842,6 +866,7 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
                                                                                      acc[t][ky * 3 + 2], 0, 0, 0);
                     }
                 }
+            }
             }
         }
     }

@@ -7,6 +7,8 @@ whoever computes it (tests/test_oracle_bf16_gap.py shows that on the CPU with tw
 and the kernel must add nothing to that.  The oracle in its bf16-operand mode (the same operand roundings, fp64
 sums; ReLU decisions taken on the same rounded values) is the tight check of the kernel itself: TIGHT on the
 whole gradient and per layer, Frobenius and element-wise."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -105,9 +107,14 @@ def sampled_full_size(cfg, sample):
     with B.Dpsgd(cfg.n, d, topo_for(cfg), cfg.gamma, ld=ld) as ctx:
         ctx.grad(model, Xd, bf16_dev(inp), torch.from_numpy(tgt).cuda(), cfg.batch, Gd, loss, input_is_bf16=True)
         torch.cuda.synchronize()
+    # one oracle call is one worker on one thread: the sampled workers and both rounding modes run side by side
+    with ThreadPoolExecutor(max_workers=2 * len(sample)) as pool:
+        jobs = {(i, mode): pool.submit(oracle.loss_grad, cfg.model_kind, cfg.widths, rows[i], inp[i], tgt[i],
+                                       bf16_operands=mode) for i in sample for mode in (True, False)}
+        done = {key: job.result() for key, job in jobs.items()}
     for i in sample:
-        l, g = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[i], inp[i], tgt[i], bf16_operands=True)
-        lp, gp = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[i], inp[i], tgt[i])
+        l, g = done[(i, True)]
+        lp, gp = done[(i, False)]
         got = Gd[i, :d].cpu().numpy()
         e, m = check_close(got, g, TIGHT, f"worker {i}", flips=True)
         gap_gpu, gap_rounding = rel_err(got, gp), rel_err(g, gp)

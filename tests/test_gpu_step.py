@@ -1,6 +1,8 @@
 """GPU parity of dpsgd_step (one whole iteration of Algorithm 1 in place; weight gradients of large MLP
 layers formed inside the mix kernel) against the CPU oracle's iteration and against the two-call
 sequence dpsgd_grad + dpsgd_mix_step on the same device data."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -215,14 +217,16 @@ def test_step_config3_full_size_one_worker(topology):
           flush=True)
     assert diff < 1e-5
     assert float(ca) == pytest.approx(float(cb), rel=1e-4)
-    _, gme = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[me], inp[me], tgt[me], bf16_operands=True)
+    with ThreadPoolExecutor(max_workers=2) as pool:   # both rounding modes of the oracle side by side
+        jobs = [pool.submit(oracle.loss_grad, cfg.model_kind, cfg.widths, rows[me], inp[me], tgt[me], bf16_operands=mode)
+                for mode in (True, False)]
+        (_, gme), (_, gplain) = [job.result() for job in jobs]
     w = np.float64(np.float32(1.0 / (1 + len(nbrs))))
     want = w * sum(rows[i].astype(np.float64) for i in (me,) + nbrs) - np.float64(np.float32(cfg.gamma)) * gme
     got = Xa[me, :d].cpu().numpy().astype(np.float64)
     e, m = check_close(got - rows[me], want - rows[me], TIGHT, f"worker {me} update vs oracle", flips=True)
     print(f"  worker {me} update vs oracle: {e:.3e} (max element {m:.3e} rms)", flush=True)
     # the un-rounded fp64 oracle binds the iterate itself at the bar of the bf16 workloads
-    _, gplain = oracle.loss_grad(cfg.model_kind, cfg.widths, rows[me], inp[me], tgt[me])
     want_plain = w * sum(rows[i].astype(np.float64) for i in (me,) + nbrs) - np.float64(np.float32(cfg.gamma)) * gplain
     check_close(got, want_plain, TOL, f"worker {me} X_next vs plain oracle")
     # every element of the fused result against the two-call one, not only the norm
