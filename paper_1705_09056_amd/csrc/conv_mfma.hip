@@ -416,7 +416,7 @@ struct ConvBlockArgs {
 };
 
 template <int C, int TH, int WMAX>   // WMAX: the widest image a launch may have (sizes the registers u waits in)
-__global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
+__global__ void __launch_bounds__(256, C == 16 ? 7 : 1) conv_block_fwd_kernel(ConvBlockArgs a)   // 16 channels: the LDS lets 7 workgroups share a CU
 {
     constexpr int KS = ksteps(C), NT = C / 16, PP = C + 8;
     // waves that split the output channels (64 channels: one tile of 16 each), and those that split the pixels
@@ -625,6 +625,27 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
                     (u32x4){0u, 0u, 0u, 0u};
         }
     }
+    // the block input at the wave's output pixels, which conv2's epilogue adds, is requested here (u has left its
+    // registers): it arrives while the bitmap leaves and the second weight set is fetched, instead of costing every
+    // pair of tiles an exposed latency
+    constexpr int MAXP2 = (TH * WMAX / 32 + WP - 1) / WP;
+    const int npair = (TH << lw) >> 5;
+    u32x4 scv[MAXP2][NTW];
+    {
+        const bf16_t *scT = a.src + img * C * H * W;
+#pragma unroll
+        for (int it = 0; it < MAXP2; ++it) {
+            const int mp = wp + WP * it;
+            const int q0 = mp * 32 + 8 * g;
+            const int y = y0 + (q0 >> lw), x0 = q0 & (W - 1);
+#pragma unroll
+            for (int t = 0; t < NTW; ++t) {
+                scv[it][t] = (u32x4){0u, 0u, 0u, 0u};
+                if (mp < npair)
+                    scv[it][t] = *reinterpret_cast<const u32x4 *>(scT + ((((wc * NTW + t) * 16 + n16) * H + y) << lw) + x0);
+            }
+        }
+    }
     flush_signs(a.usign);   // (its barrier also completes the u patch)
 
     // ---- out = ReLU(conv2(u) + b2 + in)
@@ -633,9 +654,10 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
     {
         const float bias = a.X[(i64)w * a.ld + a.b_off2];
         bf16_t *yT = a.yT + img * C * H * W;
-        const bf16_t *scT = a.src + img * C * H * W;
-        const int npair = (TH << lw) >> 5;
-        for (int mp = wp; mp < npair; mp += WP) {
+#pragma unroll
+        for (int it = 0; it < MAXP2; ++it) {
+            const int mp = wp + WP * it;
+            if (mp >= npair) break;
             const bf16_t *pa[2];
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
@@ -644,16 +666,12 @@ __global__ void __launch_bounds__(256) conv_block_fwd_kernel(ConvBlockArgs a)
             }
             const int q0 = mp * 32 + 8 * g;
             const int y = y0 + (q0 >> lw), x0 = q0 & (W - 1);
-            u32x4 sc[NTW];   // the block input, fetched before the MFMAs
-#pragma unroll
-            for (int t = 0; t < NTW; ++t)
-                sc[t] = *reinterpret_cast<const u32x4 *>(scT + ((((wc * NTW + t) * 16 + n16) * H + y) << lw) + x0);
             f32x4 acc[2][NTW];
             multiply(pa, acc);
 #pragma unroll
             for (int t = 0; t < NTW; ++t) {
                 const int o = (wc * NTW + t) * 16 + n16;
-                const unsigned d[4] = {sc[t].x, sc[t].y, sc[t].z, sc[t].w};
+                const unsigned d[4] = {scv[it][t].x, scv[it][t].y, scv[it][t].z, scv[it][t].w};
                 float r[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
