@@ -139,7 +139,7 @@ def test_config2_trajectory_full_widths(capsys):
 
 @pytest.mark.timeout(400)
 def test_config3_trajectory_full_widths(capsys):
-    run_trajectory(shrink(CONFIGS[3], n=3), 6, capsys)
+    run_trajectory(shrink(CONFIGS[3], n=3), 4, capsys)
 
 
 @pytest.mark.timeout(400)
