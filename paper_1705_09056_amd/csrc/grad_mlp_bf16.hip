@@ -1525,24 +1525,30 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
         if (wave == 0) at[buf][lane] = areg;
     };
 
-    float xm[16], xc[16], xh[16], xn[16], xf[16], s1[16], s2[4] = {0.f, 0.f, 0.f, 0.f};
+    // Four tile buffers rotate through the roles (previous worker, this worker, next worker, being fetched): the tile
+    // requested at the start of step i is first read in the epilogue of step i + 1, a whole step later, and no register
+    // is copied from one role to the next (a copy at the end of step i would have to wait for the fetch of step i).
+    float ta[16], tb[16], tc[16], td[16], xh[16], s1[16], s2[4] = {0.f, 0.f, 0.f, 0.f};
     fetch_ops(0);
-    load_tile(xt + (i64)(a.n - 1) * a.ld, rstride, xm);
-    load_tile(xt, rstride, xc);
-    load_tile(xt + (i64)(1 % a.n) * a.ld, rstride, xn);
+    load_tile(xt + (i64)(a.n - 1) * a.ld, rstride, ta);
+    load_tile(xt, rstride, tb);
+    load_tile(xt + (i64)(1 % a.n) * a.ld, rstride, tc);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        xh[v] = xc[v];
+        xh[v] = tb[v];
         s1[v] = 0.f;
     }
     stage_ops(0);
+    fetch_ops(1 < a.n ? 1 : 0);
     __syncthreads();
-    for (int i = 0; i < a.n; ++i) {
+    // one worker: xm, xc, xn hold the tiles of workers i - 1, i, i + 1; xf receives worker i + 2's.  The operands of
+    // worker i + 1 were requested before the barrier that ended step i - 1 (a step and a barrier ahead of the moment
+    // they are written to LDS, so that no wave reaches the barrier late because of them).  Both fetches are
+    // unconditional (exact wait counts): past the last worker the operand fetch repeats the last worker's and the tile
+    // fetch reads one cached line of the operand array (values never used); the operands are requested before the
+    // tile so that they can be waited for without waiting for the tile.
+    auto step = [&](int i, const float (&xm)[16], const float (&xc)[16], const float (&xn)[16], float (&xf)[16]) {
         const int buf = i & 1;
-        // both fetches are unconditional (exact wait counts): past the last worker the operand fetch repeats the last
-        // worker's and the tile fetch reads one cached line of the operand array (values never used); the operands
-        // are issued first so that they can be waited for without waiting for the tile
-        fetch_ops(i + 1 < a.n ? i + 1 : i);
         {
             const bool far = i + 2 < a.n;
             const float *src = far ? xt + (i64)(i + 2) * a.ld : reinterpret_cast<const float *>(a.dzt) + 4 * lane;
@@ -1582,9 +1588,6 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
                     s1[v] += e;
                     s2[t] += e * e;
                 }
-                xm[v] = xc[v];
-                xc[v] = nxt;
-                xn[v] = xf[v];
             }
             __builtin_nontemporal_store(out, reinterpret_cast<f32x4 *>(dst + (i64)r * rstride));
             if (SHADOW) {   // the lane's four columns of the row, 8 bytes; the wave's row piece is 512 consecutive bytes
@@ -1593,7 +1596,18 @@ __global__ void __launch_bounds__(256, 3) mlp_fused_ring_rows_kernel(FusedArgs a
             }
         }
         stage_ops(buf ^ 1);   // every wave has read this buffer's previous contents before the barrier that ended step i - 1
+        fetch_ops(i + 2 < a.n ? i + 2 : a.n - 1);
         __syncthreads();
+    };
+    for (int i = 0;;) {
+        step(i, ta, tb, tc, td);
+        if (++i >= a.n) break;
+        step(i, tb, tc, td, ta);
+        if (++i >= a.n) break;
+        step(i, tc, td, ta, tb);
+        if (++i >= a.n) break;
+        step(i, td, ta, tb, tc);
+        if (++i >= a.n) break;
     }
     if (CONS) {
         float m2 = (s2[0] + s2[1]) + (s2[2] + s2[3]);
