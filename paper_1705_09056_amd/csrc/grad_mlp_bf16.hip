@@ -607,19 +607,26 @@ __global__ void __launch_bounds__(256) mlp_fwd_ksplit_kernel(FwdArgs g)
     stage_w16(0, breg0);
     stage_w32(0);
     stage_a(0);
+    // chunk c + 2 is requested at the end of step c, before the barrier (its registers are free once chunk c + 1 is
+    // staged): it is in flight while the waves wait for each other, not only during the short multiply of step c + 1
+    if (nchunks > 1) {
+        fetch_w16(chunk_k(1), breg0);
+        fetch_w32(chunk_k(1));
+        fetch_a(chunk_k(1));
+    }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
-        if (c + 1 < nchunks) {
-            fetch_w16(chunk_k(c + 1), breg0);
-            fetch_w32(chunk_k(c + 1));
-            fetch_a(chunk_k(c + 1));
-        }
         multiply(buf);
         if (c + 1 < nchunks) {
             stage_w16(buf ^ 1, breg0);
             stage_w32(buf ^ 1);
             stage_a(buf ^ 1);
+        }
+        if (c + 2 < nchunks) {
+            fetch_w16(chunk_k(c + 2), breg0);
+            fetch_w32(chunk_k(c + 2));
+            fetch_a(chunk_k(c + 2));
         }
         __syncthreads();
     }
@@ -983,17 +990,22 @@ __global__ void __launch_bounds__(256) mlp_dgrad_kernel(DgradArgs g)
     fetch(0);
     stage_w16(0, breg0);
     stage(0);
+    // chunk c + 2 is requested at the end of step c, before the barrier (see mlp_fwd_ksplit_kernel)
+    if (nchunks > 1) {
+        fetch_w16(KC, breg0);
+        fetch(KC);
+    }
     __syncthreads();
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
-        if (c + 1 < nchunks) {
-            fetch_w16((c + 1) * KC, breg0);
-            fetch((c + 1) * KC);
-        }
         multiply(buf);
         if (c + 1 < nchunks) {
             stage_w16(buf ^ 1, breg0);
             stage(buf ^ 1);
+        }
+        if (c + 2 < nchunks) {
+            fetch_w16((c + 2) * KC, breg0);
+            fetch((c + 2) * KC);
         }
         __syncthreads();
     }
