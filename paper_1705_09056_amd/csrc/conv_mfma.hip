@@ -736,8 +736,8 @@ __host__ __device__ constexpr int wgrad_delta_ahead(int ci) { return ci <= 16 ? 
 // registers (one wave per SIMD); two groups of four waves split them instead.
 constexpr int wgrad_wave_groups(int ci, int co) { return (ci >= 64 && co >= 64) ? 2 : 1; }
 
-// RB: output rows per band, 8 or 16.  Every band costs a workgroup two exposed memory latencies (the band's first
-// delta operand, and the next band's source rows, which the short multiply does not cover); 16-row bands halve their
+// RB: output rows per band, 8 or 16.  Every band costs a workgroup two barriers and the wait for what it requested a
+// band earlier (the source rows and the delta operands, both in flight across the barriers); 16-row bands halve their
 // number where the image has them.
 template <int CI, int CO, int STRIDE, int RB>
 __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4 : 2)) conv_wgrad_mfma_kernel(WgradMfmaArgs a)
@@ -798,11 +798,28 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
             stg[q] = v;
         }
     };
-    if (nb > 0) fetch_band(0);
-    for (int j = 0; j < nb; ++j) {
+    // The delta operands of kWgradDeltaAhead k-steps of a wave (a whole band's at 16-64 channels on 32-8 pixel rows) are
+    // requested together - a k-step is 9 short matrix instructions, far less than a memory latency - and a group
+    // ahead: the next band's first group goes out right after this band's last multiply, so it is in flight across the
+    // two barriers and the staging writes of the next band instead of being waited for after them.
+    u32x4 dv[kWgradDeltaAhead];
+    auto request_delta = [&](int j, int ks0) {
         const i64 img = (i64)w * a.B + sp + (j / bands_per_img) * a.splits;
+        const int y0 = (j % bands_per_img) * RB;
+        // this lane's 8 delta pixels of k-step ks: pixels 32 ks + 8 g .. + 7 of the band (rows are contiguous)
+        const bf16_t *dband = a.doutT + ((img * CO + mi * 16 + n16) * a.Ho + y0) * a.Wo + 8 * g;
+#pragma unroll
+        for (int e = 0; e < kWgradDeltaAhead; ++e) {
+            dv[e] = (u32x4){0u, 0u, 0u, 0u};
+            if (ks0 + WK * e < kb) dv[e] = *reinterpret_cast<const u32x4 *>(dband + 32 * (ks0 + WK * e));
+        }
+    };
+    if (nb > 0) {
+        fetch_band(0);
+        request_delta(0, kq);
+    }
+    for (int j = 0; j < nb; ++j) {
         {
-            const int y0 = (j % bands_per_img) * RB;
             __syncthreads();   // previous band fully consumed
 #pragma unroll
             for (int q = 0; q < kWgradStage; ++q) {
@@ -820,20 +837,9 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
                     *reinterpret_cast<u32x2 *>(base + WPAD) = od;
                 }
             }
+            if (j + 1 < nb) fetch_band(j + 1);   // (its registers are free: in flight while the waves meet at the barrier)
             __syncthreads();
-            if (j + 1 < nb) fetch_band(j + 1);
-            // this lane's 8 delta pixels of k-step ks: pixels 32 ks + 8 g .. + 7 of the band (rows are contiguous)
-            const bf16_t *dband = a.doutT + ((img * CO + mi * 16 + n16) * a.Ho + y0) * a.Wo + 8 * g;
-            // The delta operands of kWgradDeltaAhead k-steps are requested together, before the first of them is
-            // multiplied: a k-step is 9 short matrix instructions, far less than a memory latency, so operands fetched
-            // one k-step ahead cost the wave one exposed latency per k-step; fetched together, one per group.
             for (int ks0 = kq; ks0 < kb; ks0 += WK * kWgradDeltaAhead) {
-            u32x4 dv[kWgradDeltaAhead];
-#pragma unroll
-            for (int e = 0; e < kWgradDeltaAhead; ++e) {
-                dv[e] = (u32x4){0u, 0u, 0u, 0u};
-                if (ks0 + WK * e < kb) dv[e] = *reinterpret_cast<const u32x4 *>(dband + 32 * (ks0 + WK * e));
-            }
 #pragma unroll
             for (int e = 0; e < kWgradDeltaAhead; ++e) {
                 const int ks = ks0 + WK * e;
@@ -885,6 +891,9 @@ __global__ void __launch_bounds__(256 * wgrad_wave_groups(CI, CO), (CI <= 16 ? 4
                     }
                 }
             }
+            // the group is consumed: the next one of this band, or the first of the next band, takes its registers
+            if (ks0 + WK * kWgradDeltaAhead < kb) request_delta(j, ks0 + WK * kWgradDeltaAhead);
+            else if (j + 1 < nb) request_delta(j + 1, kq);
             }
         }
     }
