@@ -138,67 +138,97 @@ dpsgd_status gemm_f32(hipStream_t s, int nworkers, const GemmArgs &g)
     return hip_status(hipGetLastError());
 }
 
-// Forward of a layer with few outputs (O <= 16, e.g. the 10 classes): one wave per (worker, sample row); lanes
-// stride over the inputs, every lane keeps O partial sums, a wave reduction finishes them.  The tiled GEMM above
-// would launch only a handful of workgroups for such a shape.
-template <int OMAX, bool VEC>
+// Forward of a layer with few outputs (O <= 16, e.g. the 10 classes): one workgroup per worker and R sample rows; its
+// four waves take every fourth 1 KB piece of the rows (lanes stride over the inputs with 16-byte loads), every lane
+// keeps R x O partial sums, a wave reduction and a sum over the four waves (in wave order) finish them.  The tiled GEMM
+// above would launch only a handful of workgroups for such a shape.  With a whole row per wave the launch was short of
+// waves (2048 rows at 128 samples x 16 workers: two waves per SIMD, each a chain of twelve dependent round trips to
+// L2: 36.8 us); with the row split over four waves the weights every workgroup pulls from L2 (120 KB, 245 MB per
+// launch) set the time (30.1 us), so a workgroup takes two rows per weight piece (23.5 us; four rows, or a wave per
+// 1 KB piece with four rows: 27.6 and 40.5 us).
+template <int OMAX, bool VEC, int R>   // R sample rows per workgroup: a weight piece fetched from L2 serves R rows
 __global__ void __launch_bounds__(256)
 linear_fwd_skinny_kernel(const float *__restrict__ act, const float *__restrict__ X, i64 ld, i64 woff, i64 boff, int B, int I,
                          int O, int relu, float *__restrict__ out)
 {
     typedef float f4 __attribute__((ext_vector_type(4)));
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);   // sample row inside the worker
+    __shared__ float part[4][R][OMAX];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row0 = blockIdx.x * R;   // first sample row inside the worker
     const int w = blockIdx.y;
-    if (row >= B) return;
-    const float *a = act + ((i64)w * B + row) * I;
+    const float *a = act + ((i64)w * B + row0) * I;
     const float *Wg = X + (i64)w * ld + woff;
-    float acc[OMAX];
+    const int nr = B - row0 < R ? B - row0 : R;
+    float acc[R][OMAX];
 #pragma unroll
-    for (int o = 0; o < OMAX; ++o) acc[o] = 0.f;
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int o = 0; o < OMAX; ++o) acc[r][o] = 0.f;
     if (VEC) {   // I % 4 == 0 and 16-byte aligned rows: 4 consecutive inputs per lane and step
-#pragma unroll 2
-        for (int k = lane * 4; k < I; k += 256) {
-            const f4 av = *reinterpret_cast<const f4 *>(a + k);
+#pragma unroll 3
+        for (int k = (wave * 64 + lane) * 4; k < I; k += 1024) {
+            f4 av[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) av[r] = *reinterpret_cast<const f4 *>(a + (i64)(r < nr ? r : 0) * I + k);
 #pragma unroll
             for (int o = 0; o < OMAX; ++o)
                 if (o < O) {
                     const f4 wv = *reinterpret_cast<const f4 *>(Wg + (i64)o * I + k);
-                    acc[o] = av.x * wv.x + acc[o];
-                    acc[o] = av.y * wv.y + acc[o];
-                    acc[o] = av.z * wv.z + acc[o];
-                    acc[o] = av.w * wv.w + acc[o];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        acc[r][o] = av[r].x * wv.x + acc[r][o];
+                        acc[r][o] = av[r].y * wv.y + acc[r][o];
+                        acc[r][o] = av[r].z * wv.z + acc[r][o];
+                        acc[r][o] = av[r].w * wv.w + acc[r][o];
+                    }
                 }
         }
     } else {
-        for (int k = lane; k < I; k += 64) {
-            const float av = a[k];
+        for (int k = wave * 64 + lane; k < I; k += 256) {
+            float av[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) av[r] = a[(i64)(r < nr ? r : 0) * I + k];
 #pragma unroll
             for (int o = 0; o < OMAX; ++o)
-                if (o < O) acc[o] = av * Wg[(i64)o * I + k] + acc[o];
+                if (o < O) {
+                    const float wv = Wg[(i64)o * I + k];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) acc[r][o] = av[r] * wv + acc[r][o];
+                }
         }
     }
 #pragma unroll
-    for (int o = 0; o < OMAX; ++o) {
-        float v = acc[o];
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-        if (lane == 0 && o < O) {
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int o = 0; o < OMAX; ++o) {
+            float v = acc[r][o];
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+            if (lane == 0) part[wave][r][o] = v;
+        }
+    __syncthreads();
+    if ((int)threadIdx.x < nr * OMAX) {
+        const int r = threadIdx.x / OMAX, o = threadIdx.x % OMAX;
+        if (o < O) {
+            float v = ((part[0][r][o] + part[1][r][o]) + part[2][r][o]) + part[3][r][o];   // in wave order
             v += X[(i64)w * ld + boff + o];
             if (relu) v = v > 0.f ? v : 0.f;
-            out[((i64)w * B + row) * O + o] = v;
+            out[((i64)w * B + row0 + r) * O + o] = v;
         }
     }
 }
 
-// gb[w][o] = sum_b dz[w][b][o]
+// gb[w][o] = sum_b dz[w][b][o]: a wave per output, its lanes stride over the samples (a thread per output walking the
+// samples one after the other was a chain of B dependent loads: 9.5 us for 10 outputs x 128 samples)
 __global__ void __launch_bounds__(256)
 bias_grad_kernel(const float *__restrict__ dz, int B, int O, float *__restrict__ G, i64 ld, i64 boff)
 {
-    const int o = blockIdx.x * 256 + threadIdx.x, w = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int o = blockIdx.x * 4 + (threadIdx.x >> 6), w = blockIdx.y;
     if (o >= O) return;
     float s = 0.f;
-    for (int b = 0; b < B; ++b) s += dz[((i64)w * B + b) * O + o];
-    G[(i64)w * ld + boff + o] = s;
+    for (int b = lane; b < B; b += 64) s += dz[((i64)w * B + b) * O + o];
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+    if (lane == 0) G[(i64)w * ld + boff + o] = s;
 }
 
 __global__ void __launch_bounds__(256) bf16_to_f32_kernel(const uint16_t *__restrict__ in, float *__restrict__ out, i64 count)
@@ -302,12 +332,13 @@ dpsgd_status launch_grad_f32(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const fl
         if (O <= 16 && I >= 256) {
             const bool vec = (I % 4) == 0 && (woff[l] % 4) == 0 && (ctx->ld % 4) == 0 &&
                              (reinterpret_cast<uintptr_t>(X) % 16) == 0 && (reinterpret_cast<uintptr_t>(act[l]) % 16) == 0;
-            dim3 sgrid((unsigned)((B + 3) / 4), (unsigned)n);
+            constexpr int R = 2;
+            dim3 sgrid((unsigned)((B + R - 1) / R), (unsigned)n);
             if (vec)
-                hipLaunchKernelGGL((linear_fwd_skinny_kernel<16, true>), sgrid, dim3(256), 0, s, act[l], X, ctx->ld, woff[l],
+                hipLaunchKernelGGL((linear_fwd_skinny_kernel<16, true, R>), sgrid, dim3(256), 0, s, act[l], X, ctx->ld, woff[l],
                                    boff[l], B, I, O, g.relu, (float *)act[l + 1]);
             else
-                hipLaunchKernelGGL((linear_fwd_skinny_kernel<16, false>), sgrid, dim3(256), 0, s, act[l], X, ctx->ld, woff[l],
+                hipLaunchKernelGGL((linear_fwd_skinny_kernel<16, false, R>), sgrid, dim3(256), 0, s, act[l], X, ctx->ld, woff[l],
                                    boff[l], B, I, O, g.relu, (float *)act[l + 1]);
             if ((st = hip_status(hipGetLastError())) != DPSGD_OK) return st;
             continue;
@@ -325,7 +356,7 @@ dpsgd_status launch_grad_f32(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const fl
         g.C = G + woff[l]; g.sCw = ctx->ld; g.sCm = I; g.sCn = 1;
         g.M = O; g.N = I; g.K = B;
         if ((st = gemm_f32(s, n, g)) != DPSGD_OK) return st;
-        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((O + 255) / 256), (unsigned)n), dim3(256), 0, s, dz, B, O, G,
+        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((O + 3) / 4), (unsigned)n), dim3(256), 0, s, dz, B, O, G,
                            ctx->ld, boff[l]);
         if (l > 0) {   // data gradient through the ReLU: dz_prev = (dz W_l) * [act_l > 0]
             GemmArgs h{};
