@@ -55,7 +55,12 @@ def test_softmax_config1():
     grad_case(cfg, synth.padded_stride(30730))
 
 
-@pytest.mark.parametrize("widths,batch,n", [((70, 3), 9, 4), ((129, 10), 65, 2), ((64, 1), 64, 3)])
+@pytest.mark.parametrize("widths,batch,n", [((70, 3), 9, 4), ((129, 10), 65, 2), ((64, 1), 64, 3),
+                                            # 256 inputs or more and at most 16 outputs: the forward that splits a pair of
+                                            # sample rows over four waves (odd minibatch: a last row alone; 259 inputs:
+                                            # no 16-byte loads; 1100: a ragged last 1 KB piece) and the bias gradient
+                                            # with a wave per output
+                                            ((300, 7), 33, 3), ((259, 16), 5, 2), ((1100, 10), 64, 2)])
 def test_softmax_ragged(widths, batch, n):
     cfg = shrink(CONFIGS[1], widths=widths, batch=batch, n=n)
     d = synth.model_dim(MODEL_SOFTMAX, widths)
