@@ -243,7 +243,7 @@ __global__ void __launch_bounds__(256) bf16_to_f32_kernel(const uint16_t *__rest
 // worker, one thread per sample.  dz = (softmax - onehot)/B, loss[w] = mean_b(lse - z[label]).
 __global__ void __launch_bounds__(256)
 softmax_xent_kernel(const float *__restrict__ z, const int *__restrict__ labels, int B, int C, float *__restrict__ dz,
-                    float *__restrict__ loss)
+                    float *__restrict__ loss, float *__restrict__ G, long long ld, long long boff)
 {
     __shared__ float red[256];
     const int w = blockIdx.x;
@@ -269,6 +269,16 @@ softmax_xent_kernel(const float *__restrict__ z, const int *__restrict__ labels,
         __syncthreads();
     }
     if (loss && threadIdx.x == 0) loss[w] = red[0] * invB;
+    if (G) {   // the class layer's bias gradient: the worker's dz rows were written by this workgroup, before the barriers
+               // above; a wave per class, lanes stride over the samples (the sums of bias_grad_kernel, bit for bit)
+        const int lane = threadIdx.x & 63;
+        for (int c = threadIdx.x >> 6; c < C; c += 4) {
+            float s = 0.f;
+            for (int b = lane; b < B; b += 64) s += dz[((i64)w * B + b) * C + c];
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+            if (lane == 0) G[(i64)w * ld + boff + c] = s;
+        }
+    }
 }
 
 size_t f32_workspace_bytes(const dpsgd_ctx *ctx, const dpsgd_model_desc &m)
@@ -347,7 +357,7 @@ dpsgd_status launch_grad_f32(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const fl
     }
     const int C = m.widths[L];
     hipLaunchKernelGGL(softmax_xent_kernel, dim3((unsigned)n), dim3(256), 0, s, act[L], (const int *)targets, B, C, dz,
-                       loss);
+                       loss, G, (long long)ctx->ld, (long long)boff[L - 1]);   // with the class layer's bias gradient
     for (int l = L - 1; l >= 0; --l) {
         const int I = m.widths[l], O = m.widths[l + 1];
         GemmArgs g{};   // weight gradient: dW[o][i] = sum_b dz[b][o] act_l[b][i]
@@ -356,8 +366,9 @@ dpsgd_status launch_grad_f32(dpsgd_ctx *ctx, const dpsgd_model_desc &m, const fl
         g.C = G + woff[l]; g.sCw = ctx->ld; g.sCm = I; g.sCn = 1;
         g.M = O; g.N = I; g.K = B;
         if ((st = gemm_f32(s, n, g)) != DPSGD_OK) return st;
-        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((O + 3) / 4), (unsigned)n), dim3(256), 0, s, dz, B, O, G,
-                           ctx->ld, boff[l]);
+        if (l < L - 1)   // (the class layer's came with the softmax launch)
+            hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((O + 3) / 4), (unsigned)n), dim3(256), 0, s, dz, B, O, G,
+                               ctx->ld, boff[l]);
         if (l > 0) {   // data gradient through the ReLU: dz_prev = (dz W_l) * [act_l > 0]
             GemmArgs h{};
             h.A = dz; h.sAw = (i64)B * O; h.sAm = O; h.sAk = 1;
